@@ -1,0 +1,187 @@
+"""Pins for the oracle's group quantization (Sec. 3.2, Eq. 1-3), the staged rounds and
+the encode/decode replay (Sec. 4.2, Eq. 7)."""
+import numpy as np
+import pytest
+
+from oracle import qvg_oracle as O
+from conftest import bits_to_f32, f32_to_bf16_bits_torch
+
+
+def _f16(bits):
+    return np.asarray(bits, np.uint16).view(np.float16).astype(np.float32)
+
+
+@pytest.mark.parametrize("B,bits", [(16, 2), (32, 2), (64, 2), (128, 2), (32, 4)])
+def test_quant_round_scale_codes_and_eq3_bound(rng, B, bits):
+    N, d = 64, 128
+    qmax = 2 ** (bits - 1) - 1
+    r = (rng.standard_normal((N, d)) * rng.lognormal(0, 1, (N, 1))).astype(np.float32)
+    q, sc, r_after = O.quant_round(r, B, bits)
+    s = _f16(sc)                                                     # numpy's f16 decode
+    # Eq. 2: scale = max|x| / qmax, stored as binary16 (numpy's conversion)
+    gmax = np.abs(r).reshape(N, d // B, B).max(-1)
+    assert np.array_equal(sc, (gmax / np.float32(qmax)).astype(np.float16).view(np.uint16))
+    # codes within the b-bit symmetric range
+    assert q.min() >= -qmax and q.max() <= qmax
+    s_el = np.repeat(s, B, axis=1)
+    # Eq. 1: what was removed is scale * q, what remains is the rounding error
+    recon = s_el.astype(np.float64) * q
+    assert np.allclose(r.astype(np.float64) - recon, r_after, rtol=0, atol=1e-6 * np.abs(r).max())
+    # Eq. 3: |x - x_hat| <= S/2, plus the slack when binary16 rounded the scale down
+    slack = np.maximum(np.repeat(gmax - qmax * s, B, axis=1), 0)
+    assert (np.abs(r_after) <= s_el / 2 * (1 + 1e-6) + slack).all()
+    # round to nearest: q is the nearest integer to r/s (within the clamp)
+    u = r.astype(np.float64) / np.where(s_el == 0, 1, s_el)
+    assert (np.abs(np.clip(np.rint(u), -qmax, qmax) - q) <= (np.abs(u - np.rint(u)) > 0.499)).all()
+
+
+def test_quant_zero_group_and_ties_to_even():
+    r = np.zeros((1, 32), np.float32)
+    q, sc, ra = O.quant_round(r, 16, 2)
+    assert (q == 0).all() and (sc == 0).all() and (ra == 0).all()
+    # scale 1: 0.5 -> 0 (tie to even), 0.75 -> 1, -0.5 -> 0, 1.0 -> 1
+    r = np.zeros((1, 16), np.float32)
+    r[0, :5] = [1.0, 0.5, 0.75, -0.5, -0.51]
+    q, sc, ra = O.quant_round(r, 16, 2)
+    assert q[0, :5].tolist() == [1, 0, 1, 0, -1]
+    assert _f16(sc)[0, 0] == 1.0
+    # 4 bit, scale 1 (max 7): 2.5 -> 2, 3.5 -> 4
+    r = np.zeros((1, 16), np.float32)
+    r[0, :3] = [7.0, 2.5, 3.5]
+    q, _, _ = O.quant_round(r, 16, 4)
+    assert q[0, :3].tolist() == [7, 2, 4]
+
+
+def test_quant_scale_saturates_at_binary16_max():
+    r = np.zeros((1, 16), np.float32)
+    r[0, :3] = [1e6, -3e5, 10.0]
+    q, sc, ra = O.quant_round(r, 16, 2)
+    assert _f16(sc)[0, 0] == 65504.0
+    assert q[0, :3].tolist() == [1, -1, 0]            # clamped, not 15 and -5
+
+
+def test_staged_error_non_increasing_and_bounded(rng):
+    N, d, B = 128, 128, 64
+    r0 = (rng.standard_normal((N, d)) * 3).astype(np.float32)
+    r = r0.copy()
+    prev = np.abs(r0)
+    gmax0 = np.repeat(np.abs(r0).reshape(N, d // B, B).max(-1), B, axis=1)
+    for t in range(1, 5):
+        q, sc, r = O.quant_round(r, B, 2)
+        assert set(np.unique(q)).issubset({-1, 0, 1})
+        assert (np.abs(r) <= prev).all()                      # elementwise, hence in any norm
+        assert (np.abs(r) <= gmax0 / 2 ** t * (1 + 2.0 ** -9)).all()
+        prev = np.abs(r)
+
+
+def _grid_input(rng, N, d, B, T):
+    """x = c + r where every element of r is zero or +-s_t for ONE round t, with
+    power-of-two scales s_t = s_1 / 4^(t-1): everything is exactly representable in
+    bf16, every group holds every level (so round t sees max = s_t, the larger levels
+    having been removed exactly and the smaller ones rounding to zero), hence encode
+    must recover q_t and s_t, and decode must return x bit for bit."""
+    c_vals = np.array([-2.0, -1.0, 1.0, 2.0])             # |c| <= 4 keeps c + s_3 within 8 bits
+    K = 4
+    cent = np.zeros((K, d), np.float32)
+    for j in range(K):
+        cent[j] = c_vals[j] * (1 + (np.arange(d) % 2))        # rows differ clearly
+    ids = rng.integers(0, K, N)
+    level = rng.integers(0, T + 1, (N, d))                    # 0 = exactly on the centroid
+    g = level.reshape(N, d // B, B)
+    for t in range(1, T + 1):
+        g[:, :, t] = t                                        # each group holds each level
+    level = g.reshape(N, d)
+    sign = rng.choice([-1, 1], (N, d))
+    s1 = 0.5
+    x = cent[ids].astype(np.float64)
+    levels = []
+    for t in range(1, T + 1):
+        s = s1 / 4 ** (t - 1)
+        q = np.where(level == t, sign, 0)
+        levels.append((s, q))
+        x = x + s * q
+    return x.astype(np.float32), cent, ids, levels
+
+
+@pytest.mark.parametrize("T", [1, 2, 3])
+def test_exact_on_grid_roundtrip(rng, T):
+    N, d, B = 96, 128, 32
+    x, cent, ids, levels = _grid_input(rng, N, d, B, T)
+    xb = f32_to_bf16_bits_torch(x)
+    assert np.array_equal(bits_to_f32(xb), x)                 # grid is representable in bf16
+    cb = f32_to_bf16_bits_torch(cent)
+    enc = O.encode_unit(xb, K=4, B=B, S=1, T=T, iters=0, init=cb[None], want_resid=True)
+    assert np.array_equal(enc["ids"][0], ids.astype(np.uint8))
+    for t, (s, q) in enumerate(levels):
+        assert np.array_equal(O.unpack(enc["codes"][:, t], 2), q.astype(np.int8))
+        assert (_f16(enc["scales"][:, t]) == np.float32(s)).all()
+    assert (enc["resid"] == 0).all()
+    out = O.decode_unit(enc["cent"], enc["ids"], enc["codes"], enc["scales"], B)
+    assert np.array_equal(out, xb)
+
+
+def test_decode_equals_closed_form(rng):
+    """Eq. 7 as one numpy expression on randomly filled storage (not produced by encode)."""
+    N, d, K, B, T, S = 50, 128, 7, 32, 3, 2
+    cent = f32_to_bf16_bits_torch(rng.standard_normal((S, K, d)))
+    ids = rng.integers(0, K, (S, N)).astype(np.uint8)
+    q = rng.integers(-1, 2, (N, T, d)).astype(np.int8)
+    codes = O.pack(q, 2)
+    sc = np.abs(rng.standard_normal((N, T, d // B))).astype(np.float16)
+    out, f32 = O.decode_unit(cent, ids, codes, sc.view(np.uint16), B, want_f32=True)
+    cf = bits_to_f32(cent).astype(np.float64)
+    want = sum(cf[s][ids[s]] for s in range(S))
+    want = want + (np.repeat(sc.astype(np.float64), B, axis=2) * q).sum(1)
+    assert np.allclose(f32, want, rtol=1e-6, atol=1e-6)
+    # bf16 output is the RNE rounding of the fp32 value (torch's conversion)
+    assert np.array_equal(out, f32_to_bf16_bits_torch(f32))
+
+
+def test_decode_encode_error_bound_and_monotone_in_T(rng):
+    from paper_2602_02958_amd.configs import CONFIGS
+    from paper_2602_02958_amd import synth
+    from conftest import bf16_bits
+    wl = CONFIGS["cfg1_tiny"]
+    x = synth.MixtureStream(wl, 1, 0).next_chunk(1024)
+    init = synth.cold_start_centroids(x, 16)
+    xb, ib = bf16_bits(x)[0], bf16_bits(init)[0]
+    xf = bits_to_f32(xb).astype(np.float64)
+    errs = []
+    for T in (1, 2, 3, 4):
+        enc = O.encode_unit(xb, K=16, B=64, S=1, T=T, iters=4, init=ib[None])
+        _, f32 = O.decode_unit(enc["cent"], enc["ids"], enc["codes"], enc["scales"], 64, want_f32=True)
+        errs.append(np.abs(xf - f32).max())
+        if T > 1:
+            # more rounds only append to the stored stream
+            assert np.array_equal(enc["codes"][:, :T - 1], prev["codes"])
+            assert np.array_equal(enc["scales"][:, :T - 1], prev["scales"])
+        prev = enc
+        r0 = xf - bits_to_f32(enc["cent"][0])[enc["ids"][0]]
+        gmax0 = np.repeat(np.abs(r0).reshape(1024, 2, 64).max(-1), 64, axis=1)
+        assert (np.abs(xf - f32) <= gmax0 / 2 ** T * (1 + 2.0 ** -9) + 1e-6).all()
+    assert all(b <= a for a, b in zip(errs, errs[1:]))
+
+
+def test_smoothing_lowers_quantization_error_on_clustered_data(rng):
+    """Direction check of Sec. 4.1: subtracting centroids shrinks the error (the paper's
+    6.9x / 2.6x are for real KV; only the direction is checked here)."""
+    from paper_2602_02958_amd.configs import CONFIGS
+    from paper_2602_02958_amd import synth
+    from conftest import bf16_bits
+    x = synth.MixtureStream(CONFIGS["cfg1_tiny"], 1, 0).next_chunk(2048)
+    xb = bf16_bits(x)[0]
+    xf = bits_to_f32(xb)
+    init = bf16_bits(synth.cold_start_centroids(x, 16))[0]
+    enc = O.encode_unit(xb, K=16, B=64, S=1, T=1, iters=10, init=init[None], want_resid=True)
+    _, _, r_plain = O.quant_round(xf, 64, 2)                 # no smoothing at all
+    mse_s = float((enc["resid"].astype(np.float64) ** 2).mean())
+    mse_p = float((r_plain.astype(np.float64) ** 2).mean())
+    assert mse_s < mse_p / 2
+    # a second smoothing stage (the paper's PRQ, S = 2) lowers it further or keeps it
+    enc2 = O.encode_unit(xb, K=16, B=64, S=2, T=1, iters=10,
+                         init_idx=np.arange(16, dtype=np.int32) * 100, want_resid=True)
+    enc1 = O.encode_unit(xb, K=16, B=64, S=1, T=1, iters=10,
+                         init_idx=np.arange(16, dtype=np.int32) * 100, want_resid=True)
+    assert (enc2["resid"].astype(np.float64) ** 2).mean() <= (enc1["resid"].astype(np.float64) ** 2).mean()
+    out2 = O.decode_unit(enc2["cent"], enc2["ids"], enc2["codes"], enc2["scales"], 64)
+    assert np.abs(bits_to_f32(out2) - xf).max() <= np.abs(enc2["resid"]).max() + 2.0 ** -7 * np.abs(xf).max()
