@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the QVG KV-cache codec hot path on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2_window21]
+
+One step = encode the new chunk + decode the whole cache + fused dequant-attention
+(paper_2602_02958_amd/workload.py).  Prints ONE JSON line.  `value` is the bf16-equivalent
+KV throughput of the whole step: 256 B x (vectors encoded + vectors decoded + vectors read by
+the fused attention) / step time, inputs resident in HBM.  Per-phase rates, the roofline of
+the dominant kernel (and of the other two phases), a large-shape supplement that does not fit
+the Infinity Cache, and the CPU oracle timed on the host cores are in the same line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def _event_ms(fn, reps):
+    """Average duration of fn() in ms over reps runs, HIP events on torch's current stream
+    (the stream the library launches on)."""
+    import torch
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    b.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def _format_bytes(wl, units, tokens, chunk):
+    """Algorithmic bytes of the stored format for `tokens` tokens of `units` units."""
+    per_tok = wl.n_stages * (wl.head_dim // 4 + 2 * wl.head_dim // wl.group_size) + 1
+    tables = -(-tokens // chunk) * wl.n_clusters * wl.head_dim * 2
+    return units * (tokens * per_tok + tables)
+
+
+def cpu_baseline(wl, seconds_hint=20.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+    import numpy as np
+    import torch
+    from oracle import qvg_oracle as O
+    from paper_2602_02958_amd import synth
+    cores = O.max_threads()
+    units = max(1, min(2 * wl.heads, cores))
+    n_enc = min(wl.chunk, 4680)
+    st = synth.MixtureStream(wl, units, 0)
+    x = st.next_chunk(n_enc)
+    init = synth.cold_start_centroids(x, wl.n_clusters)
+    xb = x.view(torch.int16).numpy().view(np.uint16)
+    ib = init.view(torch.int16).numpy().view(np.uint16)
+    t0 = time.perf_counter()
+    enc = O.encode_batch(xb, ib, wl.n_clusters, wl.group_size, wl.n_stages, wl.kmeans_iters_warm)
+    t_enc = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    reps_dec = 4
+    for _ in range(reps_dec):
+        dec = O.decode_batch(enc["cent"], enc["ids"], enc["codes"], enc["scales"], wl.group_size)
+    t_dec = (time.perf_counter() - t0) / reps_dec
+    heads_a = max(1, units // 2)
+    nq = 64
+    q = synth.queries(wl, heads_a, nq).view(torch.int16).numpy().view(np.uint16)
+    t0 = time.perf_counter()
+    O.attention_batch(q, dec[:heads_a], dec[heads_a:2 * heads_a] if units >= 2 else dec[:heads_a])
+    t_att = time.perf_counter() - t0
+    vec_enc, vec_dec = units * n_enc, units * n_enc
+    vec_att = 2 * heads_a * n_enc * (nq / max(wl.n_queries, 1))   # share of a full query batch
+    total_vec = vec_enc + vec_dec + vec_att
+    total_t = t_enc + t_dec + t_att
+    return {
+        "value": round(total_vec * 256 / total_t / 1e9, 6), "unit": "GB/s", "cores": cores,
+        "kind": "oracle",
+        "sample": (f"{units} units x {n_enc} tokens: encode (I={wl.kmeans_iters_warm}) {t_enc:.2f}s, "
+                   f"decode {t_dec:.3f}s, attention {nq} queries x {heads_a} heads over {n_enc} tokens "
+                   f"{t_att:.2f}s (attention vectors scaled by {nq}/{wl.n_queries} of a query batch)"),
+        "encode_GBps": round(vec_enc * 256 / t_enc / 1e9, 6),
+        "decode_GBps": round(vec_dec * 256 / t_dec / 1e9, 6),
+        "attn_q_tokens_per_s": round(heads_a * nq / t_att, 3),
+    }
+
+
+def large_supplement(torch, B, synth, CONFIGS):
+    """cfg3-shaped batches that exceed the 256 MB Infinity Cache: decode of 3 layers' full cache
+    and single-pass / warm encode of one chunk of all 30 layers."""
+    wl = CONFIGS["cfg3_dit_small"]
+    dev = "cuda"
+    out = {"workload": "cfg3_dit_small"}
+    # ---- encode: one chunk, all layers x heads x (K,V) = 720 units
+    units = 2 * wl.layers * wl.heads
+    st = synth.MixtureStream(wl, units, 0, dev)
+    x = st.next_chunk(wl.chunk)
+    init = synth.cold_start_centroids(x, wl.n_clusters)
+    cache = B.alloc_cache(units, wl.chunk, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
+    p = B.make_params(units, wl.n_clusters, wl.group_size, wl.n_stages, wl.kmeans_iters_cold)
+    ws = torch.empty(B.workspace_bytes(p, B.ENTRY_ENCODE, wl.chunk), dtype=torch.uint8, device=dev)
+    B.encode_chunk(x, init, wl.group_size, wl.n_stages, wl.kmeans_iters_cold, cache=cache, workspace=ws)
+    warm = cache.centroids[:, 0].contiguous()
+    vec = units * wl.chunk
+    alg = vec * 256 + _format_bytes(wl, units, wl.chunk, wl.chunk)
+    for name, iters in (("encode_I0", 0), ("encode_I3", 3), ("encode_I10", 10)):
+        fn = lambda: B.encode_chunk(x, warm if iters < 10 else init, wl.group_size, wl.n_stages, iters,
+                                    cache=cache, workspace=ws)
+        fn(); torch.cuda.synchronize()
+        ms = _event_ms(fn, 3)
+        flops = 2.0 * wl.n_clusters * wl.head_dim * (iters + 1) * vec
+        out[name] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(vec * 256 / ms / 1e6, 1),
+                     "hbm_GBps_algorithmic": round(alg / ms / 1e6, 1),
+                     "hbm_frac": round(alg / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                     "assign_TFLOPs": round(flops / ms / 1e9, 1)}
+    del x, cache, ws
+    # ---- decode: 3 layers' full cache = 72 units x 126360 tokens
+    units = 2 * 3 * wl.heads
+    n = wl.tokens_per_layer
+    big = B.alloc_cache(units, n, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
+    g = torch.Generator(device=dev); g.manual_seed(1)
+    big.ids.copy_(torch.randint(0, wl.n_clusters, big.ids.shape, generator=g, device=dev, dtype=torch.uint8))
+    # codes: every 2-bit field in {0,1,2}
+    f = torch.randint(0, 3, big.codes.shape + (4,), generator=g, device=dev, dtype=torch.uint8)
+    big.codes.copy_(f[..., 0] | (f[..., 1] << 2) | (f[..., 2] << 4) | (f[..., 3] << 6)); del f
+    big.scales.copy_(torch.rand(big.scales.shape, generator=g, device=dev).to(torch.float16))
+    big.centroids.copy_(torch.randn(big.centroids.shape, generator=g, device=dev).to(torch.bfloat16))
+    outbuf = torch.empty(units, n, wl.head_dim, dtype=torch.bfloat16, device=dev)
+    fn = lambda: B.decode(big, out=outbuf)
+    fn(); torch.cuda.synchronize()
+    ms = _event_ms(fn, 10)
+    vec = units * n
+    alg = vec * 256 + _format_bytes(wl, units, n, wl.chunk)
+    out["decode"] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(vec * 256 / ms / 1e6, 1),
+                     "hbm_GBps_algorithmic": round(alg / ms / 1e6, 1),
+                     "hbm_frac": round(alg / ms / 1e6 / HBM_PEAK_GBPS, 4), "units": units, "tokens": n}
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2_window21")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-large", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_02958_amd import binding as B
+    from paper_2602_02958_amd import synth, workload
+    from paper_2602_02958_amd.configs import CONFIGS
+    B.lib()                                    # fail loudly if the HIP library is missing
+    wl = CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    s = workload.build_streaming(wl)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        workload.step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        workload.step(s)
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    vec = workload.vectors_per_step(s)
+    total_vec = vec["encode"] + vec["decode"] + vec["attn"]
+    value = total_vec * 256 / ms_step / 1e6          # GB/s
+
+    # ---- per-phase timing (HIP events on the launch stream) -----------------
+    reps = max(5, args.steps)
+    ms_dec = _event_ms(lambda: workload.step_decode(s), reps)
+    ms_att = _event_ms(lambda: workload.step_attn(s), max(3, args.steps // 2))
+    ms_enc = {i: _event_ms(lambda i=i: workload.step_encode(s, iters=i), reps) for i in (0, wl.kmeans_iters_warm, wl.kmeans_iters_cold)}
+    units = 2 * wl.heads
+    n_tok = s.cache.ids.shape[1]
+    n_new = s.x_new.shape[1]
+    dec_alg = vec["decode"] * 256 + _format_bytes(wl, units, n_tok, wl.chunk)
+    enc_alg = vec["encode"] * 256 + _format_bytes(wl, units, n_new, wl.chunk)
+    att_flops = 4.0 * wl.n_queries * n_tok * wl.head_dim * wl.heads
+    phases = {
+        "decode": {"ms": round(ms_dec, 4), "GBps_bf16_equiv": round(vec["decode"] * 256 / ms_dec / 1e6, 1),
+                   "hbm_GBps_algorithmic": round(dec_alg / ms_dec / 1e6, 1),
+                   "hbm_frac": round(dec_alg / ms_dec / 1e6 / HBM_PEAK_GBPS, 4),
+                   "note": "cache-resident size (compressed + bf16 < 256 MB Infinity Cache)" if dec_alg < 2.6e8 else ""},
+        "attn": {"ms": round(ms_att, 4), "q_tokens_per_s": round(wl.n_queries * wl.heads / ms_att * 1e3, 1),
+                 "cache_tokens_per_s": round(n_tok * wl.heads / ms_att * 1e3, 1),
+                 "TFLOPs": round(att_flops / ms_att / 1e9, 2),
+                 "mfma_frac": round(att_flops / ms_att / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
+    }
+    for i, ms in ms_enc.items():
+        phases[f"encode_I{i}"] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(vec["encode"] * 256 / ms / 1e6, 1),
+                                  "hbm_GBps_algorithmic": round(enc_alg / ms / 1e6, 1),
+                                  "hbm_frac": round(enc_alg / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    # dominant kernel of the step by time: the fused attention kernel (one launch per step)
+    roofline = {"bound": "mfma", "kernel": "attn_kernel", "achieved": round(att_flops / ms_att / 1e9, 2),
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(att_flops / ms_att / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
+
+    result = {
+        "metric": "KV encode/decode GB/s (bf16-equiv) + fused dequant-attn tokens/s, % HBM roofline",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "units": units, "tokens_in_cache": n_tok, "chunk": n_new,
+                   "n_queries": wl.n_queries, "K": wl.n_clusters, "T": wl.n_stages, "B": wl.group_size,
+                   "kmeans_iters_in_step": wl.kmeans_iters_warm,
+                   "step": "encode chunk + decode cache + fused attention",
+                   "value_definition": "256 B x (vectors encoded + decoded + read by attention) / step time"},
+        "roofline": roofline,
+        "phases": phases,
+    }
+    if not args.no_large:
+        try:
+            result["large"] = large_supplement(torch, B, synth, CONFIGS)
+        except torch.OutOfMemoryError as e:     # a smaller card than the one this is written for
+            result["large"] = {"error": str(e)[:200]}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

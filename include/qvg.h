@@ -1,0 +1,175 @@
+/*
+ * qvg.h - C ABI of the MI355X (gfx950) KV-cache codec of Quant VideoGen.
+ *
+ * The codec compresses the K or V tensor of one chunk of video tokens of one
+ * attention head (paper Sec. 4.1: X in R^{N x d}) in two steps:
+ *   1. semantic-aware smoothing: k-means groups the N tokens into K groups and
+ *      the group centroid is subtracted from each token (Sec. 4.1, Eq. 5-6);
+ *   2. progressive residual quantization: the residual is quantized to 2 bits
+ *      per element in groups of B channels, and what that leaves is quantized
+ *      again, n_stages times (Sec. 3.2 Eq. 1-2 applied to the residual of
+ *      Sec. 4.2; each stage stores its own codes and per-group scales).
+ * Decoding replays the stages (Sec. 4.2 Eq. 7); the fused entry point decodes
+ * tile by tile inside an attention kernel, so the bf16 cache never exists.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer, 16-byte aligned, owned by the
+ *     caller; the library allocates no device memory and keeps no state.
+ *     `const qvg_params*`, `size_t*` are HOST pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     only enqueue work on it and never synchronise.
+ *   - "bf16" is the upper 16 bits of an IEEE binary32; "f16" is IEEE binary16.
+ *   - Return value: QVG_OK (0) or a negative qvg_status; on error nothing was
+ *     enqueued unless the status is QVG_ERR_LAUNCH (outputs then undefined).
+ *   - Inputs must be finite; non-finite values are not detected.
+ *
+ * Stored format of one chunk of one unit (n_heads counts independent units;
+ * K and V of all heads and layers may be stacked into it):
+ *   centroids [K][d]            bf16
+ *   ids       [N]               uint8   index of the token's centroid
+ *   codes     [N][T][d/4]       uint8   channel 4i+j in bits 2j..2j+1 of byte i,
+ *                                       code = q + 1, q in {-1,0,1} (Eq. 2, b = 2)
+ *   scales    [N][T][d/B]       f16     per group of B consecutive channels
+ * A cache of several chunks concatenates ids/codes/scales along N and keeps one
+ * centroid table per chunk: centroids [n_chunks][K][d].
+ */
+#ifndef QVG_H
+#define QVG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum qvg_status {
+    QVG_OK = 0,
+    QVG_ERR_NULL = -1,         /* a required pointer is NULL                      */
+    QVG_ERR_BAD_PARAM = -2,    /* a size or parameter is out of its stated range  */
+    QVG_ERR_UNSUPPORTED = -3,  /* valid in the paper, not built here              */
+    QVG_ERR_WORKSPACE = -4,    /* workspace missing or too small                  */
+    QVG_ERR_ALIGN = -5,        /* pointer or stride breaks the alignment rule     */
+    QVG_ERR_LAUNCH = -6        /* the HIP runtime refused a launch or a copy      */
+} qvg_status;
+
+/* Codec parameters, in the paper's symbols (Sec. 4, Sec. 5 "Implementation"). */
+typedef struct qvg_params {
+    int32_t n_heads;         /* H >= 1: independent units handled by one call           */
+    int32_t head_dim;        /* d: 128                                                  */
+    int32_t n_clusters;      /* K: 1..256, ids are uint8 (Sec. 5: K = 256)              */
+    int32_t group_size;      /* B: 16, 32, 64 or 128 consecutive channels of one token  */
+    int32_t n_stages;        /* T: 1..8 rounds of 2-bit quantization of the residual    */
+    int32_t bits;            /* 2                                                       */
+    int32_t n_smooth_stages; /* S: 1 (the paper's QVG; S > 1 is QVG-Pro, not built)     */
+    int32_t kmeans_iters;    /* I >= 0 Lloyd iterations before the final assignment     */
+} qvg_params;
+
+/* which_entry values for qvg_workspace_bytes */
+#define QVG_ENTRY_ENCODE 0
+#define QVG_ENTRY_DECODE 1
+#define QVG_ENTRY_ATTN   2
+#define QVG_ENTRY_KMEANS_UPDATE 3
+
+/*
+ * Encode one chunk (Sec. 4.1 and 4.2): I Lloyd iterations from init_centroids
+ * (Sec. 4.3: the previous chunk's centroids, or any start the caller picks),
+ * a final assignment, centroid subtraction (Eq. 5), then T rounds of 2-bit
+ * group quantization of the residual (Eq. 1-2) with bit packing.
+ *   x              [H][N][d] bf16 view: element (h,n,c) at x[h*stride_head + n*stride_token + c],
+ *                  strides in elements, multiples of 8
+ *   init_centroids [H][K][d] bf16
+ *   centroids_out  [H][K][d] bf16, unit h at centroids_out + h*cent_out_stride_head elements
+ *                  (0 = dense K*d; a multiple of 8; may equal init_centroids when I == 0 and dense)
+ *   ids_out        [H][N]           codes_out [H][N][T][d/4]   scales_out [H][N][T][d/B] f16,
+ *                  unit h starting out_stride_head_tokens tokens after unit h-1 (0 = dense N;
+ *                  >= N).  The two strides let a chunk be written straight into a cache that
+ *                  holds several chunks per unit: point the outputs at the chunk's first token
+ *                  and table, and pass the cache's tokens and table elements per unit.
+ *   workspace      qvg_workspace_bytes(p, QVG_ENTRY_ENCODE, N, 0) bytes (0 when I == 0)
+ * n_tokens in 0 .. 2^20.  n_tokens == 0 only copies the centroids.
+ * Rounding rules that fix the stored integers: a group's scale is max|r| (b = 2
+ * gives qmax = 1), saturated at 65504 and rounded to f16; q = round-half-even(r * (1/scale))
+ * with 1/scale one correctly rounded fp32 division, clamped to [-1, 1]; a zero scale gives
+ * q = 0; the next round sees fma(-scale, q, r).  Assignment: smallest squared Euclidean
+ * distance, the lowest index among exactly equal ones; a centroid is the mean of its
+ * members summed in token order in fp64, rounded to fp32 then to bf16; an empty group
+ * keeps its centroid.
+ */
+int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens,
+                     const void *x_bf16, int64_t stride_head, int64_t stride_token,
+                     const void *init_centroids_bf16, void *centroids_bf16_out,
+                     int64_t cent_out_stride_head,
+                     uint8_t *ids_out, uint8_t *codes_out, void *scales_f16_out,
+                     int64_t out_stride_head_tokens,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Decode (Sec. 4.2 "dequantization process", Eq. 7; Sec. 4.3 "Dequantization
+ * kernel": all stages in one kernel, the running value kept in registers):
+ * x_hat = centroid[id] + sum_t scale_t * q_t, fp32 fma in stage order, one
+ * rounding to bf16.
+ *   n_tokens tokens per unit in chunks of chunk_len (the last may be shorter;
+ *   chunk_len >= n_tokens means one chunk); centroids [H][n_chunks][K][d].
+ *   x_bf16_out: same view convention as the encoder's x.
+ */
+int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len,
+               const void *centroids_bf16, const uint8_t *ids, const uint8_t *codes,
+               const void *scales_f16, void *x_bf16_out, int64_t stride_head,
+               int64_t stride_token, void *stream);
+
+/*
+ * Attention over the compressed cache: O = softmax(softmax_scale * Q K_hat^T) V_hat
+ * per unit, no mask, where K_hat and V_hat are what qvg_decode would return (bf16),
+ * produced tile by tile in LDS and never written to memory.
+ *   q_bf16   [H][n_q][d] contiguous       out_bf16 [H][n_q][d] contiguous
+ *   K and V caches: n_kv_tokens tokens in chunks of chunk_len, each with the
+ *   layout qvg_decode reads; both use the parameters in *p.
+ *   lse_out  [H][n_q] fp32 natural-log sum of exp of the scaled scores, or NULL
+ *   workspace: none needed today (pass NULL, 0).
+ * n_kv_tokens >= 1; n_q == 0 is a no-op.
+ */
+int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q_bf16,
+                    int64_t n_kv_tokens, int64_t chunk_len,
+                    const void *k_centroids, const uint8_t *k_ids, const uint8_t *k_codes,
+                    const void *k_scales,
+                    const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
+                    const void *v_scales,
+                    float softmax_scale, void *out_bf16, float *lse_out,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The two k-means steps on their own (Sec. 4.1), as the encoder runs them.
+ * assign: ids_out[h][n] = index of the nearest centroid of unit h.
+ * update: centroid = mean of its members (see qvg_encode_chunk for the rounding);
+ *         counts_out [H][K] int32 may be NULL; workspace
+ *         qvg_workspace_bytes(p, QVG_ENTRY_KMEANS_UPDATE, N, 0) bytes.
+ */
+int qvg_kmeans_assign(const qvg_params *p, int64_t n_tokens,
+                      const void *x_bf16, int64_t stride_head, int64_t stride_token,
+                      const void *centroids_bf16, uint8_t *ids_out, void *stream);
+int qvg_kmeans_update(const qvg_params *p, int64_t n_tokens,
+                      const void *x_bf16, int64_t stride_head, int64_t stride_token,
+                      const uint8_t *ids, const void *centroids_prev_bf16,
+                      void *centroids_bf16_out, int32_t *counts_out,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace an entry point needs for these sizes (host call, no GPU). */
+int qvg_workspace_bytes(const qvg_params *p, int which_entry, int64_t n_tokens,
+                        int64_t n_q, size_t *out);
+
+/* Stored bytes of one chunk of n_tokens tokens for all H units: codes, scales,
+ * ids and one centroid table per unit (Sec. 5 "Memory usage breakdown").
+ * Negative qvg_status on bad parameters. */
+int64_t qvg_compressed_bytes(const qvg_params *p, int64_t n_tokens);
+
+/* Static, NUL-terminated description of a status code. */
+const char *qvg_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int qvg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QVG_H */

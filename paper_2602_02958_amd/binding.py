@@ -1,0 +1,254 @@
+"""Thin ctypes binding of libqvg.so (include/qvg.h): argument marshalling only.
+
+Every step of the codec runs in the library's HIP kernels; this module converts torch
+tensors to device pointers, allocates outputs and workspace with torch, passes torch's
+current stream, and raises on a negative status.  It never falls back to a CPU path:
+a missing library raises at the first call.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libqvg.so")
+_lib = None
+
+ENTRY_ENCODE, ENTRY_DECODE, ENTRY_ATTN, ENTRY_KMEANS_UPDATE = 0, 1, 2, 3
+
+EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_attn_decode", "qvg_kmeans_assign",
+           "qvg_kmeans_update", "qvg_workspace_bytes", "qvg_compressed_bytes",
+           "qvg_status_string", "qvg_version"]
+
+
+class QvgParams(C.Structure):
+    _fields_ = [("n_heads", C.c_int32), ("head_dim", C.c_int32), ("n_clusters", C.c_int32),
+                ("group_size", C.c_int32), ("n_stages", C.c_int32), ("bits", C.c_int32),
+                ("n_smooth_stages", C.c_int32), ("kmeans_iters", C.c_int32)]
+
+
+class QvgError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def lib():
+    """Load libqvg.so (built in-tree by paper_2602_02958_amd.build); raise if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2602_02958_amd.build` "
+                "(there is no CPU fallback)")
+        L = C.CDLL(_LIB_PATH)
+        vp, i64, u8p = C.c_void_p, C.c_int64, C.c_void_p
+        pp = C.POINTER(QvgParams)
+        L.qvg_encode_chunk.restype = C.c_int
+        L.qvg_encode_chunk.argtypes = [pp, i64, vp, i64, i64, vp, vp, i64, u8p, u8p, vp, i64, vp,
+                                       C.c_size_t, vp]
+        L.qvg_decode.restype = C.c_int
+        L.qvg_decode.argtypes = [pp, i64, i64, vp, u8p, u8p, vp, vp, i64, i64, vp]
+        L.qvg_attn_decode.restype = C.c_int
+        L.qvg_attn_decode.argtypes = [pp, i64, vp, i64, i64, vp, u8p, u8p, vp, vp, u8p, u8p, vp,
+                                      C.c_float, vp, vp, vp, C.c_size_t, vp]
+        L.qvg_kmeans_assign.restype = C.c_int
+        L.qvg_kmeans_assign.argtypes = [pp, i64, vp, i64, i64, vp, u8p, vp]
+        L.qvg_kmeans_update.restype = C.c_int
+        L.qvg_kmeans_update.argtypes = [pp, i64, vp, i64, i64, u8p, vp, vp, vp, vp, C.c_size_t, vp]
+        L.qvg_workspace_bytes.restype = C.c_int
+        L.qvg_workspace_bytes.argtypes = [pp, C.c_int, i64, i64, C.POINTER(C.c_size_t)]
+        L.qvg_compressed_bytes.restype = C.c_int64
+        L.qvg_compressed_bytes.argtypes = [pp, i64]
+        L.qvg_status_string.restype = C.c_char_p
+        L.qvg_status_string.argtypes = [C.c_int]
+        L.qvg_version.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().qvg_status_string(int(status)).decode()
+
+
+def make_params(n_heads, n_clusters, group_size, n_stages, kmeans_iters=0, head_dim=128, bits=2,
+                n_smooth_stages=1) -> QvgParams:
+    return QvgParams(n_heads, head_dim, n_clusters, group_size, n_stages, bits, n_smooth_stages,
+                     kmeans_iters)
+
+
+def workspace_bytes(p: QvgParams, entry: int, n_tokens: int, n_q: int = 0) -> int:
+    out = C.c_size_t(0)
+    st = lib().qvg_workspace_bytes(C.byref(p), entry, n_tokens, n_q, C.byref(out))
+    if st != 0:
+        raise QvgError(st, "qvg_workspace_bytes")
+    return int(out.value)
+
+
+def compressed_bytes(p: QvgParams, n_tokens: int) -> int:
+    v = int(lib().qvg_compressed_bytes(C.byref(p), n_tokens))
+    if v < 0:
+        raise QvgError(v, "qvg_compressed_bytes")
+    return v
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _check(t, dtype, name):
+    if t.dtype != dtype or not t.is_cuda:
+        raise TypeError(f"{name}: expected a cuda tensor of {dtype}, got {t.dtype} on {t.device}")
+
+
+def _view3(x, name):
+    """[H, N, d] bf16 view with a contiguous last dim -> (stride_head, stride_token)."""
+    _check(x, torch.bfloat16, name)
+    if x.dim() != 3 or x.stride(2) != 1:
+        raise ValueError(f"{name}: need [H, N, d] with unit stride along d")
+    return x.stride(0), x.stride(1)
+
+
+@dataclass
+class Encoded:
+    """Stored form of one chunk (or of a cache of chunks) for H units."""
+    centroids: torch.Tensor   # [H, n_chunks, K, d] bf16
+    ids: torch.Tensor         # [H, N] uint8
+    codes: torch.Tensor       # [H, N, T, d/4] uint8
+    scales: torch.Tensor      # [H, N, T, d/B] float16
+    chunk_len: int
+
+
+def alloc_cache(n_heads, n_tokens, chunk_len, n_clusters, group_size, n_stages, head_dim=128,
+                device="cuda") -> Encoded:
+    """Uninitialised storage for a cache of n_tokens tokens per unit in chunks of chunk_len."""
+    n_chunks = max(1, -(-n_tokens // chunk_len))
+    return Encoded(
+        torch.empty(n_heads, n_chunks, n_clusters, head_dim, dtype=torch.bfloat16, device=device),
+        torch.empty(n_heads, n_tokens, dtype=torch.uint8, device=device),
+        torch.empty(n_heads, n_tokens, n_stages, head_dim // 4, dtype=torch.uint8, device=device),
+        torch.empty(n_heads, n_tokens, n_stages, head_dim // group_size, dtype=torch.float16,
+                    device=device),
+        chunk_len)
+
+
+def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: Encoded | None = None,
+                 chunk_index: int = 0, workspace=None) -> Encoded:
+    """qvg_encode_chunk.  x [H, N, d] bf16, init_centroids [H, K, d] bf16.
+    Without `cache` a one-chunk cache is allocated and returned; with it, the chunk is written
+    in place at chunk_index (tokens chunk_index*chunk_len ...), using the output strides."""
+    sh, st_ = _view3(x, "x")
+    H, N, d = x.shape
+    _check(init_centroids, torch.bfloat16, "init_centroids")
+    init_centroids = init_centroids.contiguous()
+    K = init_centroids.shape[-2]
+    if cache is None:
+        cache = alloc_cache(H, N, max(N, 1), K, group_size, n_stages, d, x.device)
+    n_total = cache.ids.shape[1]
+    n_chunks = cache.centroids.shape[1]
+    off = chunk_index * cache.chunk_len
+    if not (0 <= chunk_index < n_chunks) or off + N > n_total or (N > cache.chunk_len):
+        raise ValueError("chunk does not fit the cache")
+    if cache.codes.shape[2] != n_stages or cache.scales.shape[3] != d // group_size or \
+            cache.centroids.shape[2] != K or cache.ids.shape[0] != H:
+        raise ValueError("cache was allocated for other parameters")
+    p = make_params(H, K, group_size, n_stages, kmeans_iters, head_dim=d)
+    need = workspace_bytes(p, ENTRY_ENCODE, N)
+    if need and (workspace is None or workspace.numel() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    T, G = n_stages, d // group_size
+    st = lib().qvg_encode_chunk(
+        C.byref(p), N, _ptr(x), sh, st_, _ptr(init_centroids),
+        C.c_void_p(cache.centroids.data_ptr() + chunk_index * K * d * 2), n_chunks * K * d,
+        C.c_void_p(cache.ids.data_ptr() + off),
+        C.c_void_p(cache.codes.data_ptr() + off * T * (d // 4)),
+        C.c_void_p(cache.scales.data_ptr() + off * T * G * 2), n_total,
+        _ptr(workspace) if need else None, need, _stream())
+    if st != 0:
+        raise QvgError(st, "qvg_encode_chunk")
+    return cache
+
+
+def decode(enc: Encoded, out=None) -> torch.Tensor:
+    """qvg_decode -> bf16 [H, N, d]."""
+    H, N = enc.ids.shape
+    K, d = enc.centroids.shape[-2:]
+    T, G = enc.codes.shape[2], enc.scales.shape[3]
+    p = make_params(H, K, d // G, T, 0, head_dim=d)
+    if out is None:
+        out = torch.empty(H, N, d, dtype=torch.bfloat16, device=enc.ids.device)
+    sh, st_ = _view3(out, "out")
+    for t, dt, nm in ((enc.centroids, torch.bfloat16, "centroids"), (enc.ids, torch.uint8, "ids"),
+                      (enc.codes, torch.uint8, "codes"), (enc.scales, torch.float16, "scales")):
+        _check(t, dt, nm)
+        if not t.is_contiguous():
+            raise ValueError(f"{nm} must be contiguous")
+    st = lib().qvg_decode(C.byref(p), N, enc.chunk_len, _ptr(enc.centroids), _ptr(enc.ids),
+                          _ptr(enc.codes), _ptr(enc.scales), _ptr(out), sh, st_, _stream())
+    if st != 0:
+        raise QvgError(st, "qvg_decode")
+    return out
+
+
+def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, out=None):
+    """qvg_attn_decode.  q [H, Nq, d] bf16 contiguous -> out bf16 [H, Nq, d] (and lse fp32 [H, Nq])."""
+    _check(q, torch.bfloat16, "q")
+    q = q.contiguous()
+    H, Nq, d = q.shape
+    Nk = k.ids.shape[1]
+    K = k.centroids.shape[-2]
+    T, G = k.codes.shape[2], k.scales.shape[3]
+    if (v.ids.shape, v.codes.shape, v.scales.shape, v.centroids.shape, v.chunk_len) != \
+            (k.ids.shape, k.codes.shape, k.scales.shape, k.centroids.shape, k.chunk_len):
+        raise ValueError("K and V caches must share shapes and parameters")
+    p = make_params(H, K, d // G, T, 0, head_dim=d)
+    if softmax_scale is None:
+        softmax_scale = 1.0 / (d ** 0.5)
+    if out is None:
+        out = torch.empty(H, Nq, d, dtype=torch.bfloat16, device=q.device)
+    lse = torch.empty(H, Nq, dtype=torch.float32, device=q.device) if want_lse else None
+    st = lib().qvg_attn_decode(C.byref(p), Nq, _ptr(q), Nk, k.chunk_len,
+                               _ptr(k.centroids), _ptr(k.ids), _ptr(k.codes), _ptr(k.scales),
+                               _ptr(v.centroids), _ptr(v.ids), _ptr(v.codes), _ptr(v.scales),
+                               C.c_float(softmax_scale), _ptr(out), _ptr(lse), None, 0, _stream())
+    if st != 0:
+        raise QvgError(st, "qvg_attn_decode")
+    return (out, lse) if want_lse else out
+
+
+def kmeans_assign(x, centroids) -> torch.Tensor:
+    """qvg_kmeans_assign -> ids uint8 [H, N]."""
+    sh, st_ = _view3(x, "x")
+    H, N, d = x.shape
+    centroids = centroids.contiguous()
+    p = make_params(H, centroids.shape[-2], 64, 1, 0, head_dim=d)
+    ids = torch.empty(H, N, dtype=torch.uint8, device=x.device)
+    st = lib().qvg_kmeans_assign(C.byref(p), N, _ptr(x), sh, st_, _ptr(centroids), _ptr(ids), _stream())
+    if st != 0:
+        raise QvgError(st, "qvg_kmeans_assign")
+    return ids
+
+
+def kmeans_update(x, ids, centroids_prev):
+    """qvg_kmeans_update -> (centroids bf16 [H, K, d], counts int32 [H, K])."""
+    sh, st_ = _view3(x, "x")
+    H, N, d = x.shape
+    centroids_prev = centroids_prev.contiguous()
+    K = centroids_prev.shape[-2]
+    p = make_params(H, K, 64, 1, 0, head_dim=d)
+    cent = torch.empty(H, K, d, dtype=torch.bfloat16, device=x.device)
+    counts = torch.empty(H, K, dtype=torch.int32, device=x.device)
+    need = workspace_bytes(p, ENTRY_KMEANS_UPDATE, N)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    st = lib().qvg_kmeans_update(C.byref(p), N, _ptr(x), sh, st_, _ptr(ids.contiguous()),
+                                 _ptr(centroids_prev), _ptr(cent), _ptr(counts), _ptr(ws), need, _stream())
+    if st != 0:
+        raise QvgError(st, "qvg_kmeans_update")
+    return cent, counts

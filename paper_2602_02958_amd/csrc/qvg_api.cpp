@@ -1,0 +1,262 @@
+// C ABI of libqvg: argument validation and the order in which kernels are enqueued.
+// Compiled as HIP host code; holds no kernel and no arithmetic of the method.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qvg.h"
+#include "qvg_internal.hpp"
+
+using namespace qvg;
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t v) { return (v + 255u) & ~(size_t)255u; }
+
+int check_params(const qvg_params *p) {
+    if (!p) return QVG_ERR_NULL;
+    if (p->n_heads < 1 || p->n_heads > 65535) return QVG_ERR_BAD_PARAM;
+    if (p->n_clusters < 1 || p->n_clusters > 256) return QVG_ERR_BAD_PARAM;
+    if (p->n_stages < 1 || p->n_stages > kMaxStages) return QVG_ERR_BAD_PARAM;
+    if (p->kmeans_iters < 0) return QVG_ERR_BAD_PARAM;
+    if (p->head_dim < 1 || p->n_smooth_stages < 1) return QVG_ERR_BAD_PARAM;
+    if (p->group_size < 1 || p->head_dim % p->group_size != 0) return QVG_ERR_BAD_PARAM;
+    if (p->bits != 2 && p->bits != 4) return QVG_ERR_BAD_PARAM;
+    // valid in the paper, not built here
+    if (p->head_dim != kHeadDim) return QVG_ERR_UNSUPPORTED;
+    if (p->bits != 2) return QVG_ERR_UNSUPPORTED;
+    if (p->n_smooth_stages != 1) return QVG_ERR_UNSUPPORTED;
+    const int B = p->group_size;
+    if (B != 16 && B != 32 && B != 64 && B != 128) return QVG_ERR_UNSUPPORTED;
+    return QVG_OK;
+}
+
+struct EncodeWs { size_t cent[2]; size_t perm; size_t offs; size_t total; };
+
+EncodeWs encode_ws(const qvg_params *p, int64_t N, bool with_tables) {
+    EncodeWs w{};
+    size_t o = 0;
+    const size_t table = round256((size_t)p->n_heads * p->n_clusters * kHeadDim * sizeof(bf16_t));
+    if (with_tables) { w.cent[0] = o; o += table; w.cent[1] = o; o += table; }
+    w.perm = o; o += round256((size_t)p->n_heads * (size_t)(N > 0 ? N : 1) * sizeof(int32_t));
+    w.offs = o; o += round256((size_t)p->n_heads * (p->n_clusters + 1) * sizeof(int32_t));
+    w.total = o;
+    return w;
+}
+
+int check_view(const void *base, int64_t stride_head, int64_t stride_token, int64_t N) {
+    if (!aligned16(base)) return QVG_ERR_ALIGN;
+    if (stride_token < kHeadDim || (stride_token & 7) || (stride_head & 7)) return QVG_ERR_ALIGN;
+    if (stride_head < 0 || (N > 0 && stride_head < stride_token)) return QVG_ERR_BAD_PARAM;
+    return QVG_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int qvg_version(void) { return 100; }
+
+const char *qvg_status_string(int status) {
+    switch (status) {
+        case QVG_OK: return "ok";
+        case QVG_ERR_NULL: return "a required pointer is NULL";
+        case QVG_ERR_BAD_PARAM: return "a size or parameter is out of range";
+        case QVG_ERR_UNSUPPORTED: return "parameter combination not built (head_dim 128, 2 bits, one smoothing stage, group 16/32/64/128)";
+        case QVG_ERR_WORKSPACE: return "workspace missing or too small";
+        case QVG_ERR_ALIGN: return "pointer not 16-byte aligned or stride not a multiple of 8 elements";
+        case QVG_ERR_LAUNCH: return "HIP runtime error while enqueuing";
+        default: return "unknown status";
+    }
+}
+
+int qvg_workspace_bytes(const qvg_params *p, int which_entry, int64_t n_tokens, int64_t n_q,
+                        size_t *out) {
+    if (!out) return QVG_ERR_NULL;
+    int st = check_params(p);
+    if (st != QVG_OK) return st;
+    if (n_tokens < 0 || n_q < 0) return QVG_ERR_BAD_PARAM;
+    switch (which_entry) {
+        case QVG_ENTRY_ENCODE:
+            *out = (p->kmeans_iters == 0 || n_tokens == 0) ? 0 : encode_ws(p, n_tokens, true).total;
+            return QVG_OK;
+        case QVG_ENTRY_KMEANS_UPDATE:
+            *out = encode_ws(p, n_tokens, false).total;
+            return QVG_OK;
+        case QVG_ENTRY_DECODE:
+        case QVG_ENTRY_ATTN:
+            *out = 0;
+            return QVG_OK;
+        default:
+            return QVG_ERR_BAD_PARAM;
+    }
+}
+
+int64_t qvg_compressed_bytes(const qvg_params *p, int64_t n_tokens) {
+    int st = check_params(p);
+    if (st != QVG_OK) return st;
+    if (n_tokens < 0) return QVG_ERR_BAD_PARAM;
+    const int64_t d = p->head_dim, T = p->n_stages;
+    const int64_t per_token = T * (d * p->bits / 8 + 2 * (d / p->group_size)) + 1;
+    return (int64_t)p->n_heads * (n_tokens * per_token + (int64_t)p->n_clusters * d * 2);
+}
+
+int qvg_kmeans_assign(const qvg_params *p, int64_t n_tokens, const void *x, int64_t stride_head,
+                      int64_t stride_token, const void *centroids, uint8_t *ids_out, void *stream) {
+    int st = check_params(p);
+    if (st != QVG_OK) return st;
+    if (n_tokens < 0 || n_tokens > kMaxTokensPerChunk) return QVG_ERR_BAD_PARAM;
+    if (n_tokens == 0) return QVG_OK;
+    if (!x || !centroids || !ids_out) return QVG_ERR_NULL;
+    if ((st = check_view(x, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
+    if (!aligned16(centroids)) return QVG_ERR_ALIGN;
+    AssignArgs a{};
+    a.x = static_cast<const bf16_t *>(x); a.stride_head = stride_head; a.stride_token = stride_token;
+    a.n_tokens = n_tokens; a.cent = static_cast<const bf16_t *>(centroids);
+    a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size; a.T = p->n_stages;
+    a.ids = ids_out; a.codes = nullptr; a.scales = nullptr; a.out_stride = n_tokens; a.fused = 0;
+    return launch_assign(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
+}
+
+int qvg_kmeans_update(const qvg_params *p, int64_t n_tokens, const void *x, int64_t stride_head,
+                      int64_t stride_token, const uint8_t *ids, const void *cent_prev,
+                      void *cent_out, int32_t *counts_out, void *workspace, size_t workspace_bytes,
+                      void *stream) {
+    int st = check_params(p);
+    if (st != QVG_OK) return st;
+    if (n_tokens < 0 || n_tokens > kMaxTokensPerChunk) return QVG_ERR_BAD_PARAM;
+    if (!cent_prev || !cent_out) return QVG_ERR_NULL;
+    if (n_tokens > 0 && (!x || !ids)) return QVG_ERR_NULL;
+    if (n_tokens > 0 && (st = check_view(x, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
+    if (!aligned16(cent_prev) || !aligned16(cent_out)) return QVG_ERR_ALIGN;
+    const EncodeWs w = encode_ws(p, n_tokens, false);
+    if (!workspace || workspace_bytes < w.total) return QVG_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return QVG_ERR_ALIGN;
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    UpdateArgs u{};
+    u.x = static_cast<const bf16_t *>(x); u.stride_head = stride_head; u.stride_token = stride_token;
+    u.n_tokens = n_tokens; u.ids = ids; u.ids_stride = n_tokens;
+    u.cent_prev = static_cast<const bf16_t *>(cent_prev);
+    u.cent_out = static_cast<bf16_t *>(cent_out); u.counts_out = counts_out;
+    u.perm = reinterpret_cast<int32_t *>(ws + w.perm); u.offsets = reinterpret_cast<int32_t *>(ws + w.offs);
+    u.H = p->n_heads; u.K = p->n_clusters;
+    return launch_update(u, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
+}
+
+int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64_t stride_head,
+                     int64_t stride_token, const void *init_centroids, void *centroids_out,
+                     int64_t cent_out_stride_head, uint8_t *ids_out, uint8_t *codes_out,
+                     void *scales_out, int64_t out_stride_head_tokens, void *workspace,
+                     size_t workspace_bytes, void *stream) {
+    int st = check_params(p);
+    if (st != QVG_OK) return st;
+    if (n_tokens < 0 || n_tokens > kMaxTokensPerChunk) return QVG_ERR_BAD_PARAM;
+    if (!init_centroids || !centroids_out) return QVG_ERR_NULL;
+    if (!aligned16(init_centroids) || !aligned16(centroids_out)) return QVG_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t row = (size_t)p->n_clusters * kHeadDim * sizeof(bf16_t);    // one unit's table
+    if (cent_out_stride_head == 0) cent_out_stride_head = (int64_t)p->n_clusters * kHeadDim;
+    if (out_stride_head_tokens == 0) out_stride_head_tokens = n_tokens;
+    if (cent_out_stride_head < (int64_t)p->n_clusters * kHeadDim || (cent_out_stride_head & 7))
+        return QVG_ERR_ALIGN;
+    if (out_stride_head_tokens < n_tokens) return QVG_ERR_BAD_PARAM;
+    // the final table goes out as H rows of K*d bf16 with the caller's pitch
+    auto copy_out = [&](const void *src) -> int {
+        if (src == centroids_out && cent_out_stride_head == (int64_t)p->n_clusters * kHeadDim) return QVG_OK;
+        return hipMemcpy2DAsync(centroids_out, (size_t)cent_out_stride_head * sizeof(bf16_t), src, row, row,
+                                (size_t)p->n_heads, hipMemcpyDeviceToDevice, s) == hipSuccess
+                   ? QVG_OK : QVG_ERR_LAUNCH;
+    };
+    if (n_tokens == 0) return copy_out(init_centroids);
+    if (!x || !ids_out || !codes_out || !scales_out) return QVG_ERR_NULL;
+    if ((st = check_view(x, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
+    if (!aligned16(codes_out) || !aligned16(scales_out)) return QVG_ERR_ALIGN;
+    const int I = p->kmeans_iters;
+    const bf16_t *cur = static_cast<const bf16_t *>(init_centroids);
+    if (I > 0) {
+        const EncodeWs w = encode_ws(p, n_tokens, true);
+        if (!workspace || workspace_bytes < w.total) return QVG_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return QVG_ERR_ALIGN;
+        unsigned char *ws = static_cast<unsigned char *>(workspace);
+        bf16_t *buf[2] = {reinterpret_cast<bf16_t *>(ws + w.cent[0]), reinterpret_cast<bf16_t *>(ws + w.cent[1])};
+        AssignArgs a{};
+        a.x = static_cast<const bf16_t *>(x); a.stride_head = stride_head; a.stride_token = stride_token;
+        a.n_tokens = n_tokens; a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size;
+        a.T = p->n_stages; a.ids = ids_out; a.out_stride = out_stride_head_tokens; a.fused = 0;
+        UpdateArgs u{};
+        u.x = a.x; u.stride_head = stride_head; u.stride_token = stride_token; u.n_tokens = n_tokens;
+        u.ids = ids_out; u.ids_stride = out_stride_head_tokens; u.counts_out = nullptr;
+        u.perm = reinterpret_cast<int32_t *>(ws + w.perm); u.offsets = reinterpret_cast<int32_t *>(ws + w.offs);
+        u.H = p->n_heads; u.K = p->n_clusters;
+        for (int it = 0; it < I; ++it) {
+            a.cent = cur;
+            if (launch_assign(a, s) != hipSuccess) return QVG_ERR_LAUNCH;
+            u.cent_prev = cur; u.cent_out = buf[it & 1];
+            if (launch_update(u, s) != hipSuccess) return QVG_ERR_LAUNCH;
+            cur = buf[it & 1];
+        }
+    }
+    AssignArgs f{};
+    f.x = static_cast<const bf16_t *>(x); f.stride_head = stride_head; f.stride_token = stride_token;
+    f.n_tokens = n_tokens; f.cent = cur; f.H = p->n_heads; f.K = p->n_clusters; f.B = p->group_size;
+    f.T = p->n_stages; f.ids = ids_out; f.codes = codes_out; f.scales = static_cast<f16_t *>(scales_out);
+    f.out_stride = out_stride_head_tokens; f.fused = 1;
+    if (launch_assign(f, s) != hipSuccess) return QVG_ERR_LAUNCH;
+    return copy_out(cur);
+}
+
+int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, const void *centroids,
+               const uint8_t *ids, const uint8_t *codes, const void *scales, void *x_out,
+               int64_t stride_head, int64_t stride_token, void *stream) {
+    int st = check_params(p);
+    if (st != QVG_OK) return st;
+    if (n_tokens < 0 || chunk_len < 1) return QVG_ERR_BAD_PARAM;
+    if (n_tokens == 0) return QVG_OK;
+    if (!centroids || !ids || !codes || !scales || !x_out) return QVG_ERR_NULL;
+    if ((st = check_view(x_out, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
+    if (!aligned16(centroids) || !aligned16(codes) || !aligned16(scales)) return QVG_ERR_ALIGN;
+    const int64_t n_chunks = (n_tokens + chunk_len - 1) / chunk_len;
+    if (n_chunks > 0x7fffffff) return QVG_ERR_BAD_PARAM;
+    DecodeArgs a{};
+    a.cent = static_cast<const bf16_t *>(centroids); a.ids = ids; a.codes = codes;
+    a.scales = static_cast<const f16_t *>(scales); a.out = static_cast<bf16_t *>(x_out);
+    a.n_tokens = n_tokens; a.chunk_len = chunk_len; a.n_chunks = (int)n_chunks;
+    a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size; a.T = p->n_stages;
+    a.stride_head = stride_head; a.stride_token = stride_token;
+    return launch_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
+}
+
+int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q, int64_t n_kv_tokens,
+                    int64_t chunk_len, const void *k_centroids, const uint8_t *k_ids,
+                    const uint8_t *k_codes, const void *k_scales, const void *v_centroids,
+                    const uint8_t *v_ids, const uint8_t *v_codes, const void *v_scales,
+                    float softmax_scale, void *out, float *lse_out, void *workspace,
+                    size_t workspace_bytes, void *stream) {
+    (void)workspace; (void)workspace_bytes;
+    int st = check_params(p);
+    if (st != QVG_OK) return st;
+    if (n_q < 0 || n_kv_tokens < 1 || chunk_len < 1) return QVG_ERR_BAD_PARAM;
+    if (!(softmax_scale == softmax_scale) || softmax_scale - softmax_scale != 0.0f) return QVG_ERR_BAD_PARAM;
+    if (n_q == 0) return QVG_OK;
+    if (!q || !out || !k_centroids || !k_ids || !k_codes || !k_scales || !v_centroids || !v_ids ||
+        !v_codes || !v_scales)
+        return QVG_ERR_NULL;
+    if (!aligned16(q) || !aligned16(out) || !aligned16(k_centroids) || !aligned16(v_centroids) ||
+        !aligned16(k_codes) || !aligned16(v_codes) || !aligned16(k_scales) || !aligned16(v_scales))
+        return QVG_ERR_ALIGN;
+    const int64_t n_chunks = (n_kv_tokens + chunk_len - 1) / chunk_len;
+    if (n_chunks > 0x7fffffff) return QVG_ERR_BAD_PARAM;
+    if ((n_q + 127) / 128 > 0x7fffffff) return QVG_ERR_BAD_PARAM;
+    AttnArgs a{};
+    a.q = static_cast<const bf16_t *>(q); a.out = static_cast<bf16_t *>(out); a.lse = lse_out;
+    a.n_q = n_q; a.n_kv = n_kv_tokens; a.chunk_len = chunk_len; a.n_chunks = (int)n_chunks;
+    a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size; a.T = p->n_stages;
+    a.scale = softmax_scale;
+    a.k_cent = static_cast<const bf16_t *>(k_centroids); a.k_ids = k_ids; a.k_codes = k_codes;
+    a.k_scales = static_cast<const f16_t *>(k_scales);
+    a.v_cent = static_cast<const bf16_t *>(v_centroids); a.v_ids = v_ids; a.v_codes = v_codes;
+    a.v_scales = static_cast<const f16_t *>(v_scales);
+    return launch_attn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
+}
+
+}  // extern "C"

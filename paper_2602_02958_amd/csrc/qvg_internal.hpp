@@ -1,0 +1,81 @@
+// Internal declarations shared by the HIP translation units of libqvg.
+// Device helpers for the number formats and the launchers each .hip file defines.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qvg.h"
+
+namespace qvg {
+
+constexpr int kHeadDim = 128;      // only head_dim the kernels are written for
+constexpr int kMaxStages = 8;
+constexpr int kMaxTokensPerChunk = 1 << 20;
+
+typedef uint16_t bf16_t;           // bit pattern of a bfloat16
+typedef uint16_t f16_t;            // bit pattern of an IEEE binary16
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
+
+// ---- number formats -------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+    a += 0x7fffu + ((a >> 16) & 1u);
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return (a >> 16) | (b & 0xffff0000u);
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+}
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {       // RNE (default mode)
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
+
+// ---- launchers (each returns a hipError_t from hipGetLastError) -----------
+struct DecodeArgs {
+    const bf16_t *cent; const uint8_t *ids; const uint8_t *codes; const f16_t *scales;
+    bf16_t *out; int64_t n_tokens; int64_t chunk_len; int n_chunks; int H; int K; int B; int T;
+    int64_t stride_head, stride_token;
+};
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
+
+struct AssignArgs {
+    const bf16_t *x; int64_t stride_head, stride_token; int64_t n_tokens;
+    const bf16_t *cent; int H; int K; int B; int T;
+    uint8_t *ids;            // always written
+    uint8_t *codes; f16_t *scales;   // written when fused != 0
+    int64_t out_stride;      // tokens between consecutive units in ids / codes / scales
+    int fused;
+};
+hipError_t launch_assign(const AssignArgs &a, hipStream_t s);
+
+struct UpdateArgs {
+    const bf16_t *x; int64_t stride_head, stride_token; int64_t n_tokens;
+    const uint8_t *ids; int64_t ids_stride;      // tokens between consecutive units in ids
+    const bf16_t *cent_prev; bf16_t *cent_out; int32_t *counts_out;
+    int32_t *perm; int32_t *offsets;     // workspace: [H][N] and [H][K+1]
+    int H; int K;
+};
+hipError_t launch_update(const UpdateArgs &a, hipStream_t s);
+
+struct AttnArgs {
+    const bf16_t *q; bf16_t *out; float *lse; int64_t n_q; int64_t n_kv; int64_t chunk_len;
+    int n_chunks; int H; int K; int B; int T; float scale;
+    const bf16_t *k_cent; const uint8_t *k_ids; const uint8_t *k_codes; const f16_t *k_scales;
+    const bf16_t *v_cent; const uint8_t *v_ids; const uint8_t *v_codes; const f16_t *v_scales;
+};
+hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
+
+}  // namespace qvg

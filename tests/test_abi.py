@@ -1,0 +1,103 @@
+"""The C-ABI library loads, exports every symbol include/qvg.h declares, and its host-side
+argument validation answers without a GPU (no kernel is launched by any call here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2602_02958_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "qvg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qvg_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    L = B.lib()
+    names = _declared()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_status_strings():
+    assert B.lib().qvg_version() >= 100
+    for st in range(0, -7, -1):
+        assert len(B.status_string(st)) > 0
+    assert B.status_string(-99) == "unknown status"
+
+
+def test_compressed_bytes_matches_format():
+    p = B.make_params(24, 256, 64, 2)
+    assert B.compressed_bytes(p, 4680) == 24 * (4680 * 73 + 256 * 128 * 2)
+    p = B.make_params(1, 64, 32, 3)
+    assert B.compressed_bytes(p, 10) == 10 * 121 + 64 * 256
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_heads=0), -2), (dict(n_clusters=0), -2), (dict(n_clusters=257), -2),
+    (dict(n_stages=0), -2), (dict(n_stages=9), -2), (dict(group_size=48), -2),
+    (dict(head_dim=64), -3), (dict(bits=4), -3), (dict(bits=3), -2),
+    (dict(n_smooth_stages=4), -3), (dict(group_size=8), -3), (dict(kmeans_iters=-1), -2),
+])
+def test_parameter_validation(kw, status):
+    base = dict(n_heads=2, n_clusters=16, group_size=64, n_stages=2, kmeans_iters=0,
+                head_dim=128, bits=2, n_smooth_stages=1)
+    base.update(kw)
+    p = B.make_params(**base)
+    out = C.c_size_t(0)
+    assert B.lib().qvg_workspace_bytes(C.byref(p), 0, 100, 0, C.byref(out)) == status
+
+
+def test_null_and_alignment_errors_are_reported_before_any_launch():
+    L = B.lib()
+    p = B.make_params(2, 16, 64, 2, kmeans_iters=1)
+    fake = C.c_void_p(0x1000)          # aligned, never dereferenced: every call below fails first
+    odd = C.c_void_p(0x1008)
+    # NULL x
+    assert L.qvg_encode_chunk(C.byref(p), 10, None, 1280, 128, fake, fake, 0, fake, fake, fake, 0,
+                              None, 0, None) == -1
+    # misaligned x
+    assert L.qvg_encode_chunk(C.byref(p), 10, odd, 1280, 128, fake, fake, 0, fake, fake, fake, 0,
+                              None, 0, None) == -5
+    # stride not a multiple of 8
+    assert L.qvg_encode_chunk(C.byref(p), 10, fake, 1284, 132, fake, fake, 0, fake, fake, fake, 0,
+                              None, 0, None) == -5
+    # workspace missing although kmeans_iters > 0
+    assert L.qvg_encode_chunk(C.byref(p), 10, fake, 1280, 128, fake, fake, 0, fake, fake, fake, 0,
+                              None, 0, None) == -4
+    # too many tokens for one chunk
+    assert L.qvg_encode_chunk(C.byref(p), (1 << 20) + 1, fake, 1 << 28, 128, fake, fake, 0, fake,
+                              fake, fake, 0, None, 0, None) == -2
+    # output stride smaller than the chunk
+    assert L.qvg_encode_chunk(C.byref(p), 10, fake, 1280, 128, fake, fake, 0, fake, fake, fake, 5,
+                              fake, 1 << 30, None) == -2
+    # decode / attention
+    assert L.qvg_decode(C.byref(p), 10, 0, fake, fake, fake, fake, fake, 1280, 128, None) == -2
+    assert L.qvg_decode(C.byref(p), 10, 10, None, fake, fake, fake, fake, 1280, 128, None) == -1
+    assert L.qvg_attn_decode(C.byref(p), 4, fake, 0, 10, fake, fake, fake, fake, fake, fake, fake,
+                             fake, C.c_float(0.1), fake, None, None, 0, None) == -2
+    assert L.qvg_attn_decode(C.byref(p), 4, fake, 10, 10, fake, fake, fake, fake, fake, fake, fake,
+                             fake, C.c_float(float("nan")), fake, None, None, 0, None) == -2
+    assert L.qvg_attn_decode(C.byref(p), 4, None, 10, 10, fake, fake, fake, fake, fake, fake, fake,
+                             fake, C.c_float(0.1), fake, None, None, 0, None) == -1
+    # zero-size calls succeed without touching the device
+    assert L.qvg_decode(C.byref(p), 0, 10, None, None, None, None, None, 0, 0, None) == 0
+    assert L.qvg_attn_decode(C.byref(p), 0, None, 10, 10, None, None, None, None, None, None, None,
+                             None, C.c_float(0.1), None, None, None, 0, None) == 0
+    assert L.qvg_kmeans_assign(C.byref(p), 0, None, 0, 0, None, None, None) == 0
+
+
+def test_workspace_sizes():
+    p = B.make_params(24, 256, 64, 2, kmeans_iters=0)
+    assert B.workspace_bytes(p, B.ENTRY_ENCODE, 4680) == 0
+    p = B.make_params(24, 256, 64, 2, kmeans_iters=3)
+    need = B.workspace_bytes(p, B.ENTRY_ENCODE, 4680)
+    assert need >= 2 * 24 * 256 * 256 + 24 * 4680 * 4 + 24 * 257 * 4
+    assert B.workspace_bytes(p, B.ENTRY_DECODE, 4680) == 0
+    assert B.workspace_bytes(p, B.ENTRY_ATTN, 4680, 128) == 0

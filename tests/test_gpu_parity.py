@@ -1,0 +1,291 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded bytes."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qvg_oracle as O
+from paper_2602_02958_amd import binding as B
+from paper_2602_02958_amd import synth
+from paper_2602_02958_amd.configs import CONFIGS
+from conftest import bf16_bits, bits_to_f32
+import parity_util as P
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _inputs(cfg, units, N, K, kv=0, chunk_skip=0):
+    wl = CONFIGS[cfg]
+    st = synth.MixtureStream(wl, units, kv)
+    for _ in range(chunk_skip):
+        st.next_chunk(N)
+    x = st.next_chunk(N)
+    init = synth.cold_start_centroids(x, K)
+    return x, init
+
+
+def _oracle_cache(x, init, K, Bg, T, iters):
+    """Oracle-encode [H,N,d] -> dict of numpy arrays (S = 1 squeezed)."""
+    enc = O.encode_batch(bf16_bits(x), bf16_bits(init), K, Bg, T, iters)
+    return dict(cent=enc["cent"][:, 0], ids=enc["ids"][:, 0], codes=enc["codes"], scales=enc["scales"])
+
+
+def _to_encoded(oc, chunk_len=None):
+    H, N = oc["ids"].shape
+    cent = oc["cent"] if oc["cent"].ndim == 4 else oc["cent"][:, None]
+    return B.Encoded(
+        torch.from_numpy(cent.view(np.int16).copy()).view(torch.bfloat16).to(DEV),
+        torch.from_numpy(oc["ids"].copy()).to(DEV),
+        torch.from_numpy(oc["codes"].copy()).to(DEV),
+        torch.from_numpy(oc["scales"].view(np.int16).copy()).view(torch.float16).to(DEV),
+        chunk_len or max(N, 1))
+
+
+# ------------------------------------------------------------------ decode
+@pytest.mark.parametrize("N,K,Bg,T", [(4096, 16, 64, 2), (1000, 64, 32, 3), (333, 256, 64, 4),
+                                      (65, 7, 16, 1), (1, 1, 128, 2), (700, 33, 128, 5)])
+def test_decode_bit_exact(N, K, Bg, T):
+    x, init = _inputs("cfg2_window21", 3, N, K)
+    oc = _oracle_cache(x, init, K, Bg, T, iters=1)
+    want = O.decode_batch(oc["cent"][:, None], oc["ids"][:, None], oc["codes"], oc["scales"], Bg)
+    got = B.decode(_to_encoded(oc))
+    torch.cuda.synchronize()
+    assert np.array_equal(P.to_np_u16(got), want)
+
+
+def test_decode_multi_chunk_strided_output():
+    """Three chunks (the last one short), each with its own table; output written into a
+    wider buffer through the strides."""
+    K, Bg, T, L = 32, 64, 2, 500
+    Ns = [500, 500, 137]
+    parts, wants = [], []
+    for i, n in enumerate(Ns):
+        x, init = _inputs("cfg3_dit_small", 2, n, K, chunk_skip=i)
+        oc = _oracle_cache(x, init, K, Bg, T, iters=1)
+        parts.append(oc)
+        wants.append(O.decode_batch(oc["cent"][:, None], oc["ids"][:, None], oc["codes"], oc["scales"], Bg))
+    oc = dict(cent=np.stack([p["cent"] for p in parts], 1),
+              ids=np.concatenate([p["ids"] for p in parts], 1),
+              codes=np.concatenate([p["codes"] for p in parts], 1),
+              scales=np.concatenate([p["scales"] for p in parts], 1))
+    enc = _to_encoded(oc, chunk_len=L)
+    N = sum(Ns)
+    buf = torch.zeros(2, N + 5, 256, dtype=torch.bfloat16, device=DEV)
+    out = buf[:, 2:2 + N, 128:]                       # stride_token 256, offset view
+    B.decode(enc, out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.to_np_u16(out), np.concatenate(wants, 1))
+    assert float(buf[:, :, :128].abs().max()) == 0 and float(buf[:, :2].abs().max()) == 0
+
+
+# ------------------------------------------------------------------ assignment and update steps
+@pytest.mark.parametrize("cfg,N,K", [("cfg1_tiny", 4096, 16), ("cfg2_window21", 1500, 64),
+                                     ("cfg3_dit_small", 2000, 256), ("cfg4_dit_large", 777, 128),
+                                     ("cfg2_window21", 31, 5), ("cfg2_window21", 20, 64)])
+def test_kmeans_steps_match_oracle(cfg, N, K):
+    """Step parity: the oracle's state after each iteration is fed to the GPU assign and update."""
+    H = 2
+    x, init = _inputs(cfg, H, N, K)
+    xb = bf16_bits(x)
+    xd = x.to(DEV)
+    cur = bf16_bits(init).copy()
+    ties = 0
+    for it in range(3):
+        cd = torch.from_numpy(cur.view(np.int16).copy()).view(torch.bfloat16).to(DEV)
+        ids_g = P.to_np_u8(B.kmeans_assign(xd, cd))
+        nxt = np.empty_like(cur)
+        for h in range(H):
+            r = bits_to_f32(xb[h])
+            ids_o = O.assign(r, cur[h])
+            ties += P.compare_ids(xb[h], cur[h], ids_g[h], ids_o).size
+            c_o, n_o = O.update(r, ids_o, cur[h])
+            nxt[h] = c_o
+        # update from the ORACLE's ids so that the two steps are checked independently
+        ids_od = torch.from_numpy(np.stack([O.assign(bits_to_f32(xb[h]), cur[h]) for h in range(H)])).to(DEV)
+        c_g, n_g = B.kmeans_update(xd, ids_od, cd)
+        torch.cuda.synchronize()
+        assert np.array_equal(P.to_np_u16(c_g), nxt), f"centroids differ at iteration {it}"
+        for h in range(H):
+            assert np.array_equal(n_g[h].cpu().numpy(), np.bincount(P.to_np_u8(ids_od[h]), minlength=K))
+        cur = nxt
+    assert ties <= 2
+
+
+def test_assign_forced_ties_and_duplicates():
+    """Hand-made exact ties: duplicated centroids and a token midway between two of them.
+    Small integers: every fp64 distance is exact, so the lowest index must win."""
+    K, N = 40, 96
+    g = torch.Generator().manual_seed(5)
+    c = torch.randint(-3, 4, (1, K, 128), generator=g).float()
+    c[0, 7] = c[0, 3]                       # duplicate: 3 must win over 7
+    c[0, 39] = c[0, 38]
+    x = c[0, torch.randint(0, K, (N,), generator=g)].clone()[None]
+    x[0, 0] = (c[0, 10] + c[0, 20]) / 2     # midway (halves are exact in bf16)
+    xb, cb = x.to(torch.bfloat16), c.to(torch.bfloat16)
+    ids_g = P.to_np_u8(B.kmeans_assign(xb.to(DEV), cb.to(DEV)))[0]
+    ids_o = O.assign(bits_to_f32(bf16_bits(xb)[0]), bf16_bits(cb)[0])
+    assert np.array_equal(ids_g, ids_o)
+    assert 7 not in ids_g and 39 not in ids_g
+
+
+# ------------------------------------------------------------------ encode
+@pytest.mark.parametrize("cfg,N,K,Bg,T", [("cfg1_tiny", 4096, 16, 64, 2), ("cfg2_window21", 2000, 64, 32, 3),
+                                          ("cfg3_dit_small", 1111, 256, 64, 2), ("cfg4_dit_large", 900, 128, 32, 3),
+                                          ("cfg5_long", 513, 256, 64, 4), ("cfg2_window21", 257, 20, 16, 1),
+                                          ("cfg2_window21", 300, 9, 128, 2), ("cfg3_dit_small", 40, 64, 64, 6)])
+def test_encode_single_pass_matches_oracle(cfg, N, K, Bg, T):
+    """I = 0: assignment against given centroids, residual, T quantization rounds, packing."""
+    H = 3
+    x, init = _inputs(cfg, H, N, K)
+    enc = B.encode_chunk(x.to(DEV), init.to(DEV), Bg, T, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.to_np_u16(enc.centroids[:, 0]), bf16_bits(init))
+    xb, cb = bf16_bits(x), bf16_bits(init)
+    ties = sum(P.check_encoded_unit(xb[h], cb[h], P.gpu_unit(enc, h), Bg, T) for h in range(H))
+    assert ties <= 2
+
+
+@pytest.mark.parametrize("cfg,N,K,Bg,T,I", [("cfg1_tiny", 4096, 16, 64, 2, 10), ("cfg2_window21", 3000, 64, 32, 3, 3),
+                                            ("cfg3_dit_small", 2500, 256, 64, 2, 4)])
+def test_encode_with_lloyd_end_to_end(cfg, N, K, Bg, T, I):
+    """Full encode against the full oracle from the same start.  The stored ids and codes must be
+    the oracle's for the GPU's own final centroids (self-consistency); the centroids themselves
+    are expected to be bit-equal to the oracle's and any difference is reported."""
+    H = 2
+    x, init = _inputs(cfg, H, N, K)
+    enc = B.encode_chunk(x.to(DEV), init.to(DEV), Bg, T, I)
+    torch.cuda.synchronize()
+    xb = bf16_bits(x)
+    cent_g = P.to_np_u16(enc.centroids[:, 0])
+    ref = _oracle_cache(x, init, K, Bg, T, I)
+    for h in range(H):
+        P.check_encoded_unit(xb[h], cent_g[h], P.gpu_unit(enc, h), Bg, T)
+    assert np.array_equal(cent_g, ref["cent"]), "Lloyd trajectories diverged from the oracle"
+    assert np.array_equal(P.to_np_u8(enc.ids), ref["ids"])
+    assert np.array_equal(P.to_np_u8(enc.codes), ref["codes"])
+    assert np.array_equal(P.to_np_u16(enc.scales), ref["scales"])
+
+
+def test_encode_degenerate_inputs():
+    """Zero residual groups, one huge outlier, an empty cluster, tiny values, N < K."""
+    K, Bg, T, N = 8, 32, 3, 70
+    g = torch.Generator().manual_seed(11)
+    c = (torch.randn(1, K, 128, generator=g) * 2).to(torch.bfloat16)
+    c[0, 5] = 300.0                                    # far away: stays empty
+    x = c[0, torch.randint(0, 5, (N,), generator=g)].float()[None]
+    x[0, 10:] += 0.1 * torch.randn(N - 10, 128, generator=g)      # tokens 0..9 sit ON a centroid
+    x[0, 11, 3] = 30000.0                              # one huge outlier
+    x[0, 12, 64:96] = x[0, 12, 64:96] * 0 + c[0, 0, 64:96].float()   # one all-zero residual group
+    x[0, 13] = c[0, 1].float() + 1e-9                  # below bf16 resolution of the centroid
+    xb = x.to(torch.bfloat16)
+    for I in (0, 2):
+        enc = B.encode_chunk(xb.to(DEV), c.to(DEV), Bg, T, I)
+        torch.cuda.synchronize()
+        ref = _oracle_cache(xb, c, K, Bg, T, I)
+        assert np.array_equal(P.to_np_u16(enc.centroids[:, 0]), ref["cent"])
+        assert np.array_equal(P.to_np_u8(enc.ids), ref["ids"])
+        assert np.array_equal(P.to_np_u8(enc.codes), ref["codes"])
+        assert np.array_equal(P.to_np_u16(enc.scales), ref["scales"])
+        dec = B.decode(enc)
+        want = O.decode_batch(ref["cent"][:, None], ref["ids"][:, None], ref["codes"], ref["scales"], Bg)
+        assert np.array_equal(P.to_np_u16(dec), want)
+    # N < K with every token its own centroid: residual exactly zero, decode returns x
+    xs = xb[:, :6]
+    init = torch.cat([xs, xs[:, :2]], 1)
+    enc = B.encode_chunk(xs.to(DEV), init.to(DEV), Bg, T, 1)
+    assert P.to_np_u8(enc.ids)[0].tolist() == list(range(6))
+    assert np.array_equal(P.to_np_u16(B.decode(enc)), bf16_bits(xs))
+
+
+def test_encode_into_cache_with_strided_input_and_runs_are_deterministic():
+    """Two chunks appended in place into a 2-chunk cache (output strides), x passed as a
+    non-contiguous view; a second run gives identical bytes."""
+    K, Bg, T, L, H = 64, 32, 3, 520, 3
+    wl = CONFIGS["cfg2_window21"]
+    st = synth.MixtureStream(wl, H, 1)
+    chunks = [st.next_chunk(L), st.next_chunk(300)]
+    init = synth.cold_start_centroids(chunks[0], K)
+    runs = []
+    for rep in range(2):
+        cache = B.alloc_cache(H, L + 300, L, K, Bg, T)
+        for t in (cache.ids, cache.codes):
+            t.fill_(0xEE)
+        cur = init.to(DEV)
+        for ci, xc in enumerate(chunks):
+            wide = torch.zeros(H, xc.shape[1], 384, dtype=torch.bfloat16, device=DEV)
+            wide[:, :, 128:256] = xc.to(DEV)
+            B.encode_chunk(wide[:, :, 128:256], cur, Bg, T, 2, cache=cache, chunk_index=ci)
+            cur = cache.centroids[:, ci].contiguous()       # warm start of the next chunk
+        torch.cuda.synchronize()
+        runs.append([P.to_np_u16(cache.centroids), P.to_np_u8(cache.ids), P.to_np_u8(cache.codes),
+                     P.to_np_u16(cache.scales)])
+    for a, b in zip(*runs):
+        assert np.array_equal(a, b)
+    cent, ids, codes, scales = runs[0]
+    prev = bf16_bits(init)
+    off = 0
+    for ci, xc in enumerate(chunks):
+        n = xc.shape[1]
+        ref = O.encode_batch(bf16_bits(xc), prev, K, Bg, T, 2)
+        assert np.array_equal(cent[:, ci], ref["cent"][:, 0])
+        assert np.array_equal(ids[:, off:off + n], ref["ids"][:, 0])
+        assert np.array_equal(codes[:, off:off + n], ref["codes"])
+        assert np.array_equal(scales[:, off:off + n], ref["scales"])
+        prev = ref["cent"][:, 0]
+        off += n
+
+
+# ------------------------------------------------------------------ fused attention
+def _attn_case(cfg, H, Nq, Ns, L, K, Bg, T, scale=None):
+    wl = CONFIGS[cfg]
+    sk, sv = synth.MixtureStream(wl, H, 0), synth.MixtureStream(wl, H, 1)
+    kparts, vparts = [], []
+    for n in Ns:
+        for stream, parts in ((sk, kparts), (sv, vparts)):
+            x = stream.next_chunk(n)
+            parts.append(_oracle_cache(x, synth.cold_start_centroids(x, K), K, Bg, T, 1))
+
+    def cat(parts):
+        return dict(cent=np.stack([p["cent"] for p in parts], 1),
+                    ids=np.concatenate([p["ids"] for p in parts], 1),
+                    codes=np.concatenate([p["codes"] for p in parts], 1),
+                    scales=np.concatenate([p["scales"] for p in parts], 1))
+
+    def dec(parts):
+        return np.concatenate([O.decode_batch(p["cent"][:, None], p["ids"][:, None], p["codes"],
+                                              p["scales"], Bg) for p in parts], 1)
+    q = synth.queries(wl, H, Nq)
+    want, lse = O.attention_batch(bf16_bits(q), dec(kparts), dec(vparts), scale=scale, want_lse=True)
+    got, lse_g = B.attn_decode(q.to(DEV), _to_encoded(cat(kparts), L), _to_encoded(cat(vparts), L),
+                               softmax_scale=scale, want_lse=True)
+    torch.cuda.synchronize()
+    ok, max_abs, worst = P.attn_tolerance_ok(P.to_np_u16(got), want)
+    assert ok, f"max abs err {max_abs}, worst err/tol {worst}"
+    assert np.allclose(lse_g.cpu().numpy(), lse, rtol=0, atol=2e-3)
+    return max_abs
+
+
+@pytest.mark.parametrize("cfg,H,Nq,Ns,L,K,Bg,T", [
+    ("cfg1_tiny", 1, 64, [4096], 4096, 16, 64, 2),
+    ("cfg2_window21", 2, 200, [600, 600, 333], 600, 64, 32, 3),
+    ("cfg3_dit_small", 2, 129, [257], 257, 256, 64, 2),
+    ("cfg5_long", 1, 33, [64, 64, 1], 64, 256, 64, 4),
+    ("cfg4_dit_large", 1, 70, [500], 500, 128, 16, 1),
+    ("cfg2_window21", 1, 5, [100], 100, 8, 128, 5),
+])
+def test_attention_matches_oracle(cfg, H, Nq, Ns, L, K, Bg, T):
+    _attn_case(cfg, H, Nq, Ns, L, K, Bg, T)
+
+
+def test_attention_single_token_cache_returns_decoded_value():
+    x, init = _inputs("cfg2_window21", 1, 1, 4, kv=1)
+    oc = _oracle_cache(x, init, 4, 64, 2, 0)
+    dec = O.decode_batch(oc["cent"][:, None], oc["ids"][:, None], oc["codes"], oc["scales"], 64)
+    q = synth.queries(CONFIGS["cfg2_window21"], 1, 40)
+    enc = _to_encoded(oc)
+    out = B.attn_decode(q.to(DEV), enc, enc)
+    assert np.array_equal(P.to_np_u16(out)[0], np.repeat(dec[0], 40, 0))
+
+
+def test_attention_custom_scale():
+    _attn_case("cfg2_window21", 1, 64, [300], 300, 32, 64, 2, scale=0.05)
