@@ -8,9 +8,13 @@
 //   2. S^T = K_tile . Q^T on v_mfma_f32_32x32x16_bf16: rows = cache tokens, columns = queries,
 //      so a lane owns one query and the soft-max statistics stay in the lane (one exchange
 //      between the two lane halves per tile);
-//   3. online soft-max in fp32 (base-2 exponent), P rounded to bf16;
-//   4. O^T += V_tile^T . P on the same MFMA; the lane's P values are already the B operand
-//      (the V tile is stored with the matching token permutation, so no cross-lane traffic).
+//   3. online soft-max in fp32 (base-2 exponent);
+//   4. O^T += V_tile^T . P on v_mfma_f32_32x32x16_f16: the probabilities go in as f16 (11
+//      significant bits; bf16's 8 would cost up to 2^-9 of |V| in the output), and the V tile,
+//      first rounded to bf16 like the stand-alone decoder's output, is stored as f16, which
+//      holds every bf16 value of magnitude 2^-14 .. 65504 exactly (larger ones saturate).
+//      The lane's P values are already the B operand: the V tile is stored with the matching
+//      token permutation, so no cross-lane traffic is needed.
 // Only the two contractions use the matrix cores; the unpack / fma / soft-max work is VALU.
 #include "qvg_internal.hpp"
 
@@ -20,7 +24,7 @@ constexpr int kAtThreads = 256;
 constexpr int kAtQPerBlock = 128;
 constexpr int kAtKv = 64;
 constexpr int kKtPitch = 136;      // bf16 per row of the K tile (272 B, 16-byte aligned, conflict-free)
-constexpr int kVtPitch = 72;       // bf16 per row of the transposed V tile (144 B)
+constexpr int kVtPitch = 72;       // f16 per row of the transposed V tile (144 B)
 
 struct CacheSide {                 // one of K / V, already offset to this unit
     const bf16_t *cent;            // [n_chunks][K][d]
@@ -86,7 +90,7 @@ template <int T_>       // T_ > 0: compile-time stage count; 0: run-time (up to 
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_kernel(AttnArgs a) {
     __shared__ __align__(16) bf16_t Kt[kAtKv * kKtPitch];
-    __shared__ __align__(16) bf16_t Vt[kHeadDim * kVtPitch];
+    __shared__ __align__(16) uint16_t Vt[kHeadDim * kVtPitch];     // f16 bits
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -144,6 +148,11 @@ void attn_kernel(AttnArgs a) {
             {
                 uint32_t hb[4][4];
                 dequant4x8<T_>(vs, vc, t0 + 4 * v_qd, cend, v_c8, T, B, K, hb);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)      // bf16 pair -> f16 pair (exact in range)
+                        hb[e][i] = pack_f16x2_rtz(bf16_lo(hb[e][i]), bf16_hi(hb[e][i]));
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     // channels 8*v_c8 + 2i (low halves) and + 2i + 1 (high halves) of 4 tokens
@@ -204,18 +213,18 @@ void attn_kernel(AttnArgs a) {
                     p[e] = __builtin_amdgcn_exp2f(S[st >> 1][(st & 1) * 8 + e] - m);
                     l += p[e];
                 }
-                pb[st] = make_uint4(pack_bf16x2(p[0], p[1]), pack_bf16x2(p[2], p[3]),
-                                    pack_bf16x2(p[4], p[5]), pack_bf16x2(p[6], p[7]));
+                pb[st] = make_uint4(pack_f16x2_rtz(p[0], p[1]), pack_f16x2_rtz(p[2], p[3]),
+                                    pack_f16x2_rtz(p[4], p[5]), pack_f16x2_rtz(p[6], p[7]));
             }
             // ---- O^T += V_tile^T . P --------------------------------------
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb) {
-                const bf16_t *vrow = Vt + (mb * 32 + col) * kVtPitch + half * 8;
+                const uint16_t *vrow = Vt + (mb * 32 + col) * kVtPitch + half * 8;
 #pragma unroll
                 for (int st = 0; st < 4; ++st) {
-                    const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(vrow + st * 16);
-                    O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        av, __builtin_bit_cast(bf16x8_t, pb[st]), O[mb], 0, 0, 0);
+                    const halfx8_t av = *reinterpret_cast<const halfx8_t *>(vrow + st * 16);
+                    O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                        av, __builtin_bit_cast(halfx8_t, pb[st]), O[mb], 0, 0, 0);
                 }
             }
         }

@@ -19,6 +19,9 @@ typedef uint16_t f16_t;            // bit pattern of an IEEE binary16
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float floatx2_t;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 halfx8_t;
+typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 halfx2_t;
 
 // ---- number formats -------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -30,11 +33,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     u += 0x7fffu + ((u >> 16) & 1u);
     return u >> 16;
 }
+// two fp32 -> packed bf16 (lo in bits 0..15), round to nearest even: v_cvt_pk_bf16_f32
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a += 0x7fffu + ((a >> 16) & 1u);
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xffff0000u);
+    const floatx2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+// two fp32 -> packed f16, round toward zero (saturates instead of overflowing): v_cvt_pkrtz_f16_f32
+__device__ __forceinline__ uint32_t pack_f16x2_rtz(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
 __device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
     return (float)__builtin_bit_cast(_Float16, (uint16_t)h);

@@ -190,7 +190,7 @@ def test_encode_degenerate_inputs():
         want = O.decode_batch(ref["cent"][:, None], ref["ids"][:, None], ref["codes"], ref["scales"], Bg)
         assert np.array_equal(P.to_np_u16(dec), want)
     # N < K with every token its own centroid: residual exactly zero, decode returns x
-    xs = xb[:, :6]
+    xs = xb[:, 20:26].contiguous()                    # six distinct (noisy) tokens
     init = torch.cat([xs, xs[:, :2]], 1)
     enc = B.encode_chunk(xs.to(DEV), init.to(DEV), Bg, T, 1)
     assert P.to_np_u8(enc.ids)[0].tolist() == list(range(6))
