@@ -141,6 +141,59 @@ def large_supplement(torch, B, synth, CONFIGS):
     return out
 
 
+def run_only(args, torch, B, synth, workload, CONFIGS):
+    """One part of the path, repeated: what rocprofv3 is pointed at."""
+    dev = "cuda"
+    if args.only == "copy":
+        n = 1 << 30
+        a = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+        b = torch.empty_like(a)
+        fn = lambda: b.copy_(a)
+        nbytes = 2 * n
+    elif args.only in ("large_decode", "large_encode"):
+        wl = CONFIGS["cfg3_dit_small"]
+        if args.only == "large_decode":
+            units, n = 2 * 3 * wl.heads, wl.tokens_per_layer
+            big = B.alloc_cache(units, n, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
+            big.ids.random_(0, wl.n_clusters); big.codes.zero_(); big.scales.fill_(0.25)
+            big.centroids.copy_(torch.randn(big.centroids.shape, device=dev).to(torch.bfloat16))
+            outbuf = torch.empty(units, n, wl.head_dim, dtype=torch.bfloat16, device=dev)
+            fn = lambda: B.decode(big, out=outbuf)
+            nbytes = units * n * 256 + _format_bytes(wl, units, n, wl.chunk)
+        else:
+            units = 2 * wl.layers * wl.heads
+            x = synth.MixtureStream(wl, units, 0, dev).next_chunk(wl.chunk)
+            init = synth.cold_start_centroids(x, wl.n_clusters)
+            cache = B.alloc_cache(units, wl.chunk, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
+            p = B.make_params(units, wl.n_clusters, wl.group_size, wl.n_stages, max(args.iters, 1))
+            ws = torch.empty(B.workspace_bytes(p, B.ENTRY_ENCODE, wl.chunk), dtype=torch.uint8, device=dev)
+            B.encode_chunk(x, init, wl.group_size, wl.n_stages, 5, cache=cache, workspace=ws)
+            warm = cache.centroids[:, 0].contiguous()
+            fn = lambda: B.encode_chunk(x, warm, wl.group_size, wl.n_stages, args.iters, cache=cache, workspace=ws)
+            nbytes = units * wl.chunk * 256 + _format_bytes(wl, units, wl.chunk, wl.chunk)
+    else:
+        wl = CONFIGS[args.workload]
+        s = workload.build_streaming(wl)
+        workload.step(s)
+        vec = workload.vectors_per_step(s)
+        units, n_tok = 2 * wl.heads, s.cache.ids.shape[1]
+        if args.only == "decode":
+            fn = lambda: workload.step_decode(s)
+            nbytes = vec["decode"] * 256 + _format_bytes(wl, units, n_tok, wl.chunk)
+        elif args.only == "encode":
+            fn = lambda: workload.step_encode(s, iters=args.iters)
+            nbytes = vec["encode"] * 256 + _format_bytes(wl, units, s.x_new.shape[1], wl.chunk)
+        else:
+            fn = lambda: workload.step_attn(s)
+            nbytes = _format_bytes(wl, units, n_tok, wl.chunk)
+    for _ in range(max(args.warmup, 1)):
+        fn()
+    torch.cuda.synchronize()
+    ms = _event_ms(fn, args.steps)
+    return {"only": args.only, "ms": round(ms, 5), "algorithmic_bytes": int(nbytes),
+            "GBps_algorithmic": round(nbytes / ms / 1e6, 1), "launches": args.steps + max(args.warmup, 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -149,6 +202,12 @@ def main():
     ap.add_argument("--workload", default="cfg2_window21")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large", action="store_true")
+    ap.add_argument("--only", default=None,
+                    choices=["decode", "encode", "attn", "copy", "large_decode", "large_encode"],
+                    help="profiling aid: run just this part --steps times and print a short JSON "
+                         "(copy = a plain device copy of 1 GiB, the reference the HBM counters "
+                         "are scaled by)")
+    ap.add_argument("--iters", type=int, default=0, help="Lloyd iterations for --only encode / large_encode")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
@@ -162,6 +221,9 @@ def main():
     B.lib()                                    # fail loudly if the HIP library is missing
     wl = CONFIGS[args.workload]
     torch.cuda.set_device(0)
+    if args.only:
+        print(json.dumps(run_only(args, torch, B, synth, workload, CONFIGS)))
+        return
     s = workload.build_streaming(wl)
     torch.cuda.synchronize()
 

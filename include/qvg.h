@@ -27,8 +27,9 @@
  * K and V of all heads and layers may be stacked into it):
  *   centroids [K][d]            bf16
  *   ids       [N]               uint8   index of the token's centroid
- *   codes     [N][T][d/4]       uint8   channel 4i+j in bits 2j..2j+1 of byte i,
- *                                       code = q + 1, q in {-1,0,1} (Eq. 2, b = 2)
+ *   codes     [N][T][d/4]       uint8   channel 4i+j in bits 2j..2j+1 of byte i, holding the
+ *                                       level q in {-1,0,1} (Eq. 2, b = 2) as 2-bit two's
+ *                                       complement: 0b00 = 0, 0b01 = +1, 0b11 = -1 (0b10 unused)
  *   scales    [N][T][d/B]       f16     per group of B consecutive channels
  * A cache of several chunks concatenates ids/codes/scales along N and keeps one
  * centroid table per chunk: centroids [n_chunks][K][d].
@@ -109,7 +110,7 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens,
  * kernel": all stages in one kernel, the running value kept in registers):
  * x_hat = centroid[id] + sum_t scale_t * q_t, fp32 fma in stage order, one
  * rounding to bf16.
- *   n_tokens tokens per unit in chunks of chunk_len (the last may be shorter;
+ *   n_tokens (0 .. 2^31-1) tokens per unit in chunks of chunk_len (the last may be shorter;
  *   chunk_len >= n_tokens means one chunk); centroids [H][n_chunks][K][d].
  *   x_bf16_out: same view convention as the encoder's x.
  */

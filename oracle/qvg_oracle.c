@@ -219,24 +219,25 @@ void qvgo_quant_round(int64_t N, int d, int B, int bits, float *r,
     }
 }
 
-/* Bit packing of the stored codes.  code = q + qmax (unsigned, 0..2^b-2).
- * Element i of a token sits in byte i/(8/b), at bit offset b*(i mod 8/b),
- * lowest bits first.  n_elems must be a multiple of 8/b. */
+/* Bit packing of the stored codes (the paper leaves the packing open).  A level q in
+ * [-qmax, qmax] is stored as its b-bit two's complement (q = -1 -> all ones), so a
+ * signed bit-field extract returns q.  Element i of a token sits in byte i/(8/b), at
+ * bit offset b*(i mod 8/b), lowest bits first.  n_elems must be a multiple of 8/b. */
 void qvgo_pack(int64_t n_elems, int bits, const int8_t *q, uint8_t *packed) {
-    const int per = 8 / bits, qmax = (1 << (bits - 1)) - 1;
+    const int per = 8 / bits, mask = (1 << bits) - 1;
     for (int64_t i = 0; i < n_elems / per; ++i) {
         unsigned byte = 0;
         for (int j = 0; j < per; ++j)
-            byte |= ((unsigned)(q[i * per + j] + qmax)) << (bits * j);
+            byte |= ((unsigned)q[i * per + j] & (unsigned)mask) << (bits * j);
         packed[i] = (uint8_t)byte;
     }
 }
 
 void qvgo_unpack(int64_t n_elems, int bits, const uint8_t *packed, int8_t *q) {
-    const int per = 8 / bits, qmax = (1 << (bits - 1)) - 1, mask = (1 << bits) - 1;
+    const int per = 8 / bits, mask = (1 << bits) - 1, sign = 1 << (bits - 1);
     for (int64_t i = 0; i < n_elems; ++i) {
         int code = (packed[i / per] >> (bits * (int)(i % per))) & mask;
-        q[i] = (int8_t)(code - qmax);
+        q[i] = (int8_t)((code & sign) ? code - (1 << bits) : code);
     }
 }
 

@@ -210,7 +210,7 @@ int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, const v
                int64_t stride_head, int64_t stride_token, void *stream) {
     int st = check_params(p);
     if (st != QVG_OK) return st;
-    if (n_tokens < 0 || chunk_len < 1) return QVG_ERR_BAD_PARAM;
+    if (n_tokens < 0 || n_tokens > 0x7fffffff || chunk_len < 1) return QVG_ERR_BAD_PARAM;
     if (n_tokens == 0) return QVG_OK;
     if (!centroids || !ids || !codes || !scales || !x_out) return QVG_ERR_NULL;
     if ((st = check_view(x_out, stride_head, stride_token, n_tokens)) != QVG_OK) return st;

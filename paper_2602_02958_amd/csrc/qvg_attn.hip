@@ -74,7 +74,7 @@ __device__ __forceinline__ void dequant4x8(const CacheSide &s, const bf16_t *cen
                     const uint32_t cw = code[e][t];
 #pragma unroll
                     for (int i = 0; i < 8; ++i)
-                        acc[i] = __builtin_fmaf(sf, (float)((int)((cw >> (2 * i)) & 3u) - 1), acc[i]);
+                        acc[i] = __builtin_fmaf(sf, (float)(((int)cw << (30 - 2 * i)) >> 30), acc[i]);
                 }
             }
 #pragma unroll

@@ -3,104 +3,219 @@
 //
 //   x_hat[n][c] = bf16( fma(s_T, q_T, ... fma(s_1, q_1, float(C[id_n][c])) ... ) )
 //
-// Pure streaming, bound by HBM: per token-vector it reads 1 id byte, T*32 code
-// bytes and T*(d/B) f16 scales, gathers one 256-byte centroid row (L2-resident:
-// a table is at most 64 KB) and writes 256 bytes of bf16.
+// Per token-vector it reads 1 id byte, T*32 code bytes and T*(d/B) f16 scales, gathers one
+// 256-byte centroid row and writes 256 bytes of bf16.  The centroid table of a chunk (at most
+// 64 KB) is staged in LDS by the workgroup that decodes the chunk: gathering the rows from L2
+// instead costs as much L2->CU traffic as the output itself and slows the writes measurably.
+// The memory side is pure streaming; the instruction side is what has to be kept lean: a
+// token costs 128*T field extractions and fmas (see add_two_stages for how a level becomes an
+// fma operand in one instruction per element), so the per-lane addressing is reduced to 32-bit
+// offsets from per-block (scalar) base pointers.
 //
 // Mapping: 16 lanes per token, 8 channels (one 16-byte store) per lane, so that a
-// wavefront's store instruction covers 4 whole token rows = 1 KB contiguous.
-// Each block walks kTokPerBlock tokens, kUnroll token rows in flight per thread.
+// wavefront's store instruction covers 4 whole token rows = 1 KB contiguous.  A workgroup of
+// 1024 threads walks its slice of a chunk 256 tokens per pass, 4 token rows per thread.
 #include "qvg_internal.hpp"
 
 namespace qvg {
 
-constexpr int kDecThreads = 256;
-constexpr int kDecRows = kDecThreads / 16;       // token rows per pass of a block
+constexpr int kDecThreads = 1024;
+constexpr int kDecRows = kDecThreads / 16;       // token rows per pass of a block (64)
 constexpr int kDecUnroll = 4;
-constexpr int kDecTokPerBlock = kDecRows * kDecUnroll;
+constexpr int kDecTokPerIter = kDecRows * kDecUnroll;      // 256 tokens per pass
+constexpr int kXcds = 8;                         // MI355X: 8 XCDs, each with its own L2
 
+__device__ __forceinline__ void unpack_bf16x8(const uint4 &c, float *acc) {
+    acc[0] = bf16_lo(c.x); acc[1] = bf16_hi(c.x); acc[2] = bf16_lo(c.y); acc[3] = bf16_hi(c.y);
+    acc[4] = bf16_lo(c.z); acc[5] = bf16_hi(c.z); acc[6] = bf16_lo(c.w); acc[7] = bf16_hi(c.w);
+}
+__device__ __forceinline__ uint4 pack_bf16x8(const float *acc) {
+    return make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
+                      pack_bf16x2(acc[4], acc[5]), pack_bf16x2(acc[6], acc[7]));
+}
+// half of an f16 scale as fp32 (exact): the extracted levels below are 2q, not q
+__device__ __forceinline__ float half_scale(uint32_t f16bits) { return 0.5f * f16_bits_to_f32(f16bits); }
+
+// A 2-bit two's complement level (sign, nonzero) moved to bits 15..14 of a 16-bit half IS the
+// f16 number 2q: 0b11 -> 0xC000 = -2, 0b01 -> 0x4000 = +2, 0b00 -> 0.  One shift and one mask
+// therefore turn the fields at the same position of both halves of a 32-bit word into two f16
+// operands, which v_fma_mix_f32 consumes directly: (s/2) * (2q) + acc, one rounding, the same
+// value as fma(s, q, acc).  w = codes of stage t (low half) and stage t+1 (high half) of one
+// token's 8 channels.
+__device__ __forceinline__ void add_two_stages(float *acc, uint32_t w, float hs0, float hs1) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const halfx2_t y = __builtin_bit_cast(halfx2_t, (w << (14 - 2 * i)) & 0xC000C000u);
+        acc[i] = __builtin_fmaf(hs0, (float)y[0], acc[i]);
+        acc[i] = __builtin_fmaf(hs1, (float)y[1], acc[i]);
+    }
+}
+// w = codes of the same (last) stage of two different tokens: low half -> accA, high half -> accB.
+__device__ __forceinline__ void add_last_stage_of_two_rows(float *accA, float *accB, uint32_t w,
+                                                           float hsA, float hsB) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const halfx2_t y = __builtin_bit_cast(halfx2_t, (w << (14 - 2 * i)) & 0xC000C000u);
+        accA[i] = __builtin_fmaf(hsA, (float)y[0], accA[i]);
+        accB[i] = __builtin_fmaf(hsB, (float)y[1], accB[i]);
+    }
+}
+
+// One pass of a block: 256 tokens, 4 rows per thread.  CHECK = false is the fast path for a pass
+// whose tokens all exist (no per-row predication).  tab: the chunk's centroid table in LDS.
+template <int T_, bool CHECK>
+__device__ __forceinline__ void decode_pass(int T, uint32_t ln0, uint32_t n_left, uint32_t lane16,
+                                            uint32_t G, uint32_t gidx, uint32_t kmax,
+                                            const uint8_t *ids_b, const uint16_t *codes_b,
+                                            const f16_t *scales_b, const bf16_t *tab, bf16_t *out_b,
+                                            int64_t stride_token) {
+    constexpr int TM = T_ > 0 ? T_ : kMaxStages;
+    uint32_t idv[kDecUnroll];
+    uint32_t code[kDecUnroll][TM];
+    uint32_t sc[kDecUnroll][TM];
+    bool ok[kDecUnroll];
+#pragma unroll
+    for (int u = 0; u < kDecUnroll; ++u) {
+        const uint32_t ln = ln0 + u * kDecRows;
+        ok[u] = !CHECK || ln < n_left;
+        if (CHECK) {
+            idv[u] = 0u;
+#pragma unroll
+            for (int t = 0; t < TM; ++t) { code[u][t] = 0u; sc[u][t] = 0u; }
+        }
+        if (ok[u]) {
+            idv[u] = ids_b[ln];
+            const uint32_t co = ln * (uint32_t)T * 16u + lane16;       // in uint16 units
+            const uint32_t so = ln * (uint32_t)T * G + gidx;
+#pragma unroll
+            for (int t = 0; t < TM; ++t)
+                if (t < T) { code[u][t] = codes_b[co + t * 16]; sc[u][t] = scales_b[so + t * G]; }
+        }
+    }
+    // rows are finished two at a time so that every shift+mask serves two 2-bit fields
+#pragma unroll
+    for (int up = 0; up < kDecUnroll; up += 2) {
+        float accA[8], accB[8];
+        // centroid rows from LDS; an id beyond the table (corrupt input) is clamped
+        unpack_bf16x8(*reinterpret_cast<const uint4 *>(tab + min(idv[up], kmax) * kHeadDim + lane16 * 8), accA);
+        unpack_bf16x8(*reinterpret_cast<const uint4 *>(tab + min(idv[up + 1], kmax) * kHeadDim + lane16 * 8), accB);
+#pragma unroll
+        for (int t = 0; t + 1 < TM; t += 2) {
+            if (t + 1 < T) {
+                add_two_stages(accA, code[up][t] | (code[up][t + 1] << 16),
+                               half_scale(sc[up][t]), half_scale(sc[up][t + 1]));
+                add_two_stages(accB, code[up + 1][t] | (code[up + 1][t + 1] << 16),
+                               half_scale(sc[up + 1][t]), half_scale(sc[up + 1][t + 1]));
+            }
+        }
+        if (T_ > 0) {
+            if (T_ & 1)
+                add_last_stage_of_two_rows(accA, accB, code[up][TM - 1] | (code[up + 1][TM - 1] << 16),
+                                           half_scale(sc[up][TM - 1]), half_scale(sc[up + 1][TM - 1]));
+        } else if (T & 1) {
+            // run-time stage count: the last odd stage sits at index T-1
+#pragma unroll
+            for (int t = 0; t < TM; t += 2)
+                if (t == T - 1)
+                    add_last_stage_of_two_rows(accA, accB, code[up][t] | (code[up + 1][t] << 16),
+                                               half_scale(sc[up][t]), half_scale(sc[up + 1][t]));
+        }
+        if (ok[up])
+            *reinterpret_cast<uint4 *>(out_b + ((int64_t)(ln0 + up * kDecRows) * stride_token + lane16 * 8)) =
+                pack_bf16x8(accA);
+        if (ok[up + 1])
+            *reinterpret_cast<uint4 *>(out_b + ((int64_t)(ln0 + (up + 1) * kDecRows) * stride_token + lane16 * 8)) =
+                pack_bf16x8(accB);
+    }
+}
+
+// One workgroup = one slice of one chunk of one unit.  It stages the chunk's centroid table
+// in LDS once (the only shared operand) and then streams its tokens.
 template <int T_>   // T_ > 0: compile-time stage count; T_ == 0: run-time
 __global__ __launch_bounds__(kDecThreads)
-void decode_kernel(DecodeArgs a) {
+void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, int blocks_per_xcd) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t *tab = reinterpret_cast<bf16_t *>(smem);                 // [K][128]
+    // Workgroups are dealt to the XCDs round-robin by their linear id; re-number them so that
+    // each XCD walks one contiguous range of (unit, chunk, slice) and writes one contiguous
+    // region of the output.
+    const int w = (int)(blockIdx.x % kXcds) * blocks_per_xcd + (int)(blockIdx.x / kXcds);
+    if (w >= n_blocks) return;
+    const int per_unit = a.n_chunks * slices;
+    const int h = w / per_unit;
+    const int c = (w - h * per_unit) / slices;
+    const int sl = w - h * per_unit - c * slices;
+    const int64_t cbeg = (int64_t)c * a.chunk_len;
+    const int64_t cend = (cbeg + a.chunk_len < a.n_tokens) ? cbeg + a.chunk_len : a.n_tokens;
+    const int64_t tok0 = cbeg + (int64_t)sl * slice_len;
+    if (tok0 >= cend) return;                                       // uniform: before any barrier
+    const uint32_t n_left = (uint32_t)((cend - tok0 < slice_len) ? cend - tok0 : slice_len);
+
     const int T = T_ > 0 ? T_ : a.T;
-    const int h = blockIdx.y;
-    const int lane16 = threadIdx.x & 15;
-    const int row = threadIdx.x >> 4;
-    const int G = kHeadDim / a.B;
-    const int gidx = (lane16 * 8) / a.B;          // scale group of this lane's 8 channels
-    const int64_t tok0 = (int64_t)blockIdx.x * kDecTokPerBlock;
+    const uint32_t lane16 = threadIdx.x & 15;
+    const uint32_t row = threadIdx.x >> 4;
+    const uint32_t G = kHeadDim / a.B;
+    const uint32_t gidx = (lane16 * 8) / a.B;     // scale group of this lane's 8 channels
 
-    uint32_t idv[kDecUnroll];
-    uint32_t code[kDecUnroll][T_ > 0 ? T_ : kMaxStages];
-    uint32_t sc[kDecUnroll][T_ > 0 ? T_ : kMaxStages];
-    uint4 cen[kDecUnroll];
-    bool ok[kDecUnroll];
+    {   // stage the table: K rows of 256 B, 16 B per thread and step
+        const bf16_t *cg = a.cent + ((int64_t)h * a.n_chunks + c) * a.K * kHeadDim;
+        for (int i = threadIdx.x; i < a.K * 16; i += kDecThreads)
+            *reinterpret_cast<uint4 *>(tab + i * 8) = *reinterpret_cast<const uint4 *>(cg + i * 8);
+    }
+    __syncthreads();
 
-#pragma unroll
-    for (int u = 0; u < kDecUnroll; ++u) {
-        const int64_t n = tok0 + u * kDecRows + row;
-        ok[u] = n < a.n_tokens;
-        if (ok[u]) {
-            const int64_t hn = (int64_t)h * a.n_tokens + n;
-            idv[u] = min((uint32_t)a.ids[hn], (uint32_t)(a.K - 1));   // stay inside the table whatever the bytes hold
-            const uint16_t *cp = reinterpret_cast<const uint16_t *>(a.codes + hn * T * 32) + lane16;
-            const f16_t *sp = a.scales + hn * T * G + gidx;
-#pragma unroll
-            for (int t = 0; t < (T_ > 0 ? T_ : kMaxStages); ++t) {
-                if (t < T) { code[u][t] = cp[t * 16]; sc[u][t] = sp[t * G]; }
-            }
-        }
+    // per-block base pointers (uniform), per-lane 32-bit offsets
+    const int64_t hn0 = (int64_t)h * a.n_tokens + tok0;
+    const uint8_t *ids_b = a.ids + hn0;
+    const uint16_t *codes_b = reinterpret_cast<const uint16_t *>(a.codes + hn0 * T * 32);
+    const f16_t *scales_b = a.scales + hn0 * T * G;
+    bf16_t *out_b = a.out + (int64_t)h * a.stride_head + tok0 * a.stride_token;
+    const uint32_t kmax = (uint32_t)a.K - 1u;
+
+    for (uint32_t first = 0; first < n_left; first += kDecTokPerIter) {
+        if (first + kDecTokPerIter <= n_left)
+            decode_pass<T_, false>(T, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
+                                   tab, out_b, a.stride_token);
+        else
+            decode_pass<T_, true>(T, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
+                                  tab, out_b, a.stride_token);
     }
-#pragma unroll
-    for (int u = 0; u < kDecUnroll; ++u) {
-        if (ok[u]) {
-            const int64_t n = tok0 + u * kDecRows + row;
-            const int64_t chunk = n / a.chunk_len;
-            const bf16_t *crow = a.cent + (((int64_t)h * a.n_chunks + chunk) * a.K + idv[u]) * kHeadDim;
-            cen[u] = *reinterpret_cast<const uint4 *>(crow + lane16 * 8);
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < kDecUnroll; ++u) {
-        if (!ok[u]) continue;
-        const int64_t n = tok0 + u * kDecRows + row;
-        float acc[8];
-        acc[0] = bf16_lo(cen[u].x); acc[1] = bf16_hi(cen[u].x);
-        acc[2] = bf16_lo(cen[u].y); acc[3] = bf16_hi(cen[u].y);
-        acc[4] = bf16_lo(cen[u].z); acc[5] = bf16_hi(cen[u].z);
-        acc[6] = bf16_lo(cen[u].w); acc[7] = bf16_hi(cen[u].w);
-#pragma unroll
-        for (int t = 0; t < (T_ > 0 ? T_ : kMaxStages); ++t) {
-            if (t < T) {
-                const float s = f16_bits_to_f32(sc[u][t]);
-                const uint32_t cw = code[u][t];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float q = (float)((int)((cw >> (2 * i)) & 3u) - 1);
-                    acc[i] = __builtin_fmaf(s, q, acc[i]);
-                }
-            }
-        }
-        uint4 o;
-        o.x = pack_bf16x2(acc[0], acc[1]); o.y = pack_bf16x2(acc[2], acc[3]);
-        o.z = pack_bf16x2(acc[4], acc[5]); o.w = pack_bf16x2(acc[6], acc[7]);
-        bf16_t *orow = a.out + (int64_t)h * a.stride_head + n * a.stride_token;
-        *reinterpret_cast<uint4 *>(orow + lane16 * 8) = o;
-    }
+}
+
+template <int T_>
+static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
+    // slices per chunk: enough workgroups to fill 256 CUs x 2 twice over, but as few as possible
+    // beyond that (every workgroup re-reads the chunk's table; measured flat from 512 to 4096)
+    const int64_t unit_chunks = (int64_t)a.H * a.n_chunks;
+    const int64_t chunk = a.chunk_len < a.n_tokens ? a.chunk_len : a.n_tokens;
+    int64_t slices = (1024 + unit_chunks - 1) / unit_chunks;
+    const int64_t max_slices = (chunk + kDecTokPerIter - 1) / kDecTokPerIter;
+    if (slices > max_slices) slices = max_slices;
+    if (slices < 1) slices = 1;
+    int64_t slice_len = (chunk + slices - 1) / slices;
+    slice_len = (slice_len + kDecTokPerIter - 1) / kDecTokPerIter * kDecTokPerIter;
+    slices = (chunk + slice_len - 1) / slice_len;
+    const int64_t nb = unit_chunks * slices;
+    if (nb > 0x7fffffff - kXcds) return hipErrorInvalidValue;
+    const int bpx = (int)((nb + kXcds - 1) / kXcds);
+    const size_t smem = (size_t)a.K * kHeadDim * sizeof(bf16_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<T_>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((decode_kernel<T_>), dim3((unsigned)(bpx * kXcds)), dim3(kDecThreads), smem, s, a,
+                       (int)slices, (uint32_t)slice_len, (int)nb, bpx);
+    return hipGetLastError();
 }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s) {
     if (a.n_tokens == 0) return hipSuccess;
-    dim3 grid((unsigned)((a.n_tokens + kDecTokPerBlock - 1) / kDecTokPerBlock), (unsigned)a.H);
-    dim3 block(kDecThreads);
     switch (a.T) {
-        case 1: hipLaunchKernelGGL(decode_kernel<1>, grid, block, 0, s, a); break;
-        case 2: hipLaunchKernelGGL(decode_kernel<2>, grid, block, 0, s, a); break;
-        case 3: hipLaunchKernelGGL(decode_kernel<3>, grid, block, 0, s, a); break;
-        case 4: hipLaunchKernelGGL(decode_kernel<4>, grid, block, 0, s, a); break;
-        default: hipLaunchKernelGGL(decode_kernel<0>, grid, block, 0, s, a); break;
+        case 1: return launch_decode_t<1>(a, s);
+        case 2: return launch_decode_t<2>(a, s);
+        case 3: return launch_decode_t<3>(a, s);
+        case 4: return launch_decode_t<4>(a, s);
+        default: return launch_decode_t<0>(a, s);
     }
-    return hipGetLastError();
 }
 
 }  // namespace qvg

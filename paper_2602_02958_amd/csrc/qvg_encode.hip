@@ -274,6 +274,13 @@ void assign_kernel(AssignArgs a, int Kpad) {
             }
             if (valid) {
                 uint8_t *cp = a.codes + (hn * a.T + t) * 32 + half * 16;
+                // word[] holds q + 1 per 2-bit field (built with one shift-add per element);
+                // the stored form is two's complement: field 00 -> 11, 01 -> 00, 10 -> 01
+#pragma unroll
+                for (int wi = 0; wi < 4; ++wi) {
+                    const uint32_t lo = ~word[wi] & 0x55555555u;
+                    word[wi] = lo | (((~word[wi] >> 1) & lo) << 1);
+                }
                 *reinterpret_cast<uint4 *>(cp) = make_uint4(word[0], word[1], word[2], word[3]);
                 f16_t *sp = a.scales + (hn * a.T + t) * G;
                 if (B_ == 128) { if (half == 0) sp[0] = (f16_t)sh[0]; }

@@ -3,47 +3,109 @@
 // The mean is defined with a fixed summation order - members in token order, fp64 -
 // so that the result does not depend on scheduling.  Two kernels:
 //   rank:  a stable counting sort of the token indices of one unit by cluster id
-//          (LDS histogram, scan, then one wavefront places 64 tokens per step using
-//          ballot-built peer masks so that equal ids keep their token order);
+//          (16 wavefronts, each histogramming and then placing its own contiguous range
+//          of tokens, ballot-built peer masks keeping equal ids in token order);
 //   mean:  one wavefront per centroid walks its members in that order, two channels
-//          per lane (a 256-byte coalesced row per member), eight rows in flight,
+//          per lane (a 256-byte coalesced row per member), sixteen rows in flight,
 //          adds in fp64, divides by the count, rounds to fp32 and then to bf16.
 //          A group without members keeps its previous centroid.
 #include "qvg_internal.hpp"
 
 namespace qvg {
 
-constexpr int kRankThreads = 256;
+constexpr int kRankThreads = 1024;
+constexpr int kRankWaves = kRankThreads / 64;      // the tokens of a unit are split into 16 ranges
+constexpr int kRankKeep = 8;                        // ids a lane keeps in registers between passes
 
+// Stable counting sort of token indices by cluster id, one workgroup per unit.
+// Wavefront w owns the w-th contiguous range of tokens: it histograms the range, and after
+// the scan (start of cluster k = tokens of lower clusters + tokens of k in earlier ranges) it
+// places the range 64 tokens at a time.  Inside a step, lanes with equal ids are ranked by
+// lane number (ballot-built peer masks), so equal ids keep their token order.
 __global__ __launch_bounds__(kRankThreads)
 void kmeans_rank_kernel(UpdateArgs a) {
-    __shared__ int cnt[256];
-    __shared__ int cursor[256];
-    const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+    __shared__ int cnt[kRankWaves][256];      // histogram per range, then running cursor
+    __shared__ int total[256];
+    const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int K = a.K;
     const int64_t N = a.n_tokens;
     const uint8_t *ids = a.ids + (int64_t)h * a.ids_stride;
     int32_t *perm = a.perm + (int64_t)h * N;
     int32_t *offs = a.offsets + (int64_t)h * (K + 1);
 
-    cnt[tid] = 0;
+    for (int i = tid; i < kRankWaves * 256; i += kRankThreads) (&cnt[0][0])[i] = 0;
     __syncthreads();
-    // ids at or above K cannot come from the assignment; such tokens are left out
-    for (int64_t n = tid; n < N; n += kRankThreads) { const int id = ids[n]; if (id < K) atomicAdd(&cnt[id], 1); }
-    __syncthreads();
-    if (tid == 0) {                       // exclusive scan over at most 256 bins
-        int run = 0;
-        for (int j = 0; j < K; ++j) { cursor[j] = run; offs[j] = run; run += cnt[j]; }
-        offs[K] = run;
+    // range of this wavefront, a multiple of 64 tokens long
+    const int64_t per = ((N + kRankWaves * 64 - 1) / (kRankWaves * 64)) * 64;
+    const int64_t beg = (int64_t)w * per;
+    const int64_t end = (beg + per < N) ? beg + per : N;
+    const int steps = (int)((per + 63) / 64);
+    const bool keep = steps <= kRankKeep;
+    int kept[kRankKeep];
+    // ids at or above K cannot come from the assignment; such tokens are left out (id = -1)
+    if (keep) {
+#pragma unroll
+        for (int i = 0; i < kRankKeep; ++i) {
+            const int64_t n = beg + (int64_t)i * 64 + lane;
+            int id = -1;
+            if (i < steps && n < end) { id = ids[n]; if (id >= K) id = -1; }
+            kept[i] = id;
+        }
+#pragma unroll
+        for (int i = 0; i < kRankKeep; ++i) if (kept[i] >= 0) atomicAdd(&cnt[w][kept[i]], 1);
+    } else {
+        for (int64_t n = beg + lane; n < end; n += 64) { const int id = ids[n]; if (id < K) atomicAdd(&cnt[w][id], 1); }
     }
     __syncthreads();
-    if (a.counts_out && tid < K) a.counts_out[(int64_t)h * K + tid] = cnt[tid];
-    if (tid >= 64) return;                // placement: wavefront 0 only, tokens in order
+    if (tid < 256) {
+        int t = 0;
+        for (int r = 0; r < kRankWaves; ++r) t += cnt[r][tid];
+        total[tid] = (tid < K) ? t : 0;
+    }
+    __syncthreads();
+    if (tid < 64) {                       // exclusive scan of total[0..255] by one wavefront
+        int v[4], run = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { v[i] = total[lane * 4 + i]; run += v[i]; }
+        int incl = run;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += o;
+        }
+        int start = incl - run;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { total[lane * 4 + i] = start; start += v[i]; }
+    }
+    __syncthreads();
+    if (tid < 256) {
+        // cursor of (range r, cluster tid) = start of the cluster + members in earlier ranges
+        int run = total[tid], c = 0;
+        for (int r = 0; r < kRankWaves; ++r) { const int t = cnt[r][tid]; cnt[r][tid] = run; run += t; c += t; }
+        if (tid < K) {
+            offs[tid] = total[tid];
+            if (a.counts_out) a.counts_out[(int64_t)h * K + tid] = c;
+            if (tid == K - 1) offs[K] = total[tid] + c;
+        }
+    }
+    __syncthreads();
 
-    for (int64_t base = 0; base < N; base += 64) {
-        const int64_t n = base + lane;
-        const int id = (n < N) ? (int)ids[n] : 0;
-        const bool valid = n < N && id < K;
+    int nxt = -1;
+    if (!keep && beg + lane < end) { nxt = ids[beg + lane]; if (nxt >= K) nxt = -1; }
+    for (int i = 0; i < steps; ++i) {
+        const int64_t n = beg + (int64_t)i * 64 + lane;
+        int id;
+        if (keep) {
+            id = -1;
+#pragma unroll
+            for (int j = 0; j < kRankKeep; ++j) if (j == i) id = kept[j];
+        } else {
+            id = nxt;
+            const int64_t nn = n + 64;
+            nxt = -1;
+            if (nn < end) { nxt = ids[nn]; if (nxt >= K) nxt = -1; }
+        }
+        const bool valid = id >= 0;
         uint64_t peers = __ballot(valid);
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
@@ -51,11 +113,10 @@ void kmeans_rank_kernel(UpdateArgs a) {
             peers &= ((id >> b) & 1) ? m : ~m;
         }
         if (valid) {
-            const uint64_t below = peers & ((1ull << lane) - 1ull);
-            const int rank = __builtin_popcountll(below);
-            const int start = cursor[id];             // read by all peers before the write below
+            const int rank = __builtin_popcountll(peers & ((1ull << lane) - 1ull));
+            const int start = cnt[w][id];             // read by all peers before the write below
             perm[start + rank] = (int32_t)n;
-            if (rank == 0) cursor[id] = start + __builtin_popcountll(peers);
+            if (rank == 0) cnt[w][id] = start + __builtin_popcountll(peers);
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -80,18 +141,22 @@ void kmeans_mean_kernel(UpdateArgs a) {
     }
     const bf16_t *xb = a.x + (int64_t)h * a.stride_head + lane * 2;
     double s0 = 0.0, s1 = 0.0;
-    int i = beg;
-    for (; i + 8 <= end; i += 8) {
-        uint32_t w[8];
+    for (int base = beg; base < end; base += 64) {
+        // 64 member indices with one coalesced load, then broadcast lane by lane
+        const int mine = (base + lane < end) ? perm[base + lane] : 0;
+        const int cntm = (end - base < 64) ? end - base : 64;
+        for (int u0 = 0; u0 < cntm; u0 += 16) {
+            uint32_t wv[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-            w[u] = *reinterpret_cast<const uint32_t *>(xb + (int64_t)perm[i + u] * a.stride_token);
+            for (int u = 0; u < 16; ++u) {
+                const int idx = __shfl(mine, u0 + u, 64);
+                wv[u] = (u0 + u < cntm)
+                    ? *reinterpret_cast<const uint32_t *>(xb + (int64_t)idx * a.stride_token) : 0u;
+            }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) { s0 += (double)bf16_lo(w[u]); s1 += (double)bf16_hi(w[u]); }
-    }
-    for (; i < end; ++i) {
-        const uint32_t w = *reinterpret_cast<const uint32_t *>(xb + (int64_t)perm[i] * a.stride_token);
-        s0 += (double)bf16_lo(w); s1 += (double)bf16_hi(w);
+            for (int u = 0; u < 16; ++u)
+                if (u0 + u < cntm) { s0 += (double)bf16_lo(wv[u]); s1 += (double)bf16_hi(wv[u]); }
+        }
     }
     const double c = (double)(end - beg);
     const float m0 = (float)(s0 / c), m1 = (float)(s1 / c);

@@ -56,8 +56,8 @@ def check_encoded_unit(x_bits, cent_bits, gpu, B, T, ref=None):
         alt = O.encode_given_ids(x_bits[ties], cent_bits, gpu["ids"][ties], B, T)
         assert np.array_equal(gpu["codes"][ties], alt["codes"])
         assert np.array_equal(gpu["scales"][ties], alt["scales"])
-    assert gpu["codes"].max() <= 0xAA and ((gpu["codes"] & 0xAA) & ((gpu["codes"] & 0x55) << 1)).max() == 0, \
-        "a 2-bit field holds the unused code 3"
+    c = gpu["codes"]
+    assert (((c & 0xAA) >> 1) & (~c & 0x55)).max() == 0, "a 2-bit field holds the unused code 0b10"
     return int(ties.size)
 
 

@@ -49,13 +49,13 @@ def test_bf16_conversions_match_torch(rng):
 
 
 def test_pack_layout_by_hand():
-    # element i of a token: byte i//4, bits 2*(i%4).. ; code = q + 1
+    # element i of a token: byte i//4, bits 2*(i%4).. ; code = two's complement of q (-1 -> 0b11)
     q = np.array([[-1, 0, 1, 0, 1, 1, -1, -1]], dtype=np.int8)
-    # codes 0,1,2,1 -> 0b01_10_01_00 = 0x64 ; codes 2,2,0,0 -> 0b00_00_10_10 = 0x0a
-    assert O.pack(q, 2).tolist() == [[0x64, 0x0A]]
-    # 4 bit: code = q + 7, low nibble first
+    # codes 3,0,1,0 -> 0b00_01_00_11 = 0x13 ; codes 1,1,3,3 -> 0b11_11_01_01 = 0xf5
+    assert O.pack(q, 2).tolist() == [[0x13, 0xF5]]
+    # 4 bit: two's complement nibble, low nibble first
     q4 = np.array([[-7, 7, 0, 1]], dtype=np.int8)
-    assert O.pack(q4, 4).tolist() == [[0x00 | (14 << 4), 7 | (8 << 4)]]
+    assert O.pack(q4, 4).tolist() == [[0x9 | (7 << 4), 0 | (1 << 4)]]
 
 
 def test_pack_unpack_roundtrip(rng):
