@@ -128,7 +128,7 @@ int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len,
  *   layout qvg_decode reads; both use the parameters in *p.
  *   lse_out  [H][n_q] fp32 natural-log sum of exp of the scaled scores, or NULL
  *   workspace: none needed today (pass NULL, 0).
- * n_kv_tokens >= 1; n_q == 0 is a no-op.
+ * n_kv_tokens >= 1; n_q == 0 is a no-op; softmax_scale must be positive and finite.
  */
 int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q_bf16,
                     int64_t n_kv_tokens, int64_t chunk_len,

@@ -2,95 +2,136 @@
 // where K_hat / V_hat are the decoded values of paper Sec. 4.2 Eq. 7, rounded to bf16 as the
 // stand-alone decoder stores them.  The decoded tiles live only in LDS.
 //
-// One workgroup = 4 wavefronts = 128 queries of one unit; it walks the cache chunk by chunk
-// (each chunk has its own centroid tables) in tiles of 64 tokens:
-//   1. all 256 threads decode the K tile (row-major) and the V tile (transposed) into LDS;
-//   2. S^T = K_tile . Q^T on v_mfma_f32_32x32x16_bf16: rows = cache tokens, columns = queries,
+// One workgroup = 8 wavefronts = 256 queries of one unit (32 per wavefront); it walks the cache
+// chunk by chunk (each chunk has its own centroid tables) in tiles of 64 tokens.  Per tile:
+//   1. S^T = K_tile . Q^T on v_mfma_f32_32x32x16_bf16: rows = cache tokens, columns = queries,
 //      so a lane owns one query and the soft-max statistics stay in the lane (one exchange
 //      between the two lane halves per tile);
-//   3. online soft-max in fp32 (base-2 exponent);
-//   4. O^T += V_tile^T . P on v_mfma_f32_32x32x16_f16: the probabilities go in as f16 (11
+//   2. online soft-max in fp32 (base-2 exponent);
+//   3. O^T += V_tile^T . P on v_mfma_f32_32x32x16_f16: the probabilities go in as f16 (11
 //      significant bits; bf16's 8 would cost up to 2^-9 of |V| in the output), and the V tile,
 //      first rounded to bf16 like the stand-alone decoder's output, is stored as f16, which
 //      holds every bf16 value of magnitude 2^-14 .. 65504 exactly (larger ones saturate).
-//      The lane's P values are already the B operand: the V tile is stored with the matching
-//      token permutation, so no cross-lane traffic is needed.
-// Only the two contractions use the matrix cores; the unpack / fma / soft-max work is VALU.
+//      The lane's P values are already the B operand: the V tile is stored transposed with
+//      the matching token permutation, so no cross-lane traffic is needed;
+//   4. all 512 threads decode the NEXT tile (2 tokens x 8 channels of K and of V each) from
+//      registers that were loaded one tile earlier, into the other LDS buffer.
+// The decode work is amortised over 256 queries; only the two contractions use the matrix
+// cores, the unpack / fma / soft-max work is VALU and is what bounds the kernel.
 #include "qvg_internal.hpp"
 
 namespace qvg {
 
-constexpr int kAtThreads = 256;
-constexpr int kAtQPerBlock = 128;
+constexpr int kAtThreads = 512;
+constexpr int kAtWaves = kAtThreads / 64;
+constexpr int kAtQPerBlock = 32 * kAtWaves;     // 256
 constexpr int kAtKv = 64;
 constexpr int kKtPitch = 136;      // bf16 per row of the K tile (272 B, 16-byte aligned, conflict-free)
 constexpr int kVtPitch = 72;       // f16 per row of the transposed V tile (144 B)
+constexpr int kKtElems = kAtKv * kKtPitch;
+constexpr int kVtElems = kHeadDim * kVtPitch;
+constexpr size_t kAtSmem = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint16_t);
 
 struct CacheSide {                 // one of K / V, already offset to this unit
     const bf16_t *cent;            // [n_chunks][K][d]
     const uint8_t *ids; const uint8_t *codes; const f16_t *scales;
 };
 
-// Decode 4 consecutive tokens x 8 channels (chunk c8 of 16).  Tokens at or after `end`
-// decode to zero.  hb[e][i]: bf16 bits of token tok0+e, channel 8*c8+i.
-template <int T_>
-__device__ __forceinline__ void dequant4x8(const CacheSide &s, const bf16_t *cent_chunk,
-                                           int64_t tok0, int64_t end, int c8, int T, int B, int K,
-                                           uint32_t hb[4][4]) {
-    constexpr int TM = T_ > 0 ? T_ : kMaxStages;
-    const int G = kHeadDim / B;
-    const int g = (c8 * 8) / B;
-    uint32_t idv[4];
-    uint32_t code[4][TM], sc[4][TM];
-    uint4 cen[4];
+struct Tile {                      // one 64-token tile; tiles never straddle a chunk
+    int chunk; int64_t t0, cend; bool valid;
+};
+
+__device__ __forceinline__ Tile first_tile(const AttnArgs &a) {
+    Tile t;
+    t.chunk = 0; t.t0 = 0; t.cend = a.chunk_len < a.n_kv ? a.chunk_len : a.n_kv; t.valid = true;
+    return t;
+}
+__device__ __forceinline__ Tile next_tile(const AttnArgs &a, Tile t) {
+    t.t0 += kAtKv;
+    if (t.t0 >= t.cend) {
+        t.chunk += 1;
+        if (t.chunk >= a.n_chunks) { t.valid = false; t.chunk = a.n_chunks - 1; }
+        else {
+            t.t0 = (int64_t)t.chunk * a.chunk_len;
+            t.cend = (t.t0 + a.chunk_len < a.n_kv) ? t.t0 + a.chunk_len : a.n_kv;
+        }
+    }
+    return t;
+}
+
+template <int TM>
+struct Raw {                       // what one thread loads for its 2 tokens x 8 channels of one side
+    uint32_t code[2][TM], sc[2][TM];
+    uint4 cen[2];
+};
+
+// ids of this thread's two tokens of a tile (0 for tokens past the chunk end / an invalid tile)
+__device__ __forceinline__ void load_ids(const CacheSide &s, const Tile &t, int tp, uint32_t kmax,
+                                         uint32_t id[2]) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const int64_t n = tok0 + e;
-        if (n < end) {
-            idv[e] = min((uint32_t)s.ids[n], (uint32_t)(K - 1));   // stay inside the table
+    for (int e = 0; e < 2; ++e) {
+        const int64_t n = t.t0 + 2 * tp + e;
+        id[e] = (t.valid && n < t.cend) ? min((uint32_t)s.ids[n], kmax) : 0u;
+    }
+}
+
+template <int T_, int TM>
+__device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int tp, int c8, int T,
+                                         int G, int g, int K, const uint32_t id[2], Raw<TM> &r) {
+    const bf16_t *cent = s.cent + (int64_t)t.chunk * K * kHeadDim;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int64_t n = t.t0 + 2 * tp + e;
+        const bool ok = t.valid && n < t.cend;
+#pragma unroll
+        for (int k = 0; k < TM; ++k) { r.code[e][k] = 0u; r.sc[e][k] = 0u; }
+        r.cen[e] = make_uint4(0u, 0u, 0u, 0u);
+        if (ok) {
             const uint16_t *cp = reinterpret_cast<const uint16_t *>(s.codes + n * T * 32) + c8;
             const f16_t *sp = s.scales + n * T * G + g;
 #pragma unroll
-            for (int t = 0; t < TM; ++t)
-                if (t < T) { code[e][t] = cp[t * 16]; sc[e][t] = sp[t * G]; }
+            for (int k = 0; k < TM; ++k)
+                if (k < T) { r.code[e][k] = cp[k * 16]; r.sc[e][k] = sp[k * G]; }
+            r.cen[e] = *reinterpret_cast<const uint4 *>(cent + (int64_t)id[e] * kHeadDim + c8 * 8);
         }
     }
+}
+
+// fp32 decoded values of the thread's two tokens (tokens that do not exist decode to zero
+// because their codes, scales and centroid were loaded as zero)
+template <int T_, int TM>
+__device__ __forceinline__ void dequant2x8(const Raw<TM> &r, int T, float *accA, float *accB) {
+    unpack_bf16x8(r.cen[0], accA);
+    unpack_bf16x8(r.cen[1], accB);
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-        if (tok0 + e < end)
-            cen[e] = *reinterpret_cast<const uint4 *>(cent_chunk + (int64_t)idv[e] * kHeadDim + c8 * 8);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        if (tok0 + e < end) {
-            float acc[8];
-            acc[0] = bf16_lo(cen[e].x); acc[1] = bf16_hi(cen[e].x);
-            acc[2] = bf16_lo(cen[e].y); acc[3] = bf16_hi(cen[e].y);
-            acc[4] = bf16_lo(cen[e].z); acc[5] = bf16_hi(cen[e].z);
-            acc[6] = bf16_lo(cen[e].w); acc[7] = bf16_hi(cen[e].w);
-#pragma unroll
-            for (int t = 0; t < TM; ++t) {
-                if (t < T) {
-                    const float sf = f16_bits_to_f32(sc[e][t]);
-                    const uint32_t cw = code[e][t];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        acc[i] = __builtin_fmaf(sf, (float)(((int)cw << (30 - 2 * i)) >> 30), acc[i]);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i) hb[e][i] = pack_bf16x2(acc[2 * i], acc[2 * i + 1]);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) hb[e][i] = 0u;
+    for (int t = 0; t + 1 < TM; t += 2) {
+        if (t + 1 < T) {
+            add_two_stages(accA, r.code[0][t] | (r.code[0][t + 1] << 16),
+                           half_scale(r.sc[0][t]), half_scale(r.sc[0][t + 1]));
+            add_two_stages(accB, r.code[1][t] | (r.code[1][t + 1] << 16),
+                           half_scale(r.sc[1][t]), half_scale(r.sc[1][t + 1]));
         }
+    }
+    if (T_ > 0) {
+        if (T_ & 1)
+            add_last_stage_of_two_rows(accA, accB, r.code[0][TM - 1] | (r.code[1][TM - 1] << 16),
+                                       half_scale(r.sc[0][TM - 1]), half_scale(r.sc[1][TM - 1]));
+    } else if (T & 1) {
+#pragma unroll
+        for (int t = 0; t < TM; t += 2)
+            if (t == T - 1)
+                add_last_stage_of_two_rows(accA, accB, r.code[0][t] | (r.code[1][t] << 16),
+                                           half_scale(r.sc[0][t]), half_scale(r.sc[1][t]));
     }
 }
 
 template <int T_>       // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages)
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_kernel(AttnArgs a) {
-    __shared__ __align__(16) bf16_t Kt[kAtKv * kKtPitch];
-    __shared__ __align__(16) uint16_t Vt[kHeadDim * kVtPitch];     // f16 bits
+    constexpr int TM = T_ > 0 ? T_ : kMaxStages;
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t *Kt = reinterpret_cast<uint16_t *>(smem);                  // [2][64][136] bf16
+    uint16_t *Vt = Kt + 2 * kKtElems;                                   // [2][128][72] f16, transposed
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -99,6 +140,7 @@ void attn_kernel(AttnArgs a) {
     const bool qvalid = qrow < a.n_q;
     const int T = T_ > 0 ? T_ : a.T, B = a.B, K = a.K;
     const int G = kHeadDim / B;
+    const uint32_t kmax = (uint32_t)K - 1u;
 
     CacheSide ks, vs;
     ks.ids = a.k_ids + (int64_t)h * a.n_kv;  ks.codes = a.k_codes + (int64_t)h * a.n_kv * T * 32;
@@ -107,6 +149,16 @@ void attn_kernel(AttnArgs a) {
     vs.ids = a.v_ids + (int64_t)h * a.n_kv;  vs.codes = a.v_codes + (int64_t)h * a.n_kv * T * 32;
     vs.scales = a.v_scales + (int64_t)h * a.n_kv * T * G;
     vs.cent = a.v_cent + (int64_t)h * a.n_chunks * K * kHeadDim;
+
+    // decode mapping: 16 adjacent lanes cover the 16 channel chunks of a token pair (coalesced)
+    const int c8 = tid & 15, tp = tid >> 4;            // tp 0..31: tokens 2*tp, 2*tp+1 of the tile
+    const int g = (c8 * 8) / B;
+    // position of the token pair in a transposed V row: token 16*st + 8*a + 4*hh + e sits at
+    // 16*st + 8*hh + 4*a + e (the order in which a lane's soft-max values feed the PV MFMA);
+    // the 16-byte group index is XOR-ed with the channel chunk to spread the banks
+    const int tok = 2 * tp;
+    const int v_pos = 16 * (tok >> 4) + 8 * ((tok >> 2) & 1) + 4 * ((tok >> 3) & 1) + (tok & 3);
+    const int v_off = ((v_pos >> 3) ^ (c8 & 7)) * 8 + (v_pos & 7);      // in f16 units
 
     // Q as the B operand of S^T = K Q^T: lane (col, half) holds Q[q][16*kk + 8*half .. +7].
     uint4 qa[8];
@@ -124,110 +176,123 @@ void attn_kernel(AttnArgs a) {
     float m = -INFINITY, l = 0.0f;
     const float scale2 = a.scale * 1.4426950408889634f;
 
-    // thread -> (token quad, channel chunk) for the two tile layouts
-    const int k_c8 = tid & 15, k_qd = tid >> 4;       // K tile: a row's 16 chunks are adjacent lanes
-    const int v_qd = tid & 15, v_c8 = tid >> 4;       // V tile: a channel's 16 quads are adjacent lanes
-    // position of quad v_qd in a transposed row: tokens 16*st + 8*a + 4*hh + e -> 16*st + 8*hh + 4*a + e
-    const int v_pos = 16 * (v_qd >> 2) + 8 * (v_qd & 1) + 4 * ((v_qd >> 1) & 1);
+    auto decode_to_lds = [&](const Raw<TM> &rk, const Raw<TM> &rv, int buf) {
+        float accA[8], accB[8];
+        dequant2x8<T_, TM>(rk, T, accA, accB);
+        uint16_t *kt = Kt + buf * kKtElems;
+        *reinterpret_cast<uint4 *>(kt + (tok + 0) * kKtPitch + c8 * 8) = pack_bf16x8(accA);
+        *reinterpret_cast<uint4 *>(kt + (tok + 1) * kKtPitch + c8 * 8) = pack_bf16x8(accB);
+        dequant2x8<T_, TM>(rv, T, accA, accB);
+        uint16_t *vt = Vt + buf * kVtElems + v_off;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            // round to bf16 (the decoder's output), then to f16 (exact in range): channels e, e+1
+            const uint32_t pa = pack_bf16x2(accA[e], accA[e + 1]);
+            const uint32_t pb = pack_bf16x2(accB[e], accB[e + 1]);
+            *reinterpret_cast<uint32_t *>(vt + (c8 * 8 + e) * kVtPitch) = pack_f16x2_rtz(bf16_lo(pa), bf16_lo(pb));
+            *reinterpret_cast<uint32_t *>(vt + (c8 * 8 + e + 1) * kVtPitch) = pack_f16x2_rtz(bf16_hi(pa), bf16_hi(pb));
+        }
+    };
 
-    for (int c = 0; c < a.n_chunks; ++c) {
-        const int64_t cbeg = (int64_t)c * a.chunk_len;
-        const int64_t cend = (cbeg + a.chunk_len < a.n_kv) ? cbeg + a.chunk_len : a.n_kv;
-        const bf16_t *kc = ks.cent + (int64_t)c * K * kHeadDim;
-        const bf16_t *vc = vs.cent + (int64_t)c * K * kHeadDim;
-        for (int64_t t0 = cbeg; t0 < cend; t0 += kAtKv) {
-            __syncthreads();
-            {
-                uint32_t hb[4][4];
-                dequant4x8<T_>(ks, kc, t0 + 4 * k_qd, cend, k_c8, T, B, K, hb);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    *reinterpret_cast<uint4 *>(Kt + (4 * k_qd + e) * kKtPitch + k_c8 * 8) =
-                        make_uint4(hb[e][0], hb[e][1], hb[e][2], hb[e][3]);
-            }
-            {
-                uint32_t hb[4][4];
-                dequant4x8<T_>(vs, vc, t0 + 4 * v_qd, cend, v_c8, T, B, K, hb);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)      // bf16 pair -> f16 pair (exact in range)
-                        hb[e][i] = pack_f16x2_rtz(bf16_lo(hb[e][i]), bf16_hi(hb[e][i]));
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    // channels 8*v_c8 + 2i (low halves) and + 2i + 1 (high halves) of 4 tokens
-                    const uint32_t lo01 = (hb[0][i] & 0xffffu) | (hb[1][i] << 16);
-                    const uint32_t lo23 = (hb[2][i] & 0xffffu) | (hb[3][i] << 16);
-                    const uint32_t hi01 = (hb[0][i] >> 16) | (hb[1][i] & 0xffff0000u);
-                    const uint32_t hi23 = (hb[2][i] >> 16) | (hb[3][i] & 0xffff0000u);
-                    *reinterpret_cast<uint2 *>(Vt + (8 * v_c8 + 2 * i) * kVtPitch + v_pos) = make_uint2(lo01, lo23);
-                    *reinterpret_cast<uint2 *>(Vt + (8 * v_c8 + 2 * i + 1) * kVtPitch + v_pos) = make_uint2(hi01, hi23);
-                }
-            }
-            __syncthreads();
+    // ---- prologue: tile 0 into buffer 0, raw data of tile 1 in flight -------------------
+    Tile cur = first_tile(a);
+    Tile nxt = next_tile(a, cur);
+    Tile nn = nxt.valid ? next_tile(a, nxt) : nxt;
+    uint32_t idk[2], idv[2];
+    Raw<TM> rk, rv;
+    load_ids(ks, cur, tp, kmax, idk);
+    load_ids(vs, cur, tp, kmax, idv);
+    load_raw<T_, TM>(ks, cur, tp, c8, T, G, g, K, idk, rk);
+    load_raw<T_, TM>(vs, cur, tp, c8, T, G, g, K, idv, rv);
+    load_ids(ks, nxt, tp, kmax, idk);
+    load_ids(vs, nxt, tp, kmax, idv);
+    decode_to_lds(rk, rv, 0);
+    __syncthreads();
 
-            // ---- S^T = K_tile . Q^T -------------------------------------
-            floatx16_t S[2];
+    int buf = 0;
+    while (true) {
+        // raw data of the next tile (consumed at the end of this iteration), ids of the one after
+        if (nxt.valid) {
+            load_raw<T_, TM>(ks, nxt, tp, c8, T, G, g, K, idk, rk);
+            load_raw<T_, TM>(vs, nxt, tp, c8, T, G, g, K, idv, rv);
+            load_ids(ks, nn, tp, kmax, idk);
+            load_ids(vs, nn, tp, kmax, idv);
+        }
+        const uint16_t *kt = Kt + buf * kKtElems;
+        const uint16_t *vt = Vt + buf * kVtElems;
+
+        // ---- S^T = K_tile . Q^T -------------------------------------------
+        floatx16_t S[2];
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
+        for (int nb = 0; nb < 2; ++nb) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) S[nb][r] = 0.0f;
-                const bf16_t *arow = Kt + (nb * 32 + col) * kKtPitch + half * 8;
+            for (int r = 0; r < 16; ++r) S[nb][r] = 0.0f;
+            const uint16_t *arow = kt + (nb * 32 + col) * kKtPitch + half * 8;
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kk * 16);
-                    S[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        av, __builtin_bit_cast(bf16x8_t, qa[kk]), S[nb], 0, 0, 0);
-                }
+            for (int kk = 0; kk < 8; ++kk) {
+                const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kk * 16);
+                S[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    av, __builtin_bit_cast(bf16x8_t, qa[kk]), S[nb], 0, 0, 0);
             }
-            // ---- online soft-max (base 2) --------------------------------
-            const int ntile = (int)((cend - t0 < kAtKv) ? cend - t0 : kAtKv);
-            float tmax = -INFINITY;
+        }
+        // ---- online soft-max (base 2) --------------------------------------
+        const int ntile = (int)((cur.cend - cur.t0 < kAtKv) ? cur.cend - cur.t0 : kAtKv);
+        if (ntile < kAtKv) {                                   // uniform: last tile of a chunk
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int kv = nb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-                    float z = S[nb][r] * scale2;
-                    if (kv >= ntile) z = -INFINITY;
-                    S[nb][r] = z;
-                    tmax = fmaxf(tmax, z);
+                    if (kv >= ntile) S[nb][r] = -INFINITY;
                 }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float m_new = fmaxf(m, tmax);
-            if (__ballot(m_new > m)) {                 // uniform: skip when no maximum moved
-                const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-                l *= alpha;
+        }
+        float tmax = -INFINITY;
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
+        for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
+            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, S[nb][r]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * scale2;     // the scale is positive: order kept
+        const float m_new = fmaxf(m, tmax);
+        if (__ballot(m_new > m)) {                 // uniform: skip when no maximum moved
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            l *= alpha;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
+        }
+        m = m_new;
+        uint4 pb[4];
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            float p[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[st >> 1][(st & 1) * 8 + e], scale2, -m));
+                l += p[e];
             }
-            m = m_new;
-            uint4 pb[4];
+            pb[st] = make_uint4(pack_f16x2_rtz(p[0], p[1]), pack_f16x2_rtz(p[2], p[3]),
+                                pack_f16x2_rtz(p[4], p[5]), pack_f16x2_rtz(p[6], p[7]));
+        }
+        // ---- O^T += V_tile^T . P --------------------------------------------
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            const int key = (mb * 4 + (col >> 3)) & 7;            // swizzle key of row 32*mb + col
+            const uint16_t *vrow = vt + (mb * 32 + col) * kVtPitch;
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
-                float p[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    p[e] = __builtin_amdgcn_exp2f(S[st >> 1][(st & 1) * 8 + e] - m);
-                    l += p[e];
-                }
-                pb[st] = make_uint4(pack_f16x2_rtz(p[0], p[1]), pack_f16x2_rtz(p[2], p[3]),
-                                    pack_f16x2_rtz(p[4], p[5]), pack_f16x2_rtz(p[6], p[7]));
-            }
-            // ---- O^T += V_tile^T . P --------------------------------------
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb) {
-                const uint16_t *vrow = Vt + (mb * 32 + col) * kVtPitch + half * 8;
-#pragma unroll
-                for (int st = 0; st < 4; ++st) {
-                    const halfx8_t av = *reinterpret_cast<const halfx8_t *>(vrow + st * 16);
-                    O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                        av, __builtin_bit_cast(halfx8_t, pb[st]), O[mb], 0, 0, 0);
-                }
+                const halfx8_t av = *reinterpret_cast<const halfx8_t *>(vrow + (((2 * st + half) ^ key) * 8));
+                O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                    av, __builtin_bit_cast(halfx8_t, pb[st]), O[mb], 0, 0, 0);
             }
         }
+        if (!nxt.valid) break;
+        // ---- decode the next tile into the other buffer ------------------------
+        decode_to_lds(rk, rv, buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+        cur = nxt; nxt = nn;
+        nn = nn.valid ? next_tile(a, nn) : nn;
     }
     // ---- normalise and store: lane holds channels 32*mb + 8*g + 4*half + 0..3 of its query ----
     const float ltot = l + __shfl_xor(l, 32, 64);
@@ -237,28 +302,36 @@ void attn_kernel(AttnArgs a) {
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
+            for (int gq = 0; gq < 4; ++gq) {
                 const uint2 o = make_uint2(
-                    pack_bf16x2(O[mb][4 * g + 0] * inv, O[mb][4 * g + 1] * inv),
-                    pack_bf16x2(O[mb][4 * g + 2] * inv, O[mb][4 * g + 3] * inv));
-                *reinterpret_cast<uint2 *>(op + mb * 32 + g * 8) = o;
+                    pack_bf16x2(O[mb][4 * gq + 0] * inv, O[mb][4 * gq + 1] * inv),
+                    pack_bf16x2(O[mb][4 * gq + 2] * inv, O[mb][4 * gq + 3] * inv));
+                *reinterpret_cast<uint2 *>(op + mb * 32 + gq * 8) = o;
             }
         if (a.lse && half == 0)
             a.lse[(int64_t)h * a.n_q + qrow] = (m + __builtin_log2f(ltot)) * 0.6931471805599453f;
     }
 }
 
+template <int T_>
+static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<T_>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmem);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
+    hipLaunchKernelGGL((attn_kernel<T_>), grid, dim3(kAtThreads), kAtSmem, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     if (a.n_q == 0) return hipSuccess;
-    dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
     switch (a.T) {
-        case 1: hipLaunchKernelGGL(attn_kernel<1>, grid, dim3(kAtThreads), 0, s, a); break;
-        case 2: hipLaunchKernelGGL(attn_kernel<2>, grid, dim3(kAtThreads), 0, s, a); break;
-        case 3: hipLaunchKernelGGL(attn_kernel<3>, grid, dim3(kAtThreads), 0, s, a); break;
-        case 4: hipLaunchKernelGGL(attn_kernel<4>, grid, dim3(kAtThreads), 0, s, a); break;
-        default: hipLaunchKernelGGL(attn_kernel<0>, grid, dim3(kAtThreads), 0, s, a); break;
+        case 1: return launch_attn_t<1>(a, s);
+        case 2: return launch_attn_t<2>(a, s);
+        case 3: return launch_attn_t<3>(a, s);
+        case 4: return launch_attn_t<4>(a, s);
+        default: return launch_attn_t<0>(a, s);
     }
-    return hipGetLastError();
 }
 
 }  // namespace qvg

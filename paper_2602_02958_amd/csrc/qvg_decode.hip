@@ -25,42 +25,6 @@ constexpr int kDecUnroll = 4;
 constexpr int kDecTokPerIter = kDecRows * kDecUnroll;      // 256 tokens per pass
 constexpr int kXcds = 8;                         // MI355X: 8 XCDs, each with its own L2
 
-__device__ __forceinline__ void unpack_bf16x8(const uint4 &c, float *acc) {
-    acc[0] = bf16_lo(c.x); acc[1] = bf16_hi(c.x); acc[2] = bf16_lo(c.y); acc[3] = bf16_hi(c.y);
-    acc[4] = bf16_lo(c.z); acc[5] = bf16_hi(c.z); acc[6] = bf16_lo(c.w); acc[7] = bf16_hi(c.w);
-}
-__device__ __forceinline__ uint4 pack_bf16x8(const float *acc) {
-    return make_uint4(pack_bf16x2(acc[0], acc[1]), pack_bf16x2(acc[2], acc[3]),
-                      pack_bf16x2(acc[4], acc[5]), pack_bf16x2(acc[6], acc[7]));
-}
-// half of an f16 scale as fp32 (exact): the extracted levels below are 2q, not q
-__device__ __forceinline__ float half_scale(uint32_t f16bits) { return 0.5f * f16_bits_to_f32(f16bits); }
-
-// A 2-bit two's complement level (sign, nonzero) moved to bits 15..14 of a 16-bit half IS the
-// f16 number 2q: 0b11 -> 0xC000 = -2, 0b01 -> 0x4000 = +2, 0b00 -> 0.  One shift and one mask
-// therefore turn the fields at the same position of both halves of a 32-bit word into two f16
-// operands, which v_fma_mix_f32 consumes directly: (s/2) * (2q) + acc, one rounding, the same
-// value as fma(s, q, acc).  w = codes of stage t (low half) and stage t+1 (high half) of one
-// token's 8 channels.
-__device__ __forceinline__ void add_two_stages(float *acc, uint32_t w, float hs0, float hs1) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const halfx2_t y = __builtin_bit_cast(halfx2_t, (w << (14 - 2 * i)) & 0xC000C000u);
-        acc[i] = __builtin_fmaf(hs0, (float)y[0], acc[i]);
-        acc[i] = __builtin_fmaf(hs1, (float)y[1], acc[i]);
-    }
-}
-// w = codes of the same (last) stage of two different tokens: low half -> accA, high half -> accB.
-__device__ __forceinline__ void add_last_stage_of_two_rows(float *accA, float *accB, uint32_t w,
-                                                           float hsA, float hsB) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const halfx2_t y = __builtin_bit_cast(halfx2_t, (w << (14 - 2 * i)) & 0xC000C000u);
-        accA[i] = __builtin_fmaf(hsA, (float)y[0], accA[i]);
-        accB[i] = __builtin_fmaf(hsB, (float)y[1], accB[i]);
-    }
-}
-
 // One pass of a block: 256 tokens, 4 rows per thread.  CHECK = false is the fast path for a pass
 // whose tokens all exist (no per-row predication).  tab: the chunk's centroid table in LDS.
 template <int T_, bool CHECK>

@@ -86,6 +86,9 @@ def test_null_and_alignment_errors_are_reported_before_any_launch():
                              fake, C.c_float(float("nan")), fake, None, None, 0, None) == -2
     assert L.qvg_attn_decode(C.byref(p), 4, None, 10, 10, fake, fake, fake, fake, fake, fake, fake,
                              fake, C.c_float(0.1), fake, None, None, 0, None) == -1
+    for bad in (0.0, -0.5, float("inf")):
+        assert L.qvg_attn_decode(C.byref(p), 4, fake, 10, 10, fake, fake, fake, fake, fake, fake, fake,
+                                 fake, C.c_float(bad), fake, None, None, 0, None) == -2
     # zero-size calls succeed without touching the device
     assert L.qvg_decode(C.byref(p), 0, 10, None, None, None, None, None, 0, 0, None) == 0
     assert L.qvg_attn_decode(C.byref(p), 0, None, 10, 10, None, None, None, None, None, None, None,
