@@ -235,7 +235,7 @@ int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q, int64_t n_k
     (void)workspace; (void)workspace_bytes;
     int st = check_params(p);
     if (st != QVG_OK) return st;
-    if (n_q < 0 || n_kv_tokens < 1 || chunk_len < 1) return QVG_ERR_BAD_PARAM;
+    if (n_q < 0 || n_kv_tokens < 1 || n_kv_tokens > 0x7fffffff || chunk_len < 1) return QVG_ERR_BAD_PARAM;
     if (!(softmax_scale > 0.0f) || softmax_scale - softmax_scale != 0.0f) return QVG_ERR_BAD_PARAM;   // positive, finite
     if (n_q == 0) return QVG_OK;
     if (!q || !out || !k_centroids || !k_ids || !k_codes || !k_scales || !v_centroids || !v_ids ||

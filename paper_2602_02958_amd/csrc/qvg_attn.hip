@@ -38,12 +38,12 @@ struct CacheSide {                 // one of K / V, already offset to this unit
 };
 
 struct Tile {                      // one 64-token tile; tiles never straddle a chunk
-    int chunk; int64_t t0, cend; bool valid;
+    int chunk; int t0, cend; bool valid;     // token indices fit 31 bits (checked by the caller)
 };
 
 __device__ __forceinline__ Tile first_tile(const AttnArgs &a) {
     Tile t;
-    t.chunk = 0; t.t0 = 0; t.cend = a.chunk_len < a.n_kv ? a.chunk_len : a.n_kv; t.valid = true;
+    t.chunk = 0; t.t0 = 0; t.cend = (int)(a.chunk_len < a.n_kv ? a.chunk_len : a.n_kv); t.valid = true;
     return t;
 }
 __device__ __forceinline__ Tile next_tile(const AttnArgs &a, Tile t) {
@@ -52,8 +52,9 @@ __device__ __forceinline__ Tile next_tile(const AttnArgs &a, Tile t) {
         t.chunk += 1;
         if (t.chunk >= a.n_chunks) { t.valid = false; t.chunk = a.n_chunks - 1; }
         else {
-            t.t0 = (int64_t)t.chunk * a.chunk_len;
-            t.cend = (t.t0 + a.chunk_len < a.n_kv) ? t.t0 + a.chunk_len : a.n_kv;
+            const int64_t b = (int64_t)t.chunk * a.chunk_len;
+            t.t0 = (int)b;
+            t.cend = (int)((b + a.chunk_len < a.n_kv) ? b + a.chunk_len : a.n_kv);
         }
     }
     return t;
@@ -70,7 +71,7 @@ __device__ __forceinline__ void load_ids(const CacheSide &s, const Tile &t, int 
                                          uint32_t id[2]) {
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
-        const int64_t n = t.t0 + 2 * tp + e;
+        const int n = t.t0 + 2 * tp + e;
         id[e] = (t.valid && n < t.cend) ? min((uint32_t)s.ids[n], kmax) : 0u;
     }
 }
@@ -81,14 +82,14 @@ __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int 
     const bf16_t *cent = s.cent + (int64_t)t.chunk * K * kHeadDim;
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
-        const int64_t n = t.t0 + 2 * tp + e;
+        const int n = t.t0 + 2 * tp + e;
         const bool ok = t.valid && n < t.cend;
 #pragma unroll
         for (int k = 0; k < TM; ++k) { r.code[e][k] = 0u; r.sc[e][k] = 0u; }
         r.cen[e] = make_uint4(0u, 0u, 0u, 0u);
         if (ok) {
-            const uint16_t *cp = reinterpret_cast<const uint16_t *>(s.codes + n * T * 32) + c8;
-            const f16_t *sp = s.scales + n * T * G + g;
+            const uint16_t *cp = reinterpret_cast<const uint16_t *>(s.codes + (int64_t)n * T * 32) + c8;
+            const f16_t *sp = s.scales + (int64_t)n * T * G + g;
 #pragma unroll
             for (int k = 0; k < TM; ++k)
                 if (k < T) { r.code[e][k] = cp[k * 16]; r.sc[e][k] = sp[k * G]; }
@@ -125,9 +126,11 @@ __device__ __forceinline__ void dequant2x8(const Raw<TM> &r, int T, float *accA,
     }
 }
 
+// Variant that loads every thread's codes and scales straight from global memory (many small
+// loads): used only for stage counts above 4, whose staging area would not fit in LDS.
 template <int T_>       // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages)
 __global__ __launch_bounds__(kAtThreads, 2)
-void attn_kernel(AttnArgs a) {
+void attn_kernel_direct(AttnArgs a) {
     constexpr int TM = T_ > 0 ? T_ : kMaxStages;
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t *Kt = reinterpret_cast<uint16_t *>(smem);                  // [2][64][136] bf16
@@ -313,24 +316,329 @@ void attn_kernel(AttnArgs a) {
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Main variant (1..4 stages).  The packed codes, scales and ids of a tile are brought in with a
+// few wide loads per thread two tiles ahead and parked in an LDS staging area; the per-thread
+// 2-byte reads that the decode needs then hit LDS instead of issuing dozens of tiny global
+// loads.  Only the centroid rows are gathered from global memory (L2), one tile ahead.
+// ---------------------------------------------------------------------------------------------
+constexpr int kStMaxT = 4;
+constexpr int kStMaxG = 8;
+constexpr int kStCodes = kAtKv * kStMaxT * 32;            // bytes of one side's codes of a tile
+constexpr int kStScales = kAtKv * kStMaxT * kStMaxG * 2;  // bytes of one side's scales
+constexpr int kStBytes = 2 * kStCodes + 2 * kStScales + 2 * kAtKv;   // K and V: codes, scales, ids
+constexpr size_t kAtSmemStaged = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint16_t) + 2 * kStBytes;
+
+template <int T_>
+__global__ __launch_bounds__(kAtThreads, 2)
+void attn_kernel_staged(AttnArgs a) {
+    constexpr int T = T_;
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t *Kt = reinterpret_cast<uint16_t *>(smem);                  // [2][64][136] bf16
+    uint16_t *Vt = Kt + 2 * kKtElems;                                   // [2][128][72] f16, transposed
+    unsigned char *stage = reinterpret_cast<unsigned char *>(Vt + 2 * kVtElems);   // [2][kStBytes]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const int h = blockIdx.y;
+    const int64_t qrow = (int64_t)blockIdx.x * kAtQPerBlock + wave * 32 + col;
+    const bool qvalid = qrow < a.n_q;
+    const int B = a.B, K = a.K;
+    const int G = kHeadDim / B;
+    const uint32_t kmax = (uint32_t)K - 1u;
+
+    const uint8_t *k_ids = a.k_ids + (int64_t)h * a.n_kv, *v_ids = a.v_ids + (int64_t)h * a.n_kv;
+    const uint8_t *k_codes = a.k_codes + (int64_t)h * a.n_kv * T * 32, *v_codes = a.v_codes + (int64_t)h * a.n_kv * T * 32;
+    const unsigned char *k_scales = reinterpret_cast<const unsigned char *>(a.k_scales + (int64_t)h * a.n_kv * T * G);
+    const unsigned char *v_scales = reinterpret_cast<const unsigned char *>(a.v_scales + (int64_t)h * a.n_kv * T * G);
+    const bf16_t *k_cent = a.k_cent + (int64_t)h * a.n_chunks * K * kHeadDim;
+    const bf16_t *v_cent = a.v_cent + (int64_t)h * a.n_chunks * K * kHeadDim;
+
+    const int c8 = tid & 15, tp = tid >> 4;            // tp 0..31: tokens 2*tp, 2*tp+1 of the tile
+    const int g = (c8 * 8) / B;
+    const int tok = 2 * tp;
+    const int v_pos = 16 * (tok >> 4) + 8 * ((tok >> 2) & 1) + 4 * ((tok >> 3) & 1) + (tok & 3);
+    const int v_off = ((v_pos >> 3) ^ (c8 & 7)) * 8 + (v_pos & 7);      // in f16 units
+
+    uint4 qa[8];
+    {
+        const bf16_t *qp = a.q + ((int64_t)h * a.n_q + qrow) * kHeadDim + half * 8;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+            qa[kk] = qvalid ? *reinterpret_cast<const uint4 *>(qp + kk * 16) : make_uint4(0u, 0u, 0u, 0u);
+    }
+    floatx16_t O[4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) O[mb][r] = 0.0f;
+    float m = -INFINITY, l = 0.0f;
+    const float scale2 = a.scale * 1.4426950408889634f;
+
+    // ---- staging: what a thread fetches for a tile ------------------------------------------
+    // 16-byte pieces, both sides: codes (a token-stage record is 32 B, always 16-byte aligned;
+    // piece p of a side belongs to token p / (2T)) and scales (T*G*2 bytes per token, contiguous
+    // over the tile; the host picks this kernel only when chunks start 16-byte aligned).
+    constexpr int kPieces = 2 * kAtKv * T * 2;                       // code pieces, both sides
+    constexpr int kPiecesPerThread = (kPieces + kAtThreads - 1) / kAtThreads;
+    const int scPiecesSide = kAtKv * T * G / 8;                      // scale pieces per side (<= 256)
+    const int scBytesTok = T * G * 2;
+    struct Fetch { uint4 code[kPiecesPerThread]; uint4 sc; uint32_t id; };
+
+    auto fetch_tile = [&](const Tile &t, Fetch &f) {
+        const int nvalid = t.valid ? (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv) : 0;
+#pragma unroll
+        for (int i = 0; i < kPiecesPerThread; ++i) {
+            const int p = tid + i * kAtThreads;
+            f.code[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (p < kPieces) {
+                const bool vside = p >= kPieces / 2;
+                const int ps = p - (vside ? kPieces / 2 : 0);
+                if (ps / (2 * T) < nvalid)
+                    f.code[i] = *reinterpret_cast<const uint4 *>((vside ? v_codes : k_codes) +
+                                                                 ((int64_t)t.t0 * T * 32 + (int64_t)ps * 16));
+            }
+        }
+        f.sc = make_uint4(0u, 0u, 0u, 0u);
+        if (tid < 2 * scPiecesSide) {
+            const bool vside = tid >= scPiecesSide;
+            const int ps = tid - (vside ? scPiecesSide : 0);
+            // a piece is fetched when its first byte belongs to an existing token; the bytes of
+            // later, missing tokens it may drag along are never used (their rows are masked)
+            // and still lie inside this unit's scale array, except in the unit's very last
+            // piece, which is fetched only if it ends inside the array
+            const int64_t first = (int64_t)t.t0 * scBytesTok + (int64_t)ps * 16;
+            if ((ps * 16) / scBytesTok < nvalid && first + 16 <= (int64_t)a.n_kv * scBytesTok)
+                f.sc = *reinterpret_cast<const uint4 *>((vside ? v_scales : k_scales) + first);
+            else if ((ps * 16) / scBytesTok < nvalid) {
+                // tail of the unit's array: 2 bytes at a time
+                uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int b = 0; b < 8; ++b)
+                    if (first + 2 * b + 2 <= (int64_t)a.n_kv * scBytesTok)
+                        w[b >> 1] |= (uint32_t)*reinterpret_cast<const uint16_t *>((vside ? v_scales : k_scales) + first + 2 * b)
+                                     << (16 * (b & 1));
+                f.sc = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+        f.id = 0u;
+        if (tid < 2 * kAtKv) {
+            const int n = tid & 63;
+            if (n < nvalid) f.id = min((uint32_t)((tid >> 6) ? v_ids : k_ids)[t.t0 + n], kmax);
+        }
+    };
+    auto park_tile = [&](const Fetch &f, int sb) {
+        unsigned char *st = stage + sb * kStBytes;
+#pragma unroll
+        for (int i = 0; i < kPiecesPerThread; ++i) {
+            const int p = tid + i * kAtThreads;
+            if (p < kPieces) {
+                const bool vside = p >= kPieces / 2;
+                const int ps = p - (vside ? kPieces / 2 : 0);
+                *reinterpret_cast<uint4 *>(st + (vside ? kStCodes : 0) + ps * 16) = f.code[i];
+            }
+        }
+        if (tid < 2 * scPiecesSide) {
+            const bool vside = tid >= scPiecesSide;
+            const int ps = tid - (vside ? scPiecesSide : 0);
+            *reinterpret_cast<uint4 *>(st + 2 * kStCodes + (vside ? kStScales : 0) + ps * 16) = f.sc;
+        }
+        if (tid < 2 * kAtKv) st[2 * kStCodes + 2 * kStScales + tid] = (unsigned char)f.id;
+    };
+    // centroid rows of this thread's two tokens, both sides, using the parked ids
+    auto gather_rows = [&](const Tile &t, int sb, uint4 cen[2][2]) {
+        const unsigned char *st = stage + sb * kStBytes + 2 * kStCodes + 2 * kStScales;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const bf16_t *cent = (s ? v_cent : k_cent) + (int64_t)t.chunk * K * kHeadDim + c8 * 8;
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                cen[s][e] = *reinterpret_cast<const uint4 *>(cent + (int)st[s * kAtKv + tok + e] * kHeadDim);
+        }
+    };
+    // decode the tile parked in staging buffer sb (rows gathered in cen) into tile buffer buf;
+    // tokens that do not exist have zero codes and scales, and their rows are masked in the
+    // soft-max, so whatever centroid row was gathered for them is harmless for K; V is zeroed
+    auto decode_to_lds = [&](const Tile &t, int sb, const uint4 cen[2][2], int buf) {
+        const unsigned char *st = stage + sb * kStBytes;
+        const int nvalid = (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv);
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            Raw<T> r;
+            const uint16_t *cp = reinterpret_cast<const uint16_t *>(st + s * kStCodes) + tok * T * 16 + c8;
+            const uint16_t *sp = reinterpret_cast<const uint16_t *>(st + 2 * kStCodes + s * kStScales) + tok * T * G + g;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+#pragma unroll
+                for (int k = 0; k < T; ++k) {
+                    r.code[e][k] = cp[(e * T + k) * 16];
+                    r.sc[e][k] = sp[(e * T + k) * G];
+                }
+                r.cen[e] = (tok + e < nvalid) ? cen[s][e] : make_uint4(0u, 0u, 0u, 0u);
+            }
+            float accA[8], accB[8];
+            dequant2x8<T, T>(r, T, accA, accB);
+            if (s == 0) {
+                uint16_t *kt = Kt + buf * kKtElems;
+                *reinterpret_cast<uint4 *>(kt + (tok + 0) * kKtPitch + c8 * 8) = pack_bf16x8(accA);
+                *reinterpret_cast<uint4 *>(kt + (tok + 1) * kKtPitch + c8 * 8) = pack_bf16x8(accB);
+            } else {
+                uint16_t *vt = Vt + buf * kVtElems + v_off;
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const uint32_t pa = pack_bf16x2(accA[e], accA[e + 1]);
+                    const uint32_t pb2 = pack_bf16x2(accB[e], accB[e + 1]);
+                    *reinterpret_cast<uint32_t *>(vt + (c8 * 8 + e) * kVtPitch) = pack_f16x2_rtz(bf16_lo(pa), bf16_lo(pb2));
+                    *reinterpret_cast<uint32_t *>(vt + (c8 * 8 + e + 1) * kVtPitch) = pack_f16x2_rtz(bf16_hi(pa), bf16_hi(pb2));
+                }
+            }
+        }
+    };
+
+    // ---- prologue: tile 0 decoded into buffer 0, tile 1 parked, tile 2 in registers ---------
+    Tile cur = first_tile(a);
+    Tile nxt = next_tile(a, cur);
+    Tile nn = nxt.valid ? next_tile(a, nxt) : nxt;
+    Fetch f;
+    uint4 cen[2][2];
+    fetch_tile(cur, f);  park_tile(f, 0);
+    fetch_tile(nxt, f);  park_tile(f, 1);
+    __syncthreads();
+    gather_rows(cur, 0, cen);
+    decode_to_lds(cur, 0, cen, 0);
+    if (nxt.valid) gather_rows(nxt, 1, cen);
+    __syncthreads();                 // tile 0 ready; staging buffer 0 free again
+
+    int buf = 0;                     // tile buffer of `cur`; the staging buffer of `nxt` is buf ^ 1
+    while (true) {
+        if (nn.valid) fetch_tile(nn, f);            // lands during this iteration
+        const uint16_t *kt = Kt + buf * kKtElems;
+        const uint16_t *vt = Vt + buf * kVtElems;
+        floatx16_t S[2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) S[nb][r] = 0.0f;
+            const uint16_t *arow = kt + (nb * 32 + col) * kKtPitch + half * 8;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kk * 16);
+                S[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    av, __builtin_bit_cast(bf16x8_t, qa[kk]), S[nb], 0, 0, 0);
+            }
+        }
+        const int ntile = (int)((cur.cend - cur.t0 < kAtKv) ? cur.cend - cur.t0 : kAtKv);
+        if (ntile < kAtKv) {                                   // uniform: last tile of a chunk
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kv = nb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                    if (kv >= ntile) S[nb][r] = -INFINITY;
+                }
+        }
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, S[nb][r]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * scale2;     // the scale is positive: order kept
+        const float m_new = fmaxf(m, tmax);
+        if (__ballot(m_new > m)) {                 // uniform: skip when no maximum moved
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            l *= alpha;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
+        }
+        m = m_new;
+        uint4 pb[4];
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            float p[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[st >> 1][(st & 1) * 8 + e], scale2, -m));
+                l += p[e];
+            }
+            pb[st] = make_uint4(pack_f16x2_rtz(p[0], p[1]), pack_f16x2_rtz(p[2], p[3]),
+                                pack_f16x2_rtz(p[4], p[5]), pack_f16x2_rtz(p[6], p[7]));
+        }
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            const int key = (mb * 4 + (col >> 3)) & 7;            // swizzle key of row 32*mb + col
+            const uint16_t *vrow = vt + (mb * 32 + col) * kVtPitch;
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                const halfx8_t av = *reinterpret_cast<const halfx8_t *>(vrow + (((2 * st + half) ^ key) * 8));
+                O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                    av, __builtin_bit_cast(halfx8_t, pb[st]), O[mb], 0, 0, 0);
+            }
+        }
+        if (!nxt.valid) break;
+        // decode the next tile (parked in staging buf^1, rows already gathered) into tile buffer
+        // buf^1, then park the tile after it in staging buf (free since the last barrier)
+        decode_to_lds(nxt, buf ^ 1, cen, buf ^ 1);
+        if (nn.valid) park_tile(f, buf);
+        __syncthreads();
+        if (nn.valid) gather_rows(nn, buf, cen);     // ids of nn are visible now; rows land next iteration
+        buf ^= 1;
+        cur = nxt; nxt = nn;
+        nn = nn.valid ? next_tile(a, nn) : nn;
+    }
+    const float ltot = l + __shfl_xor(l, 32, 64);
+    if (qvalid) {
+        const float inv = 1.0f / ltot;
+        bf16_t *op = a.out + ((int64_t)h * a.n_q + qrow) * kHeadDim + half * 4;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const uint2 o = make_uint2(
+                    pack_bf16x2(O[mb][4 * gq + 0] * inv, O[mb][4 * gq + 1] * inv),
+                    pack_bf16x2(O[mb][4 * gq + 2] * inv, O[mb][4 * gq + 3] * inv));
+                *reinterpret_cast<uint2 *>(op + mb * 32 + gq * 8) = o;
+            }
+        if (a.lse && half == 0)
+            a.lse[(int64_t)h * a.n_q + qrow] = (m + __builtin_log2f(ltot)) * 0.6931471805599453f;
+    }
+}
+
+template <int T_>
+static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmemStaged);
+    if (e != hipSuccess) return e;
+    dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
+    hipLaunchKernelGGL((attn_kernel_staged<T_>), grid, dim3(kAtThreads), kAtSmemStaged, s, a);
+    return hipGetLastError();
+}
+
 template <int T_>
 static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<T_>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmem);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
-    hipLaunchKernelGGL((attn_kernel<T_>), grid, dim3(kAtThreads), kAtSmem, s, a);
+    hipLaunchKernelGGL((attn_kernel_direct<T_>), grid, dim3(kAtThreads), kAtSmem, s, a);
     return hipGetLastError();
 }
 
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     if (a.n_q == 0) return hipSuccess;
     switch (a.T) {
-        case 1: return launch_attn_t<1>(a, s);
-        case 2: return launch_attn_t<2>(a, s);
-        case 3: return launch_attn_t<3>(a, s);
-        case 4: return launch_attn_t<4>(a, s);
-        default: return launch_attn_t<0>(a, s);
+        default: break;
+    }
+    // the staged kernel fetches scales in 16-byte pieces: every chunk must start on one
+    const bool aligned = (a.chunk_len % 8 == 0) || a.n_chunks == 1;
+    if (!aligned || a.T > kStMaxT) return launch_attn_t<0>(a, s);
+    switch (a.T) {
+        case 1: return launch_attn_staged<1>(a, s);
+        case 2: return launch_attn_staged<2>(a, s);
+        case 3: return launch_attn_staged<3>(a, s);
+        default: return launch_attn_staged<4>(a, s);
     }
 }
 
