@@ -24,6 +24,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
+# HBM bytes per launch read off rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each scaled by what the
+# same counter reads for a plain 1 GiB device copy); the runs are summarised under profiles/.
+# None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {("cfg2_window21", "attn"): 924770468}   # profiles/attn_cfg2_window21_hbm_counters.txt
+
 
 def _event_ms(fn, reps):
     """Average duration of fn() in ms over reps runs, HIP events on torch's current stream
@@ -45,47 +50,59 @@ def _format_bytes(wl, units, tokens, chunk):
     return units * (tokens * per_tok + tables)
 
 
-def cpu_baseline(wl, seconds_hint=20.0):
-    """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
+def cpu_baseline(wl, budget_s=12.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same step: all units
+    encode one chunk, a cache of the workload's length is decoded (the encoded chunk repeated: the
+    oracle's decode cost does not depend on the content), and a subset of the queries attends over
+    the decoded cache.  The number of queries is chosen from a 16-query trial to fill budget_s."""
     import numpy as np
     import torch
     from oracle import qvg_oracle as O
     from paper_2602_02958_amd import synth
     cores = O.max_threads()
-    units = max(1, min(2 * wl.heads, cores))
-    n_enc = min(wl.chunk, 4680)
-    st = synth.MixtureStream(wl, units, 0)
-    x = st.next_chunk(n_enc)
+    heads = wl.heads
+    units = 2 * heads
+    n_enc = wl.chunk
+    n_chunks = wl.n_chunks
+    xk = synth.MixtureStream(wl, heads, 0).next_chunk(n_enc)
+    xv = synth.MixtureStream(wl, heads, 1).next_chunk(n_enc)
+    x = torch.cat([xk, xv], 0)
     init = synth.cold_start_centroids(x, wl.n_clusters)
     xb = x.view(torch.int16).numpy().view(np.uint16)
     ib = init.view(torch.int16).numpy().view(np.uint16)
     t0 = time.perf_counter()
     enc = O.encode_batch(xb, ib, wl.n_clusters, wl.group_size, wl.n_stages, wl.kmeans_iters_warm)
     t_enc = time.perf_counter() - t0
+    cent = np.repeat(enc["cent"], n_chunks, axis=1)
+    ids = np.tile(enc["ids"].reshape(units, 1, n_enc), (1, n_chunks, 1))
+    codes = np.tile(enc["codes"], (1, n_chunks, 1, 1))
+    scales = np.tile(enc["scales"], (1, n_chunks, 1, 1))
     t0 = time.perf_counter()
-    reps_dec = 4
-    for _ in range(reps_dec):
-        dec = O.decode_batch(enc["cent"], enc["ids"], enc["codes"], enc["scales"], wl.group_size)
-    t_dec = (time.perf_counter() - t0) / reps_dec
-    heads_a = max(1, units // 2)
-    nq = 64
-    q = synth.queries(wl, heads_a, nq).view(torch.int16).numpy().view(np.uint16)
+    dec = O.decode_batch(cent, ids, codes, scales, wl.group_size)
+    t_dec = time.perf_counter() - t0
+    n_tok = dec.shape[1]
+    qall = synth.queries(wl, heads, wl.n_queries).view(torch.int16).numpy().view(np.uint16)
     t0 = time.perf_counter()
-    O.attention_batch(q, dec[:heads_a], dec[heads_a:2 * heads_a] if units >= 2 else dec[:heads_a])
+    O.attention_batch(np.ascontiguousarray(qall[:, :16]), dec[:heads], dec[heads:])
+    t_trial = time.perf_counter() - t0
+    nq = int(min(wl.n_queries, max(16, 16 * budget_s / max(t_trial, 1e-3))))
+    t0 = time.perf_counter()
+    O.attention_batch(np.ascontiguousarray(qall[:, :nq]), dec[:heads], dec[heads:])
     t_att = time.perf_counter() - t0
-    vec_enc, vec_dec = units * n_enc, units * n_enc
-    vec_att = 2 * heads_a * n_enc * (nq / max(wl.n_queries, 1))   # share of a full query batch
+    vec_enc, vec_dec = units * n_enc, units * n_tok
+    vec_att = units * n_tok * (nq / wl.n_queries)          # share of a full query batch
     total_vec = vec_enc + vec_dec + vec_att
     total_t = t_enc + t_dec + t_att
     return {
         "value": round(total_vec * 256 / total_t / 1e9, 6), "unit": "GB/s", "cores": cores,
         "kind": "oracle",
-        "sample": (f"{units} units x {n_enc} tokens: encode (I={wl.kmeans_iters_warm}) {t_enc:.2f}s, "
-                   f"decode {t_dec:.3f}s, attention {nq} queries x {heads_a} heads over {n_enc} tokens "
-                   f"{t_att:.2f}s (attention vectors scaled by {nq}/{wl.n_queries} of a query batch)"),
+        "sample": (f"{units} units: encode of one {n_enc}-token chunk (I={wl.kmeans_iters_warm}) {t_enc:.2f}s, "
+                   f"decode of {n_tok} tokens {t_dec:.2f}s, attention of {nq} of {wl.n_queries} queries x "
+                   f"{heads} heads over {n_tok} tokens {t_att:.2f}s (its vectors counted as {nq}/{wl.n_queries} "
+                   f"of a step's)"),
         "encode_GBps": round(vec_enc * 256 / t_enc / 1e9, 6),
         "decode_GBps": round(vec_dec * 256 / t_dec / 1e9, 6),
-        "attn_q_tokens_per_s": round(heads_a * nq / t_att, 3),
+        "attn_q_tokens_per_s": round(heads * nq / t_att, 3),
     }
 
 
@@ -230,11 +247,20 @@ def main():
     for _ in range(args.warmup):
         workload.step(s)
     torch.cuda.synchronize()
+    # HIP events around the dominant kernel's launch in every timed step, on the stream the library
+    # launches on (torch's current stream)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        workload.step(s)
+    for i in range(args.steps):
+        workload.step_encode(s)
+        workload.step_decode(s)
+        ev[i][0].record()
+        workload.step_attn(s)
+        ev[i][1].record()
     torch.cuda.synchronize()
     ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_att_in_step = sum(a.elapsed_time(b) for a, b in ev) / max(args.steps, 1)
 
     vec = workload.vectors_per_step(s)
     total_vec = vec["encode"] + vec["decode"] + vec["attn"]
@@ -265,11 +291,15 @@ def main():
         phases[f"encode_I{i}"] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(vec["encode"] * 256 / ms / 1e6, 1),
                                   "hbm_GBps_algorithmic": round(enc_alg / ms / 1e6, 1),
                                   "hbm_frac": round(enc_alg / ms / 1e6 / HBM_PEAK_GBPS, 4)}
-    # dominant kernel of the step by time: the fused attention kernel (one launch per step)
-    roofline = {"bound": "mfma", "kernel": "attn_kernel", "achieved": round(att_flops / ms_att / 1e9, 2),
+    # dominant kernel of the step by time: the fused attention kernel (one launch per step); its
+    # duration is the HIP-event average over the timed steps above
+    att_tflops = att_flops / ms_att_in_step / 1e9
+    roofline = {"bound": "mfma", "kernel": "attn_kernel_staged", "achieved": round(att_tflops, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(att_flops / ms_att / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None}
-
+                "frac": round(att_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                "ms_per_launch": round(ms_att_in_step, 4),
+                "flops_per_launch": att_flops,
+                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, "attn"))}
     result = {
         "metric": "KV encode/decode GB/s (bf16-equiv) + fused dequant-attn tokens/s, % HBM roofline",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
