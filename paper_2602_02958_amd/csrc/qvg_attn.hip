@@ -330,19 +330,28 @@ constexpr int kStScales = kAtKv * kStMaxT * kStMaxG * 2;  // bytes of one side's
 constexpr int kStBytes = 2 * kStCodes + 2 * kStScales + 2 * kAtKv;   // K and V: codes, scales, ids
 constexpr size_t kAtSmemStaged = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint16_t) + 2 * kStBytes;
 
+template <bool V> struct BoolC { static constexpr bool value = V; };
+
 template <int T_>
 __global__ __launch_bounds__(kAtThreads, 2)
-void attn_kernel_staged(AttnArgs a) {
+void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_xcd) {
     constexpr int T = T_;
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t *Kt = reinterpret_cast<uint16_t *>(smem);                  // [2][64][136] bf16
     uint16_t *Vt = Kt + 2 * kKtElems;                                   // [2][128][72] f16, transposed
     unsigned char *stage = reinterpret_cast<unsigned char *>(Vt + 2 * kVtElems);   // [2][kStBytes]
 
+    // Workgroups are dealt to the 8 XCDs round-robin by their linear id; re-number them so that
+    // the query blocks of one unit run on one XCD (two at a boundary) and the unit's compressed
+    // cache is fetched into that XCD's L2 only, not into all eight.
+    const int w = (int)(blockIdx.x % 8u) * blocks_per_xcd + (int)(blockIdx.x / 8u);
+    if (w >= n_blocks) return;                                          // uniform, before any barrier
+    const int h = w / n_qblocks;
+    const int qblock = w - h * n_qblocks;
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
-    const int h = blockIdx.y;
-    const int64_t qrow = (int64_t)blockIdx.x * kAtQPerBlock + wave * 32 + col;
+    const int64_t qrow = (int64_t)qblock * kAtQPerBlock + wave * 32 + col;
     const bool qvalid = qrow < a.n_q;
     const int B = a.B, K = a.K;
     const int G = kHeadDim / B;
@@ -380,52 +389,56 @@ void attn_kernel_staged(AttnArgs a) {
     // 16-byte pieces, both sides: codes (a token-stage record is 32 B, always 16-byte aligned;
     // piece p of a side belongs to token p / (2T)) and scales (T*G*2 bytes per token, contiguous
     // over the tile; the host picks this kernel only when chunks start 16-byte aligned).
+    // Every step below comes in two forms: FULL (the tile has all 64 tokens: no per-token
+    // predicates at all, the common case) and the general one.
     constexpr int kPieces = 2 * kAtKv * T * 2;                       // code pieces, both sides
     constexpr int kPiecesPerThread = (kPieces + kAtThreads - 1) / kAtThreads;
     const int scPiecesSide = kAtKv * T * G / 8;                      // scale pieces per side (<= 256)
     const int scBytesTok = T * G * 2;
     struct Fetch { uint4 code[kPiecesPerThread]; uint4 sc; uint32_t id; };
 
-    auto fetch_tile = [&](const Tile &t, Fetch &f) {
-        const int nvalid = t.valid ? (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv) : 0;
+    auto fetch_tile = [&](auto full, const Tile &t, Fetch &f) {
+        constexpr bool FULL = decltype(full)::value;
+        const int nvalid = FULL ? kAtKv : (t.valid ? (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv) : 0);
 #pragma unroll
         for (int i = 0; i < kPiecesPerThread; ++i) {
             const int p = tid + i * kAtThreads;
-            f.code[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (!FULL) f.code[i] = make_uint4(0u, 0u, 0u, 0u);
             if (p < kPieces) {
                 const bool vside = p >= kPieces / 2;
                 const int ps = p - (vside ? kPieces / 2 : 0);
-                if (ps / (2 * T) < nvalid)
+                if (FULL || ps / (2 * T) < nvalid)
                     f.code[i] = *reinterpret_cast<const uint4 *>((vside ? v_codes : k_codes) +
                                                                  ((int64_t)t.t0 * T * 32 + (int64_t)ps * 16));
             }
         }
-        f.sc = make_uint4(0u, 0u, 0u, 0u);
+        if (!FULL) f.sc = make_uint4(0u, 0u, 0u, 0u);
         if (tid < 2 * scPiecesSide) {
             const bool vside = tid >= scPiecesSide;
             const int ps = tid - (vside ? scPiecesSide : 0);
             // a piece is fetched when its first byte belongs to an existing token; the bytes of
             // later, missing tokens it may drag along are never used (their rows are masked)
             // and still lie inside this unit's scale array, except in the unit's very last
-            // piece, which is fetched only if it ends inside the array
+            // piece, which is fetched only if it ends inside the array.  All pieces of a full
+            // tile lie inside the tile's own 64 records.
             const int64_t first = (int64_t)t.t0 * scBytesTok + (int64_t)ps * 16;
-            if ((ps * 16) / scBytesTok < nvalid && first + 16 <= (int64_t)a.n_kv * scBytesTok)
+            if (FULL || ((ps * 16) / scBytesTok < nvalid && first + 16 <= (int64_t)a.n_kv * scBytesTok))
                 f.sc = *reinterpret_cast<const uint4 *>((vside ? v_scales : k_scales) + first);
             else if ((ps * 16) / scBytesTok < nvalid) {
                 // tail of the unit's array: 2 bytes at a time
-                uint32_t w[4] = {0u, 0u, 0u, 0u};
+                uint32_t w4[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
                 for (int b = 0; b < 8; ++b)
                     if (first + 2 * b + 2 <= (int64_t)a.n_kv * scBytesTok)
-                        w[b >> 1] |= (uint32_t)*reinterpret_cast<const uint16_t *>((vside ? v_scales : k_scales) + first + 2 * b)
-                                     << (16 * (b & 1));
-                f.sc = make_uint4(w[0], w[1], w[2], w[3]);
+                        w4[b >> 1] |= (uint32_t)*reinterpret_cast<const uint16_t *>((vside ? v_scales : k_scales) + first + 2 * b)
+                                      << (16 * (b & 1));
+                f.sc = make_uint4(w4[0], w4[1], w4[2], w4[3]);
             }
         }
-        f.id = 0u;
+        if (!FULL) f.id = 0u;
         if (tid < 2 * kAtKv) {
             const int n = tid & 63;
-            if (n < nvalid) f.id = min((uint32_t)((tid >> 6) ? v_ids : k_ids)[t.t0 + n], kmax);
+            if (FULL || n < nvalid) f.id = min((uint32_t)((tid >> 6) ? v_ids : k_ids)[t.t0 + n], kmax);
         }
     };
     auto park_tile = [&](const Fetch &f, int sb) {
@@ -446,7 +459,8 @@ void attn_kernel_staged(AttnArgs a) {
         }
         if (tid < 2 * kAtKv) st[2 * kStCodes + 2 * kStScales + tid] = (unsigned char)f.id;
     };
-    // centroid rows of this thread's two tokens, both sides, using the parked ids
+    // centroid rows of this thread's two tokens, both sides, using the parked ids (the id of a
+    // token that does not exist is parked as 0)
     auto gather_rows = [&](const Tile &t, int sb, uint4 cen[2][2]) {
         const unsigned char *st = stage + sb * kStBytes + 2 * kStCodes + 2 * kStScales;
 #pragma unroll
@@ -460,9 +474,10 @@ void attn_kernel_staged(AttnArgs a) {
     // decode the tile parked in staging buffer sb (rows gathered in cen) into tile buffer buf;
     // tokens that do not exist have zero codes and scales, and their rows are masked in the
     // soft-max, so whatever centroid row was gathered for them is harmless for K; V is zeroed
-    auto decode_to_lds = [&](const Tile &t, int sb, const uint4 cen[2][2], int buf) {
+    auto decode_to_lds = [&](auto full, const Tile &t, int sb, const uint4 cen[2][2], int buf) {
+        constexpr bool FULL = decltype(full)::value;
         const unsigned char *st = stage + sb * kStBytes;
-        const int nvalid = (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv);
+        const int nvalid = FULL ? kAtKv : (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv);
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             Raw<T> r;
@@ -475,7 +490,7 @@ void attn_kernel_staged(AttnArgs a) {
                     r.code[e][k] = cp[(e * T + k) * 16];
                     r.sc[e][k] = sp[(e * T + k) * G];
                 }
-                r.cen[e] = (tok + e < nvalid) ? cen[s][e] : make_uint4(0u, 0u, 0u, 0u);
+                r.cen[e] = (FULL || tok + e < nvalid) ? cen[s][e] : make_uint4(0u, 0u, 0u, 0u);
             }
             float accA[8], accB[8];
             dequant2x8<T, T>(r, T, accA, accB);
@@ -495,6 +510,7 @@ void attn_kernel_staged(AttnArgs a) {
             }
         }
     };
+    auto is_full = [&](const Tile &t) { return t.valid && t.cend - t.t0 >= kAtKv; };
 
     // ---- prologue: tile 0 decoded into buffer 0, tile 1 parked, tile 2 in registers ---------
     Tile cur = first_tile(a);
@@ -502,17 +518,20 @@ void attn_kernel_staged(AttnArgs a) {
     Tile nn = nxt.valid ? next_tile(a, nxt) : nxt;
     Fetch f;
     uint4 cen[2][2];
-    fetch_tile(cur, f);  park_tile(f, 0);
-    fetch_tile(nxt, f);  park_tile(f, 1);
+    fetch_tile(BoolC<false>{}, cur, f);  park_tile(f, 0);
+    fetch_tile(BoolC<false>{}, nxt, f);  park_tile(f, 1);
     __syncthreads();
     gather_rows(cur, 0, cen);
-    decode_to_lds(cur, 0, cen, 0);
+    decode_to_lds(BoolC<false>{}, cur, 0, cen, 0);
     if (nxt.valid) gather_rows(nxt, 1, cen);
     __syncthreads();                 // tile 0 ready; staging buffer 0 free again
 
     int buf = 0;                     // tile buffer of `cur`; the staging buffer of `nxt` is buf ^ 1
-    while (true) {
-        if (nn.valid) fetch_tile(nn, f);            // lands during this iteration
+    // One tile of the main loop: S, soft-max, PV on `cur`; decode of `nxt`; fetch of `nn`.
+    // FULL: cur, nxt and nn all hold 64 tokens.  Returns false after the last tile.
+    auto tile_step = [&](auto full) -> bool {
+        constexpr bool FULL = decltype(full)::value;
+        if (FULL || nn.valid) fetch_tile(full, nn, f);             // lands during this iteration
         const uint16_t *kt = Kt + buf * kKtElems;
         const uint16_t *vt = Vt + buf * kVtElems;
         floatx16_t S[2];
@@ -528,15 +547,17 @@ void attn_kernel_staged(AttnArgs a) {
                     av, __builtin_bit_cast(bf16x8_t, qa[kk]), S[nb], 0, 0, 0);
             }
         }
-        const int ntile = (int)((cur.cend - cur.t0 < kAtKv) ? cur.cend - cur.t0 : kAtKv);
-        if (ntile < kAtKv) {                                   // uniform: last tile of a chunk
+        if (!FULL) {
+            const int ntile = (int)((cur.cend - cur.t0 < kAtKv) ? cur.cend - cur.t0 : kAtKv);
+            if (ntile < kAtKv) {                                   // uniform: last tile of a chunk
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
+                for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kv = nb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-                    if (kv >= ntile) S[nb][r] = -INFINITY;
-                }
+                    for (int r = 0; r < 16; ++r) {
+                        const int kv = nb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                        if (kv >= ntile) S[nb][r] = -INFINITY;
+                    }
+            }
         }
         float tmax = -INFINITY;
 #pragma unroll
@@ -577,16 +598,22 @@ void attn_kernel_staged(AttnArgs a) {
                     av, __builtin_bit_cast(halfx8_t, pb[st]), O[mb], 0, 0, 0);
             }
         }
-        if (!nxt.valid) break;
+        if (!FULL && !nxt.valid) return false;
         // decode the next tile (parked in staging buf^1, rows already gathered) into tile buffer
         // buf^1, then park the tile after it in staging buf (free since the last barrier)
-        decode_to_lds(nxt, buf ^ 1, cen, buf ^ 1);
-        if (nn.valid) park_tile(f, buf);
+        decode_to_lds(full, nxt, buf ^ 1, cen, buf ^ 1);
+        if (FULL || nn.valid) park_tile(f, buf);
         __syncthreads();
-        if (nn.valid) gather_rows(nn, buf, cen);     // ids of nn are visible now; rows land next iteration
+        if (FULL || nn.valid) gather_rows(nn, buf, cen);   // ids of nn are visible now; rows land next iteration
         buf ^= 1;
         cur = nxt; nxt = nn;
         nn = nn.valid ? next_tile(a, nn) : nn;
+        return true;
+    };
+    while (true) {
+        while (is_full(cur) && is_full(nxt) && is_full(nn))      // uniform
+            tile_step(BoolC<true>{});
+        if (!tile_step(BoolC<false>{})) break;
     }
     const float ltot = l + __shfl_xor(l, 32, 64);
     if (qvalid) {
@@ -608,11 +635,19 @@ void attn_kernel_staged(AttnArgs a) {
 
 template <int T_>
 static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmemStaged);
-    if (e != hipSuccess) return e;
-    dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
-    hipLaunchKernelGGL((attn_kernel_staged<T_>), grid, dim3(kAtThreads), kAtSmemStaged, s, a);
+    static bool configured = false;          // the attribute is per function, set once per process
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmemStaged);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    const int64_t nqb = (a.n_q + kAtQPerBlock - 1) / kAtQPerBlock;
+    const int64_t nb = nqb * a.H;
+    if (nb > 0x7fffffff - 8) return hipErrorInvalidValue;
+    const int bpx = (int)((nb + 7) / 8);
+    hipLaunchKernelGGL((attn_kernel_staged<T_>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmemStaged, s, a,
+                       (int)nqb, (int)nb, bpx);
     return hipGetLastError();
 }
 
