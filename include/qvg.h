@@ -71,6 +71,7 @@ typedef struct qvg_params {
 #define QVG_ENTRY_DECODE 1
 #define QVG_ENTRY_ATTN   2
 #define QVG_ENTRY_KMEANS_UPDATE 3
+#define QVG_ENTRY_KMEANS_ASSIGN 4
 
 /*
  * Encode one chunk (Sec. 4.1 and 4.2): I Lloyd iterations from init_centroids
@@ -87,7 +88,7 @@ typedef struct qvg_params {
  *                  >= N).  The two strides let a chunk be written straight into a cache that
  *                  holds several chunks per unit: point the outputs at the chunk's first token
  *                  and table, and pass the cache's tokens and table elements per unit.
- *   workspace      qvg_workspace_bytes(p, QVG_ENTRY_ENCODE, N, 0) bytes (0 when I == 0)
+ *   workspace      qvg_workspace_bytes(p, QVG_ENTRY_ENCODE, N, 0) bytes (a few KB per unit when I == 0)
  * n_tokens in 0 .. 2^20.  n_tokens == 0 only copies the centroids.
  * Rounding rules that fix the stored integers: a group's scale is max|r| (b = 2
  * gives qmax = 1), saturated at 65504 and rounded to f16; q = round-half-even(r * (1/scale))
@@ -141,14 +142,16 @@ int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q_bf16,
 
 /*
  * The two k-means steps on their own (Sec. 4.1), as the encoder runs them.
- * assign: ids_out[h][n] = index of the nearest centroid of unit h.
+ * assign: ids_out[h][n] = index of the nearest centroid of unit h; workspace
+ *         qvg_workspace_bytes(p, QVG_ENTRY_KMEANS_ASSIGN, N, 0) bytes.
  * update: centroid = mean of its members (see qvg_encode_chunk for the rounding);
  *         counts_out [H][K] int32 may be NULL; workspace
  *         qvg_workspace_bytes(p, QVG_ENTRY_KMEANS_UPDATE, N, 0) bytes.
  */
 int qvg_kmeans_assign(const qvg_params *p, int64_t n_tokens,
                       const void *x_bf16, int64_t stride_head, int64_t stride_token,
-                      const void *centroids_bf16, uint8_t *ids_out, void *stream);
+                      const void *centroids_bf16, uint8_t *ids_out,
+                      void *workspace, size_t workspace_bytes, void *stream);
 int qvg_kmeans_update(const qvg_params *p, int64_t n_tokens,
                       const void *x_bf16, int64_t stride_head, int64_t stride_token,
                       const uint8_t *ids, const void *centroids_prev_bf16,

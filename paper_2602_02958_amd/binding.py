@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libqvg.so")
 _lib = None
 
-ENTRY_ENCODE, ENTRY_DECODE, ENTRY_ATTN, ENTRY_KMEANS_UPDATE = 0, 1, 2, 3
+ENTRY_ENCODE, ENTRY_DECODE, ENTRY_ATTN, ENTRY_KMEANS_UPDATE, ENTRY_KMEANS_ASSIGN = 0, 1, 2, 3, 4
 
 EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_attn_decode", "qvg_kmeans_assign",
            "qvg_kmeans_update", "qvg_workspace_bytes", "qvg_compressed_bytes",
@@ -56,7 +56,7 @@ def lib():
         L.qvg_attn_decode.argtypes = [pp, i64, vp, i64, i64, vp, u8p, u8p, vp, vp, u8p, u8p, vp,
                                       C.c_float, vp, vp, vp, C.c_size_t, vp]
         L.qvg_kmeans_assign.restype = C.c_int
-        L.qvg_kmeans_assign.argtypes = [pp, i64, vp, i64, i64, vp, u8p, vp]
+        L.qvg_kmeans_assign.argtypes = [pp, i64, vp, i64, i64, vp, u8p, vp, C.c_size_t, vp]
         L.qvg_kmeans_update.restype = C.c_int
         L.qvg_kmeans_update.argtypes = [pp, i64, vp, i64, i64, u8p, vp, vp, vp, vp, C.c_size_t, vp]
         L.qvg_workspace_bytes.restype = C.c_int
@@ -230,7 +230,10 @@ def kmeans_assign(x, centroids) -> torch.Tensor:
     centroids = centroids.contiguous()
     p = make_params(H, centroids.shape[-2], 64, 1, 0, head_dim=d)
     ids = torch.empty(H, N, dtype=torch.uint8, device=x.device)
-    st = lib().qvg_kmeans_assign(C.byref(p), N, _ptr(x), sh, st_, _ptr(centroids), _ptr(ids), _stream())
+    need = workspace_bytes(p, ENTRY_KMEANS_ASSIGN, N)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+    st = lib().qvg_kmeans_assign(C.byref(p), N, _ptr(x), sh, st_, _ptr(centroids), _ptr(ids), _ptr(ws), need,
+                                 _stream())
     if st != 0:
         raise QvgError(st, "qvg_kmeans_assign")
     return ids

@@ -31,15 +31,20 @@ int check_params(const qvg_params *p) {
     return QVG_OK;
 }
 
-struct EncodeWs { size_t cent[2]; size_t perm; size_t offs; size_t total; };
+struct EncodeWs { size_t assign; size_t cent[2]; size_t perm; size_t offs; size_t total; };
 
-EncodeWs encode_ws(const qvg_params *p, int64_t N, bool with_tables) {
+// with_assign: scratch of the assignment kernel; with_tables: two centroid tables for the Lloyd
+// loop; with_update: permutation and offsets of the update step
+EncodeWs encode_ws(const qvg_params *p, int64_t N, bool with_assign, bool with_tables, bool with_update = true) {
     EncodeWs w{};
     size_t o = 0;
+    if (with_assign) { w.assign = o; o += assign_workspace_bytes(p->n_heads, p->n_clusters); }
     const size_t table = round256((size_t)p->n_heads * p->n_clusters * kHeadDim * sizeof(bf16_t));
     if (with_tables) { w.cent[0] = o; o += table; w.cent[1] = o; o += table; }
-    w.perm = o; o += round256((size_t)p->n_heads * (size_t)(N > 0 ? N : 1) * sizeof(int32_t));
-    w.offs = o; o += round256((size_t)p->n_heads * (p->n_clusters + 1) * sizeof(int32_t));
+    if (with_update) {
+        w.perm = o; o += round256((size_t)p->n_heads * (size_t)(N > 0 ? N : 1) * sizeof(int32_t));
+        w.offs = o; o += round256((size_t)p->n_heads * (p->n_clusters + 1) * sizeof(int32_t));
+    }
     w.total = o;
     return w;
 }
@@ -78,10 +83,13 @@ int qvg_workspace_bytes(const qvg_params *p, int which_entry, int64_t n_tokens, 
     if (n_tokens < 0 || n_q < 0) return QVG_ERR_BAD_PARAM;
     switch (which_entry) {
         case QVG_ENTRY_ENCODE:
-            *out = (p->kmeans_iters == 0 || n_tokens == 0) ? 0 : encode_ws(p, n_tokens, true).total;
+            *out = n_tokens == 0 ? 0 : encode_ws(p, n_tokens, true, p->kmeans_iters > 0, p->kmeans_iters > 0).total;
             return QVG_OK;
         case QVG_ENTRY_KMEANS_UPDATE:
-            *out = encode_ws(p, n_tokens, false).total;
+            *out = encode_ws(p, n_tokens, false, false).total;
+            return QVG_OK;
+        case QVG_ENTRY_KMEANS_ASSIGN:
+            *out = n_tokens == 0 ? 0 : encode_ws(p, n_tokens, true, false, false).total;
             return QVG_OK;
         case QVG_ENTRY_DECODE:
         case QVG_ENTRY_ATTN:
@@ -102,7 +110,8 @@ int64_t qvg_compressed_bytes(const qvg_params *p, int64_t n_tokens) {
 }
 
 int qvg_kmeans_assign(const qvg_params *p, int64_t n_tokens, const void *x, int64_t stride_head,
-                      int64_t stride_token, const void *centroids, uint8_t *ids_out, void *stream) {
+                      int64_t stride_token, const void *centroids, uint8_t *ids_out, void *workspace,
+                      size_t workspace_bytes, void *stream) {
     int st = check_params(p);
     if (st != QVG_OK) return st;
     if (n_tokens < 0 || n_tokens > kMaxTokensPerChunk) return QVG_ERR_BAD_PARAM;
@@ -110,7 +119,11 @@ int qvg_kmeans_assign(const qvg_params *p, int64_t n_tokens, const void *x, int6
     if (!x || !centroids || !ids_out) return QVG_ERR_NULL;
     if ((st = check_view(x, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
     if (!aligned16(centroids)) return QVG_ERR_ALIGN;
+    const EncodeWs w = encode_ws(p, n_tokens, true, false, false);
+    if (!workspace || workspace_bytes < w.total) return QVG_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return QVG_ERR_ALIGN;
     AssignArgs a{};
+    assign_workspace_split(static_cast<unsigned char *>(workspace) + w.assign, p->n_heads, p->n_clusters, &a.nh3, &a.cmax);
     a.x = static_cast<const bf16_t *>(x); a.stride_head = stride_head; a.stride_token = stride_token;
     a.n_tokens = n_tokens; a.cent = static_cast<const bf16_t *>(centroids);
     a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size; a.T = p->n_stages;
@@ -129,7 +142,7 @@ int qvg_kmeans_update(const qvg_params *p, int64_t n_tokens, const void *x, int6
     if (n_tokens > 0 && (!x || !ids)) return QVG_ERR_NULL;
     if (n_tokens > 0 && (st = check_view(x, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
     if (!aligned16(cent_prev) || !aligned16(cent_out)) return QVG_ERR_ALIGN;
-    const EncodeWs w = encode_ws(p, n_tokens, false);
+    const EncodeWs w = encode_ws(p, n_tokens, false, false);
     if (!workspace || workspace_bytes < w.total) return QVG_ERR_WORKSPACE;
     if (!aligned16(workspace)) return QVG_ERR_ALIGN;
     unsigned char *ws = static_cast<unsigned char *>(workspace);
@@ -173,16 +186,19 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
     if (!aligned16(codes_out) || !aligned16(scales_out)) return QVG_ERR_ALIGN;
     const int I = p->kmeans_iters;
     const bf16_t *cur = static_cast<const bf16_t *>(init_centroids);
+    const EncodeWs w = encode_ws(p, n_tokens, true, I > 0, I > 0);
+    if (!workspace || workspace_bytes < w.total) return QVG_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return QVG_ERR_ALIGN;
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    uint2 *nh3; float *cmax;
+    assign_workspace_split(ws + w.assign, p->n_heads, p->n_clusters, &nh3, &cmax);
     if (I > 0) {
-        const EncodeWs w = encode_ws(p, n_tokens, true);
-        if (!workspace || workspace_bytes < w.total) return QVG_ERR_WORKSPACE;
-        if (!aligned16(workspace)) return QVG_ERR_ALIGN;
-        unsigned char *ws = static_cast<unsigned char *>(workspace);
         bf16_t *buf[2] = {reinterpret_cast<bf16_t *>(ws + w.cent[0]), reinterpret_cast<bf16_t *>(ws + w.cent[1])};
         AssignArgs a{};
         a.x = static_cast<const bf16_t *>(x); a.stride_head = stride_head; a.stride_token = stride_token;
         a.n_tokens = n_tokens; a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size;
         a.T = p->n_stages; a.ids = ids_out; a.out_stride = out_stride_head_tokens; a.fused = 0;
+        a.nh3 = nh3; a.cmax = cmax;
         UpdateArgs u{};
         u.x = a.x; u.stride_head = stride_head; u.stride_token = stride_token; u.n_tokens = n_tokens;
         u.ids = ids_out; u.ids_stride = out_stride_head_tokens; u.counts_out = nullptr;
@@ -200,7 +216,7 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
     f.x = static_cast<const bf16_t *>(x); f.stride_head = stride_head; f.stride_token = stride_token;
     f.n_tokens = n_tokens; f.cent = cur; f.H = p->n_heads; f.K = p->n_clusters; f.B = p->group_size;
     f.T = p->n_stages; f.ids = ids_out; f.codes = codes_out; f.scales = static_cast<f16_t *>(scales_out);
-    f.out_stride = out_stride_head_tokens; f.fused = 1;
+    f.out_stride = out_stride_head_tokens; f.fused = 1; f.nh3 = nh3; f.cmax = cmax;
     if (launch_assign(f, s) != hipSuccess) return QVG_ERR_LAUNCH;
     return copy_out(cur);
 }

@@ -3,19 +3,23 @@
 // (Sec. 3.2 Eq. 1-2, applied progressively as in Sec. 4.2) and bit packing.
 //
 // Assignment = argmin_j ||x - c_j||^2 = argmax_j ( x.c_j - ||c_j||^2 / 2 ).
-// The N x K matrix of dot products is a dense contraction and runs on the matrix
-// cores (v_mfma_f32_32x32x16_bf16; bf16 x bf16 products are exact in fp32), with the
-// centroid table of the unit staged once per workgroup in LDS.  The MFMA is issued
-// transposed (rows = centroids, columns = tokens) so that one lane owns one token and
-// the argmax over centroids is a per-lane running maximum followed by a single
-// exchange between the two lane halves.
+// The N x K matrix of scores is a dense contraction and runs on the matrix cores
+// (v_mfma_f32_32x32x16_bf16; bf16 x bf16 products are exact in fp32), with the centroid
+// table of the unit staged once per workgroup in LDS.  The MFMA is issued transposed
+// (rows = centroids, columns = tokens) so that one lane owns one token and the argmax over
+// centroids is a per-lane running maximum followed by a single exchange between the two
+// lane halves.  A wavefront works on 64 tokens at a time: every centroid operand read from
+// LDS feeds two MFMAs (two blocks of 32 tokens), which halves the LDS traffic per flop and
+// gives two independent accumulation chains.  The term -||c||^2/2 enters through one extra
+// MFMA step: a small kernel has split it, per centroid, into three bf16 pieces whose sum is
+// the fp32 value exactly, and the matching token operand holds three ones.
 //
 // Exactness.  The reference result is the argmin of fp64 distances.  The fp32 scores
 // carry a rounding error, so the kernel keeps the three largest scores per token
 // (cluster index carried in the 7 low mantissa bits) and certifies the winner only
 // when it leads by more than a bound on that error,
 //     thr = 2^-14 * (||x||^2 / 2 + max_j ||c_j||^2),
-// which covers 128 accumulation roundings of one ulp each plus the index tag for both
+// which covers the 131 accumulation roundings of one ulp each plus the index tag for both
 // scores.  Otherwise the candidates are re-evaluated in fp64: the two leaders
 // cooperatively by the wavefront, or, if the third score is inside the band as well,
 // all K centroids with the channels summed in index order (the reference order).
@@ -26,10 +30,10 @@ namespace qvg {
 
 constexpr int kAsgThreads = 256;
 constexpr int kAsgWaves = kAsgThreads / 64;
-constexpr int kAsgTile = 32;                    // tokens per wavefront tile
-constexpr int kAsgTokPerBlock = 256;
-constexpr int kCPitch = 136;                    // bf16 elements per LDS centroid row (272 B)
+constexpr int kAsgTile = 64;                    // tokens per wavefront step (two MFMA column blocks)
+constexpr int kCPitch = 136;                    // bf16 elements per LDS centroid row (272 B): 128 + (hi, mid, lo of -||c||^2/2) + 5 zeros
 constexpr uint32_t kTagMask = 0xFFFFFF80u;
+constexpr int kPrepThreads = 256;
 
 __device__ __forceinline__ void insert3(float v, int idx, float &b1, float &b2, float &b3,
                                         int &i1, int &i2) {
@@ -39,52 +43,25 @@ __device__ __forceinline__ void insert3(float v, int idx, float &b1, float &b2, 
 }
 
 __device__ __forceinline__ double shfl_xor_f64(double v, int m) { return __shfl_xor(v, m, 64); }
+template <bool V> struct BoolK { static constexpr bool value = V; };
 
-// One round of 2-bit quantization of n_ consecutive residuals held by a lane
-// (Eq. 2 with b = 2: scale = max|r|, levels -1, 0, 1).  m is the group maximum.
-// Returns the f16 bits of the scale; codes are added into word[] (16 codes per word).
-template <int N_>
-__device__ __forceinline__ uint32_t quant_group(float *r, float m, uint32_t *word, int first) {
-    const float s32 = fminf(m, 65504.0f);
-    const uint32_t sh = f32_to_f16_bits(s32);
-    const float sf = f16_bits_to_f32(sh);
-    const float inv = (sf == 0.0f) ? 0.0f : 1.0f / sf;
-#pragma unroll
-    for (int i = 0; i < N_; ++i) {
-        const float u = r[i] * inv;
-        float q = __builtin_rintf(u);
-        q = __builtin_amdgcn_fmed3f(q, -1.0f, 1.0f);
-        r[i] = __builtin_fmaf(-sf, q, r[i]);
-        const int e = first + i;
-        word[e >> 4] += ((uint32_t)(int)q) << (2 * (e & 15));
-    }
-    return sh;
-}
-
-template <int B_, bool FUSED>
-__global__ __launch_bounds__(kAsgThreads, 2)
-void assign_kernel(AssignArgs a, int Kpad) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t *lc = reinterpret_cast<bf16_t *>(smem);                       // [Kpad][kCPitch]
-    float *lcnh = reinterpret_cast<float *>(smem + (size_t)Kpad * kCPitch * 2);   // -||c||^2/2
-    uint32_t *lcmax = reinterpret_cast<uint32_t *>(lcnh + Kpad);         // bits of max ||c||^2
-    bf16_t *lscr = reinterpret_cast<bf16_t *>(lcmax + 4);                // [waves][128]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int half = lane >> 5, col = lane & 31;
-    const int h = blockIdx.y;
-    const int K = a.K;
-    const int64_t N = a.n_tokens;
-
-    // ---- stage the centroid table and its norms -------------------------
-    if (tid == 0) lcmax[0] = 0u;
+// ---------------------------------------------------------------------------------------------
+// Per centroid: nh = fp32(-||c||^2 / 2) from an fp64 sum, split into three bf16 pieces by
+// truncation (8 significant bits each, so hi + mid + lo == nh exactly); rows K..Kpad-1 get a
+// huge negative value so that they never win.  Per unit: an upper bound of max ||c||^2.
+// One workgroup per unit, 16 lanes per row.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kPrepThreads)
+void centroid_prep_kernel(const bf16_t *cent, int K, int Kpad, uint2 *nh3, float *cmax_out) {
+    __shared__ uint32_t smax;
+    const int h = blockIdx.x, tid = threadIdx.x;
+    if (tid == 0) smax = 0u;
     __syncthreads();
-    const bf16_t *cg = a.cent + (int64_t)h * K * kHeadDim;
-    for (int i = tid; i < Kpad * 16; i += kAsgThreads) {
+    const bf16_t *cg = cent + (int64_t)h * K * kHeadDim;
+    for (int i = tid; i < Kpad * 16; i += kPrepThreads) {          // Kpad*16 is a multiple of 64: whole waves
         const int row = i >> 4, c16 = i & 15;
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (row < K) v = *reinterpret_cast<const uint4 *>(cg + (int64_t)row * kHeadDim + c16 * 8);
-        *reinterpret_cast<uint4 *>(lc + row * kCPitch + c16 * 8) = v;
         double s = 0.0;
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -95,158 +72,274 @@ void assign_kernel(AssignArgs a, int Kpad) {
         s += shfl_xor_f64(s, 1); s += shfl_xor_f64(s, 2);
         s += shfl_xor_f64(s, 4); s += shfl_xor_f64(s, 8);
         if (c16 == 0) {
+            float nh = -3.0e38f;
             if (row < K) {
-                lcnh[row] = (float)(-0.5 * s);
+                nh = (float)(-0.5 * s);
                 // upper bound of ||c||^2 in fp32 (one ulp up), kept as its bit pattern
                 const float up = (float)s * (1.0f + 0x1p-22f);
-                atomicMax(lcmax, __float_as_uint(up));
-            } else {
-                lcnh[row] = -3.0e38f;
+                atomicMax(&smax, __float_as_uint(up));
             }
+            const float hi = __uint_as_float(__float_as_uint(nh) & 0xffff0000u);
+            const float r1 = nh - hi;
+            const float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
+            const float lo = __uint_as_float(__float_as_uint(r1 - mid) & 0xffff0000u);
+            nh3[(int64_t)h * Kpad + row] =
+                make_uint2((__float_as_uint(hi) >> 16) | (__float_as_uint(mid) & 0xffff0000u), __float_as_uint(lo) >> 16);
         }
     }
     __syncthreads();
-    const float cmax = __uint_as_float(lcmax[0]);
+    if (tid == 0) cmax_out[h] = __uint_as_float(smax);
+}
+
+// T rounds of Eq. 2 (b = 2: scale = max|r|, levels -1, 0, 1) on the 64 residuals r[] a lane
+// holds of one token (channels 64*half ..), packed and stored as they are made.
+// GL groups of NL elements lie inside the lane (B_ = 128: one group shared with the other half).
+template <int B_>
+__device__ __forceinline__ void quantize_token(float *r, int T, bool valid, int half, uint8_t *codes_tok,
+                                               f16_t *scales_tok) {
+    constexpr int G = kHeadDim / B_;                 // groups per token
+    constexpr int GL = (B_ >= 64) ? 1 : 64 / B_;     // groups held by this lane
+    constexpr int NL = (B_ >= 64) ? 64 : B_;         // elements per group in this lane
+    for (int t = 0; t < T; ++t) {
+        uint32_t word[4];
+        uint32_t sh[GL];
+#pragma unroll
+        for (int g = 0; g < GL; ++g) {
+            float *rg = r + g * NL;
+            float m = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NL; i += 2) m = fmaxf(fmaxf(m, fabsf(rg[i])), fabsf(rg[i + 1]));
+            if (B_ == 128) m = fmaxf(m, __shfl_xor(m, 32, 64));
+            const float s32 = fminf(m, 65504.0f);
+            sh[g] = f32_to_f16_bits(s32);
+            const float sf = f16_bits_to_f32(sh[g]);
+            const float inv = (sf == 0.0f) ? 0.0f : 1.0f / sf;
+            // 8 levels -> one 16-bit field group: sum (q_i + 1) 4^i, exact in fp32.
+            // |r / sf| <= 1 + 2^-11 unless the scale saturated, so the rounded level is already
+            // in [-1, 1]; only a saturated group needs the clamp of Eq. 2.
+            auto rounds = [&](auto clamp) {
+#pragma unroll
+                for (int o = 0; o < NL; o += 8) {
+                    float cf = 21845.0f;             // 0x5555: the +1 of every field
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        float q = __builtin_rintf(rg[o + i] * inv);
+                        if (decltype(clamp)::value) q = __builtin_amdgcn_fmed3f(q, -1.0f, 1.0f);
+                        rg[o + i] = __builtin_fmaf(-sf, q, rg[o + i]);
+                        cf = __builtin_fmaf(q, (float)(1 << (2 * i)), cf);
+                    }
+                    const int e = g * NL + o;        // first channel (within the lane) of this field group
+                    const uint32_t c16 = (uint32_t)cf;
+                    if ((e >> 3) & 1) word[e >> 4] |= c16 << 16; else word[e >> 4] = c16;
+                }
+            };
+            if (m > 65504.0f) rounds(BoolK<true>{}); else rounds(BoolK<false>{});
+        }
+        if (valid) {
+            // word[] holds q + 1 per 2-bit field; the stored form is two's complement:
+            // field 00 -> 11, 01 -> 00, 10 -> 01
+#pragma unroll
+            for (int wi = 0; wi < 4; ++wi) {
+                const uint32_t lo = ~word[wi] & 0x55555555u;
+                word[wi] = lo | (((~word[wi] >> 1) & lo) << 1);
+            }
+            *reinterpret_cast<uint4 *>(codes_tok + t * 32 + half * 16) = make_uint4(word[0], word[1], word[2], word[3]);
+            f16_t *sp = scales_tok + t * G;
+            if (B_ == 128) { if (half == 0) sp[0] = (f16_t)sh[0]; }
+            else if (B_ == 64) sp[half] = (f16_t)sh[0];
+            else if (B_ == 32)
+                *reinterpret_cast<uint32_t *>(sp + half * 2) = sh[0] | (sh[GL - 1] << 16);
+            else
+                *reinterpret_cast<uint2 *>(sp + half * 4) =
+                    make_uint2(sh[0] | (sh[1 % GL] << 16), sh[2 % GL] | (sh[3 % GL] << 16));
+        }
+    }
+}
+
+// grid: x = unit, y = block of 256 * tiles_per_wave tokens.  With the unit as the fastest grid
+// index and H a multiple of 8, all blocks of a unit run on one XCD and share its table in L2.
+template <int B_, bool FUSED>
+__global__ __launch_bounds__(kAsgThreads, 2)
+void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t *lc = reinterpret_cast<bf16_t *>(smem);                       // [Kpad][kCPitch]
+    bf16_t *lscr = lc + (size_t)Kpad * kCPitch;                          // [waves][128]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const int h = blockIdx.x;
+    const int K = a.K;
+    const int64_t N = a.n_tokens;
+
+    // ---- stage the centroid table (rows K.. are zero) and the split -||c||^2/2 ----
+    const bf16_t *cg = a.cent + (int64_t)h * K * kHeadDim;
+    for (int i = tid; i < Kpad * 16; i += kAsgThreads) {
+        const int row = i >> 4, c16 = i & 15;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (row < K) v = *reinterpret_cast<const uint4 *>(cg + (int64_t)row * kHeadDim + c16 * 8);
+        *reinterpret_cast<uint4 *>(lc + row * kCPitch + c16 * 8) = v;
+    }
+    for (int row = tid; row < Kpad; row += kAsgThreads) {
+        const uint2 p = a.nh3[(int64_t)h * Kpad + row];
+        *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) = make_uint4(p.x, p.y, 0u, 0u);
+    }
+    const float cmax = a.cmax[h];
+    __syncthreads();
     bf16_t *scr = lscr + wave * kHeadDim;
+    // token operand of the extra MFMA step: three ones against (hi, mid, lo), lanes 0..31 only
+    const uint4 ones = half ? make_uint4(0u, 0u, 0u, 0u) : make_uint4(0x3F803F80u, 0x00003F80u, 0u, 0u);
 
-    const int64_t blk0 = (int64_t)blockIdx.x * kAsgTokPerBlock;
-    for (int tile = wave; tile < kAsgTokPerBlock / kAsgTile; tile += kAsgWaves) {
-        const int64_t n0 = blk0 + (int64_t)tile * kAsgTile;
+    const int64_t blk0 = (int64_t)blockIdx.y * tiles_per_wave * (kAsgWaves * kAsgTile);
+    for (int k = 0; k < tiles_per_wave; ++k) {
+        const int64_t n0 = blk0 + (int64_t)(k * kAsgWaves + wave) * kAsgTile;
         if (n0 >= N) break;                                  // uniform per wavefront
-        const int64_t n = n0 + col;
-        const bool valid = n < N;
-
-        // ---- this lane's 64 channels of its token (the MFMA B operand) ----
-        uint4 xa[8];
-        {
-            const bf16_t *xp = a.x + (int64_t)h * a.stride_head + n * a.stride_token + half * 64;
+        int64_t n[2];
+        bool valid[2];
+        // ---- this lane's 64 channels of its two tokens (the MFMA B operands) ----
+        uint4 xa[2][8];
+        float xn[2];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            n[tb] = n0 + tb * 32 + col;
+            valid[tb] = n[tb] < N;
+            const bf16_t *xp = a.x + (int64_t)h * a.stride_head + n[tb] * a.stride_token + half * 64;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk)
-                xa[kk] = valid ? *reinterpret_cast<const uint4 *>(xp + kk * 8) : make_uint4(0u, 0u, 0u, 0u);
+                xa[tb][kk] = valid[tb] ? *reinterpret_cast<const uint4 *>(xp + kk * 8) : make_uint4(0u, 0u, 0u, 0u);
         }
-        float xn = 0.0f;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const uint32_t w[4] = {xa[kk].x, xa[kk].y, xa[kk].z, xa[kk].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bf16x2_t p = __builtin_bit_cast(bf16x2_t, w[e]);
-                xn = __builtin_amdgcn_fdot2_f32_bf16(p, p, xn, false);
-            }
-        }
-        xn += __shfl_xor(xn, 32, 64);
-
-        // ---- scores on the matrix cores, running top three per lane -------
-        float b1 = -INFINITY, b2 = -INFINITY, b3 = -INFINITY;
-        for (int jb = 0; jb < (Kpad >> 5); ++jb) {
-            floatx16_t acc;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const float4 v = *reinterpret_cast<const float4 *>(lcnh + jb * 32 + g * 8 + half * 4);
-                acc[4 * g + 0] = v.x; acc[4 * g + 1] = v.y; acc[4 * g + 2] = v.z; acc[4 * g + 3] = v.w;
-            }
-            const bf16_t *arow = lc + (jb * 32 + col) * kCPitch + half * 64;
+        for (int tb = 0; tb < 2; ++tb) {
+            float s = 0.0f;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kk * 8);
-                const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, xa[kk]);
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+                const uint32_t w[4] = {xa[tb][kk].x, xa[tb][kk].y, xa[tb][kk].z, xa[tb][kk].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bf16x2_t p = __builtin_bit_cast(bf16x2_t, w[e]);
+                    s = __builtin_amdgcn_fdot2_f32_bf16(p, p, s, false);
+                }
+            }
+            xn[tb] = s + __shfl_xor(s, 32, 64);
+        }
+
+        // ---- scores on the matrix cores, running top three per lane and token ----
+        float b1[2] = {-INFINITY, -INFINITY}, b2[2] = {-INFINITY, -INFINITY}, b3[2] = {-INFINITY, -INFINITY};
+        for (int jb = 0; jb < (Kpad >> 5); ++jb) {
+            floatx16_t acc[2];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc[0][r] = 0.0f; acc[1][r] = 0.0f; }
+            const bf16_t *arow = lc + (jb * 32 + col) * kCPitch;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + half * 64 + kk * 8);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, xa[0][kk]), acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, xa[1][kk]), acc[1], 0, 0, 0);
+            }
+            {
+                const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kHeadDim);
+                const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, ones);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[1], 0, 0, 0);
             }
             const uint32_t tag0 = (uint32_t)jb << 4;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float v = __uint_as_float((__float_as_uint(acc[r]) & kTagMask) | (tag0 + r));
-                b3 = __builtin_amdgcn_fmed3f(b2, b3, v);
-                b2 = __builtin_amdgcn_fmed3f(b1, b2, v);
-                b1 = fmaxf(b1, v);
-            }
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float v = __uint_as_float((__float_as_uint(acc[tb][r]) & kTagMask) | (tag0 + r));
+                    b3[tb] = __builtin_amdgcn_fmed3f(b2[tb], b3[tb], v);
+                    b2[tb] = __builtin_amdgcn_fmed3f(b1[tb], b2[tb], v);
+                    b1[tb] = fmaxf(b1[tb], v);
+                }
         }
         // tag -> centroid index: row 8*(r/4) + 4*half + r%4 of block jb
         auto tag_to_idx = [&](float v) {
             const uint32_t t = __float_as_uint(v) & 0x7Fu;
             return (int)((t >> 4) * 32 + ((t >> 2) & 3) * 8 + half * 4 + (t & 3));
         };
-        int i1 = tag_to_idx(b1), i2 = tag_to_idx(b2);
-        {   // merge with the other half of the wavefront (same token, other centroids)
-            const float p1 = __shfl_xor(b1, 32, 64), p2 = __shfl_xor(b2, 32, 64),
-                        p3 = __shfl_xor(b3, 32, 64);
-            const int q1 = __shfl_xor(i1, 32, 64), q2 = __shfl_xor(i2, 32, 64);
-            insert3(p1, q1, b1, b2, b3, i1, i2);
-            insert3(p2, q2, b1, b2, b3, i1, i2);
-            insert3(p3, 0, b1, b2, b3, i1, i2);
-        }
-        const float thr = 0x1p-14f * (0.5f * xn + cmax);
-        int id = i1;
-        const bool amb = valid && (i2 < K) && !(b1 - b2 > thr);
-        const bool full = !(b1 - b3 > thr);
-
-        // ---- fp64 re-evaluation of tokens the fp32 scores cannot decide ----
-        uint64_t mask = __ballot(amb) & 0xffffffffull;
-        while (mask) {
-            const int tk = __builtin_ctzll(mask);
-            mask &= mask - 1;
-            if (col == tk) {
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk)
-                    *reinterpret_cast<uint4 *>(scr + half * 64 + kk * 8) = xa[kk];
+        for (int tb = 0; tb < 2; ++tb) {
+            if (n0 + tb * 32 >= N) break;                        // uniform: second block past the end
+            float c1 = b1[tb], c2 = b2[tb], c3 = b3[tb];
+            int i1 = tag_to_idx(c1), i2 = tag_to_idx(c2);
+            {   // merge with the other half of the wavefront (same token, other centroids)
+                const float p1 = __shfl_xor(c1, 32, 64), p2 = __shfl_xor(c2, 32, 64),
+                            p3 = __shfl_xor(c3, 32, 64);
+                const int q1 = __shfl_xor(i1, 32, 64), q2 = __shfl_xor(i2, 32, 64);
+                insert3(p1, q1, c1, c2, c3, i1, i2);
+                insert3(p2, q2, c1, c2, c3, i1, i2);
+                insert3(p3, 0, c1, c2, c3, i1, i2);
             }
-            __builtin_amdgcn_wave_barrier();
-            const int c1 = __shfl(i1, tk, 64), c2 = __shfl(i2, tk, 64);
-            const int fl = __shfl((int)full, tk, 64);
-            int winner;
-            if (!fl) {
-                const int cand = half ? c2 : c1;
-                const uint2 xv = *reinterpret_cast<const uint2 *>(scr + col * 4);
-                const uint2 cv = *reinterpret_cast<const uint2 *>(lc + cand * kCPitch + col * 4);
-                const double d0 = (double)bf16_lo(xv.x) - (double)bf16_lo(cv.x);
-                const double d1 = (double)bf16_hi(xv.x) - (double)bf16_hi(cv.x);
-                const double d2 = (double)bf16_lo(xv.y) - (double)bf16_lo(cv.y);
-                const double d3 = (double)bf16_hi(xv.y) - (double)bf16_hi(cv.y);
-                double d = d0 * d0; d += d1 * d1; d += d2 * d2; d += d3 * d3;
-                d += shfl_xor_f64(d, 16); d += shfl_xor_f64(d, 8); d += shfl_xor_f64(d, 4);
-                d += shfl_xor_f64(d, 2); d += shfl_xor_f64(d, 1);
-                const double D1 = __shfl(d, 0, 64), D2 = __shfl(d, 32, 64);
-                winner = (D2 < D1 || (D2 == D1 && c2 < c1)) ? c2 : c1;
-            } else {
-                double bd = INFINITY; int bj = 0x7fffffff;
-                for (int j = lane; j < K; j += 64) {
-                    const bf16_t *cr = lc + j * kCPitch;
-                    double acc = 0.0;
-                    for (int c = 0; c < kHeadDim; c += 2) {
-                        const uint32_t xw = *reinterpret_cast<const uint32_t *>(scr + c);
-                        const uint32_t cw = *reinterpret_cast<const uint32_t *>(cr + c);
-                        const double e0 = (double)bf16_lo(xw) - (double)bf16_lo(cw);
-                        acc += e0 * e0;
-                        const double e1 = (double)bf16_hi(xw) - (double)bf16_hi(cw);
-                        acc += e1 * e1;
+            const float thr = 0x1p-14f * (0.5f * xn[tb] + cmax);
+            int id = i1;
+            const bool amb = valid[tb] && (i2 < K) && !(c1 - c2 > thr);
+            const bool full = !(c1 - c3 > thr);
+
+            // ---- fp64 re-evaluation of tokens the fp32 scores cannot decide ----
+            uint64_t mask = __ballot(amb) & 0xffffffffull;
+            while (mask) {
+                const int tk = __builtin_ctzll(mask);
+                mask &= mask - 1;
+                if (col == tk) {
+#pragma unroll
+                    for (int kk = 0; kk < 8; ++kk)
+                        *reinterpret_cast<uint4 *>(scr + half * 64 + kk * 8) = xa[tb][kk];
+                }
+                __builtin_amdgcn_wave_barrier();
+                const int d1 = __shfl(i1, tk, 64), d2 = __shfl(i2, tk, 64);
+                const int fl = __shfl((int)full, tk, 64);
+                int winner;
+                if (!fl) {
+                    const int cand = half ? d2 : d1;
+                    const uint2 xv = *reinterpret_cast<const uint2 *>(scr + col * 4);
+                    const uint2 cv = *reinterpret_cast<const uint2 *>(lc + cand * kCPitch + col * 4);
+                    const double e0 = (double)bf16_lo(xv.x) - (double)bf16_lo(cv.x);
+                    const double e1 = (double)bf16_hi(xv.x) - (double)bf16_hi(cv.x);
+                    const double e2 = (double)bf16_lo(xv.y) - (double)bf16_lo(cv.y);
+                    const double e3 = (double)bf16_hi(xv.y) - (double)bf16_hi(cv.y);
+                    double d = e0 * e0; d += e1 * e1; d += e2 * e2; d += e3 * e3;
+                    d += shfl_xor_f64(d, 16); d += shfl_xor_f64(d, 8); d += shfl_xor_f64(d, 4);
+                    d += shfl_xor_f64(d, 2); d += shfl_xor_f64(d, 1);
+                    const double D1 = __shfl(d, 0, 64), D2 = __shfl(d, 32, 64);
+                    winner = (D2 < D1 || (D2 == D1 && d2 < d1)) ? d2 : d1;
+                } else {
+                    double bd = INFINITY; int bj = 0x7fffffff;
+                    for (int j = lane; j < K; j += 64) {
+                        const bf16_t *cr = lc + j * kCPitch;
+                        double acc = 0.0;
+                        for (int c = 0; c < kHeadDim; c += 2) {
+                            const uint32_t xw = *reinterpret_cast<const uint32_t *>(scr + c);
+                            const uint32_t cw = *reinterpret_cast<const uint32_t *>(cr + c);
+                            const double f0 = (double)bf16_lo(xw) - (double)bf16_lo(cw);
+                            acc += f0 * f0;
+                            const double f1 = (double)bf16_hi(xw) - (double)bf16_hi(cw);
+                            acc += f1 * f1;
+                        }
+                        if (acc < bd) { bd = acc; bj = j; }
                     }
-                    if (acc < bd) { bd = acc; bj = j; }
-                }
 #pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    const double od = shfl_xor_f64(bd, off);
-                    const int oj = __shfl_xor(bj, off, 64);
-                    if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+                    for (int off = 32; off >= 1; off >>= 1) {
+                        const double od = shfl_xor_f64(bd, off);
+                        const int oj = __shfl_xor(bj, off, 64);
+                        if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+                    }
+                    winner = bj;
                 }
-                winner = bj;
+                if (col == tk) id = winner;
+                __builtin_amdgcn_wave_barrier();
             }
-            if (col == tk) id = winner;
-            __builtin_amdgcn_wave_barrier();
-        }
 
-        if (!FUSED) {
-            if (valid && half == 0) a.ids[(int64_t)h * a.out_stride + n] = (uint8_t)id;
-            continue;
-        }
+            const int64_t hn = (int64_t)h * a.out_stride + n[tb];
+            if (valid[tb] && half == 0) a.ids[hn] = (uint8_t)id;
+            if (!FUSED) continue;
 
-        // ---- Eq. 5: residual against the assigned centroid -----------------
-        float r[64];
-        {
+            // ---- Eq. 5: residual against the assigned centroid, then the T rounds ----
+            float r[64];
             const bf16_t *crow = lc + id * kCPitch + half * 64;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
                 const uint4 cv = *reinterpret_cast<const uint4 *>(crow + kk * 8);
-                const uint32_t xw[4] = {xa[kk].x, xa[kk].y, xa[kk].z, xa[kk].w};
+                const uint32_t xw[4] = {xa[tb][kk].x, xa[tb][kk].y, xa[tb][kk].z, xa[tb][kk].w};
                 const uint32_t cw[4] = {cv.x, cv.y, cv.z, cv.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -254,49 +347,14 @@ void assign_kernel(AssignArgs a, int Kpad) {
                     r[kk * 8 + 2 * e + 1] = bf16_hi(xw[e]) - bf16_hi(cw[e]);
                 }
             }
-        }
-        // ---- T rounds of 2-bit group quantization, packed as they are made --
-        constexpr int G = kHeadDim / B_;                 // groups per token
-        constexpr int GL = (B_ >= 64) ? 1 : 64 / B_;     // groups held by this lane
-        constexpr int NL = (B_ >= 64) ? 64 : B_;         // elements per group in this lane
-        const int64_t hn = (int64_t)h * a.out_stride + n;
-        if (valid && half == 0) a.ids[hn] = (uint8_t)id;
-        for (int t = 0; t < a.T; ++t) {
-            uint32_t word[4] = {0x55555555u, 0x55555555u, 0x55555555u, 0x55555555u};
-            uint32_t sh[GL];
-#pragma unroll
-            for (int g = 0; g < GL; ++g) {
-                float m = 0.0f;
-#pragma unroll
-                for (int i = 0; i < NL; ++i) m = fmaxf(m, fabsf(r[g * NL + i]));
-                if (B_ == 128) m = fmaxf(m, __shfl_xor(m, 32, 64));
-                sh[g] = quant_group<NL>(r + g * NL, m, word, g * NL);
-            }
-            if (valid) {
-                uint8_t *cp = a.codes + (hn * a.T + t) * 32 + half * 16;
-                // word[] holds q + 1 per 2-bit field (built with one shift-add per element);
-                // the stored form is two's complement: field 00 -> 11, 01 -> 00, 10 -> 01
-#pragma unroll
-                for (int wi = 0; wi < 4; ++wi) {
-                    const uint32_t lo = ~word[wi] & 0x55555555u;
-                    word[wi] = lo | (((~word[wi] >> 1) & lo) << 1);
-                }
-                *reinterpret_cast<uint4 *>(cp) = make_uint4(word[0], word[1], word[2], word[3]);
-                f16_t *sp = a.scales + (hn * a.T + t) * G;
-                if (B_ == 128) { if (half == 0) sp[0] = (f16_t)sh[0]; }
-                else if (B_ == 64) sp[half] = (f16_t)sh[0];
-                else if (B_ == 32)
-                    *reinterpret_cast<uint32_t *>(sp + half * 2) = sh[0] | (sh[1] << 16);
-                else
-                    *reinterpret_cast<uint2 *>(sp + half * 4) =
-                        make_uint2(sh[0] | (sh[1] << 16), sh[2] | (sh[3] << 16));
-            }
+            quantize_token<B_>(r, a.T, valid[tb], half, a.codes + hn * a.T * 32,
+                               a.scales + hn * a.T * (kHeadDim / B_));
         }
     }
 }
 
 static size_t assign_smem_bytes(int Kpad) {
-    return (size_t)Kpad * kCPitch * 2 + (size_t)Kpad * 4 + 16 + (size_t)kAsgWaves * kHeadDim * 2;
+    return (size_t)Kpad * kCPitch * 2 + (size_t)kAsgWaves * kHeadDim * 2;
 }
 
 template <int B_, bool FUSED>
@@ -306,8 +364,19 @@ static hipError_t launch_assign_t(const AssignArgs &a, hipStream_t s) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    dim3 grid((unsigned)((a.n_tokens + kAsgTokPerBlock - 1) / kAsgTokPerBlock), (unsigned)a.H);
-    hipLaunchKernelGGL((assign_kernel<B_, FUSED>), grid, dim3(kAsgThreads), smem, s, a, Kpad);
+    // tokens per workgroup: 256 per step; more steps per workgroup amortise the table staging
+    // once there are enough workgroups to fill the chip several times over
+    const int64_t steps = (a.n_tokens + kAsgWaves * kAsgTile - 1) / (kAsgWaves * kAsgTile);
+    int tpw = 1;
+    while (tpw < 4 && (steps / (2 * tpw)) * a.H >= 2048) tpw *= 2;
+    const int64_t gy = (steps + tpw - 1) / tpw;
+    if (gy > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(centroid_prep_kernel, dim3((unsigned)a.H), dim3(kPrepThreads), 0, s, a.cent, a.K, Kpad,
+                       a.nh3, a.cmax);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((assign_kernel<B_, FUSED>), dim3((unsigned)a.H, (unsigned)gy), dim3(kAsgThreads), smem, s, a,
+                       Kpad, tpw);
     return hipGetLastError();
 }
 
@@ -320,6 +389,16 @@ hipError_t launch_assign(const AssignArgs &a, hipStream_t s) {
         case 64: return launch_assign_t<64, true>(a, s);
         default: return launch_assign_t<128, true>(a, s);
     }
+}
+
+size_t assign_workspace_bytes(int H, int K) {
+    const size_t Kpad = (size_t)((K + 31) & ~31);
+    return ((size_t)H * Kpad * sizeof(uint2) + 255) / 256 * 256 + ((size_t)H * sizeof(float) + 255) / 256 * 256;
+}
+void assign_workspace_split(void *ws, int H, int K, uint2 **nh3, float **cmax) {
+    const size_t Kpad = (size_t)((K + 31) & ~31);
+    *nh3 = static_cast<uint2 *>(ws);
+    *cmax = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + ((size_t)H * Kpad * sizeof(uint2) + 255) / 256 * 256);
 }
 
 }  // namespace qvg

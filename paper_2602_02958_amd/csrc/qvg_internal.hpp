@@ -101,8 +101,12 @@ struct AssignArgs {
     uint8_t *codes; f16_t *scales;   // written when fused != 0
     int64_t out_stride;      // tokens between consecutive units in ids / codes / scales
     int fused;
+    uint2 *nh3; float *cmax; // scratch of assign_workspace_bytes(H, K): split -||c||^2/2 per row, max ||c||^2 per unit
 };
+// launches the centroid preparation and the assignment (fused with quantization when a.fused)
 hipError_t launch_assign(const AssignArgs &a, hipStream_t s);
+size_t assign_workspace_bytes(int H, int K);
+void assign_workspace_split(void *ws, int H, int K, uint2 **nh3, float **cmax);
 
 struct UpdateArgs {
     const bf16_t *x; int64_t stride_head, stride_token; int64_t n_tokens;

@@ -93,12 +93,16 @@ def test_null_and_alignment_errors_are_reported_before_any_launch():
     assert L.qvg_decode(C.byref(p), 0, 10, None, None, None, None, None, 0, 0, None) == 0
     assert L.qvg_attn_decode(C.byref(p), 0, None, 10, 10, None, None, None, None, None, None, None,
                              None, C.c_float(0.1), None, None, None, 0, None) == 0
-    assert L.qvg_kmeans_assign(C.byref(p), 0, None, 0, 0, None, None, None) == 0
+    assert L.qvg_kmeans_assign(C.byref(p), 0, None, 0, 0, None, None, None, 0, None) == 0
 
 
 def test_workspace_sizes():
     p = B.make_params(24, 256, 64, 2, kmeans_iters=0)
-    assert B.workspace_bytes(p, B.ENTRY_ENCODE, 4680) == 0
+    # a single pass needs only the assignment's scratch: 8 bytes per centroid row, 4 per unit
+    small = B.workspace_bytes(p, B.ENTRY_ENCODE, 4680)
+    assert 24 * 256 * 8 + 24 * 4 <= small <= 24 * 256 * 8 + 24 * 4 + 1024
+    assert B.workspace_bytes(p, B.ENTRY_KMEANS_ASSIGN, 4680) == small
+    assert B.workspace_bytes(p, B.ENTRY_ENCODE, 0) == 0
     p = B.make_params(24, 256, 64, 2, kmeans_iters=3)
     need = B.workspace_bytes(p, B.ENTRY_ENCODE, 4680)
     assert need >= 2 * 24 * 256 * 256 + 24 * 4680 * 4 + 24 * 257 * 4
