@@ -44,6 +44,15 @@ __device__ __forceinline__ void insert3(float v, int idx, float &b1, float &b2, 
 
 __device__ __forceinline__ double shfl_xor_f64(double v, int m) { return __shfl_xor(v, m, 64); }
 template <bool V> struct BoolK { static constexpr bool value = V; };
+// (a & mask) | (b & ~mask): v_bfi_b32
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
+// a constant the compiler must keep in a vector register (so that the other, scalar operand of a
+// three-operand VALU instruction is the only one on the constant bus)
+__device__ __forceinline__ uint32_t vgpr_const(uint32_t c) {
+    uint32_t v;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(v) : "s"(c));
+    return v;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Per centroid: nh = fp32(-||c||^2 / 2) from an fp64 sum, split into three bf16 pieces by
@@ -187,25 +196,33 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
     __syncthreads();
     bf16_t *scr = lscr + wave * kHeadDim;
     // token operand of the extra MFMA step: three ones against (hi, mid, lo), lanes 0..31 only
+    const uint32_t tagmask = vgpr_const(kTagMask);
     const uint4 ones = half ? make_uint4(0u, 0u, 0u, 0u) : make_uint4(0x3F803F80u, 0x00003F80u, 0u, 0u);
 
     const int64_t blk0 = (int64_t)blockIdx.y * tiles_per_wave * (kAsgWaves * kAsgTile);
+    const bf16_t *xh = a.x + (int64_t)h * a.stride_head + half * 64;
     for (int k = 0; k < tiles_per_wave; ++k) {
         const int64_t n0 = blk0 + (int64_t)(k * kAsgWaves + wave) * kAsgTile;
         if (n0 >= N) break;                                  // uniform per wavefront
+        // this lane's 64 channels of its two tokens of the step (the MFMA B operands); a token
+        // past the end of the chunk reads as zero.  (Fetching the next step's tokens ahead was
+        // measured: no gain, and the registers are needed elsewhere.)
+        uint4 xa[2][8];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            const int64_t nn = n0 + tb * 32 + col;
+            const bf16_t *xp = xh + nn * a.stride_token;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                xa[tb][kk] = (nn < N) ? *reinterpret_cast<const uint4 *>(xp + kk * 8) : make_uint4(0u, 0u, 0u, 0u);
+        }
         int64_t n[2];
         bool valid[2];
-        // ---- this lane's 64 channels of its two tokens (the MFMA B operands) ----
-        uint4 xa[2][8];
         float xn[2];
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
             n[tb] = n0 + tb * 32 + col;
             valid[tb] = n[tb] < N;
-            const bf16_t *xp = a.x + (int64_t)h * a.stride_head + n[tb] * a.stride_token + half * 64;
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk)
-                xa[tb][kk] = valid[tb] ? *reinterpret_cast<const uint4 *>(xp + kk * 8) : make_uint4(0u, 0u, 0u, 0u);
         }
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
@@ -223,9 +240,11 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
         }
 
         // ---- scores on the matrix cores, running top three per lane and token ----
+        // Blocks of 32 centroids, software-pipelined: the MFMAs of block jb+1 are issued between
+        // the VALU instructions that rank the scores of block jb (an MFMA occupies the matrix
+        // pipe for 8 VALU issue slots), so one wavefront keeps both pipes busy.
         float b1[2] = {-INFINITY, -INFINITY}, b2[2] = {-INFINITY, -INFINITY}, b3[2] = {-INFINITY, -INFINITY};
-        for (int jb = 0; jb < (Kpad >> 5); ++jb) {
-            floatx16_t acc[2];
+        auto score_block = [&](int jb, floatx16_t (&acc)[2]) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) { acc[0][r] = 0.0f; acc[1][r] = 0.0f; }
             const bf16_t *arow = lc + (jb * 32 + col) * kCPitch;
@@ -235,22 +254,51 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                 acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, xa[0][kk]), acc[0], 0, 0, 0);
                 acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, xa[1][kk]), acc[1], 0, 0, 0);
             }
-            {
-                const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kHeadDim);
-                const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, ones);
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[1], 0, 0, 0);
-            }
+            const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kHeadDim);
+            const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, ones);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[1], 0, 0, 0);
+        };
+        auto rank_block = [&](int jb, const floatx16_t (&acc)[2]) {
             const uint32_t tag0 = (uint32_t)jb << 4;
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float v = __uint_as_float((__float_as_uint(acc[tb][r]) & kTagMask) | (tag0 + r));
+                    // (score & ~0x7F) | tag: one v_and_or_b32, the tag is scalar arithmetic.
+                    // max(a, b) is written med3(a, b, +inf): no NaN-quieting copy is needed.
+                    const float v = __uint_as_float((__float_as_uint(acc[tb][r]) & tagmask) | (tag0 + r));
                     b3[tb] = __builtin_amdgcn_fmed3f(b2[tb], b3[tb], v);
                     b2[tb] = __builtin_amdgcn_fmed3f(b1[tb], b2[tb], v);
-                    b1[tb] = fmaxf(b1[tb], v);
+                    b1[tb] = __builtin_amdgcn_fmed3f(b1[tb], v, INFINITY);
                 }
+        };
+        // issue order of one pipelined pair: operand reads run two MFMAs ahead
+        auto interleave = [&]() {
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+            for (int i = 0; i < 9; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
+                if (i < 7) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        };
+        if (FUSED) {
+            // the fused pass has no registers for a second set of accumulators
+            floatx16_t acc[2];
+            for (int jb = 0; jb < (Kpad >> 5); ++jb) { score_block(jb, acc); rank_block(jb, acc); }
+        } else {
+            const int nb = Kpad >> 5;                    // even: Kpad is a multiple of 64
+            floatx16_t accA[2], accB[2];
+            score_block(0, accA);
+            for (int jb = 0; jb + 2 < nb; jb += 2) {
+                score_block(jb + 1, accB);  rank_block(jb, accA);      interleave();
+                score_block(jb + 2, accA);  rank_block(jb + 1, accB);  interleave();
+            }
+            score_block(nb - 1, accB);  rank_block(nb - 2, accA);  interleave();
+            rank_block(nb - 1, accB);
         }
         // tag -> centroid index: row 8*(r/4) + 4*half + r%4 of block jb
         auto tag_to_idx = [&](float v) {
@@ -349,6 +397,7 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             }
             quantize_token<B_>(r, a.T, valid[tb], half, a.codes + hn * a.T * 32,
                                a.scales + hn * a.T * (kHeadDim / B_));
+            __builtin_amdgcn_sched_barrier(0);       // keep the two tokens' passes apart: each needs most registers
         }
     }
 }
@@ -359,7 +408,7 @@ static size_t assign_smem_bytes(int Kpad) {
 
 template <int B_, bool FUSED>
 static hipError_t launch_assign_t(const AssignArgs &a, hipStream_t s) {
-    const int Kpad = (a.K + 31) & ~31;
+    const int Kpad = (a.K + 63) & ~63;
     const size_t smem = assign_smem_bytes(Kpad);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -392,11 +441,11 @@ hipError_t launch_assign(const AssignArgs &a, hipStream_t s) {
 }
 
 size_t assign_workspace_bytes(int H, int K) {
-    const size_t Kpad = (size_t)((K + 31) & ~31);
+    const size_t Kpad = (size_t)((K + 63) & ~63);
     return ((size_t)H * Kpad * sizeof(uint2) + 255) / 256 * 256 + ((size_t)H * sizeof(float) + 255) / 256 * 256;
 }
 void assign_workspace_split(void *ws, int H, int K, uint2 **nh3, float **cmax) {
-    const size_t Kpad = (size_t)((K + 31) & ~31);
+    const size_t Kpad = (size_t)((K + 63) & ~63);
     *nh3 = static_cast<uint2 *>(ws);
     *cmax = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + ((size_t)H * Kpad * sizeof(uint2) + 255) / 256 * 256);
 }
