@@ -327,8 +327,8 @@ constexpr int kStMaxT = 4;
 constexpr int kStMaxG = 8;
 constexpr int kStCodes = kAtKv * kStMaxT * 32;            // bytes of one side's codes of a tile
 constexpr int kStScales = kAtKv * kStMaxT * kStMaxG * 2;  // bytes of one side's scales
-constexpr int kStBytes = 2 * kStCodes + 2 * kStScales + 2 * kAtKv;   // K and V: codes, scales, ids
-constexpr size_t kAtSmemStaged = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint16_t) + 2 * kStBytes;
+constexpr int kStBytes = 2 * kStCodes + 2 * kStScales;   // K and V: codes, scales
+constexpr size_t kAtSmemStaged = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint16_t) + 2 * kStBytes + 4 * 2 * kAtKv;
 
 template <bool V> struct BoolC { static constexpr bool value = V; };
 
@@ -340,6 +340,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     uint16_t *Kt = reinterpret_cast<uint16_t *>(smem);                  // [2][64][136] bf16
     uint16_t *Vt = Kt + 2 * kKtElems;                                   // [2][128][72] f16, transposed
     unsigned char *stage = reinterpret_cast<unsigned char *>(Vt + 2 * kVtElems);   // [2][kStBytes]
+    unsigned char *idring = stage + 2 * kStBytes;                       // [4][2][64]: ids run one tile further ahead
 
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id; re-number them so that
     // the query blocks of one unit run on one XCD (two at a boundary) and the unit's compressed
@@ -349,7 +350,8 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     const int h = w / n_qblocks;
     const int qblock = w - h * n_qblocks;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // uniform: lets whole waves branch
     const int col = lane & 31, half = lane >> 5;
     const int64_t qrow = (int64_t)qblock * kAtQPerBlock + wave * 32 + col;
     const bool qvalid = qrow < a.n_q;
@@ -435,11 +437,19 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
                 f.sc = make_uint4(w4[0], w4[1], w4[2], w4[3]);
             }
         }
-        if (!FULL) f.id = 0u;
+    };
+    // ids run one tile further ahead than codes and scales (the centroid rows they select are
+    // gathered a whole tile before they are needed); a token that does not exist gets id 0
+    auto fetch_ids = [&](const Tile &t, Fetch &f) {
+        f.id = 0u;
         if (tid < 2 * kAtKv) {
+            const int nvalid = t.valid ? (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv) : 0;
             const int n = tid & 63;
-            if (FULL || n < nvalid) f.id = min((uint32_t)((tid >> 6) ? v_ids : k_ids)[t.t0 + n], kmax);
+            if (n < nvalid) f.id = min((uint32_t)((tid >> 6) ? v_ids : k_ids)[t.t0 + n], kmax);
         }
+    };
+    auto park_ids = [&](const Fetch &f, int ordinal) {
+        if (tid < 2 * kAtKv) idring[(ordinal & 3) * 2 * kAtKv + tid] = (unsigned char)f.id;
     };
     auto park_tile = [&](const Fetch &f, int sb) {
         unsigned char *st = stage + sb * kStBytes;
@@ -457,12 +467,11 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
             const int ps = tid - (vside ? scPiecesSide : 0);
             *reinterpret_cast<uint4 *>(st + 2 * kStCodes + (vside ? kStScales : 0) + ps * 16) = f.sc;
         }
-        if (tid < 2 * kAtKv) st[2 * kStCodes + 2 * kStScales + tid] = (unsigned char)f.id;
     };
     // centroid rows of this thread's two tokens, both sides, using the parked ids (the id of a
     // token that does not exist is parked as 0)
-    auto gather_rows = [&](const Tile &t, int sb, uint4 cen[2][2]) {
-        const unsigned char *st = stage + sb * kStBytes + 2 * kStCodes + 2 * kStScales;
+    auto gather_rows = [&](const Tile &t, int ordinal, uint4 cen[2][2]) {
+        const unsigned char *st = idring + (ordinal & 3) * 2 * kAtKv;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const bf16_t *cent = (s ? v_cent : k_cent) + (int64_t)t.chunk * K * kHeadDim + c8 * 8;
@@ -512,14 +521,16 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     };
     auto is_full = [&](const Tile &t) { return t.valid && t.cend - t.t0 >= kAtKv; };
 
-    // ---- prologue: tile 0 decoded into buffer 0, tile 1 parked, tile 2 in registers ---------
+    // ---- prologue: tile 0 decoded into buffer 0, tile 1 parked, ids of tiles 0..2 parked ------
     Tile cur = first_tile(a);
     Tile nxt = next_tile(a, cur);
     Tile nn = nxt.valid ? next_tile(a, nxt) : nxt;
+    Tile n3 = nn.valid ? next_tile(a, nn) : nn;
     Fetch f;
     uint4 cen[2][2];
-    fetch_tile(BoolC<false>{}, cur, f);  park_tile(f, 0);
-    fetch_tile(BoolC<false>{}, nxt, f);  park_tile(f, 1);
+    fetch_tile(BoolC<false>{}, cur, f);  fetch_ids(cur, f);  park_tile(f, 0);  park_ids(f, 0);
+    fetch_tile(BoolC<false>{}, nxt, f);  fetch_ids(nxt, f);  park_tile(f, 1);  park_ids(f, 1);
+    fetch_ids(nn, f);  park_ids(f, 2);
     __syncthreads();
     gather_rows(cur, 0, cen);
     decode_to_lds(BoolC<false>{}, cur, 0, cen, 0);
@@ -527,11 +538,10 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     __syncthreads();                 // tile 0 ready; staging buffer 0 free again
 
     int buf = 0;                     // tile buffer of `cur`; the staging buffer of `nxt` is buf ^ 1
-    // One tile of the main loop: S, soft-max, PV on `cur`; decode of `nxt`; fetch of `nn`.
-    // FULL: cur, nxt and nn all hold 64 tokens.  Returns false after the last tile.
-    auto tile_step = [&](auto full) -> bool {
+    int jt = 0;                      // ordinal of `cur`
+    // S, soft-max and PV on `cur`
+    auto compute = [&](auto full) {
         constexpr bool FULL = decltype(full)::value;
-        if (FULL || nn.valid) fetch_tile(full, nn, f);             // lands during this iteration
         const uint16_t *kt = Kt + buf * kKtElems;
         const uint16_t *vt = Vt + buf * kVtElems;
         floatx16_t S[2];
@@ -598,22 +608,43 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
                     av, __builtin_bit_cast(halfx8_t, pb[st]), O[mb], 0, 0, 0);
             }
         }
+    };
+    // One tile of the main loop.  Two independent parts: compute on `cur`, and decode of `nxt`
+    // into the other tile buffer (its raw data was parked before the previous barrier, its rows
+    // were gathered an iteration ago) followed by the gather for `nn`.  Half of the wavefronts
+    // run the parts in the opposite order (decode_first), so that on every SIMD one wavefront is
+    // in a matrix-core phase while the other is in a VALU phase.  Codes and scales of `nn` and
+    // ids of `n3` are fetched at the top and parked at the bottom.  FULL: cur, nxt and nn all
+    // hold 64 tokens.  Returns false after the last tile.
+    auto tile_step = [&](auto full, bool decode_first /* uniform; only honoured with FULL */) -> bool {
+        constexpr bool FULL = decltype(full)::value;
+        if (FULL || nn.valid) fetch_tile(full, nn, f);             // lands during this iteration
+        fetch_ids(n3, f);
+        if (FULL && decode_first) {
+            decode_to_lds(full, nxt, buf ^ 1, cen, buf ^ 1);
+            gather_rows(nn, jt + 2, cen);
+        }
+        compute(full);
         if (!FULL && !nxt.valid) return false;
-        // decode the next tile (parked in staging buf^1, rows already gathered) into tile buffer
-        // buf^1, then park the tile after it in staging buf (free since the last barrier)
-        decode_to_lds(full, nxt, buf ^ 1, cen, buf ^ 1);
-        if (FULL || nn.valid) park_tile(f, buf);
+        if (!(FULL && decode_first)) {
+            decode_to_lds(full, nxt, buf ^ 1, cen, buf ^ 1);
+            if (FULL || nn.valid) gather_rows(nn, jt + 2, cen);
+        }
+        if (FULL || nn.valid) park_tile(f, buf);                   // staging buf is free since the last barrier
+        park_ids(f, jt + 3);
         __syncthreads();
-        if (FULL || nn.valid) gather_rows(nn, buf, cen);   // ids of nn are visible now; rows land next iteration
         buf ^= 1;
-        cur = nxt; nxt = nn;
-        nn = nn.valid ? next_tile(a, nn) : nn;
+        jt += 1;
+        cur = nxt; nxt = nn; nn = n3;
+        n3 = n3.valid ? next_tile(a, n3) : n3;
         return true;
     };
+    // wavefronts w and w + 4 share a SIMD: the first four decode first (measured: 3 % over all
+    // wavefronts in the same order; matrix-core and VALU work of two wavefronts overlap only little)
+    const bool decode_first = wave < kAtWaves / 2;
     while (true) {
-        while (is_full(cur) && is_full(nxt) && is_full(nn))      // uniform
-            tile_step(BoolC<true>{});
-        if (!tile_step(BoolC<false>{})) break;
+        while (is_full(cur) && is_full(nxt) && is_full(nn)) tile_step(BoolC<true>{}, decode_first);
+        if (!tile_step(BoolC<false>{}, false)) break;
     }
     const float ltot = l + __shfl_xor(l, 32, 64);
     if (qvalid) {
