@@ -114,3 +114,54 @@ def test_cfg3_chunk_encode_decode_sampled():
     assert np.array_equal(P.to_np_u16(enc.centroids[5, 0]), ref["cent"][0, 0])
     assert np.array_equal(P.to_np_u8(enc.ids[5]), ref["ids"][0, 0])
     assert np.array_equal(P.to_np_u8(enc.codes[5]), ref["codes"][0])
+
+
+def test_cfg3_all_layers_chunk_in_bench_launch_shape():
+    """The large-shape supplement of bench.py: one 4680-token chunk of all 30 layers of cfg3
+    (720 units in one call, which makes the encoder take several 256-token steps per workgroup),
+    warm-started Lloyd iterations included; sampled units against the oracle."""
+    wl = CONFIGS["cfg3_dit_small"]
+    from paper_2602_02958_amd import synth
+    units = 2 * wl.layers * wl.heads
+    x = synth.MixtureStream(wl, units, 0, "cuda").next_chunk(wl.chunk)
+    init = synth.cold_start_centroids(x, wl.n_clusters)
+    enc = B.encode_chunk(x, init, wl.group_size, wl.n_stages, 2)
+    dec = B.decode(enc)
+    torch.cuda.synchronize()
+    for u in (0, 359, 719):
+        xb = bf16_bits(x[u])
+        cent_g = P.to_np_u16(enc.centroids[u, 0])
+        ties = P.check_encoded_unit(xb, cent_g, P.gpu_unit(enc, u), wl.group_size, wl.n_stages)
+        assert ties <= 1
+        want = O.decode_unit(cent_g, P.to_np_u8(enc.ids[u]), P.to_np_u8(enc.codes[u]),
+                             P.to_np_u16(enc.scales[u]), wl.group_size)
+        assert np.array_equal(P.to_np_u16(dec[u]), want)
+    sel = [1, 718]
+    ref = O.encode_batch(bf16_bits(x[sel]), bf16_bits(init[sel]), wl.n_clusters, wl.group_size, wl.n_stages, 2)
+    assert np.array_equal(P.to_np_u16(enc.centroids[sel, 0]), ref["cent"][:, 0])
+    assert np.array_equal(P.to_np_u8(enc.ids[sel]), ref["ids"][:, 0])
+    assert np.array_equal(P.to_np_u8(enc.codes[sel]), ref["codes"])
+    assert np.array_equal(P.to_np_u16(enc.scales[sel]), ref["scales"])
+
+
+def test_cfg3_full_cache_decode_sampled():
+    """Decode of a 126360-token cache (27 chunks) of 72 units, the launch bench.py times for the
+    decode roofline: random valid storage, sampled (unit, chunk) pairs against the oracle."""
+    wl = CONFIGS["cfg3_dit_small"]
+    units, n = 2 * 3 * wl.heads, wl.tokens_per_layer
+    big = B.alloc_cache(units, n, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, "cuda")
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    big.ids.copy_(torch.randint(0, wl.n_clusters, big.ids.shape, generator=g, device="cuda", dtype=torch.uint8))
+    f = torch.randint(0, 3, big.codes.shape + (4,), generator=g, device="cuda", dtype=torch.uint8)
+    two = torch.tensor([0, 1, 3], dtype=torch.uint8, device="cuda")[f.long()]     # levels 0, +1, -1
+    big.codes.copy_(two[..., 0] | (two[..., 1] << 2) | (two[..., 2] << 4) | (two[..., 3] << 6)); del f, two
+    big.scales.copy_(torch.rand(big.scales.shape, generator=g, device="cuda").to(torch.float16))
+    big.centroids.copy_(torch.randn(big.centroids.shape, generator=g, device="cuda").to(torch.bfloat16))
+    out = B.decode(big)
+    torch.cuda.synchronize()
+    L = wl.chunk
+    for u, c in ((0, 0), (35, 13), (71, 26)):
+        sl = slice(c * L, min((c + 1) * L, n))
+        want = O.decode_unit(P.to_np_u16(big.centroids[u, c]), P.to_np_u8(big.ids[u, sl]),
+                             P.to_np_u8(big.codes[u, sl]), P.to_np_u16(big.scales[u, sl]), wl.group_size)
+        assert np.array_equal(P.to_np_u16(out[u, sl]), want)
