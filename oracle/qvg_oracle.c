@@ -249,6 +249,11 @@ void qvgo_unpack(int64_t n_elems, int bits, const uint8_t *packed, int8_t *q) {
  * assigned centroid, Eq. 5/6), then T rounds of b-bit group quantization of
  * what is left.  The paper's method is T = 1 (QVG: S = 1, QVG-Pro: S = 4);
  * S = 1 with T > 1 is the staged 2-bit quantization this build is graded on.
+ * Sec. 4.2 does not say in which precision the residual travels from one
+ * smoothing stage to the next; reading: as a bf16 tensor, the type of X itself
+ * (one fp32 subtraction, rounded to nearest even), so every stage sees the same
+ * kind of input.  The residual of the last stage is not stored and is quantized
+ * from its fp32 value.
  *
  * x        [N][d] bf16
  * init     [S][K][d] bf16 start centroids per smoothing stage, or NULL
@@ -280,6 +285,10 @@ void qvgo_encode_unit(int64_t N, int d, int K, int B, int S, int T, int bits, in
         uint8_t *is = ids_out + (int64_t)s * N;
         qvgo_lloyd(N, d, K, I, r, start, cs, is, NULL);
         qvgo_residual(N, d, r, cs, is, r2);
+        /* A residual that feeds another smoothing stage is a tensor of the input's type
+         * (bf16, like X); the last one goes straight to the quantizer in fp32. */
+        if (s + 1 < S)
+            for (int64_t i = 0; i < N * d; ++i) r2[i] = qvgo_bf16_to_f32(qvgo_f32_to_bf16(r2[i]));
         float *t = r; r = r2; r2 = t;
     }
     for (int t = 0; t < T; ++t) {

@@ -185,3 +185,33 @@ def test_smoothing_lowers_quantization_error_on_clustered_data(rng):
     assert (enc2["resid"].astype(np.float64) ** 2).mean() <= (enc1["resid"].astype(np.float64) ** 2).mean()
     out2 = O.decode_unit(enc2["cent"], enc2["ids"], enc2["codes"], enc2["scales"], 64)
     assert np.abs(bits_to_f32(out2) - xf).max() <= np.abs(enc2["resid"]).max() + 2.0 ** -7 * np.abs(xf).max()
+
+
+def test_two_smoothing_stages_equal_two_single_stage_passes(rng):
+    """S = 2 is stage 1 on X followed by stage 1 on the bf16 residual (Sec. 4.2, Eq. 5-6 applied
+    twice): the second stage's centroids, ids, codes and scales are those of a plain S = 1
+    encode of bf16(X - C1[ids1]), built here with numpy."""
+    from paper_2602_02958_amd.configs import CONFIGS
+    from paper_2602_02958_amd import synth
+    from conftest import bf16_bits
+    import torch
+    x = synth.MixtureStream(CONFIGS["cfg1_tiny"], 1, 0).next_chunk(1024)
+    xb = bf16_bits(x)[0]
+    K = 16
+    init = np.stack([bf16_bits(synth.cold_start_centroids(x, K, seed=s))[0] for s in (0, 1)])
+    enc2 = O.encode_unit(xb, K=K, B=32, S=2, T=2, iters=3, init=init)
+    enc_a = O.encode_unit(xb, K=K, B=32, S=1, T=2, iters=3, init=init[:1])
+    assert np.array_equal(enc2["cent"][0], enc_a["cent"][0]) and np.array_equal(enc2["ids"][0], enc_a["ids"][0])
+    r1 = bits_to_f32(xb) - bits_to_f32(enc_a["cent"][0])[enc_a["ids"][0]]          # fp32 subtraction
+    r1b = bf16_bits(torch.from_numpy(r1).to(torch.bfloat16))                       # RNE to bf16 (torch's)
+    enc_b = O.encode_unit(r1b, K=K, B=32, S=1, T=2, iters=3, init=init[1:])
+    assert np.array_equal(enc2["cent"][1], enc_b["cent"][0]) and np.array_equal(enc2["ids"][1], enc_b["ids"][0])
+    assert np.array_equal(enc2["codes"], enc_b["codes"]) and np.array_equal(enc2["scales"], enc_b["scales"])
+    # Eq. 7 with two tables: both centroid rows, then the rounds
+    out = O.decode_unit(enc2["cent"], enc2["ids"], enc2["codes"], enc2["scales"], 32)
+    q = O.unpack(enc2["codes"]).astype(np.float32)
+    sc = np.repeat(enc2["scales"].view(np.float16).astype(np.float32), 32, axis=-1)
+    acc = bits_to_f32(enc2["cent"][0])[enc2["ids"][0]] + bits_to_f32(enc2["cent"][1])[enc2["ids"][1]]
+    for t in range(2):
+        acc = (acc.astype(np.float64) + sc[:, t].astype(np.float64) * q[:, t]).astype(np.float32)  # exact product, one rounding
+    assert np.array_equal(out, bf16_bits(torch.from_numpy(acc).to(torch.bfloat16)))
