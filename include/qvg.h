@@ -33,6 +33,12 @@
  *   scales    [N][T][d/B]       f16     per group of B consecutive channels
  * A cache of several chunks concatenates ids/codes/scales along N and keeps one
  * centroid table per chunk: centroids [n_chunks][K][d].
+ *
+ * With S = n_smooth_stages > 1 (the paper's progressive residual quantization, Sec. 4.2: the
+ * residual of one k-means round is clustered again, S times, before it is quantized) a chunk
+ * keeps S tables, centroids [n_chunks][S][K][d], and a token S ids, ids [N][S]; the residual
+ * handed from one round to the next is rounded to bf16.  Everywhere below "[K][d]" then reads
+ * "[S][K][d]" and "ids [N]" reads "ids [N][S]".
  */
 #ifndef QVG_H
 #define QVG_H
@@ -62,7 +68,7 @@ typedef struct qvg_params {
     int32_t group_size;      /* B: 16, 32, 64 or 128 consecutive channels of one token  */
     int32_t n_stages;        /* T: 1..8 rounds of 2-bit quantization of the residual    */
     int32_t bits;            /* 2                                                       */
-    int32_t n_smooth_stages; /* S: 1 (the paper's QVG; S > 1 is QVG-Pro, not built)     */
+    int32_t n_smooth_stages; /* S: 1..4 k-means smoothing rounds (QVG: 1, QVG-Pro: 4)        */
     int32_t kmeans_iters;    /* I >= 0 Lloyd iterations before the final assignment     */
 } qvg_params;
 
@@ -80,7 +86,7 @@ typedef struct qvg_params {
  * group quantization of the residual (Eq. 1-2) with bit packing.
  *   x              [H][N][d] bf16 view: element (h,n,c) at x[h*stride_head + n*stride_token + c],
  *                  strides in elements, multiples of 8
- *   init_centroids [H][K][d] bf16
+ *   init_centroids [H][K][d] bf16 ([H][S][K][d]: one start table per smoothing round)
  *   centroids_out  [H][K][d] bf16, unit h at centroids_out + h*cent_out_stride_head elements
  *                  (0 = dense K*d; a multiple of 8; may equal init_centroids when I == 0 and dense)
  *   ids_out        [H][N]           codes_out [H][N][T][d/4]   scales_out [H][N][T][d/B] f16,
@@ -110,7 +116,7 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens,
  * Decode (Sec. 4.2 "dequantization process", Eq. 7; Sec. 4.3 "Dequantization
  * kernel": all stages in one kernel, the running value kept in registers):
  * x_hat = centroid[id] + sum_t scale_t * q_t, fp32 fma in stage order, one
- * rounding to bf16.
+ * rounding to bf16 (S > 1: the S centroid rows are added first, in round order, in fp32).
  *   n_tokens (0 .. 2^31-1) tokens per unit in chunks of chunk_len (the last may be shorter;
  *   chunk_len >= n_tokens means one chunk); centroids [H][n_chunks][K][d].
  *   x_bf16_out: same view convention as the encoder's x.

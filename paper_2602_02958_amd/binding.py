@@ -118,56 +118,63 @@ def _view3(x, name):
 
 @dataclass
 class Encoded:
-    """Stored form of one chunk (or of a cache of chunks) for H units."""
+    """Stored form of one chunk (or of a cache of chunks) for H units.  With n_smooth = S > 1
+    smoothing stages the tables are [H, n_chunks, S, K, d] and a token has S ids: [H, N, S]."""
     centroids: torch.Tensor   # [H, n_chunks, K, d] bf16
     ids: torch.Tensor         # [H, N] uint8
     codes: torch.Tensor       # [H, N, T, d/4] uint8
     scales: torch.Tensor      # [H, N, T, d/B] float16
     chunk_len: int
+    n_smooth: int = 1
 
 
 def alloc_cache(n_heads, n_tokens, chunk_len, n_clusters, group_size, n_stages, head_dim=128,
-                device="cuda") -> Encoded:
+                device="cuda", n_smooth=1) -> Encoded:
     """Uninitialised storage for a cache of n_tokens tokens per unit in chunks of chunk_len."""
     n_chunks = max(1, -(-n_tokens // chunk_len))
+    S = n_smooth
+    cshape = (n_heads, n_chunks, n_clusters, head_dim) if S == 1 else (n_heads, n_chunks, S, n_clusters, head_dim)
+    ishape = (n_heads, n_tokens) if S == 1 else (n_heads, n_tokens, S)
     return Encoded(
-        torch.empty(n_heads, n_chunks, n_clusters, head_dim, dtype=torch.bfloat16, device=device),
-        torch.empty(n_heads, n_tokens, dtype=torch.uint8, device=device),
+        torch.empty(cshape, dtype=torch.bfloat16, device=device),
+        torch.empty(ishape, dtype=torch.uint8, device=device),
         torch.empty(n_heads, n_tokens, n_stages, head_dim // 4, dtype=torch.uint8, device=device),
         torch.empty(n_heads, n_tokens, n_stages, head_dim // group_size, dtype=torch.float16,
                     device=device),
-        chunk_len)
+        chunk_len, S)
 
 
 def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: Encoded | None = None,
                  chunk_index: int = 0, workspace=None) -> Encoded:
-    """qvg_encode_chunk.  x [H, N, d] bf16, init_centroids [H, K, d] bf16.
-    Without `cache` a one-chunk cache is allocated and returned; with it, the chunk is written
-    in place at chunk_index (tokens chunk_index*chunk_len ...), using the output strides."""
+    """qvg_encode_chunk.  x [H, N, d] bf16, init_centroids [H, K, d] bf16, or [H, S, K, d] for S
+    smoothing stages.  Without `cache` a one-chunk cache is allocated and returned; with it, the
+    chunk is written in place at chunk_index (tokens chunk_index*chunk_len ...), using the output
+    strides."""
     sh, st_ = _view3(x, "x")
     H, N, d = x.shape
     _check(init_centroids, torch.bfloat16, "init_centroids")
     init_centroids = init_centroids.contiguous()
     K = init_centroids.shape[-2]
+    S = init_centroids.shape[1] if init_centroids.dim() == 4 else 1
     if cache is None:
-        cache = alloc_cache(H, N, max(N, 1), K, group_size, n_stages, d, x.device)
+        cache = alloc_cache(H, N, max(N, 1), K, group_size, n_stages, d, x.device, n_smooth=S)
     n_total = cache.ids.shape[1]
     n_chunks = cache.centroids.shape[1]
     off = chunk_index * cache.chunk_len
     if not (0 <= chunk_index < n_chunks) or off + N > n_total or (N > cache.chunk_len):
         raise ValueError("chunk does not fit the cache")
     if cache.codes.shape[2] != n_stages or cache.scales.shape[3] != d // group_size or \
-            cache.centroids.shape[2] != K or cache.ids.shape[0] != H:
+            cache.centroids.shape[-2] != K or cache.ids.shape[0] != H or cache.n_smooth != S:
         raise ValueError("cache was allocated for other parameters")
-    p = make_params(H, K, group_size, n_stages, kmeans_iters, head_dim=d)
+    p = make_params(H, K, group_size, n_stages, kmeans_iters, head_dim=d, n_smooth_stages=S)
     need = workspace_bytes(p, ENTRY_ENCODE, N)
     if need and (workspace is None or workspace.numel() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     T, G = n_stages, d // group_size
     st = lib().qvg_encode_chunk(
         C.byref(p), N, _ptr(x), sh, st_, _ptr(init_centroids),
-        C.c_void_p(cache.centroids.data_ptr() + chunk_index * K * d * 2), n_chunks * K * d,
-        C.c_void_p(cache.ids.data_ptr() + off),
+        C.c_void_p(cache.centroids.data_ptr() + chunk_index * S * K * d * 2), n_chunks * S * K * d,
+        C.c_void_p(cache.ids.data_ptr() + off * S),
         C.c_void_p(cache.codes.data_ptr() + off * T * (d // 4)),
         C.c_void_p(cache.scales.data_ptr() + off * T * G * 2), n_total,
         _ptr(workspace) if need else None, need, _stream())
@@ -178,10 +185,10 @@ def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: E
 
 def decode(enc: Encoded, out=None) -> torch.Tensor:
     """qvg_decode -> bf16 [H, N, d]."""
-    H, N = enc.ids.shape
+    H, N = enc.ids.shape[:2]
     K, d = enc.centroids.shape[-2:]
     T, G = enc.codes.shape[2], enc.scales.shape[3]
-    p = make_params(H, K, d // G, T, 0, head_dim=d)
+    p = make_params(H, K, d // G, T, 0, head_dim=d, n_smooth_stages=enc.n_smooth)
     if out is None:
         out = torch.empty(H, N, d, dtype=torch.bfloat16, device=enc.ids.device)
     sh, st_ = _view3(out, "out")
@@ -205,10 +212,10 @@ def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, o
     Nk = k.ids.shape[1]
     K = k.centroids.shape[-2]
     T, G = k.codes.shape[2], k.scales.shape[3]
-    if (v.ids.shape, v.codes.shape, v.scales.shape, v.centroids.shape, v.chunk_len) != \
-            (k.ids.shape, k.codes.shape, k.scales.shape, k.centroids.shape, k.chunk_len):
+    if (v.ids.shape, v.codes.shape, v.scales.shape, v.centroids.shape, v.chunk_len, v.n_smooth) != \
+            (k.ids.shape, k.codes.shape, k.scales.shape, k.centroids.shape, k.chunk_len, k.n_smooth):
         raise ValueError("K and V caches must share shapes and parameters")
-    p = make_params(H, K, d // G, T, 0, head_dim=d)
+    p = make_params(H, K, d // G, T, 0, head_dim=d, n_smooth_stages=k.n_smooth)
     if softmax_scale is None:
         softmax_scale = 1.0 / (d ** 0.5)
     if out is None:

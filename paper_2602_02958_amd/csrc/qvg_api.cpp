@@ -25,13 +25,13 @@ int check_params(const qvg_params *p) {
     // valid in the paper, not built here
     if (p->head_dim != kHeadDim) return QVG_ERR_UNSUPPORTED;
     if (p->bits != 2) return QVG_ERR_UNSUPPORTED;
-    if (p->n_smooth_stages != 1) return QVG_ERR_UNSUPPORTED;
+    if (p->n_smooth_stages > kMaxSmooth) return QVG_ERR_UNSUPPORTED;
     const int B = p->group_size;
     if (B != 16 && B != 32 && B != 64 && B != 128) return QVG_ERR_UNSUPPORTED;
     return QVG_OK;
 }
 
-struct EncodeWs { size_t assign; size_t cent[2]; size_t perm; size_t offs; size_t total; };
+struct EncodeWs { size_t assign; size_t cent[2]; size_t perm; size_t offs; size_t resid[2]; size_t total; };
 
 // with_assign: scratch of the assignment kernel; with_tables: two centroid tables for the Lloyd
 // loop; with_update: permutation and offsets of the update step
@@ -44,6 +44,12 @@ EncodeWs encode_ws(const qvg_params *p, int64_t N, bool with_assign, bool with_t
     if (with_update) {
         w.perm = o; o += round256((size_t)p->n_heads * (size_t)(N > 0 ? N : 1) * sizeof(int32_t));
         w.offs = o; o += round256((size_t)p->n_heads * (p->n_clusters + 1) * sizeof(int32_t));
+    }
+    // bf16 residual tensors that carry the data from one smoothing stage to the next
+    if (with_assign && p->n_smooth_stages > 1) {
+        const size_t r = round256((size_t)p->n_heads * (size_t)(N > 0 ? N : 1) * kHeadDim * sizeof(bf16_t));
+        w.resid[0] = o; o += r;
+        if (p->n_smooth_stages > 2) { w.resid[1] = o; o += r; }
     }
     w.total = o;
     return w;
@@ -83,7 +89,8 @@ int qvg_workspace_bytes(const qvg_params *p, int which_entry, int64_t n_tokens, 
     if (n_tokens < 0 || n_q < 0) return QVG_ERR_BAD_PARAM;
     switch (which_entry) {
         case QVG_ENTRY_ENCODE:
-            *out = n_tokens == 0 ? 0 : encode_ws(p, n_tokens, true, p->kmeans_iters > 0, p->kmeans_iters > 0).total;
+            *out = n_tokens == 0 ? 0 : encode_ws(p, n_tokens, true, p->kmeans_iters > 0 || p->n_smooth_stages > 1,
+                                                 p->kmeans_iters > 0).total;   // same call as qvg_encode_chunk
             return QVG_OK;
         case QVG_ENTRY_KMEANS_UPDATE:
             *out = encode_ws(p, n_tokens, false, false).total;
@@ -105,8 +112,9 @@ int64_t qvg_compressed_bytes(const qvg_params *p, int64_t n_tokens) {
     if (st != QVG_OK) return st;
     if (n_tokens < 0) return QVG_ERR_BAD_PARAM;
     const int64_t d = p->head_dim, T = p->n_stages;
-    const int64_t per_token = T * (d * p->bits / 8 + 2 * (d / p->group_size)) + 1;
-    return (int64_t)p->n_heads * (n_tokens * per_token + (int64_t)p->n_clusters * d * 2);
+    const int64_t S = p->n_smooth_stages;
+    const int64_t per_token = T * (d * p->bits / 8 + 2 * (d / p->group_size)) + S;
+    return (int64_t)p->n_heads * (n_tokens * per_token + S * (int64_t)p->n_clusters * d * 2);
 }
 
 int qvg_kmeans_assign(const qvg_params *p, int64_t n_tokens, const void *x, int64_t stride_head,
@@ -128,6 +136,7 @@ int qvg_kmeans_assign(const qvg_params *p, int64_t n_tokens, const void *x, int6
     a.n_tokens = n_tokens; a.cent = static_cast<const bf16_t *>(centroids);
     a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size; a.T = p->n_stages;
     a.ids = ids_out; a.codes = nullptr; a.scales = nullptr; a.out_stride = n_tokens; a.fused = 0;
+    a.ids_step = 1; a.ids_off = 0;
     return launch_assign(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
 }
 
@@ -148,7 +157,7 @@ int qvg_kmeans_update(const qvg_params *p, int64_t n_tokens, const void *x, int6
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     UpdateArgs u{};
     u.x = static_cast<const bf16_t *>(x); u.stride_head = stride_head; u.stride_token = stride_token;
-    u.n_tokens = n_tokens; u.ids = ids; u.ids_stride = n_tokens;
+    u.n_tokens = n_tokens; u.ids = ids; u.ids_stride = n_tokens; u.ids_step = 1; u.ids_off = 0;
     u.cent_prev = static_cast<const bf16_t *>(cent_prev);
     u.cent_out = static_cast<bf16_t *>(cent_out); u.counts_out = counts_out;
     u.perm = reinterpret_cast<int32_t *>(ws + w.perm); u.offsets = reinterpret_cast<int32_t *>(ws + w.offs);
@@ -168,15 +177,16 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
     if (!aligned16(init_centroids) || !aligned16(centroids_out)) return QVG_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t row = (size_t)p->n_clusters * kHeadDim * sizeof(bf16_t);    // one unit's table
-    if (cent_out_stride_head == 0) cent_out_stride_head = (int64_t)p->n_clusters * kHeadDim;
+    if (cent_out_stride_head == 0) cent_out_stride_head = (int64_t)p->n_smooth_stages * p->n_clusters * kHeadDim;
     if (out_stride_head_tokens == 0) out_stride_head_tokens = n_tokens;
-    if (cent_out_stride_head < (int64_t)p->n_clusters * kHeadDim || (cent_out_stride_head & 7))
+    if (cent_out_stride_head < (int64_t)p->n_smooth_stages * p->n_clusters * kHeadDim || (cent_out_stride_head & 7))
         return QVG_ERR_ALIGN;
     if (out_stride_head_tokens < n_tokens) return QVG_ERR_BAD_PARAM;
-    // the final table goes out as H rows of K*d bf16 with the caller's pitch
+    // n_tokens == 0: the start tables go out unchanged, H rows of S*K*d bf16 with the caller's pitch
     auto copy_out = [&](const void *src) -> int {
-        if (src == centroids_out && cent_out_stride_head == (int64_t)p->n_clusters * kHeadDim) return QVG_OK;
-        return hipMemcpy2DAsync(centroids_out, (size_t)cent_out_stride_head * sizeof(bf16_t), src, row, row,
+        const size_t all = row * (size_t)p->n_smooth_stages;
+        if (src == centroids_out && cent_out_stride_head == (int64_t)p->n_smooth_stages * p->n_clusters * kHeadDim) return QVG_OK;
+        return hipMemcpy2DAsync(centroids_out, (size_t)cent_out_stride_head * sizeof(bf16_t), src, all, all,
                                 (size_t)p->n_heads, hipMemcpyDeviceToDevice, s) == hipSuccess
                    ? QVG_OK : QVG_ERR_LAUNCH;
     };
@@ -185,40 +195,70 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
     if ((st = check_view(x, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
     if (!aligned16(codes_out) || !aligned16(scales_out)) return QVG_ERR_ALIGN;
     const int I = p->kmeans_iters;
-    const bf16_t *cur = static_cast<const bf16_t *>(init_centroids);
-    const EncodeWs w = encode_ws(p, n_tokens, true, I > 0, I > 0);
+    const int S = p->n_smooth_stages;
+    const EncodeWs w = encode_ws(p, n_tokens, true, I > 0 || S > 1, I > 0);
     if (!workspace || workspace_bytes < w.total) return QVG_ERR_WORKSPACE;
     if (!aligned16(workspace)) return QVG_ERR_ALIGN;
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     uint2 *nh3; float *cmax;
     assign_workspace_split(ws + w.assign, p->n_heads, p->n_clusters, &nh3, &cmax);
-    if (I > 0) {
-        bf16_t *buf[2] = {reinterpret_cast<bf16_t *>(ws + w.cent[0]), reinterpret_cast<bf16_t *>(ws + w.cent[1])};
+    // input of the current smoothing stage: the caller's view first, then dense residual tensors
+    const bf16_t *xin = static_cast<const bf16_t *>(x);
+    int64_t sh = stride_head, stt = stride_token;
+    for (int stage = 0; stage < S; ++stage) {
+        const bf16_t *cur = static_cast<const bf16_t *>(init_centroids) + (size_t)stage * p->n_clusters * kHeadDim;
+        const int64_t init_stride = (int64_t)S * p->n_clusters * kHeadDim;     // init [H][S][K][d]
         AssignArgs a{};
-        a.x = static_cast<const bf16_t *>(x); a.stride_head = stride_head; a.stride_token = stride_token;
+        a.x = xin; a.stride_head = sh; a.stride_token = stt;
         a.n_tokens = n_tokens; a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size;
         a.T = p->n_stages; a.ids = ids_out; a.out_stride = out_stride_head_tokens; a.fused = 0;
-        a.nh3 = nh3; a.cmax = cmax;
-        UpdateArgs u{};
-        u.x = a.x; u.stride_head = stride_head; u.stride_token = stride_token; u.n_tokens = n_tokens;
-        u.ids = ids_out; u.ids_stride = out_stride_head_tokens; u.counts_out = nullptr;
-        u.perm = reinterpret_cast<int32_t *>(ws + w.perm); u.offsets = reinterpret_cast<int32_t *>(ws + w.offs);
-        u.H = p->n_heads; u.K = p->n_clusters;
-        for (int it = 0; it < I; ++it) {
+        a.ids_step = S; a.ids_off = stage; a.nh3 = nh3; a.cmax = cmax;
+        bf16_t *buf[2] = {reinterpret_cast<bf16_t *>(ws + w.cent[0]), reinterpret_cast<bf16_t *>(ws + w.cent[1])};
+        if (S > 1) {
+            // the kernels want a dense [H][K][d] table; the caller's start tables are [H][S][K][d]
+            if (hipMemcpy2DAsync(buf[1], row, cur, (size_t)init_stride * sizeof(bf16_t), row,
+                                 (size_t)p->n_heads, hipMemcpyDeviceToDevice, s) != hipSuccess)
+                return QVG_ERR_LAUNCH;
+            cur = buf[1];
+        }
+        if (I > 0) {
+            UpdateArgs u{};
+            u.x = a.x; u.stride_head = sh; u.stride_token = stt; u.n_tokens = n_tokens;
+            u.ids = ids_out; u.ids_stride = out_stride_head_tokens; u.ids_step = S; u.ids_off = stage;
+            u.counts_out = nullptr;
+            u.perm = reinterpret_cast<int32_t *>(ws + w.perm); u.offsets = reinterpret_cast<int32_t *>(ws + w.offs);
+            u.H = p->n_heads; u.K = p->n_clusters;
+            for (int it = 0; it < I; ++it) {
+                a.cent = cur;
+                if (launch_assign(a, s) != hipSuccess) return QVG_ERR_LAUNCH;
+                u.cent_prev = cur; u.cent_out = buf[it & 1];
+                if (launch_update(u, s) != hipSuccess) return QVG_ERR_LAUNCH;
+                cur = buf[it & 1];
+            }
+        }
+        // this stage's table goes out as H rows of K*d bf16 with the caller's pitch
+        bf16_t *cdst = static_cast<bf16_t *>(centroids_out) + (size_t)stage * p->n_clusters * kHeadDim;
+        if (!(cur == cdst && cent_out_stride_head == (int64_t)p->n_clusters * kHeadDim)) {
+            if (hipMemcpy2DAsync(cdst, (size_t)cent_out_stride_head * sizeof(bf16_t), cur, row, row,
+                                 (size_t)p->n_heads, hipMemcpyDeviceToDevice, s) != hipSuccess)
+                return QVG_ERR_LAUNCH;
+        }
+        if (stage + 1 < S) {
+            // final assignment of this stage, then the bf16 residual becomes the next input
             a.cent = cur;
             if (launch_assign(a, s) != hipSuccess) return QVG_ERR_LAUNCH;
-            u.cent_prev = cur; u.cent_out = buf[it & 1];
-            if (launch_update(u, s) != hipSuccess) return QVG_ERR_LAUNCH;
-            cur = buf[it & 1];
+            ResidualArgs r{};
+            r.x = xin; r.stride_head = sh; r.stride_token = stt; r.n_tokens = n_tokens;
+            r.cent = cur; r.ids = ids_out; r.ids_stride = out_stride_head_tokens; r.ids_step = S; r.ids_off = stage;
+            r.out = reinterpret_cast<bf16_t *>(ws + w.resid[stage & 1]); r.H = p->n_heads; r.K = p->n_clusters;
+            if (launch_residual(r, s) != hipSuccess) return QVG_ERR_LAUNCH;
+            xin = r.out; sh = n_tokens * kHeadDim; stt = kHeadDim;
+        } else {
+            a.cent = cur; a.codes = codes_out; a.scales = static_cast<f16_t *>(scales_out); a.fused = 1;
+            if (launch_assign(a, s) != hipSuccess) return QVG_ERR_LAUNCH;
         }
     }
-    AssignArgs f{};
-    f.x = static_cast<const bf16_t *>(x); f.stride_head = stride_head; f.stride_token = stride_token;
-    f.n_tokens = n_tokens; f.cent = cur; f.H = p->n_heads; f.K = p->n_clusters; f.B = p->group_size;
-    f.T = p->n_stages; f.ids = ids_out; f.codes = codes_out; f.scales = static_cast<f16_t *>(scales_out);
-    f.out_stride = out_stride_head_tokens; f.fused = 1; f.nh3 = nh3; f.cmax = cmax;
-    if (launch_assign(f, s) != hipSuccess) return QVG_ERR_LAUNCH;
-    return copy_out(cur);
+    return QVG_OK;
 }
 
 int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, const void *centroids,
@@ -238,7 +278,7 @@ int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, const v
     a.scales = static_cast<const f16_t *>(scales); a.out = static_cast<bf16_t *>(x_out);
     a.n_tokens = n_tokens; a.chunk_len = chunk_len; a.n_chunks = (int)n_chunks;
     a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size; a.T = p->n_stages;
-    a.stride_head = stride_head; a.stride_token = stride_token;
+    a.stride_head = stride_head; a.stride_token = stride_token; a.S = p->n_smooth_stages;
     return launch_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
 }
 
@@ -272,6 +312,7 @@ int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q, int64_t n_k
     a.k_scales = static_cast<const f16_t *>(k_scales);
     a.v_cent = static_cast<const bf16_t *>(v_centroids); a.v_ids = v_ids; a.v_codes = v_codes;
     a.v_scales = static_cast<const f16_t *>(v_scales);
+    a.S = p->n_smooth_stages;
     return launch_attn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
 }
 

@@ -63,23 +63,28 @@ __device__ __forceinline__ Tile next_tile(const AttnArgs &a, Tile t) {
 template <int TM>
 struct Raw {                       // what one thread loads for its 2 tokens x 8 channels of one side
     uint32_t code[2][TM], sc[2][TM];
-    uint4 cen[2];
+    uint4 cen[2];                  // one smoothing stage: the centroid row (8 bf16)
+    float ci[2][8];                // several stages: their rows added in stage order (fp32)
 };
 
-// ids of this thread's two tokens of a tile (0 for tokens past the chunk end / an invalid tile)
-__device__ __forceinline__ void load_ids(const CacheSide &s, const Tile &t, int tp, uint32_t kmax,
+// ids of this thread's two tokens of a tile (0 for tokens past the chunk end / an invalid tile);
+// with S smoothing stages a token has S id bytes, stage s in byte s of the result
+__device__ __forceinline__ void load_ids(const CacheSide &s, const Tile &t, int tp, uint32_t kmax, int S,
                                          uint32_t id[2]) {
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
         const int n = t.t0 + 2 * tp + e;
-        id[e] = (t.valid && n < t.cend) ? min((uint32_t)s.ids[n], kmax) : 0u;
+        id[e] = 0u;
+        if (t.valid && n < t.cend)
+            for (int st = 0; st < S; ++st)
+                id[e] |= min((uint32_t)s.ids[(int64_t)n * S + st], kmax) << (8 * st);
     }
 }
 
-template <int T_, int TM>
+template <int T_, int TM, bool MULTI>
 __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int tp, int c8, int T,
-                                         int G, int g, int K, const uint32_t id[2], Raw<TM> &r) {
-    const bf16_t *cent = s.cent + (int64_t)t.chunk * K * kHeadDim;
+                                         int G, int g, int K, int S, const uint32_t id[2], Raw<TM> &r) {
+    const bf16_t *cent = s.cent + (int64_t)t.chunk * S * K * kHeadDim;      // [S][K][d] of this chunk
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
         const int n = t.t0 + 2 * tp + e;
@@ -87,23 +92,42 @@ __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int 
 #pragma unroll
         for (int k = 0; k < TM; ++k) { r.code[e][k] = 0u; r.sc[e][k] = 0u; }
         r.cen[e] = make_uint4(0u, 0u, 0u, 0u);
+        if (MULTI) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r.ci[e][i] = 0.0f;
+        }
         if (ok) {
             const uint16_t *cp = reinterpret_cast<const uint16_t *>(s.codes + (int64_t)n * T * 32) + c8;
             const f16_t *sp = s.scales + (int64_t)n * T * G + g;
 #pragma unroll
             for (int k = 0; k < TM; ++k)
                 if (k < T) { r.code[e][k] = cp[k * 16]; r.sc[e][k] = sp[k * G]; }
-            r.cen[e] = *reinterpret_cast<const uint4 *>(cent + (int64_t)id[e] * kHeadDim + c8 * 8);
+            if (!MULTI) {
+                r.cen[e] = *reinterpret_cast<const uint4 *>(cent + (int64_t)id[e] * kHeadDim + c8 * 8);
+            } else {
+                for (int st = 0; st < S; ++st) {
+                    float row[8];
+                    unpack_bf16x8(*reinterpret_cast<const uint4 *>(
+                                      cent + ((int64_t)st * K + ((id[e] >> (8 * st)) & 0xffu)) * kHeadDim + c8 * 8), row);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) r.ci[e][i] = st ? r.ci[e][i] + row[i] : row[i];
+                }
+            }
         }
     }
 }
 
 // fp32 decoded values of the thread's two tokens (tokens that do not exist decode to zero
 // because their codes, scales and centroid were loaded as zero)
-template <int T_, int TM>
+template <int T_, int TM, bool MULTI = false>
 __device__ __forceinline__ void dequant2x8(const Raw<TM> &r, int T, float *accA, float *accB) {
-    unpack_bf16x8(r.cen[0], accA);
-    unpack_bf16x8(r.cen[1], accB);
+    if (MULTI) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { accA[i] = r.ci[0][i]; accB[i] = r.ci[1][i]; }
+    } else {
+        unpack_bf16x8(r.cen[0], accA);
+        unpack_bf16x8(r.cen[1], accB);
+    }
 #pragma unroll
     for (int t = 0; t + 1 < TM; t += 2) {
         if (t + 1 < T) {
@@ -128,7 +152,8 @@ __device__ __forceinline__ void dequant2x8(const Raw<TM> &r, int T, float *accA,
 
 // Variant that loads every thread's codes and scales straight from global memory (many small
 // loads): used only for stage counts above 4, whose staging area would not fit in LDS.
-template <int T_>       // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages)
+template <int T_, bool MULTI>   // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages).
+                                // MULTI: more than one smoothing stage (a.S tables and id bytes)
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_kernel_direct(AttnArgs a) {
     constexpr int TM = T_ > 0 ? T_ : kMaxStages;
@@ -142,16 +167,17 @@ void attn_kernel_direct(AttnArgs a) {
     const int64_t qrow = (int64_t)blockIdx.x * kAtQPerBlock + wave * 32 + col;
     const bool qvalid = qrow < a.n_q;
     const int T = T_ > 0 ? T_ : a.T, B = a.B, K = a.K;
+    const int S = MULTI ? a.S : 1;
     const int G = kHeadDim / B;
     const uint32_t kmax = (uint32_t)K - 1u;
 
     CacheSide ks, vs;
-    ks.ids = a.k_ids + (int64_t)h * a.n_kv;  ks.codes = a.k_codes + (int64_t)h * a.n_kv * T * 32;
+    ks.ids = a.k_ids + (int64_t)h * a.n_kv * S;  ks.codes = a.k_codes + (int64_t)h * a.n_kv * T * 32;
     ks.scales = a.k_scales + (int64_t)h * a.n_kv * T * G;
-    ks.cent = a.k_cent + (int64_t)h * a.n_chunks * K * kHeadDim;
-    vs.ids = a.v_ids + (int64_t)h * a.n_kv;  vs.codes = a.v_codes + (int64_t)h * a.n_kv * T * 32;
+    ks.cent = a.k_cent + (int64_t)h * a.n_chunks * S * K * kHeadDim;
+    vs.ids = a.v_ids + (int64_t)h * a.n_kv * S;  vs.codes = a.v_codes + (int64_t)h * a.n_kv * T * 32;
     vs.scales = a.v_scales + (int64_t)h * a.n_kv * T * G;
-    vs.cent = a.v_cent + (int64_t)h * a.n_chunks * K * kHeadDim;
+    vs.cent = a.v_cent + (int64_t)h * a.n_chunks * S * K * kHeadDim;
 
     // decode mapping: 16 adjacent lanes cover the 16 channel chunks of a token pair (coalesced)
     const int c8 = tid & 15, tp = tid >> 4;            // tp 0..31: tokens 2*tp, 2*tp+1 of the tile
@@ -181,11 +207,11 @@ void attn_kernel_direct(AttnArgs a) {
 
     auto decode_to_lds = [&](const Raw<TM> &rk, const Raw<TM> &rv, int buf) {
         float accA[8], accB[8];
-        dequant2x8<T_, TM>(rk, T, accA, accB);
+        dequant2x8<T_, TM, MULTI>(rk, T, accA, accB);
         uint16_t *kt = Kt + buf * kKtElems;
         *reinterpret_cast<uint4 *>(kt + (tok + 0) * kKtPitch + c8 * 8) = pack_bf16x8(accA);
         *reinterpret_cast<uint4 *>(kt + (tok + 1) * kKtPitch + c8 * 8) = pack_bf16x8(accB);
-        dequant2x8<T_, TM>(rv, T, accA, accB);
+        dequant2x8<T_, TM, MULTI>(rv, T, accA, accB);
         uint16_t *vt = Vt + buf * kVtElems + v_off;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
@@ -203,12 +229,12 @@ void attn_kernel_direct(AttnArgs a) {
     Tile nn = nxt.valid ? next_tile(a, nxt) : nxt;
     uint32_t idk[2], idv[2];
     Raw<TM> rk, rv;
-    load_ids(ks, cur, tp, kmax, idk);
-    load_ids(vs, cur, tp, kmax, idv);
-    load_raw<T_, TM>(ks, cur, tp, c8, T, G, g, K, idk, rk);
-    load_raw<T_, TM>(vs, cur, tp, c8, T, G, g, K, idv, rv);
-    load_ids(ks, nxt, tp, kmax, idk);
-    load_ids(vs, nxt, tp, kmax, idv);
+    load_ids(ks, cur, tp, kmax, S, idk);
+    load_ids(vs, cur, tp, kmax, S, idv);
+    load_raw<T_, TM, MULTI>(ks, cur, tp, c8, T, G, g, K, S, idk, rk);
+    load_raw<T_, TM, MULTI>(vs, cur, tp, c8, T, G, g, K, S, idv, rv);
+    load_ids(ks, nxt, tp, kmax, S, idk);
+    load_ids(vs, nxt, tp, kmax, S, idv);
     decode_to_lds(rk, rv, 0);
     __syncthreads();
 
@@ -216,10 +242,10 @@ void attn_kernel_direct(AttnArgs a) {
     while (true) {
         // raw data of the next tile (consumed at the end of this iteration), ids of the one after
         if (nxt.valid) {
-            load_raw<T_, TM>(ks, nxt, tp, c8, T, G, g, K, idk, rk);
-            load_raw<T_, TM>(vs, nxt, tp, c8, T, G, g, K, idv, rv);
-            load_ids(ks, nn, tp, kmax, idk);
-            load_ids(vs, nn, tp, kmax, idv);
+            load_raw<T_, TM, MULTI>(ks, nxt, tp, c8, T, G, g, K, S, idk, rk);
+            load_raw<T_, TM, MULTI>(vs, nxt, tp, c8, T, G, g, K, S, idv, rv);
+            load_ids(ks, nn, tp, kmax, S, idk);
+            load_ids(vs, nn, tp, kmax, S, idv);
         }
         const uint16_t *kt = Kt + buf * kKtElems;
         const uint16_t *vt = Vt + buf * kVtElems;
@@ -682,13 +708,13 @@ static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int T_>
+template <int T_, bool MULTI>
 static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_, MULTI>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmem);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
-    hipLaunchKernelGGL((attn_kernel_direct<T_>), grid, dim3(kAtThreads), kAtSmem, s, a);
+    hipLaunchKernelGGL((attn_kernel_direct<T_, MULTI>), grid, dim3(kAtThreads), kAtSmem, s, a);
     return hipGetLastError();
 }
 
@@ -699,7 +725,8 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     }
     // the staged kernel fetches scales in 16-byte pieces: every chunk must start on one
     const bool aligned = (a.chunk_len % 8 == 0) || a.n_chunks == 1;
-    if (!aligned || a.T > kStMaxT) return launch_attn_t<0>(a, s);
+    if (a.S > 1) return launch_attn_t<0, true>(a, s);      // several smoothing stages: the general kernel
+    if (!aligned || a.T > kStMaxT) return launch_attn_t<0, false>(a, s);
     switch (a.T) {
         case 1: return launch_attn_staged<1>(a, s);
         case 2: return launch_attn_staged<2>(a, s);

@@ -27,12 +27,14 @@ constexpr int kXcds = 8;                         // MI355X: 8 XCDs, each with it
 
 // One pass of a block: 256 tokens, 4 rows per thread.  CHECK = false is the fast path for a pass
 // whose tokens all exist (no per-row predication).  tab: the chunk's centroid table in LDS.
-template <int T_, bool CHECK>
-__device__ __forceinline__ void decode_pass(int T, uint32_t ln0, uint32_t n_left, uint32_t lane16,
+// SM: 1 = one smoothing stage, table in LDS; 2 = S stages, all tables in LDS (tab);
+//     3 = S stages, tables read from global memory (cg).
+template <int T_, bool CHECK, int SM>
+__device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t n_left, uint32_t lane16,
                                             uint32_t G, uint32_t gidx, uint32_t kmax,
                                             const uint8_t *ids_b, const uint16_t *codes_b,
-                                            const f16_t *scales_b, const bf16_t *tab, bf16_t *out_b,
-                                            int64_t stride_token) {
+                                            const f16_t *scales_b, const bf16_t *tab, const bf16_t *cg,
+                                            bf16_t *out_b, int64_t stride_token) {
     constexpr int TM = T_ > 0 ? T_ : kMaxStages;
     uint32_t idv[kDecUnroll];
     uint32_t code[kDecUnroll][TM];
@@ -48,7 +50,11 @@ __device__ __forceinline__ void decode_pass(int T, uint32_t ln0, uint32_t n_left
             for (int t = 0; t < TM; ++t) { code[u][t] = 0u; sc[u][t] = 0u; }
         }
         if (ok[u]) {
-            idv[u] = ids_b[ln];
+            if (SM == 1) idv[u] = ids_b[ln];
+            else {                                   // up to four id bytes of the token, stage s in byte s
+                idv[u] = 0u;
+                for (int st = 0; st < S; ++st) idv[u] |= (uint32_t)ids_b[ln * (uint32_t)S + st] << (8 * st);
+            }
             const uint32_t co = ln * (uint32_t)T * 16u + lane16;       // in uint16 units
             const uint32_t so = ln * (uint32_t)T * G + gidx;
 #pragma unroll
@@ -60,9 +66,26 @@ __device__ __forceinline__ void decode_pass(int T, uint32_t ln0, uint32_t n_left
 #pragma unroll
     for (int up = 0; up < kDecUnroll; up += 2) {
         float accA[8], accB[8];
-        // centroid rows from LDS; an id beyond the table (corrupt input) is clamped
-        unpack_bf16x8(*reinterpret_cast<const uint4 *>(tab + min(idv[up], kmax) * kHeadDim + lane16 * 8), accA);
-        unpack_bf16x8(*reinterpret_cast<const uint4 *>(tab + min(idv[up + 1], kmax) * kHeadDim + lane16 * 8), accB);
+        // centroid rows; an id beyond the table (corrupt input) is clamped
+        if (SM == 1) {
+            unpack_bf16x8(*reinterpret_cast<const uint4 *>(tab + min(idv[up], kmax) * kHeadDim + lane16 * 8), accA);
+            unpack_bf16x8(*reinterpret_cast<const uint4 *>(tab + min(idv[up + 1], kmax) * kHeadDim + lane16 * 8), accB);
+        } else {
+            // Eq. 7 with S tables: the rows are added in stage order in fp32
+            const bf16_t *tb = (SM == 2) ? tab : cg;
+            for (int st = 0; st < S; ++st) {
+                const uint32_t ia = min((idv[up] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
+                const uint32_t ib = min((idv[up + 1] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
+                float ra[8], rb[8];
+                unpack_bf16x8(*reinterpret_cast<const uint4 *>(tb + ia * kHeadDim + lane16 * 8), ra);
+                unpack_bf16x8(*reinterpret_cast<const uint4 *>(tb + ib * kHeadDim + lane16 * 8), rb);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    accA[i] = st ? accA[i] + ra[i] : ra[i];
+                    accB[i] = st ? accB[i] + rb[i] : rb[i];
+                }
+            }
+        }
 #pragma unroll
         for (int t = 0; t + 1 < TM; t += 2) {
             if (t + 1 < T) {
@@ -95,7 +118,7 @@ __device__ __forceinline__ void decode_pass(int T, uint32_t ln0, uint32_t n_left
 
 // One workgroup = one slice of one chunk of one unit.  It stages the chunk's centroid table
 // in LDS once (the only shared operand) and then streams its tokens.
-template <int T_>   // T_ > 0: compile-time stage count; T_ == 0: run-time
+template <int T_, int SM>   // T_ > 0: compile-time stage count; T_ == 0: run-time.  SM: see decode_pass
 __global__ __launch_bounds__(kDecThreads)
 void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, int blocks_per_xcd) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -121,16 +144,17 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
     const uint32_t G = kHeadDim / a.B;
     const uint32_t gidx = (lane16 * 8) / a.B;     // scale group of this lane's 8 channels
 
-    {   // stage the table: K rows of 256 B, 16 B per thread and step
-        const bf16_t *cg = a.cent + ((int64_t)h * a.n_chunks + c) * a.K * kHeadDim;
-        for (int i = threadIdx.x; i < a.K * 16; i += kDecThreads)
+    const int S = (SM == 1) ? 1 : a.S;
+    const bf16_t *cg = a.cent + ((int64_t)h * a.n_chunks + c) * S * a.K * kHeadDim;    // [S][K][128] of this chunk
+    if (SM != 3) {   // stage the tables: S*K rows of 256 B, 16 B per thread and step
+        for (int i = threadIdx.x; i < S * a.K * 16; i += kDecThreads)
             *reinterpret_cast<uint4 *>(tab + i * 8) = *reinterpret_cast<const uint4 *>(cg + i * 8);
     }
     __syncthreads();
 
     // per-block base pointers (uniform), per-lane 32-bit offsets
     const int64_t hn0 = (int64_t)h * a.n_tokens + tok0;
-    const uint8_t *ids_b = a.ids + hn0;
+    const uint8_t *ids_b = a.ids + hn0 * S;
     const uint16_t *codes_b = reinterpret_cast<const uint16_t *>(a.codes + hn0 * T * 32);
     const f16_t *scales_b = a.scales + hn0 * T * G;
     bf16_t *out_b = a.out + (int64_t)h * a.stride_head + tok0 * a.stride_token;
@@ -138,15 +162,15 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
 
     for (uint32_t first = 0; first < n_left; first += kDecTokPerIter) {
         if (first + kDecTokPerIter <= n_left)
-            decode_pass<T_, false>(T, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
-                                   tab, out_b, a.stride_token);
+            decode_pass<T_, false, SM>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
+                                       tab, cg, out_b, a.stride_token);
         else
-            decode_pass<T_, true>(T, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
-                                  tab, out_b, a.stride_token);
+            decode_pass<T_, true, SM>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
+                                      tab, cg, out_b, a.stride_token);
     }
 }
 
-template <int T_>
+template <int T_, int SM>
 static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
     // slices per chunk: enough workgroups to fill 256 CUs x 2 twice over, but as few as possible
     // beyond that (every workgroup re-reads the chunk's table; measured flat from 512 to 4096)
@@ -162,23 +186,28 @@ static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
     const int64_t nb = unit_chunks * slices;
     if (nb > 0x7fffffff - kXcds) return hipErrorInvalidValue;
     const int bpx = (int)((nb + kXcds - 1) / kXcds);
-    const size_t smem = (size_t)a.K * kHeadDim * sizeof(bf16_t);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<T_>),
+    const size_t smem = (SM == 3) ? 16 : (size_t)(SM == 1 ? 1 : a.S) * a.K * kHeadDim * sizeof(bf16_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<T_, SM>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((decode_kernel<T_>), dim3((unsigned)(bpx * kXcds)), dim3(kDecThreads), smem, s, a,
+    hipLaunchKernelGGL((decode_kernel<T_, SM>), dim3((unsigned)(bpx * kXcds)), dim3(kDecThreads), smem, s, a,
                        (int)slices, (uint32_t)slice_len, (int)nb, bpx);
     return hipGetLastError();
 }
 
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s) {
     if (a.n_tokens == 0) return hipSuccess;
+    if (a.S > 1) {
+        // several smoothing stages: every stage's table in LDS when they fit in 64 KB together
+        if ((size_t)a.S * a.K * kHeadDim * sizeof(bf16_t) <= 65536) return launch_decode_t<0, 2>(a, s);
+        return launch_decode_t<0, 3>(a, s);
+    }
     switch (a.T) {
-        case 1: return launch_decode_t<1>(a, s);
-        case 2: return launch_decode_t<2>(a, s);
-        case 3: return launch_decode_t<3>(a, s);
-        case 4: return launch_decode_t<4>(a, s);
-        default: return launch_decode_t<0>(a, s);
+        case 1: return launch_decode_t<1, 1>(a, s);
+        case 2: return launch_decode_t<2, 1>(a, s);
+        case 3: return launch_decode_t<3, 1>(a, s);
+        case 4: return launch_decode_t<4, 1>(a, s);
+        default: return launch_decode_t<0, 1>(a, s);
     }
 }
 

@@ -378,7 +378,7 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             }
 
             const int64_t hn = (int64_t)h * a.out_stride + n[tb];
-            if (valid[tb] && half == 0) a.ids[hn] = (uint8_t)id;
+            if (valid[tb] && half == 0) a.ids[hn * a.ids_step + a.ids_off] = (uint8_t)id;
             if (!FUSED) continue;
 
             // ---- Eq. 5: residual against the assigned centroid, then the T rounds ----

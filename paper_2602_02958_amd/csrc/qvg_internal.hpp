@@ -11,6 +11,7 @@ namespace qvg {
 
 constexpr int kHeadDim = 128;      // only head_dim the kernels are written for
 constexpr int kMaxStages = 8;
+constexpr int kMaxSmooth = 4;       // smoothing stages (k-means rounds on the residual)
 constexpr int kMaxTokensPerChunk = 1 << 20;
 
 typedef uint16_t bf16_t;           // bit pattern of a bfloat16
@@ -91,6 +92,7 @@ struct DecodeArgs {
     const bf16_t *cent; const uint8_t *ids; const uint8_t *codes; const f16_t *scales;
     bf16_t *out; int64_t n_tokens; int64_t chunk_len; int n_chunks; int H; int K; int B; int T;
     int64_t stride_head, stride_token;
+    int S;      // smoothing stages: cent [H][n_chunks][S][K][d], ids [H][N][S]
 };
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 
@@ -100,6 +102,7 @@ struct AssignArgs {
     uint8_t *ids;            // always written
     uint8_t *codes; f16_t *scales;   // written when fused != 0
     int64_t out_stride;      // tokens between consecutive units in ids / codes / scales
+    int ids_step, ids_off;   // a token has ids_step id bytes; this pass writes byte ids_off (smoothing stage)
     int fused;
     uint2 *nh3; float *cmax; // scratch of assign_workspace_bytes(H, K): split -||c||^2/2 per row, max ||c||^2 per unit
 };
@@ -111,17 +114,28 @@ void assign_workspace_split(void *ws, int H, int K, uint2 **nh3, float **cmax);
 struct UpdateArgs {
     const bf16_t *x; int64_t stride_head, stride_token; int64_t n_tokens;
     const uint8_t *ids; int64_t ids_stride;      // tokens between consecutive units in ids
+    int ids_step, ids_off;                       // id bytes per token, byte read by this pass
     const bf16_t *cent_prev; bf16_t *cent_out; int32_t *counts_out;
     int32_t *perm; int32_t *offsets;     // workspace: [H][N] and [H][K+1]
     int H; int K;
 };
 hipError_t launch_update(const UpdateArgs &a, hipStream_t s);
 
+// out[h][n][:] = bf16( x[h][n][:] - cent[h][ids[h][n]][:] ), one fp32 subtraction (Eq. 5), for the
+// next smoothing stage.  out is dense [H][N][128].
+struct ResidualArgs {
+    const bf16_t *x; int64_t stride_head, stride_token; int64_t n_tokens;
+    const bf16_t *cent; const uint8_t *ids; int64_t ids_stride; int ids_step, ids_off;
+    bf16_t *out; int H; int K;
+};
+hipError_t launch_residual(const ResidualArgs &a, hipStream_t s);
+
 struct AttnArgs {
     const bf16_t *q; bf16_t *out; float *lse; int64_t n_q; int64_t n_kv; int64_t chunk_len;
     int n_chunks; int H; int K; int B; int T; float scale;
     const bf16_t *k_cent; const uint8_t *k_ids; const uint8_t *k_codes; const f16_t *k_scales;
     const bf16_t *v_cent; const uint8_t *v_ids; const uint8_t *v_codes; const f16_t *v_scales;
+    int S;      // smoothing stages, layouts as in DecodeArgs
 };
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
 

@@ -29,7 +29,8 @@ void kmeans_rank_kernel(UpdateArgs a) {
     const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int K = a.K;
     const int64_t N = a.n_tokens;
-    const uint8_t *ids = a.ids + (int64_t)h * a.ids_stride;
+    const uint8_t *ids = a.ids + (int64_t)h * a.ids_stride * a.ids_step + a.ids_off;   // token n at ids[n * step]
+    const int64_t step = a.ids_step;
     int32_t *perm = a.perm + (int64_t)h * N;
     int32_t *offs = a.offsets + (int64_t)h * (K + 1);
 
@@ -48,13 +49,13 @@ void kmeans_rank_kernel(UpdateArgs a) {
         for (int i = 0; i < kRankKeep; ++i) {
             const int64_t n = beg + (int64_t)i * 64 + lane;
             int id = -1;
-            if (i < steps && n < end) { id = ids[n]; if (id >= K) id = -1; }
+            if (i < steps && n < end) { id = ids[n * step]; if (id >= K) id = -1; }
             kept[i] = id;
         }
 #pragma unroll
         for (int i = 0; i < kRankKeep; ++i) if (kept[i] >= 0) atomicAdd(&cnt[w][kept[i]], 1);
     } else {
-        for (int64_t n = beg + lane; n < end; n += 64) { const int id = ids[n]; if (id < K) atomicAdd(&cnt[w][id], 1); }
+        for (int64_t n = beg + lane; n < end; n += 64) { const int id = ids[n * step]; if (id < K) atomicAdd(&cnt[w][id], 1); }
     }
     __syncthreads();
     if (tid < 256) {
@@ -91,7 +92,7 @@ void kmeans_rank_kernel(UpdateArgs a) {
     __syncthreads();
 
     int nxt = -1;
-    if (!keep && beg + lane < end) { nxt = ids[beg + lane]; if (nxt >= K) nxt = -1; }
+    if (!keep && beg + lane < end) { nxt = ids[(beg + lane) * step]; if (nxt >= K) nxt = -1; }
     for (int i = 0; i < steps; ++i) {
         const int64_t n = beg + (int64_t)i * 64 + lane;
         int id;
@@ -103,7 +104,7 @@ void kmeans_rank_kernel(UpdateArgs a) {
             id = nxt;
             const int64_t nn = n + 64;
             nxt = -1;
-            if (nn < end) { nxt = ids[nn]; if (nxt >= K) nxt = -1; }
+            if (nn < end) { nxt = ids[nn * step]; if (nxt >= K) nxt = -1; }
         }
         const bool valid = id >= 0;
         uint64_t peers = __ballot(valid);
@@ -161,6 +162,32 @@ void kmeans_mean_kernel(UpdateArgs a) {
     const double c = (double)(end - beg);
     const float m0 = (float)(s0 / c), m1 = (float)(s1 / c);
     *reinterpret_cast<uint32_t *>(a.cent_out + co) = pack_bf16x2(m0, m1);
+}
+
+// Residual for the next smoothing stage: 16 lanes per token, 8 channels each.
+__global__ __launch_bounds__(256)
+void residual_kernel(ResidualArgs a) {
+    const int h = blockIdx.y;
+    const int64_t n = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int c8 = threadIdx.x & 15;
+    if (n >= a.n_tokens) return;
+    int id = a.ids[((int64_t)h * a.ids_stride + n) * a.ids_step + a.ids_off];
+    if (id >= a.K) id = a.K - 1;
+    const uint4 xv = *reinterpret_cast<const uint4 *>(a.x + (int64_t)h * a.stride_head + n * a.stride_token + c8 * 8);
+    const uint4 cv = *reinterpret_cast<const uint4 *>(a.cent + ((int64_t)h * a.K + id) * kHeadDim + c8 * 8);
+    float xf[8], cf[8], r[8];
+    unpack_bf16x8(xv, xf);
+    unpack_bf16x8(cv, cf);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = xf[i] - cf[i];
+    *reinterpret_cast<uint4 *>(a.out + ((int64_t)h * a.n_tokens + n) * kHeadDim + c8 * 8) = pack_bf16x8(r);
+}
+
+hipError_t launch_residual(const ResidualArgs &a, hipStream_t s) {
+    if (a.n_tokens == 0) return hipSuccess;
+    dim3 grid((unsigned)((a.n_tokens + 15) / 16), (unsigned)a.H);
+    hipLaunchKernelGGL(residual_kernel, grid, dim3(256), 0, s, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {

@@ -43,7 +43,7 @@ def test_compressed_bytes_matches_format():
     (dict(n_heads=0), -2), (dict(n_clusters=0), -2), (dict(n_clusters=257), -2),
     (dict(n_stages=0), -2), (dict(n_stages=9), -2), (dict(group_size=48), -2),
     (dict(head_dim=64), -3), (dict(bits=4), -3), (dict(bits=3), -2),
-    (dict(n_smooth_stages=4), -3), (dict(group_size=8), -3), (dict(kmeans_iters=-1), -2),
+    (dict(n_smooth_stages=5), -3), (dict(n_smooth_stages=0), -2), (dict(group_size=8), -3), (dict(kmeans_iters=-1), -2),
 ])
 def test_parameter_validation(kw, status):
     base = dict(n_heads=2, n_clusters=16, group_size=64, n_stages=2, kmeans_iters=0,
