@@ -158,6 +158,49 @@ def large_supplement(torch, B, synth, CONFIGS):
     return out
 
 
+def pro_supplement(torch, B, synth, CONFIGS, S=4, group_size=16, n_stages=1, n_clusters=256):
+    """The paper's QVG-Pro preset (S = 4 smoothing stages, B = 16, one 2-bit round) on the cfg2
+    window: 24 units, 8 chunks of 4680 tokens, 4680 queries."""
+    wl = CONFIGS["cfg2_window21"]
+    dev = "cuda"
+    heads, units, L, n = wl.heads, 2 * wl.heads, wl.chunk, wl.tokens_per_layer
+    cache = B.alloc_cache(units, n, L, n_clusters, group_size, n_stages, wl.head_dim, dev, n_smooth=S)
+    sk, sv = synth.MixtureStream(wl, heads, 0, dev), synth.MixtureStream(wl, heads, 1, dev)
+    x = init = None
+    for c in range(wl.n_chunks):
+        x = torch.cat([sk.next_chunk(L), sv.next_chunk(L)], 0)
+        init = (torch.stack([synth.cold_start_centroids(x, n_clusters, seed=st) for st in range(S)], 1)
+                if c == 0 else cache.centroids[:, c - 1].contiguous())
+        B.encode_chunk(x, init, group_size, n_stages, 10 if c == 0 else 3, cache=cache, chunk_index=c)
+    out = {"preset": f"S={S} B={group_size} T={n_stages} K={n_clusters}", "units": units, "tokens": n}
+    p = B.make_params(units, n_clusters, group_size, n_stages, 3, n_smooth_stages=S)
+    ws = torch.empty(B.workspace_bytes(p, B.ENTRY_ENCODE, L), dtype=torch.uint8, device=dev)
+    fn = lambda: B.encode_chunk(x, init, group_size, n_stages, 3, cache=cache, chunk_index=wl.n_chunks - 1, workspace=ws)
+    fn(); torch.cuda.synchronize()
+    ms = _event_ms(fn, 5)
+    out["encode_I3"] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(units * L * 256 / ms / 1e6, 1)}
+    dec = torch.empty(units, n, wl.head_dim, dtype=torch.bfloat16, device=dev)
+    fn = lambda: B.decode(cache, out=dec)
+    fn(); torch.cuda.synchronize()
+    ms = _event_ms(fn, 10)
+    per_tok = n_stages * (wl.head_dim // 4 + 2 * wl.head_dim // group_size) + S
+    alg = units * n * (256 + per_tok) + units * wl.n_chunks * S * n_clusters * wl.head_dim * 2
+    out["decode"] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(units * n * 256 / ms / 1e6, 1),
+                     "hbm_GBps_algorithmic": round(alg / ms / 1e6, 1)}
+    q = synth.queries(wl, heads, wl.n_queries, dev)
+    k = B.Encoded(cache.centroids[:heads], cache.ids[:heads], cache.codes[:heads], cache.scales[:heads], L, S)
+    v = B.Encoded(cache.centroids[heads:], cache.ids[heads:], cache.codes[heads:], cache.scales[heads:], L, S)
+    o = torch.empty(heads, wl.n_queries, wl.head_dim, dtype=torch.bfloat16, device=dev)
+    fn = lambda: B.attn_decode(q, k, v, out=o)
+    fn(); torch.cuda.synchronize()
+    ms = _event_ms(fn, 3)
+    flops = 4.0 * wl.n_queries * n * wl.head_dim * heads
+    out["attn"] = {"ms": round(ms, 4), "TFLOPs": round(flops / ms / 1e9, 1)}
+    out["compression_ratio"] = round(units * n * 256 / B.compressed_bytes(
+        B.make_params(units, n_clusters, group_size, n_stages, 0, n_smooth_stages=S), L) / wl.n_chunks, 3)
+    return out
+
+
 def run_only(args, torch, B, synth, workload, CONFIGS):
     """One part of the path, repeated: what rocprofv3 is pointed at."""
     dev = "cuda"
@@ -220,7 +263,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large", action="store_true")
     ap.add_argument("--only", default=None,
-                    choices=["decode", "encode", "attn", "copy", "large_decode", "large_encode"],
+                    choices=["decode", "encode", "attn", "copy", "large_decode", "large_encode", "pro"],
                     help="profiling aid: run just this part --steps times and print a short JSON "
                          "(copy = a plain device copy of 1 GiB, the reference the HBM counters "
                          "are scaled by)")
@@ -238,6 +281,9 @@ def main():
     B.lib()                                    # fail loudly if the HIP library is missing
     wl = CONFIGS[args.workload]
     torch.cuda.set_device(0)
+    if args.only == "pro":
+        print(json.dumps(pro_supplement(torch, B, synth, CONFIGS)))
+        return
     if args.only:
         print(json.dumps(run_only(args, torch, B, synth, workload, CONFIGS)))
         return
@@ -318,6 +364,8 @@ def main():
             result["large"] = large_supplement(torch, B, synth, CONFIGS)
         except torch.OutOfMemoryError as e:     # a smaller card than the one this is written for
             result["large"] = {"error": str(e)[:200]}
+    if not args.no_large:
+        result["qvg_pro"] = pro_supplement(torch, B, synth, CONFIGS)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(result))
