@@ -158,6 +158,40 @@ def large_supplement(torch, B, synth, CONFIGS):
     return out
 
 
+def warm_start_supplement(torch, B, synth, wl):
+    """Centroid caching (Sec. 4.3): the fit of a chunk started from the previous chunk's centroids
+    with few Lloyd iterations, against a cold fit (seeded token picks, more iterations): time of the
+    encode call and k-means inertia (sum of squared distances to the assigned centroid, fp32 on
+    the GPU with torch: a measurement, not part of the path)."""
+    dev = "cuda"
+    units, L = 2 * wl.heads, wl.chunk
+    sk, sv = synth.MixtureStream(wl, wl.heads, 0, dev), synth.MixtureStream(wl, wl.heads, 1, dev)
+    prev = torch.cat([sk.next_chunk(L), sv.next_chunk(L)], 0)
+    x = torch.cat([sk.next_chunk(L), sv.next_chunk(L)], 0)
+    enc_prev = B.encode_chunk(prev, synth.cold_start_centroids(prev, wl.n_clusters), wl.group_size,
+                              wl.n_stages, wl.kmeans_iters_cold)
+    warm_init = enc_prev.centroids[:, 0].contiguous()
+    cold_init = synth.cold_start_centroids(x, wl.n_clusters, seed=1)
+    p = B.make_params(units, wl.n_clusters, wl.group_size, wl.n_stages, wl.kmeans_iters_cold)
+    ws = torch.empty(B.workspace_bytes(p, B.ENTRY_ENCODE, L), dtype=torch.uint8, device=dev)
+    cache = B.alloc_cache(units, L, L, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
+
+    def inertia():
+        c = cache.centroids[:, 0].float()
+        idx = cache.ids.long()[:, :, None].expand(-1, -1, wl.head_dim)
+        return float(((x.float() - torch.gather(c, 1, idx)) ** 2).sum())
+
+    out = {}
+    for name, init, iters in (("cold", cold_init, wl.kmeans_iters_cold), ("warm", warm_init, wl.kmeans_iters_warm),
+                              ("warm_no_iterations", warm_init, 0)):
+        fn = lambda: B.encode_chunk(x, init, wl.group_size, wl.n_stages, iters, cache=cache, workspace=ws)
+        fn(); torch.cuda.synchronize()
+        out[name] = {"iters": iters, "ms": round(_event_ms(fn, 10), 4), "inertia": round(inertia(), 1)}
+    out["speedup_warm_vs_cold"] = round(out["cold"]["ms"] / out["warm"]["ms"], 2)
+    out["inertia_warm_over_cold"] = round(out["warm"]["inertia"] / out["cold"]["inertia"], 4)
+    return out
+
+
 def pro_supplement(torch, B, synth, CONFIGS, S=4, group_size=16, n_stages=1, n_clusters=256):
     """The paper's QVG-Pro preset (S = 4 smoothing stages, B = 16, one 2-bit round) on the cfg2
     window: 24 units, 8 chunks of 4680 tokens, 4680 queries."""
@@ -283,6 +317,7 @@ def main():
     torch.cuda.set_device(0)
     if args.only == "pro":
         print(json.dumps(pro_supplement(torch, B, synth, CONFIGS)))
+        print(json.dumps(warm_start_supplement(torch, B, synth, wl)))
         return
     if args.only:
         print(json.dumps(run_only(args, torch, B, synth, workload, CONFIGS)))
@@ -366,6 +401,7 @@ def main():
             result["large"] = {"error": str(e)[:200]}
     if not args.no_large:
         result["qvg_pro"] = pro_supplement(torch, B, synth, CONFIGS)
+        result["warm_start"] = warm_start_supplement(torch, B, synth, wl)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(result))
