@@ -141,8 +141,9 @@ def large_supplement(torch, B, synth, CONFIGS):
     big = B.alloc_cache(units, n, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
     g = torch.Generator(device=dev); g.manual_seed(1)
     big.ids.copy_(torch.randint(0, wl.n_clusters, big.ids.shape, generator=g, device=dev, dtype=torch.uint8))
-    # codes: every 2-bit field in {0,1,2}
-    f = torch.randint(0, 3, big.codes.shape + (4,), generator=g, device=dev, dtype=torch.uint8)
+    # codes: every 2-bit field one of the levels 0, +1, -1 (0b00, 0b01, 0b11)
+    f = torch.tensor([0, 1, 3], dtype=torch.uint8, device=dev)[
+        torch.randint(0, 3, big.codes.shape + (4,), generator=g, device=dev)]
     big.codes.copy_(f[..., 0] | (f[..., 1] << 2) | (f[..., 2] << 4) | (f[..., 3] << 6)); del f
     big.scales.copy_(torch.rand(big.scales.shape, generator=g, device=dev).to(torch.float16))
     big.centroids.copy_(torch.randn(big.centroids.shape, generator=g, device=dev).to(torch.bfloat16))
@@ -155,6 +156,21 @@ def large_supplement(torch, B, synth, CONFIGS):
     out["decode"] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(vec * 256 / ms / 1e6, 1),
                      "hbm_GBps_algorithmic": round(alg / ms / 1e6, 1),
                      "hbm_frac": round(alg / ms / 1e6 / HBM_PEAK_GBPS, 4), "units": units, "tokens": n}
+    del outbuf
+    # ---- fused attention: one layer, 4680 queries of 12 heads over the 126360-token cache
+    hd = wl.heads
+    k = B.Encoded(big.centroids[:hd], big.ids[:hd], big.codes[:hd], big.scales[:hd], wl.chunk)
+    v = B.Encoded(big.centroids[hd:2 * hd], big.ids[hd:2 * hd], big.codes[hd:2 * hd], big.scales[hd:2 * hd], wl.chunk)
+    q = synth.queries(wl, hd, wl.n_queries, dev)
+    o = torch.empty(hd, wl.n_queries, wl.head_dim, dtype=torch.bfloat16, device=dev)
+    fn = lambda: B.attn_decode(q, k, v, out=o)
+    fn(); torch.cuda.synchronize()
+    ms = _event_ms(fn, 3)
+    flops = 4.0 * wl.n_queries * n * wl.head_dim * hd
+    out["attn_one_layer"] = {"ms": round(ms, 4), "TFLOPs": round(flops / ms / 1e9, 1),
+                             "mfma_frac": round(flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                             "q_tokens_per_s": round(wl.n_queries * hd / ms * 1e3, 1),
+                             "cache_tokens_per_s": round(n * hd / ms * 1e3, 1)}
     return out
 
 
