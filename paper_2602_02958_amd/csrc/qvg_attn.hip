@@ -14,10 +14,13 @@
 //      holds every bf16 value of magnitude 2^-14 .. 65504 exactly (larger ones saturate).
 //      The lane's P values are already the B operand: the V tile is stored transposed with
 //      the matching token permutation, so no cross-lane traffic is needed;
-//   4. all 512 threads decode the NEXT tile (2 tokens x 8 channels of K and of V each) from
-//      registers that were loaded one tile earlier, into the other LDS buffer.
+//   4. all 512 threads decode the NEXT tile (2 tokens x 8 channels of K and of V each) into the
+//      other LDS buffer, from data that was requested one or two tiles earlier.
 // The decode work is amortised over 256 queries; only the two contractions use the matrix
 // cores, the unpack / fma / soft-max work is VALU and is what bounds the kernel.
+// Two kernels: attn_kernel_staged (one smoothing stage, 1..4 quantization rounds, chunks that
+// start on 16-byte boundaries of the scale array: the measured path) and attn_kernel_direct
+// (everything else).
 #include "qvg_internal.hpp"
 
 namespace qvg {
@@ -150,8 +153,10 @@ __device__ __forceinline__ void dequant2x8(const Raw<TM> &r, int T, float *accA,
     }
 }
 
-// Variant that loads every thread's codes and scales straight from global memory (many small
-// loads): used only for stage counts above 4, whose staging area would not fit in LDS.
+// General variant: every thread loads its codes, scales and centroid rows straight from global
+// memory (many small loads).  Used for more than 4 quantization rounds (their staging area would
+// not fit in LDS), for chunks whose scale records do not start on 16-byte boundaries, and for
+// several smoothing stages (the rows of all stages are added as they arrive).
 template <int T_, bool MULTI>   // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages).
                                 // MULTI: more than one smoothing stage (a.S tables and id bytes)
 __global__ __launch_bounds__(kAtThreads, 2)
@@ -344,10 +349,12 @@ void attn_kernel_direct(AttnArgs a) {
 
 
 // ---------------------------------------------------------------------------------------------
-// Main variant (1..4 stages).  The packed codes, scales and ids of a tile are brought in with a
-// few wide loads per thread two tiles ahead and parked in an LDS staging area; the per-thread
-// 2-byte reads that the decode needs then hit LDS instead of issuing dozens of tiny global
-// loads.  Only the centroid rows are gathered from global memory (L2), one tile ahead.
+// Main variant (one smoothing stage, 1..4 rounds).  The packed codes and scales of a tile are
+// brought in with a few wide loads per thread two tiles ahead and parked in an LDS staging
+// area; the per-thread 2-byte reads that the decode needs then hit LDS instead of issuing
+// dozens of tiny global loads.  The ids run three tiles ahead (a small ring in LDS), so that the
+// centroid rows, the only per-thread gathers from global memory (L2), are requested a whole
+// tile before they are used.
 // ---------------------------------------------------------------------------------------------
 constexpr int kStMaxT = 4;
 constexpr int kStMaxG = 8;
