@@ -12,6 +12,10 @@
 // fma operand in one instruction per element), so the per-lane addressing is reduced to 32-bit
 // offsets from per-block (scalar) base pointers.
 //
+// With S > 1 smoothing stages a token has S ids and S centroid rows, added in stage order in fp32
+// before the rounds; the S tables of a chunk sit in LDS together when they fit in 64 KB, else the
+// rows are read from global memory (a general, slower variant of the same kernel).
+//
 // Mapping: 16 lanes per token, 8 channels (one 16-byte store) per lane, so that a
 // wavefront's store instruction covers 4 whole token rows = 1 KB contiguous.  A workgroup of
 // 1024 threads walks its slice of a chunk 256 tokens per pass, 4 token rows per thread.

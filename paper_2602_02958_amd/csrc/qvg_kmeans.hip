@@ -9,6 +9,8 @@
 //          per lane (a 256-byte coalesced row per member), sixteen rows in flight,
 //          adds in fp64, divides by the count, rounds to fp32 and then to bf16.
 //          A group without members keeps its previous centroid.
+// Also here: the residual pass that turns one smoothing stage's output into the next one's
+// input (Eq. 5 on whole tensors, result rounded to bf16).
 #include "qvg_internal.hpp"
 
 namespace qvg {
