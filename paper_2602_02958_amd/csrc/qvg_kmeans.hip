@@ -6,7 +6,7 @@
 //          (16 wavefronts, each histogramming and then placing its own contiguous range
 //          of tokens, ballot-built peer masks keeping equal ids in token order);
 //   mean:  one wavefront per centroid walks its members in that order, two channels
-//          per lane (a 256-byte coalesced row per member), sixteen rows in flight,
+//          per lane (a 256-byte coalesced row per member), up to 128 rows in flight,
 //          adds in fp64, divides by the count, rounds to fp32 and then to bf16.
 //          A group without members keeps its previous centroid.
 // Also here: the residual pass that turns one smoothing stage's output into the next one's
@@ -127,6 +127,8 @@ void kmeans_rank_kernel(UpdateArgs a) {
 
 constexpr int kMeanThreads = 256;           // 4 wavefronts = 4 centroids per block
 
+// WIDE: many members per centroid (few, long waves): see the comments inside
+template <bool WIDE>
 __global__ __launch_bounds__(kMeanThreads)
 void kmeans_mean_kernel(UpdateArgs a) {
     const int h = blockIdx.y, lane = threadIdx.x & 63;
@@ -142,23 +144,66 @@ void kmeans_mean_kernel(UpdateArgs a) {
         *reinterpret_cast<uint32_t *>(a.cent_out + co) = *reinterpret_cast<const uint32_t *>(a.cent_prev + co);
         return;
     }
-    const bf16_t *xb = a.x + (int64_t)h * a.stride_head + lane * 2;
     double s0 = 0.0, s1 = 0.0;
-    for (int base = beg; base < end; base += 64) {
-        // 64 member indices with one coalesced load, then broadcast lane by lane
-        const int mine = (base + lane < end) ? perm[base + lane] : 0;
-        const int cntm = (end - base < 64) ? end - base : 64;
-        for (int u0 = 0; u0 < cntm; u0 += 16) {
-            uint32_t wv[16];
+    if (!WIDE) {
+        // few members per centroid (many small waves): 16 rows in flight, few registers
+        const bf16_t *xb = a.x + (int64_t)h * a.stride_head + lane * 2;
+        for (int base = beg; base < end; base += 64) {
+            // 64 member indices with one coalesced load, then broadcast lane by lane
+            const int mine = (base + lane < end) ? perm[base + lane] : 0;
+            const int cntm = (end - base < 64) ? end - base : 64;
+            for (int u0 = 0; u0 < cntm; u0 += 16) {
+                uint32_t wv[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const int idx = __shfl(mine, u0 + u, 64);
-                wv[u] = (u0 + u < cntm)
-                    ? *reinterpret_cast<const uint32_t *>(xb + (int64_t)idx * a.stride_token) : 0u;
+                for (int u = 0; u < 16; ++u) {
+                    const int idx = __shfl(mine, u0 + u, 64);
+                    wv[u] = (u0 + u < cntm)
+                        ? *reinterpret_cast<const uint32_t *>(xb + (int64_t)idx * a.stride_token) : 0u;
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    if (u0 + u < cntm) { s0 += (double)bf16_lo(wv[u]); s1 += (double)bf16_hi(wv[u]); }
             }
+        }
+    } else {
+        // Members are walked 64 at a time: one coalesced load brings their indices (one group
+        // ahead), a constant-lane read moves each index into a scalar register, so the row address is
+        // scalar arithmetic, and all 64 rows of the NEXT group are requested before the current
+        // group is added.  The additions are strictly ordered (fp64, token order); with two groups
+        // in flight they run in the shadow of the loads.
+        const bf16_t *xu = a.x + (int64_t)h * a.stride_head;
+        auto load64 = [&](int mine, int cntm, uint32_t (&wv)[64]) {
 #pragma unroll
-            for (int u = 0; u < 16; ++u)
-                if (u0 + u < cntm) { s0 += (double)bf16_lo(wv[u]); s1 += (double)bf16_hi(wv[u]); }
+            for (int u = 0; u < 64; ++u) {
+                const int idx = __builtin_amdgcn_readlane(mine, u);
+                const bf16_t *row = xu + (int64_t)idx * a.stride_token;
+                wv[u] = (u < cntm) ? *reinterpret_cast<const uint32_t *>(row + lane * 2) : 0u;   // uniform condition
+            }
+        };
+        auto add64 = [&](int cntm, const uint32_t (&wv)[64]) {
+            if (cntm == 64) {
+#pragma unroll
+                for (int u = 0; u < 64; ++u) { s0 += (double)bf16_lo(wv[u]); s1 += (double)bf16_hi(wv[u]); }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 64; ++u)
+                    if (u < cntm) { s0 += (double)bf16_lo(wv[u]); s1 += (double)bf16_hi(wv[u]); }
+            }
+        };
+        auto count_at = [&](int base) { return (end - base < 64) ? end - base : 64; };
+        auto indices_at = [&](int base) { return (base + lane < end) ? perm[base + lane] : 0; };
+        uint32_t wa[64], wb[64];
+        int mine_b = indices_at(beg + 64);
+        load64(indices_at(beg), count_at(beg), wa);
+        for (int base = beg; base < end; base += 128) {
+            // group B = [base + 64, base + 128), group A' = [base + 128, base + 192)
+            const int mine_a = indices_at(base + 128);
+            if (base + 64 < end) load64(mine_b, count_at(base + 64), wb);
+            add64(count_at(base), wa);
+            if (base + 64 >= end) break;
+            mine_b = indices_at(base + 192);
+            if (base + 128 < end) load64(mine_a, count_at(base + 128), wa);
+            add64(count_at(base + 64), wb);
         }
     }
     const double c = (double)(end - beg);
@@ -197,7 +242,9 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.K + 3) / 4), (unsigned)a.H);
-    hipLaunchKernelGGL(kmeans_mean_kernel, grid, dim3(kMeanThreads), 0, s, a);
+    // long member lists are latency-bound on their ordered sums: more rows in flight pays there
+    if (a.n_tokens / a.K >= 48) hipLaunchKernelGGL(kmeans_mean_kernel<true>, grid, dim3(kMeanThreads), 0, s, a);
+    else hipLaunchKernelGGL(kmeans_mean_kernel<false>, grid, dim3(kMeanThreads), 0, s, a);
     return hipGetLastError();
 }
 
