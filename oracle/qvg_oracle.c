@@ -85,6 +85,34 @@ uint16_t qvgo_f32_to_f16(float f) {
     return (uint16_t)(sign | (be << 10) | mant);
 }
 
+/* FP8 E4M3 (Sec. 5 "Implementation": the format of the per-group scales in the paper's
+ * own kernels; the OCP 8-bit layout: 1 sign, 4 exponent bits with bias 7, 3 mantissa
+ * bits, no infinity, S.1111.111 = NaN, largest finite 448, subnormals m/8 * 2^-6). */
+float qvgo_e4m3_to_f32(uint8_t b) {
+    int sign = (b >> 7) & 1, e = (b >> 3) & 0xf, m = b & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m / 8.0, -6);
+    else        v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return (float)(sign ? -v : v);
+}
+
+/* binary32 -> E4M3: the nearest finite value, ties to the even code, found by
+ * looking at every non-negative finite code.  Magnitudes beyond 448 saturate to
+ * 448 (a scale must stay finite).  NaN -> the NaN code. */
+uint8_t qvgo_f32_to_e4m3(float f) {
+    uint8_t sign = (uint8_t)(signbit(f) ? 0x80 : 0);
+    if (isnan(f)) return (uint8_t)(sign | 0x7f);
+    double a = fabs((double)f);
+    int best = 0;
+    double bd = a;                                   /* distance to code 0 */
+    for (int c = 1; c <= 0x7e; ++c) {
+        double dist = fabs((double)qvgo_e4m3_to_f32((uint8_t)c) - a);
+        if (dist < bd || (dist == bd && (c & 1) == 0)) { bd = dist; best = c; }
+    }
+    return (uint8_t)(sign | best);
+}
+
 /* ------------------------------------------------------------------ */
 /* Sec. 4.1: semantic-based grouping (k-means)                        */
 /* ------------------------------------------------------------------ */
@@ -184,13 +212,31 @@ void qvgo_residual(int64_t N, int d, const float *r_in, const uint16_t *cent,
 /* ------------------------------------------------------------------ */
 
 /* One round of b-bit group quantization of r, groups of B consecutive
- * channels of one token.  Scale = max|r| / qmax, stored as binary16; the
+ * channels of one token.  Scale = max|r| / qmax, stored in the scale format:
+ * scale_fmt 0 = binary16, 1 = FP8 E4M3 (Sec. 5 "Implementation"), each rounded to
+ * nearest even and saturated at the format's largest finite value; the
  * STORED scale is the one divided by, so that encode and decode agree.
  * q = round-half-even(r / scale) clamped to [-qmax, qmax].
  * The quantized part is removed from r in place: r <- r - scale*q (one fma),
  * which is what the next round sees.
- * q_out [N][d] signed levels; scales_out [N][d/B] binary16 bits. */
-void qvgo_quant_round(int64_t N, int d, int B, int bits, float *r,
+ * q_out [N][d] signed levels; scales_out [N][d/B]: binary16 bits, or the E4M3
+ * code in the low byte. */
+static float scale_store(float s32, int scale_fmt, uint16_t *stored) {
+    if (scale_fmt == 1) {
+        if (s32 > 448.0f) s32 = 448.0f;                /* largest finite E4M3 */
+        uint8_t c = qvgo_f32_to_e4m3(s32);
+        *stored = c;
+        return qvgo_e4m3_to_f32(c);
+    }
+    if (s32 > 65504.0f) s32 = 65504.0f;                /* largest finite binary16 */
+    *stored = qvgo_f32_to_f16(s32);
+    return qvgo_f16_to_f32(*stored);
+}
+static float scale_load(uint16_t stored, int scale_fmt) {
+    return scale_fmt == 1 ? qvgo_e4m3_to_f32((uint8_t)stored) : qvgo_f16_to_f32(stored);
+}
+
+void qvgo_quant_round(int64_t N, int d, int B, int bits, int scale_fmt, float *r,
                       int8_t *q_out, uint16_t *scales_out) {
     const float qmax = (float)((1 << (bits - 1)) - 1);
     const int G = d / B;
@@ -200,11 +246,7 @@ void qvgo_quant_round(int64_t N, int d, int B, int bits, float *r,
             int8_t *qg = q_out + n * d + (int64_t)g * B;
             float m = 0.0f;
             for (int i = 0; i < B; ++i) { float a = fabsf(rg[i]); if (a > m) m = a; }
-            float s32 = m / qmax;
-            if (s32 > 65504.0f) s32 = 65504.0f;            /* largest finite binary16 */
-            uint16_t sh = qvgo_f32_to_f16(s32);
-            scales_out[n * G + g] = sh;
-            float s = qvgo_f16_to_f32(sh);
+            float s = scale_store(m / qmax, scale_fmt, &scales_out[n * G + g]);
             if (s == 0.0f) { for (int i = 0; i < B; ++i) qg[i] = 0; continue; }
             float inv = 1.0f / s;
             for (int i = 0; i < B; ++i) {
@@ -261,9 +303,9 @@ void qvgo_unpack(int64_t n_elems, int bits, const uint8_t *packed, int8_t *q) {
  *          tokens of its own input residual, rounded to bf16
  * I        Lloyd iterations (I = 0: one assign pass against the start centroids)
  * cent_out [S][K][d] bf16, ids_out [S][N]
- * codes_out [N][T][d*b/8], scales_out [N][T][d/B] binary16
+ * codes_out [N][T][d*b/8], scales_out [N][T][d/B] (see qvgo_quant_round)
  * resid_out (nullable) [N][d] fp32: what remains after all rounds */
-void qvgo_encode_unit(int64_t N, int d, int K, int B, int S, int T, int bits, int I,
+void qvgo_encode_unit(int64_t N, int d, int K, int B, int S, int T, int bits, int scale_fmt, int I,
                       const uint16_t *x, const uint16_t *init, const int32_t *init_idx,
                       uint16_t *cent_out, uint8_t *ids_out,
                       uint8_t *codes_out, uint16_t *scales_out, float *resid_out) {
@@ -292,7 +334,7 @@ void qvgo_encode_unit(int64_t N, int d, int K, int B, int S, int T, int bits, in
         float *t = r; r = r2; r2 = t;
     }
     for (int t = 0; t < T; ++t) {
-        qvgo_quant_round(N, d, B, bits, r, q, sc);
+        qvgo_quant_round(N, d, B, bits, scale_fmt, r, q, sc);
         for (int64_t n = 0; n < N; ++n) {
             qvgo_pack(d, bits, q + n * d, codes_out + (n * T + t) * cb);
             memcpy(scales_out + (n * T + t) * G, sc + n * G, (size_t)G * 2);
@@ -304,17 +346,17 @@ void qvgo_encode_unit(int64_t N, int d, int K, int B, int S, int T, int bits, in
 
 /* Same as above but the centroids are given and kept (no Lloyd update):
  * assignment, residual, quantization rounds.  S = 1 only. */
-void qvgo_encode_given_centroids(int64_t N, int d, int K, int B, int T, int bits,
+void qvgo_encode_given_centroids(int64_t N, int d, int K, int B, int T, int bits, int scale_fmt,
                                  const uint16_t *x, const uint16_t *cent,
                                  uint8_t *ids_out, uint8_t *codes_out, uint16_t *scales_out) {
     uint16_t *cdump = (uint16_t *)malloc((size_t)K * d * 2);
-    qvgo_encode_unit(N, d, K, B, 1, T, bits, 0, x, cent, NULL, cdump, ids_out,
+    qvgo_encode_unit(N, d, K, B, 1, T, bits, scale_fmt, 0, x, cent, NULL, cdump, ids_out,
                      codes_out, scales_out, NULL);
     free(cdump);
 }
 
 /* Same, with the assignment given too: residual and quantization rounds. */
-void qvgo_encode_given_ids(int64_t N, int d, int B, int T, int bits,
+void qvgo_encode_given_ids(int64_t N, int d, int B, int T, int bits, int scale_fmt,
                            const uint16_t *x, const uint16_t *cent, const uint8_t *ids,
                            uint8_t *codes_out, uint16_t *scales_out) {
     const int G = d / B, cb = d * bits / 8;
@@ -325,7 +367,7 @@ void qvgo_encode_given_ids(int64_t N, int d, int B, int T, int bits,
     for (int64_t i = 0; i < N * d; ++i) r[i] = qvgo_bf16_to_f32(x[i]);
     qvgo_residual(N, d, r, cent, ids, r2);
     for (int t = 0; t < T; ++t) {
-        qvgo_quant_round(N, d, B, bits, r2, q, sc);
+        qvgo_quant_round(N, d, B, bits, scale_fmt, r2, q, sc);
         for (int64_t n = 0; n < N; ++n) {
             qvgo_pack(d, bits, q + n * d, codes_out + (n * T + t) * cb);
             memcpy(scales_out + (n * T + t) * G, sc + n * G, (size_t)G * 2);
@@ -343,7 +385,7 @@ void qvgo_encode_given_ids(int64_t N, int d, int B, int T, int bits,
  * round once to bf16.
  * cent [S][K][d], ids [S][N], codes [N][T][d*b/8], scales [N][T][d/B].
  * out_bf16 [N][d]; out_f32 (nullable) the value before the final rounding. */
-void qvgo_decode_unit(int64_t N, int d, int K, int B, int S, int T, int bits,
+void qvgo_decode_unit(int64_t N, int d, int K, int B, int S, int T, int bits, int scale_fmt,
                       const uint16_t *cent, const uint8_t *ids, const uint8_t *codes,
                       const uint16_t *scales, uint16_t *out_bf16, float *out_f32) {
     const int G = d / B, cb = d * bits / 8;
@@ -361,7 +403,7 @@ void qvgo_decode_unit(int64_t N, int d, int K, int B, int S, int T, int bits,
         for (int t = 0; t < T; ++t) {
             qvgo_unpack(d, bits, codes + (n * T + t) * cb, q);
             for (int ch = 0; ch < d; ++ch) {
-                float s = qvgo_f16_to_f32(scales[(n * T + t) * G + ch / B]);
+                float s = scale_load(scales[(n * T + t) * G + ch / B], scale_fmt);
                 acc[ch] = fmaf(s, (float)q[ch], acc[ch]);
             }
         }
@@ -426,26 +468,26 @@ double qvgo_chunk_bytes(int64_t N, int d, int K, int B, int S, int T, int bits,
 /* batched drivers: independent (head, K-or-V) units in parallel      */
 /* ------------------------------------------------------------------ */
 
-void qvgo_encode_batch(int H, int64_t N, int d, int K, int B, int S, int T, int bits, int I,
+void qvgo_encode_batch(int H, int64_t N, int d, int K, int B, int S, int T, int bits, int scale_fmt, int I,
                        const uint16_t *x, const uint16_t *init,
                        uint16_t *cent_out, uint8_t *ids_out,
                        uint8_t *codes_out, uint16_t *scales_out) {
     const int G = d / B, cb = d * bits / 8;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int h = 0; h < H; ++h)
-        qvgo_encode_unit(N, d, K, B, S, T, bits, I,
+        qvgo_encode_unit(N, d, K, B, S, T, bits, scale_fmt, I,
                          x + (int64_t)h * N * d, init + (int64_t)h * S * K * d, NULL,
                          cent_out + (int64_t)h * S * K * d, ids_out + (int64_t)h * S * N,
                          codes_out + (int64_t)h * N * T * cb, scales_out + (int64_t)h * N * T * G, NULL);
 }
 
-void qvgo_decode_batch(int H, int64_t N, int d, int K, int B, int S, int T, int bits,
+void qvgo_decode_batch(int H, int64_t N, int d, int K, int B, int S, int T, int bits, int scale_fmt,
                        const uint16_t *cent, const uint8_t *ids, const uint8_t *codes,
                        const uint16_t *scales, uint16_t *out_bf16) {
     const int G = d / B, cb = d * bits / 8;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int h = 0; h < H; ++h)
-        qvgo_decode_unit(N, d, K, B, S, T, bits,
+        qvgo_decode_unit(N, d, K, B, S, T, bits, scale_fmt,
                          cent + (int64_t)h * S * K * d, ids + (int64_t)h * S * N,
                          codes + (int64_t)h * N * T * cb, scales + (int64_t)h * N * T * G,
                          out_bf16 + (int64_t)h * N * d, NULL);

@@ -44,6 +44,10 @@ def lib():
         _lib.qvgo_f16_to_f32.argtypes = [C.c_uint16]
         _lib.qvgo_f32_to_f16.restype = C.c_uint16
         _lib.qvgo_f32_to_f16.argtypes = [C.c_float]
+        _lib.qvgo_e4m3_to_f32.restype = C.c_float
+        _lib.qvgo_e4m3_to_f32.argtypes = [C.c_uint8]
+        _lib.qvgo_f32_to_e4m3.restype = C.c_uint8
+        _lib.qvgo_f32_to_e4m3.argtypes = [C.c_float]
         _lib.qvgo_chunk_bytes.restype = C.c_double
         _lib.qvgo_chunk_bytes.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                           C.c_int, C.c_double, C.c_double]
@@ -97,6 +101,31 @@ def f32_to_f16(x) -> np.ndarray:
     for i in range(xf.size):
         of[i] = L.qvgo_f32_to_f16(float(xf[i]))
     return out
+
+
+def e4m3_to_f32(codes) -> np.ndarray:
+    """FP8 E4M3 codes (uint8) -> float32 (exact)."""
+    L = lib()
+    codes = _c(codes, np.uint8)
+    out = np.empty(codes.shape, np.float32)
+    cf, of = codes.ravel(), out.ravel()
+    for i in range(cf.size):
+        of[i] = L.qvgo_e4m3_to_f32(int(cf[i]))
+    return out
+
+
+def f32_to_e4m3(x) -> np.ndarray:
+    """float32 -> FP8 E4M3 code, nearest even, saturating at 448."""
+    L = lib()
+    x = _c(x, np.float32)
+    out = np.empty(x.shape, np.uint8)
+    xf, of = x.ravel(), out.ravel()
+    for i in range(xf.size):
+        of[i] = L.qvgo_f32_to_e4m3(float(xf[i]))
+    return out
+
+
+SCALE_F16, SCALE_E4M3 = 0, 1
 
 
 # ---------------------------------------------------------------- k-means (Sec. 4.1)
@@ -153,12 +182,13 @@ def residual(r, cent, ids):
 
 
 # ---------------------------------------------------------------- quantization (Eq. 1-2)
-def quant_round(r, B, bits=2):
-    """One round of group quantization. -> (q int8 [N,d], scales f16 bits [N,d/B], r_after)."""
+def quant_round(r, B, bits=2, scale_fmt=0):
+    """One round of group quantization. -> (q int8 [N,d], scales [N,d/B] uint16: f16 bits, or the
+    E4M3 code when scale_fmt == SCALE_E4M3; r_after)."""
     r = np.array(r, dtype=np.float32, order="C", copy=True)
     N, d = r.shape
     q = np.empty((N, d), np.int8); sc = np.empty((N, d // B), np.uint16)
-    lib().qvgo_quant_round(C.c_int64(N), d, B, bits, _p(r, np.float32), _p(q, np.int8),
+    lib().qvgo_quant_round(C.c_int64(N), d, B, bits, scale_fmt, _p(r, np.float32), _p(q, np.int8),
                            _p(sc, np.uint16))
     return q, sc, r
 
@@ -179,7 +209,7 @@ def unpack(packed, bits=2):
 
 
 # ---------------------------------------------------------------- encode / decode (Sec. 4.2)
-def encode_unit(x, K, B, S, T, iters, init=None, init_idx=None, bits=2, want_resid=False):
+def encode_unit(x, K, B, S, T, iters, init=None, init_idx=None, bits=2, want_resid=False, scale_fmt=0):
     """Encode one chunk of one head.  x [N,d] bf16 bits.
     init [S,K,d] bf16 bits, or init_idx [K] token indices (see the C comment).
     -> dict(cent [S,K,d], ids [S,N], codes [N,T,d*bits/8], scales [N,T,d/B], resid?)"""
@@ -193,7 +223,7 @@ def encode_unit(x, K, B, S, T, iters, init=None, init_idx=None, bits=2, want_res
     cent = np.empty((S, K, d), np.uint16); ids = np.empty((S, N), np.uint8)
     codes = np.empty((N, T, d * bits // 8), np.uint8); sc = np.empty((N, T, d // B), np.uint16)
     resid = np.empty((N, d), np.float32) if want_resid else None
-    lib().qvgo_encode_unit(C.c_int64(N), d, K, B, S, T, bits, iters, _p(x, np.uint16),
+    lib().qvgo_encode_unit(C.c_int64(N), d, K, B, S, T, bits, scale_fmt, iters, _p(x, np.uint16),
                            _p(init, np.uint16), _p(init_idx, np.int32), _p(cent, np.uint16),
                            _p(ids, np.uint8), _p(codes, np.uint8), _p(sc, np.uint16),
                            _p(resid, np.float32))
@@ -203,28 +233,28 @@ def encode_unit(x, K, B, S, T, iters, init=None, init_idx=None, bits=2, want_res
     return out
 
 
-def encode_given_centroids(x, cent, B, T, bits=2):
+def encode_given_centroids(x, cent, B, T, bits=2, scale_fmt=0):
     x = _c(x, np.uint16); cent = _c(cent, np.uint16)
     N, d = x.shape; K = cent.shape[0]
     ids = np.empty(N, np.uint8)
     codes = np.empty((N, T, d * bits // 8), np.uint8); sc = np.empty((N, T, d // B), np.uint16)
-    lib().qvgo_encode_given_centroids(C.c_int64(N), d, K, B, T, bits, _p(x, np.uint16),
+    lib().qvgo_encode_given_centroids(C.c_int64(N), d, K, B, T, bits, scale_fmt, _p(x, np.uint16),
                                       _p(cent, np.uint16), _p(ids, np.uint8),
                                       _p(codes, np.uint8), _p(sc, np.uint16))
     return dict(ids=ids, codes=codes, scales=sc)
 
 
-def encode_given_ids(x, cent, ids, B, T, bits=2):
+def encode_given_ids(x, cent, ids, B, T, bits=2, scale_fmt=0):
     x = _c(x, np.uint16); cent = _c(cent, np.uint16); ids = _c(ids, np.uint8)
     N, d = x.shape
     codes = np.empty((N, T, d * bits // 8), np.uint8); sc = np.empty((N, T, d // B), np.uint16)
-    lib().qvgo_encode_given_ids(C.c_int64(N), d, B, T, bits, _p(x, np.uint16),
+    lib().qvgo_encode_given_ids(C.c_int64(N), d, B, T, bits, scale_fmt, _p(x, np.uint16),
                                 _p(cent, np.uint16), _p(ids, np.uint8),
                                 _p(codes, np.uint8), _p(sc, np.uint16))
     return dict(codes=codes, scales=sc)
 
 
-def decode_unit(cent, ids, codes, scales, B, bits=2, want_f32=False):
+def decode_unit(cent, ids, codes, scales, B, bits=2, want_f32=False, scale_fmt=0):
     """Eq. 7 replay.  cent [S,K,d] (or [K,d]), ids [S,N] (or [N]). -> bf16 bits [N,d]."""
     cent = _c(cent, np.uint16); ids = _c(ids, np.uint8)
     codes = _c(codes, np.uint8); scales = _c(scales, np.uint16)
@@ -236,7 +266,7 @@ def decode_unit(cent, ids, codes, scales, B, bits=2, want_f32=False):
     N, T = codes.shape[0], codes.shape[1]
     out = np.empty((N, d), np.uint16)
     f32 = np.empty((N, d), np.float32) if want_f32 else None
-    lib().qvgo_decode_unit(C.c_int64(N), d, K, B, S, T, bits, _p(cent, np.uint16),
+    lib().qvgo_decode_unit(C.c_int64(N), d, K, B, S, T, bits, scale_fmt, _p(cent, np.uint16),
                            _p(ids, np.uint8), _p(codes, np.uint8), _p(scales, np.uint16),
                            _p(out, np.uint16), _p(f32, np.float32))
     return (out, f32) if want_f32 else out
@@ -257,26 +287,26 @@ def attention(q, k, v, scale=None, want_lse=False):
 
 
 # ---------------------------------------------------------------- batched (H independent units)
-def encode_batch(x, init, K, B, T, iters, S=1, bits=2):
+def encode_batch(x, init, K, B, T, iters, S=1, bits=2, scale_fmt=0):
     """x [H,N,d] bf16 bits, init [H,S,K,d] (or [H,K,d] when S == 1)."""
     x = _c(x, np.uint16); init = _c(init, np.uint16)
     H, N, d = x.shape
     init = init.reshape(H, S, K, d)
     cent = np.empty((H, S, K, d), np.uint16); ids = np.empty((H, S, N), np.uint8)
     codes = np.empty((H, N, T, d * bits // 8), np.uint8); sc = np.empty((H, N, T, d // B), np.uint16)
-    lib().qvgo_encode_batch(H, C.c_int64(N), d, K, B, S, T, bits, iters, _p(x, np.uint16),
+    lib().qvgo_encode_batch(H, C.c_int64(N), d, K, B, S, T, bits, scale_fmt, iters, _p(x, np.uint16),
                             _p(init, np.uint16), _p(cent, np.uint16), _p(ids, np.uint8),
                             _p(codes, np.uint8), _p(sc, np.uint16))
     return dict(cent=cent, ids=ids, codes=codes, scales=sc)
 
 
-def decode_batch(cent, ids, codes, scales, B, bits=2):
+def decode_batch(cent, ids, codes, scales, B, bits=2, scale_fmt=0):
     cent = _c(cent, np.uint16); ids = _c(ids, np.uint8)
     codes = _c(codes, np.uint8); scales = _c(scales, np.uint16)
     H, S, K, d = cent.shape
     N, T = codes.shape[1], codes.shape[2]
     out = np.empty((H, N, d), np.uint16)
-    lib().qvgo_decode_batch(H, C.c_int64(N), d, K, B, S, T, bits, _p(cent, np.uint16),
+    lib().qvgo_decode_batch(H, C.c_int64(N), d, K, B, S, T, bits, scale_fmt, _p(cent, np.uint16),
                             _p(ids, np.uint8), _p(codes, np.uint8), _p(scales, np.uint16),
                             _p(out, np.uint16))
     return out

@@ -63,3 +63,42 @@ def test_pack_unpack_roundtrip(rng):
     assert np.array_equal(O.unpack(O.pack(q, 2), 2), q)
     q4 = rng.integers(-7, 8, size=(5, 128)).astype(np.int8)
     assert np.array_equal(O.unpack(O.pack(q4, 4), 4), q4)
+
+
+# ---- FP8 E4M3 (the scale format of Sec. 5 "Implementation"), pinned to torch.float8_e4m3fn ----
+def test_e4m3_decode_all_codes_matches_torch():
+    codes = np.arange(256, dtype=np.uint8)
+    want = torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()
+    got = O.e4m3_to_f32(codes)
+    assert ((got == want) | (np.isnan(got) & np.isnan(want))).all()
+    # the layout's landmarks, by hand: smallest subnormal, smallest normal, one, largest finite
+    assert got[0x01] == 2.0 ** -9 and got[0x08] == 2.0 ** -6 and got[0x38] == 1.0 and got[0x7E] == 448.0
+    assert np.isnan(got[0x7F]) and got[0x80 | 0x38] == -1.0
+
+
+def test_e4m3_encode_rne_matches_torch_in_range(rng):
+    # random values over the whole range, every exact midpoint between neighbouring codes (ties)
+    # and points just off the midpoints
+    codes = np.arange(0, 0x7E, dtype=np.uint8)
+    lo = O.e4m3_to_f32(codes).astype(np.float64)
+    hi = O.e4m3_to_f32(codes + 1).astype(np.float64)
+    mid = ((lo + hi) / 2).astype(np.float32)                       # exact in fp32
+    x = np.concatenate([
+        np.exp(rng.uniform(np.log(2.0 ** -11), np.log(448.0), 20000)).astype(np.float32),
+        mid, np.nextafter(mid, np.float32(0)), np.nextafter(mid, np.float32(1e9)),
+        lo.astype(np.float32), np.array([0.0, 448.0, 2.0 ** -10, 2.0 ** -11], np.float32)])
+    x = x[x <= 448.0]
+    want = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(O.f32_to_e4m3(x), want)
+    assert np.array_equal(O.f32_to_e4m3(-x[x > 2.0 ** -10]), want[x > 2.0 ** -10] | 0x80)
+    # ties go to the even code: 1.0625 lies between 1.0 (0x38) and 1.125 (0x39)
+    assert O.f32_to_e4m3(np.array([1.0625, 1.1875], np.float32)).tolist() == [0x38, 0x3A]
+    # half of the smallest subnormal is a tie with zero and goes to zero
+    assert O.f32_to_e4m3(np.array([2.0 ** -10, np.nextafter(np.float32(2.0 ** -10), np.float32(1))],
+                                  np.float32)).tolist() == [0, 1]
+
+
+def test_e4m3_encode_saturates_beyond_448():
+    x = np.array([448.0, 449.0, 464.0, 480.0, 1e6, 3e38], np.float32)
+    assert (O.f32_to_e4m3(x) == 0x7E).all()
+    assert (O.f32_to_e4m3(-x) == 0xFE).all()

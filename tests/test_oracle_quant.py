@@ -35,6 +35,78 @@ def test_quant_round_scale_codes_and_eq3_bound(rng, B, bits):
     assert (np.abs(np.clip(np.rint(u), -qmax, qmax) - q) <= (np.abs(u - np.rint(u)) > 0.499)).all()
 
 
+def _e4m3(codes):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(codes, np.uint8)).view(torch.float8_e4m3fn).float().numpy()
+
+
+@pytest.mark.parametrize("B,bits", [(16, 2), (64, 2), (128, 2), (16, 4), (64, 4)])
+def test_quant_round_with_e4m3_scales(rng, B, bits):
+    """Sec. 5 "Implementation": per-group scales stored as FP8 E4M3.  The stored code is torch's
+    conversion of max|r| / qmax; the levels are the nearest integers to r / (decoded scale),
+    clamped; the error bound of Eq. 3 holds up to the slack a scale rounded DOWN leaves."""
+    import torch
+    N, d = 64, 128
+    qmax = 2 ** (bits - 1) - 1
+    r = (rng.standard_normal((N, d)) * rng.lognormal(0, 1.5, (N, 1))).astype(np.float32)
+    r[3] *= 1e-4                                            # scales in the subnormal range and zero
+    r[5, :B] = 0.0
+    q, sc, r_after = O.quant_round(r, B, bits, scale_fmt=O.SCALE_E4M3)
+    assert sc.max() <= 0x7E                                 # a code in the low byte, never NaN
+    gmax = np.abs(r).reshape(N, d // B, B).max(-1)
+    want = torch.from_numpy(np.minimum(gmax / np.float32(qmax), np.float32(448.0))).to(torch.float8_e4m3fn)
+    assert np.array_equal(sc.astype(np.uint8), want.view(torch.uint8).numpy())
+    s = _e4m3(sc.astype(np.uint8))
+    s_el = np.repeat(s, B, axis=1)
+    assert q.min() >= -qmax and q.max() <= qmax
+    assert (q[np.repeat(s == 0, B, axis=1)] == 0).all()
+    recon = s_el.astype(np.float64) * q
+    assert np.allclose(r.astype(np.float64) - recon, r_after, rtol=0, atol=1e-6 * np.abs(r).max())
+    slack = np.maximum(np.repeat(gmax - qmax * s, B, axis=1), 0)
+    assert (np.abs(r_after) <= s_el / 2 * (1 + 1e-6) + slack).all()
+    u = r.astype(np.float64) / np.where(s_el == 0, 1, s_el)
+    assert (np.abs(np.clip(np.rint(u), -qmax, qmax) - q) <= (np.abs(u - np.rint(u)) > 0.499)).all()
+
+
+def test_e4m3_scale_saturates_and_levels_clamp():
+    r = np.zeros((1, 16), np.float32)
+    r[0, :4] = [1000.0, -700.0, 300.0, 100.0]
+    q, sc, ra = O.quant_round(r, 16, 2, scale_fmt=O.SCALE_E4M3)
+    assert sc[0, 0] == 0x7E                                  # 448
+    assert q[0, :4].tolist() == [1, -1, 1, 0]                # 2.2 -> clamp 1, -1.6 -> -1, 0.67 -> 1, 0.22 -> 0
+    assert ra[0, :4].tolist() == [552.0, -252.0, -148.0, 100.0]
+    # 4 bit: max 70 -> scale 10 (exact in E4M3), 26 -> 2.6 -> 3, 25 -> 2.5 -> 2 (tie to even)
+    r = np.zeros((1, 16), np.float32)
+    r[0, :3] = [70.0, 26.0, 25.0]
+    q, sc, _ = O.quant_round(r, 16, 4, scale_fmt=O.SCALE_E4M3)
+    assert _e4m3(sc.astype(np.uint8))[0, 0] == 10.0 and q[0, :3].tolist() == [7, 3, 2]
+
+
+@pytest.mark.parametrize("bits,fmt", [(2, 1), (4, 0), (4, 1)])
+def test_encode_decode_replay_in_the_other_formats(rng, bits, fmt):
+    """decode(encode(x)) = x - (what the last round left), for 4-bit levels and E4M3 scales: the
+    replay of Eq. 7 in fp64 from the stored integers, against the oracle's fp32 replay and the
+    residual the encoder reports."""
+    N, d, K, B, T = 96, 128, 8, 32, 2
+    x = f32_to_bf16_bits_torch((rng.standard_normal((N, d)) * 2).astype(np.float32))
+    init = x[rng.permutation(N)[:K]]
+    enc = O.encode_unit(x, K, B, 1, T, 2, init=init[None], bits=bits, scale_fmt=fmt, want_resid=True)
+    xhat, f32 = O.decode_unit(enc["cent"], enc["ids"], enc["codes"], enc["scales"], B, bits=bits,
+                              want_f32=True, scale_fmt=fmt)
+    s = _e4m3(enc["scales"].astype(np.uint8)) if fmt else _f16(enc["scales"])
+    qv = O.unpack(enc["codes"], bits).astype(np.float64)            # [N,T,d]
+    recon = bits_to_f32(enc["cent"][0][enc["ids"][0]]).astype(np.float64)
+    for t in range(T):
+        recon += np.repeat(s[:, t], B, axis=1).astype(np.float64) * qv[:, t]
+    assert np.allclose(recon, f32, rtol=0, atol=2e-6 * np.abs(recon).max())
+    assert np.allclose(bits_to_f32(x).astype(np.float64) - recon, enc["resid"], rtol=0,
+                       atol=4e-6 * np.abs(recon).max())
+    assert np.array_equal(xhat, f32_to_bf16_bits_torch(f32))
+    # a second round can only shrink what is left, whatever the format
+    e1 = O.encode_unit(x, K, B, 1, 1, 2, init=init[None], bits=bits, scale_fmt=fmt, want_resid=True)
+    assert (np.abs(enc["resid"]) <= np.abs(e1["resid"]) + 1e-7).all()
+
+
 def test_quant_zero_group_and_ties_to_even():
     r = np.zeros((1, 32), np.float32)
     q, sc, ra = O.quant_round(r, 16, 2)
