@@ -31,6 +31,12 @@
  *                                       level q in {-1,0,1} (Eq. 2, b = 2) as 2-bit two's
  *                                       complement: 0b00 = 0, 0b01 = +1, 0b11 = -1 (0b10 unused)
  *   scales    [N][T][d/B]       f16     per group of B consecutive channels
+ * Format variants (Sec. 5 "Implementation"): with bits = 4 (INT4) the levels are -7..7 as 4-bit
+ * two's complement, codes [N][T][d/2], channel 2i+j in bits 4j..4j+3 of byte i; with
+ * scale_format = QVG_SCALE_E4M3 a scale is one byte in the OCP FP8 E4M3 layout (1 sign, 4
+ * exponent bits with bias 7, 3 mantissa bits; largest finite value 448, no infinity, subnormals
+ * m/8 * 2^-6), scales [N][T][d/B] uint8; the encoder never writes the NaN code 0x7F, and a
+ * decoder that meets it reads 480.  E4M3 scale arrays need no alignment.
  * A cache of several chunks concatenates ids/codes/scales along N and keeps one
  * centroid table per chunk: centroids [n_chunks][K][d].
  *
@@ -66,11 +72,15 @@ typedef struct qvg_params {
     int32_t head_dim;        /* d: 128                                                  */
     int32_t n_clusters;      /* K: 1..256, ids are uint8 (Sec. 5: K = 256)              */
     int32_t group_size;      /* B: 16, 32, 64 or 128 consecutive channels of one token  */
-    int32_t n_stages;        /* T: 1..8 rounds of 2-bit quantization of the residual    */
-    int32_t bits;            /* 2                                                       */
+    int32_t n_stages;        /* T: 1..8 rounds of b-bit quantization of the residual    */
+    int32_t bits;            /* b: 2 or 4 bits per level (Sec. 5: INT2 / INT4)          */
     int32_t n_smooth_stages; /* S: 1..4 k-means smoothing rounds (QVG: 1, QVG-Pro: 4)        */
     int32_t kmeans_iters;    /* I >= 0 Lloyd iterations before the final assignment     */
+    int32_t scale_format;    /* QVG_SCALE_F16 or QVG_SCALE_E4M3 (Sec. 5 "Implementation") */
 } qvg_params;
+
+#define QVG_SCALE_F16  0
+#define QVG_SCALE_E4M3 1
 
 /* which_entry values for qvg_workspace_bytes */
 #define QVG_ENTRY_ENCODE 0
@@ -96,9 +106,10 @@ typedef struct qvg_params {
  *                  and table, and pass the cache's tokens and table elements per unit.
  *   workspace      qvg_workspace_bytes(p, QVG_ENTRY_ENCODE, N, 0) bytes (a few KB per unit when I == 0)
  * n_tokens in 0 .. 2^20.  n_tokens == 0 only copies the centroids.
- * Rounding rules that fix the stored integers: a group's scale is max|r| (b = 2
- * gives qmax = 1), saturated at 65504 and rounded to f16; q = round-half-even(r * (1/scale))
- * with 1/scale one correctly rounded fp32 division, clamped to [-1, 1]; a zero scale gives
+ * Rounding rules that fix the stored integers: a group's scale is max|r| / qmax (one fp32
+ * division; qmax = 2^(b-1) - 1, so 1 for b = 2), saturated at the scale format's largest finite
+ * value (65504 or 448) and rounded to nearest even; q = round-half-even(r * (1/scale))
+ * with 1/scale one correctly rounded fp32 division, clamped to [-qmax, qmax]; a zero scale gives
  * q = 0; the next round sees fma(-scale, q, r).  Assignment: smallest squared Euclidean
  * distance, the lowest index among exactly equal ones; a centroid is the mean of its
  * members summed in token order in fp64, rounded to fp32 then to bf16; an empty group

@@ -18,6 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libqvg.so")
 _lib = None
 
 ENTRY_ENCODE, ENTRY_DECODE, ENTRY_ATTN, ENTRY_KMEANS_UPDATE, ENTRY_KMEANS_ASSIGN = 0, 1, 2, 3, 4
+SCALE_F16, SCALE_E4M3 = 0, 1
 
 EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_attn_decode", "qvg_kmeans_assign",
            "qvg_kmeans_update", "qvg_workspace_bytes", "qvg_compressed_bytes",
@@ -27,7 +28,7 @@ EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_attn_decode", "qvg_kmeans_assi
 class QvgParams(C.Structure):
     _fields_ = [("n_heads", C.c_int32), ("head_dim", C.c_int32), ("n_clusters", C.c_int32),
                 ("group_size", C.c_int32), ("n_stages", C.c_int32), ("bits", C.c_int32),
-                ("n_smooth_stages", C.c_int32), ("kmeans_iters", C.c_int32)]
+                ("n_smooth_stages", C.c_int32), ("kmeans_iters", C.c_int32), ("scale_format", C.c_int32)]
 
 
 class QvgError(RuntimeError):
@@ -75,9 +76,9 @@ def status_string(status: int) -> str:
 
 
 def make_params(n_heads, n_clusters, group_size, n_stages, kmeans_iters=0, head_dim=128, bits=2,
-                n_smooth_stages=1) -> QvgParams:
+                n_smooth_stages=1, scale_format=SCALE_F16) -> QvgParams:
     return QvgParams(n_heads, head_dim, n_clusters, group_size, n_stages, bits, n_smooth_stages,
-                     kmeans_iters)
+                     kmeans_iters, scale_format)
 
 
 def workspace_bytes(p: QvgParams, entry: int, n_tokens: int, n_q: int = 0) -> int:
@@ -119,17 +120,27 @@ def _view3(x, name):
 @dataclass
 class Encoded:
     """Stored form of one chunk (or of a cache of chunks) for H units.  With n_smooth = S > 1
-    smoothing stages the tables are [H, n_chunks, S, K, d] and a token has S ids: [H, N, S]."""
+    smoothing stages the tables are [H, n_chunks, S, K, d] and a token has S ids: [H, N, S].
+    The formats are read off the tensors: 4-bit levels have d/2 code bytes per round, FP8 E4M3
+    scales are a uint8 tensor."""
     centroids: torch.Tensor   # [H, n_chunks, K, d] bf16
     ids: torch.Tensor         # [H, N] uint8
-    codes: torch.Tensor       # [H, N, T, d/4] uint8
-    scales: torch.Tensor      # [H, N, T, d/B] float16
+    codes: torch.Tensor       # [H, N, T, d*bits/8] uint8
+    scales: torch.Tensor      # [H, N, T, d/B] float16, or uint8 (E4M3)
     chunk_len: int
     n_smooth: int = 1
 
+    @property
+    def bits(self) -> int:
+        return self.codes.shape[3] * 8 // self.centroids.shape[-1]
+
+    @property
+    def scale_format(self) -> int:
+        return SCALE_E4M3 if self.scales.dtype == torch.uint8 else SCALE_F16
+
 
 def alloc_cache(n_heads, n_tokens, chunk_len, n_clusters, group_size, n_stages, head_dim=128,
-                device="cuda", n_smooth=1) -> Encoded:
+                device="cuda", n_smooth=1, bits=2, scale_format=SCALE_F16) -> Encoded:
     """Uninitialised storage for a cache of n_tokens tokens per unit in chunks of chunk_len."""
     n_chunks = max(1, -(-n_tokens // chunk_len))
     S = n_smooth
@@ -138,18 +149,18 @@ def alloc_cache(n_heads, n_tokens, chunk_len, n_clusters, group_size, n_stages, 
     return Encoded(
         torch.empty(cshape, dtype=torch.bfloat16, device=device),
         torch.empty(ishape, dtype=torch.uint8, device=device),
-        torch.empty(n_heads, n_tokens, n_stages, head_dim // 4, dtype=torch.uint8, device=device),
-        torch.empty(n_heads, n_tokens, n_stages, head_dim // group_size, dtype=torch.float16,
-                    device=device),
+        torch.empty(n_heads, n_tokens, n_stages, head_dim * bits // 8, dtype=torch.uint8, device=device),
+        torch.empty(n_heads, n_tokens, n_stages, head_dim // group_size,
+                    dtype=torch.uint8 if scale_format == SCALE_E4M3 else torch.float16, device=device),
         chunk_len, S)
 
 
 def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: Encoded | None = None,
-                 chunk_index: int = 0, workspace=None) -> Encoded:
+                 chunk_index: int = 0, workspace=None, bits=2, scale_format=SCALE_F16) -> Encoded:
     """qvg_encode_chunk.  x [H, N, d] bf16, init_centroids [H, K, d] bf16, or [H, S, K, d] for S
     smoothing stages.  Without `cache` a one-chunk cache is allocated and returned; with it, the
     chunk is written in place at chunk_index (tokens chunk_index*chunk_len ...), using the output
-    strides."""
+    strides; the cache's formats then apply (bits and scale_format describe a new cache)."""
     sh, st_ = _view3(x, "x")
     H, N, d = x.shape
     _check(init_centroids, torch.bfloat16, "init_centroids")
@@ -157,7 +168,9 @@ def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: E
     K = init_centroids.shape[-2]
     S = init_centroids.shape[1] if init_centroids.dim() == 4 else 1
     if cache is None:
-        cache = alloc_cache(H, N, max(N, 1), K, group_size, n_stages, d, x.device, n_smooth=S)
+        cache = alloc_cache(H, N, max(N, 1), K, group_size, n_stages, d, x.device, n_smooth=S, bits=bits,
+                            scale_format=scale_format)
+    bits, scale_format = cache.bits, cache.scale_format
     n_total = cache.ids.shape[1]
     n_chunks = cache.centroids.shape[1]
     off = chunk_index * cache.chunk_len
@@ -166,7 +179,8 @@ def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: E
     if cache.codes.shape[2] != n_stages or cache.scales.shape[3] != d // group_size or \
             cache.centroids.shape[-2] != K or cache.ids.shape[0] != H or cache.n_smooth != S:
         raise ValueError("cache was allocated for other parameters")
-    p = make_params(H, K, group_size, n_stages, kmeans_iters, head_dim=d, n_smooth_stages=S)
+    p = make_params(H, K, group_size, n_stages, kmeans_iters, head_dim=d, n_smooth_stages=S, bits=bits,
+                    scale_format=scale_format)
     need = workspace_bytes(p, ENTRY_ENCODE, N)
     if need and (workspace is None or workspace.numel() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
@@ -175,8 +189,8 @@ def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: E
         C.byref(p), N, _ptr(x), sh, st_, _ptr(init_centroids),
         C.c_void_p(cache.centroids.data_ptr() + chunk_index * S * K * d * 2), n_chunks * S * K * d,
         C.c_void_p(cache.ids.data_ptr() + off * S),
-        C.c_void_p(cache.codes.data_ptr() + off * T * (d // 4)),
-        C.c_void_p(cache.scales.data_ptr() + off * T * G * 2), n_total,
+        C.c_void_p(cache.codes.data_ptr() + off * T * (d * bits // 8)),
+        C.c_void_p(cache.scales.data_ptr() + off * T * G * cache.scales.element_size()), n_total,
         _ptr(workspace) if need else None, need, _stream())
     if st != 0:
         raise QvgError(st, "qvg_encode_chunk")
@@ -188,12 +202,13 @@ def decode(enc: Encoded, out=None) -> torch.Tensor:
     H, N = enc.ids.shape[:2]
     K, d = enc.centroids.shape[-2:]
     T, G = enc.codes.shape[2], enc.scales.shape[3]
-    p = make_params(H, K, d // G, T, 0, head_dim=d, n_smooth_stages=enc.n_smooth)
+    p = make_params(H, K, d // G, T, 0, head_dim=d, n_smooth_stages=enc.n_smooth, bits=enc.bits,
+                    scale_format=enc.scale_format)
     if out is None:
         out = torch.empty(H, N, d, dtype=torch.bfloat16, device=enc.ids.device)
     sh, st_ = _view3(out, "out")
     for t, dt, nm in ((enc.centroids, torch.bfloat16, "centroids"), (enc.ids, torch.uint8, "ids"),
-                      (enc.codes, torch.uint8, "codes"), (enc.scales, torch.float16, "scales")):
+                      (enc.codes, torch.uint8, "codes"), (enc.scales, enc.scales.dtype, "scales")):
         _check(t, dt, nm)
         if not t.is_contiguous():
             raise ValueError(f"{nm} must be contiguous")
@@ -212,10 +227,11 @@ def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, o
     Nk = k.ids.shape[1]
     K = k.centroids.shape[-2]
     T, G = k.codes.shape[2], k.scales.shape[3]
-    if (v.ids.shape, v.codes.shape, v.scales.shape, v.centroids.shape, v.chunk_len, v.n_smooth) != \
-            (k.ids.shape, k.codes.shape, k.scales.shape, k.centroids.shape, k.chunk_len, k.n_smooth):
+    if (v.ids.shape, v.codes.shape, v.scales.shape, v.scales.dtype, v.centroids.shape, v.chunk_len, v.n_smooth) != \
+            (k.ids.shape, k.codes.shape, k.scales.shape, k.scales.dtype, k.centroids.shape, k.chunk_len, k.n_smooth):
         raise ValueError("K and V caches must share shapes and parameters")
-    p = make_params(H, K, d // G, T, 0, head_dim=d, n_smooth_stages=k.n_smooth)
+    p = make_params(H, K, d // G, T, 0, head_dim=d, n_smooth_stages=k.n_smooth, bits=k.bits,
+                    scale_format=k.scale_format)
     if softmax_scale is None:
         softmax_scale = 1.0 / (d ** 0.5)
     if out is None:

@@ -22,13 +22,21 @@ int check_params(const qvg_params *p) {
     if (p->head_dim < 1 || p->n_smooth_stages < 1) return QVG_ERR_BAD_PARAM;
     if (p->group_size < 1 || p->head_dim % p->group_size != 0) return QVG_ERR_BAD_PARAM;
     if (p->bits != 2 && p->bits != 4) return QVG_ERR_BAD_PARAM;
+    if (p->scale_format != QVG_SCALE_F16 && p->scale_format != QVG_SCALE_E4M3) return QVG_ERR_BAD_PARAM;
     // valid in the paper, not built here
     if (p->head_dim != kHeadDim) return QVG_ERR_UNSUPPORTED;
-    if (p->bits != 2) return QVG_ERR_UNSUPPORTED;
     if (p->n_smooth_stages > kMaxSmooth) return QVG_ERR_UNSUPPORTED;
     const int B = p->group_size;
     if (B != 16 && B != 32 && B != 64 && B != 128) return QVG_ERR_UNSUPPORTED;
     return QVG_OK;
+}
+
+inline int format_of(const qvg_params *p) {
+    return (p->bits == 4 ? kFmtInt4 : 0) | (p->scale_format == QVG_SCALE_E4M3 ? kFmtE4M3 : 0);
+}
+// scale arrays: binary16 arrays follow the 16-byte rule, E4M3 bytes may start anywhere
+inline bool scales_aligned(const qvg_params *p, const void *sc) {
+    return p->scale_format == QVG_SCALE_E4M3 || aligned16(sc);
 }
 
 struct EncodeWs { size_t assign; size_t cent[2]; size_t perm; size_t offs; size_t resid[2]; size_t total; };
@@ -73,7 +81,7 @@ const char *qvg_status_string(int status) {
         case QVG_OK: return "ok";
         case QVG_ERR_NULL: return "a required pointer is NULL";
         case QVG_ERR_BAD_PARAM: return "a size or parameter is out of range";
-        case QVG_ERR_UNSUPPORTED: return "parameter combination not built (head_dim 128, 2 bits, one smoothing stage, group 16/32/64/128)";
+        case QVG_ERR_UNSUPPORTED: return "parameter combination not built (head_dim 128, up to 4 smoothing stages, group 16/32/64/128)";
         case QVG_ERR_WORKSPACE: return "workspace missing or too small";
         case QVG_ERR_ALIGN: return "pointer not 16-byte aligned or stride not a multiple of 8 elements";
         case QVG_ERR_LAUNCH: return "HIP runtime error while enqueuing";
@@ -113,7 +121,8 @@ int64_t qvg_compressed_bytes(const qvg_params *p, int64_t n_tokens) {
     if (n_tokens < 0) return QVG_ERR_BAD_PARAM;
     const int64_t d = p->head_dim, T = p->n_stages;
     const int64_t S = p->n_smooth_stages;
-    const int64_t per_token = T * (d * p->bits / 8 + 2 * (d / p->group_size)) + S;
+    const int64_t scale_bytes = p->scale_format == QVG_SCALE_E4M3 ? 1 : 2;
+    const int64_t per_token = T * (d * p->bits / 8 + scale_bytes * (d / p->group_size)) + S;
     return (int64_t)p->n_heads * (n_tokens * per_token + S * (int64_t)p->n_clusters * d * 2);
 }
 
@@ -193,8 +202,9 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
     if (n_tokens == 0) return copy_out(init_centroids);
     if (!x || !ids_out || !codes_out || !scales_out) return QVG_ERR_NULL;
     if ((st = check_view(x, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
-    if (!aligned16(codes_out) || !aligned16(scales_out)) return QVG_ERR_ALIGN;
+    if (!aligned16(codes_out) || !scales_aligned(p, scales_out)) return QVG_ERR_ALIGN;
     const int I = p->kmeans_iters;
+    const int fmt = format_of(p);
     const int S = p->n_smooth_stages;
     const EncodeWs w = encode_ws(p, n_tokens, true, I > 0 || S > 1, I > 0);
     if (!workspace || workspace_bytes < w.total) return QVG_ERR_WORKSPACE;
@@ -253,9 +263,19 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
             r.out = reinterpret_cast<bf16_t *>(ws + w.resid[stage & 1]); r.H = p->n_heads; r.K = p->n_clusters;
             if (launch_residual(r, s) != hipSuccess) return QVG_ERR_LAUNCH;
             xin = r.out; sh = n_tokens * kHeadDim; stt = kHeadDim;
-        } else {
+        } else if (fmt == 0) {
             a.cent = cur; a.codes = codes_out; a.scales = static_cast<f16_t *>(scales_out); a.fused = 1;
             if (launch_assign(a, s) != hipSuccess) return QVG_ERR_LAUNCH;
+        } else {
+            // the other stored formats: assignment, then the quantization kernel
+            a.cent = cur;
+            if (launch_assign(a, s) != hipSuccess) return QVG_ERR_LAUNCH;
+            QuantArgs q{};
+            q.x = xin; q.stride_head = sh; q.stride_token = stt; q.n_tokens = n_tokens; q.cent = cur;
+            q.ids = ids_out; q.ids_step = S; q.ids_off = stage; q.codes = codes_out; q.scales = scales_out;
+            q.out_stride = out_stride_head_tokens; q.H = p->n_heads; q.K = p->n_clusters; q.B = p->group_size;
+            q.T = p->n_stages; q.fmt = fmt;
+            if (launch_quantize(q, s) != hipSuccess) return QVG_ERR_LAUNCH;
         }
     }
     return QVG_OK;
@@ -270,7 +290,7 @@ int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, const v
     if (n_tokens == 0) return QVG_OK;
     if (!centroids || !ids || !codes || !scales || !x_out) return QVG_ERR_NULL;
     if ((st = check_view(x_out, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
-    if (!aligned16(centroids) || !aligned16(codes) || !aligned16(scales)) return QVG_ERR_ALIGN;
+    if (!aligned16(centroids) || !aligned16(codes) || !scales_aligned(p, scales)) return QVG_ERR_ALIGN;
     const int64_t n_chunks = (n_tokens + chunk_len - 1) / chunk_len;
     if (n_chunks > 0x7fffffff) return QVG_ERR_BAD_PARAM;
     DecodeArgs a{};
@@ -278,7 +298,7 @@ int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, const v
     a.scales = static_cast<const f16_t *>(scales); a.out = static_cast<bf16_t *>(x_out);
     a.n_tokens = n_tokens; a.chunk_len = chunk_len; a.n_chunks = (int)n_chunks;
     a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size; a.T = p->n_stages;
-    a.stride_head = stride_head; a.stride_token = stride_token; a.S = p->n_smooth_stages;
+    a.stride_head = stride_head; a.stride_token = stride_token; a.S = p->n_smooth_stages; a.fmt = format_of(p);
     return launch_decode(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
 }
 
@@ -298,7 +318,7 @@ int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q, int64_t n_k
         !v_codes || !v_scales)
         return QVG_ERR_NULL;
     if (!aligned16(q) || !aligned16(out) || !aligned16(k_centroids) || !aligned16(v_centroids) ||
-        !aligned16(k_codes) || !aligned16(v_codes) || !aligned16(k_scales) || !aligned16(v_scales))
+        !aligned16(k_codes) || !aligned16(v_codes) || !scales_aligned(p, k_scales) || !scales_aligned(p, v_scales))
         return QVG_ERR_ALIGN;
     const int64_t n_chunks = (n_kv_tokens + chunk_len - 1) / chunk_len;
     if (n_chunks > 0x7fffffff) return QVG_ERR_BAD_PARAM;
@@ -312,7 +332,7 @@ int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q, int64_t n_k
     a.k_scales = static_cast<const f16_t *>(k_scales);
     a.v_cent = static_cast<const bf16_t *>(v_centroids); a.v_ids = v_ids; a.v_codes = v_codes;
     a.v_scales = static_cast<const f16_t *>(v_scales);
-    a.S = p->n_smooth_stages;
+    a.S = p->n_smooth_stages; a.fmt = format_of(p);
     return launch_attn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
 }
 

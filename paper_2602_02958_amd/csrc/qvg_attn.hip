@@ -21,6 +21,8 @@
 // Two kernels: attn_kernel_staged (one smoothing stage, 1..4 quantization rounds, chunks that
 // start on 16-byte boundaries of the scale array: the measured path) and attn_kernel_direct
 // (everything else).
+#include <type_traits>
+
 #include "qvg_internal.hpp"
 
 namespace qvg {
@@ -37,7 +39,8 @@ constexpr size_t kAtSmem = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint16_t);
 
 struct CacheSide {                 // one of K / V, already offset to this unit
     const bf16_t *cent;            // [n_chunks][K][d]
-    const uint8_t *ids; const uint8_t *codes; const f16_t *scales;
+    const uint8_t *ids; const uint8_t *codes;
+    const uint8_t *scales;         // binary16 or E4M3 bytes, per the format
 };
 
 struct Tile {                      // one 64-token tile; tiles never straddle a chunk
@@ -84,7 +87,9 @@ __device__ __forceinline__ void load_ids(const CacheSide &s, const Tile &t, int 
     }
 }
 
-template <int T_, int TM, bool MULTI>
+// FMT: stored format (kFmt* bits); with 4-bit levels a thread's 8 channels of a round are one
+// 32-bit word, else one 16-bit word
+template <int T_, int TM, bool MULTI, int FMT>
 __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int tp, int c8, int T,
                                          int G, int g, int K, int S, const uint32_t id[2], Raw<TM> &r) {
     const bf16_t *cent = s.cent + (int64_t)t.chunk * S * K * kHeadDim;      // [S][K][d] of this chunk
@@ -100,8 +105,11 @@ __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int 
             for (int i = 0; i < 8; ++i) r.ci[e][i] = 0.0f;
         }
         if (ok) {
-            const uint16_t *cp = reinterpret_cast<const uint16_t *>(s.codes + (int64_t)n * T * 32) + c8;
-            const f16_t *sp = s.scales + (int64_t)n * T * G + g;
+            constexpr bool FP8 = (FMT & kFmtE4M3) != 0, I4 = (FMT & kFmtInt4) != 0;
+            typedef typename std::conditional<I4, uint32_t, uint16_t>::type code_t;
+            typedef typename std::conditional<FP8, uint8_t, f16_t>::type scale_t;
+            const code_t *cp = reinterpret_cast<const code_t *>(s.codes + (int64_t)n * T * (I4 ? 64 : 32)) + c8;
+            const scale_t *sp = reinterpret_cast<const scale_t *>(s.scales) + (int64_t)n * T * G + g;
 #pragma unroll
             for (int k = 0; k < TM; ++k)
                 if (k < T) { r.code[e][k] = cp[k * 16]; r.sc[e][k] = sp[k * G]; }
@@ -122,7 +130,7 @@ __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int 
 
 // fp32 decoded values of the thread's two tokens (tokens that do not exist decode to zero
 // because their codes, scales and centroid were loaded as zero)
-template <int T_, int TM, bool MULTI = false>
+template <int T_, int TM, bool MULTI = false, int FMT = 0>
 __device__ __forceinline__ void dequant2x8(const Raw<TM> &r, int T, float *accA, float *accB) {
     if (MULTI) {
 #pragma unroll
@@ -130,6 +138,22 @@ __device__ __forceinline__ void dequant2x8(const Raw<TM> &r, int T, float *accA,
     } else {
         unpack_bf16x8(r.cen[0], accA);
         unpack_bf16x8(r.cen[1], accB);
+    }
+    if (FMT != 0) {
+        constexpr bool FP8 = (FMT & kFmtE4M3) != 0;
+#pragma unroll
+        for (int t = 0; t < TM; ++t) {
+            if (t < T) {
+                const float sa = scale_bits_to_f32<FP8>(r.sc[0][t]), sb = scale_bits_to_f32<FP8>(r.sc[1][t]);
+                if (FMT & kFmtInt4) {
+                    add_stage_int4(accA, r.code[0][t], sa);
+                    add_stage_int4(accB, r.code[1][t], sb);
+                } else {
+                    add_last_stage_of_two_rows(accA, accB, r.code[0][t] | (r.code[1][t] << 16), 0.5f * sa, 0.5f * sb);
+                }
+            }
+        }
+        return;
     }
 #pragma unroll
     for (int t = 0; t + 1 < TM; t += 2) {
@@ -157,8 +181,9 @@ __device__ __forceinline__ void dequant2x8(const Raw<TM> &r, int T, float *accA,
 // memory (many small loads).  Used for more than 4 quantization rounds (their staging area would
 // not fit in LDS), for chunks whose scale records do not start on 16-byte boundaries, and for
 // several smoothing stages (the rows of all stages are added as they arrive).
-template <int T_, bool MULTI>   // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages).
+template <int T_, bool MULTI, int FMT>   // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages).
                                 // MULTI: more than one smoothing stage (a.S tables and id bytes)
+                                // FMT: stored format (kFmt* bits)
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_kernel_direct(AttnArgs a) {
     constexpr int TM = T_ > 0 ? T_ : kMaxStages;
@@ -177,11 +202,12 @@ void attn_kernel_direct(AttnArgs a) {
     const uint32_t kmax = (uint32_t)K - 1u;
 
     CacheSide ks, vs;
-    ks.ids = a.k_ids + (int64_t)h * a.n_kv * S;  ks.codes = a.k_codes + (int64_t)h * a.n_kv * T * 32;
-    ks.scales = a.k_scales + (int64_t)h * a.n_kv * T * G;
+    constexpr int kCodeBytes = (FMT & kFmtInt4) ? 64 : 32, kScaleBytes = (FMT & kFmtE4M3) ? 1 : 2;
+    ks.ids = a.k_ids + (int64_t)h * a.n_kv * S;  ks.codes = a.k_codes + (int64_t)h * a.n_kv * T * kCodeBytes;
+    ks.scales = reinterpret_cast<const uint8_t *>(a.k_scales) + (int64_t)h * a.n_kv * T * G * kScaleBytes;
     ks.cent = a.k_cent + (int64_t)h * a.n_chunks * S * K * kHeadDim;
-    vs.ids = a.v_ids + (int64_t)h * a.n_kv * S;  vs.codes = a.v_codes + (int64_t)h * a.n_kv * T * 32;
-    vs.scales = a.v_scales + (int64_t)h * a.n_kv * T * G;
+    vs.ids = a.v_ids + (int64_t)h * a.n_kv * S;  vs.codes = a.v_codes + (int64_t)h * a.n_kv * T * kCodeBytes;
+    vs.scales = reinterpret_cast<const uint8_t *>(a.v_scales) + (int64_t)h * a.n_kv * T * G * kScaleBytes;
     vs.cent = a.v_cent + (int64_t)h * a.n_chunks * S * K * kHeadDim;
 
     // decode mapping: 16 adjacent lanes cover the 16 channel chunks of a token pair (coalesced)
@@ -212,11 +238,11 @@ void attn_kernel_direct(AttnArgs a) {
 
     auto decode_to_lds = [&](const Raw<TM> &rk, const Raw<TM> &rv, int buf) {
         float accA[8], accB[8];
-        dequant2x8<T_, TM, MULTI>(rk, T, accA, accB);
+        dequant2x8<T_, TM, MULTI, FMT>(rk, T, accA, accB);
         uint16_t *kt = Kt + buf * kKtElems;
         *reinterpret_cast<uint4 *>(kt + (tok + 0) * kKtPitch + c8 * 8) = pack_bf16x8(accA);
         *reinterpret_cast<uint4 *>(kt + (tok + 1) * kKtPitch + c8 * 8) = pack_bf16x8(accB);
-        dequant2x8<T_, TM, MULTI>(rv, T, accA, accB);
+        dequant2x8<T_, TM, MULTI, FMT>(rv, T, accA, accB);
         uint16_t *vt = Vt + buf * kVtElems + v_off;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
@@ -236,8 +262,8 @@ void attn_kernel_direct(AttnArgs a) {
     Raw<TM> rk, rv;
     load_ids(ks, cur, tp, kmax, S, idk);
     load_ids(vs, cur, tp, kmax, S, idv);
-    load_raw<T_, TM, MULTI>(ks, cur, tp, c8, T, G, g, K, S, idk, rk);
-    load_raw<T_, TM, MULTI>(vs, cur, tp, c8, T, G, g, K, S, idv, rv);
+    load_raw<T_, TM, MULTI, FMT>(ks, cur, tp, c8, T, G, g, K, S, idk, rk);
+    load_raw<T_, TM, MULTI, FMT>(vs, cur, tp, c8, T, G, g, K, S, idv, rv);
     load_ids(ks, nxt, tp, kmax, S, idk);
     load_ids(vs, nxt, tp, kmax, S, idv);
     decode_to_lds(rk, rv, 0);
@@ -247,8 +273,8 @@ void attn_kernel_direct(AttnArgs a) {
     while (true) {
         // raw data of the next tile (consumed at the end of this iteration), ids of the one after
         if (nxt.valid) {
-            load_raw<T_, TM, MULTI>(ks, nxt, tp, c8, T, G, g, K, S, idk, rk);
-            load_raw<T_, TM, MULTI>(vs, nxt, tp, c8, T, G, g, K, S, idv, rv);
+            load_raw<T_, TM, MULTI, FMT>(ks, nxt, tp, c8, T, G, g, K, S, idk, rk);
+            load_raw<T_, TM, MULTI, FMT>(vs, nxt, tp, c8, T, G, g, K, S, idv, rv);
             load_ids(ks, nn, tp, kmax, S, idk);
             load_ids(vs, nn, tp, kmax, S, idv);
         }
@@ -715,20 +741,31 @@ static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int T_, bool MULTI>
+template <int T_, bool MULTI, int FMT = 0>
 static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_, MULTI>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_, MULTI, FMT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmem);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
-    hipLaunchKernelGGL((attn_kernel_direct<T_, MULTI>), grid, dim3(kAtThreads), kAtSmem, s, a);
+    hipLaunchKernelGGL((attn_kernel_direct<T_, MULTI, FMT>), grid, dim3(kAtThreads), kAtSmem, s, a);
     return hipGetLastError();
+}
+
+// the other stored formats run on the general kernel
+template <int FMT>
+static hipError_t launch_attn_fmt(const AttnArgs &a, hipStream_t s) {
+    if (a.S > 1) return launch_attn_t<0, true, FMT>(a, s);
+    if (a.T == 1) return launch_attn_t<1, false, FMT>(a, s);       // the paper's single round
+    return launch_attn_t<0, false, FMT>(a, s);
 }
 
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     if (a.n_q == 0) return hipSuccess;
-    switch (a.T) {
-        default: break;
+    switch (a.fmt) {
+        case 0: break;
+        case kFmtE4M3: return launch_attn_fmt<kFmtE4M3>(a, s);
+        case kFmtInt4: return launch_attn_fmt<kFmtInt4>(a, s);
+        default: return launch_attn_fmt<kFmtInt4 | kFmtE4M3>(a, s);
     }
     // the staged kernel fetches scales in 16-byte pieces: every chunk must start on one
     const bool aligned = (a.chunk_len % 8 == 0) || a.n_chunks == 1;

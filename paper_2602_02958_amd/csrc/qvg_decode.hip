@@ -19,6 +19,8 @@
 // Mapping: 16 lanes per token, 8 channels (one 16-byte store) per lane, so that a
 // wavefront's store instruction covers 4 whole token rows = 1 KB contiguous.  A workgroup of
 // 1024 threads walks its slice of a chunk 256 tokens per pass, 4 token rows per thread.
+#include <type_traits>
+
 #include "qvg_internal.hpp"
 
 namespace qvg {
@@ -33,13 +35,21 @@ constexpr int kXcds = 8;                         // MI355X: 8 XCDs, each with it
 // whose tokens all exist (no per-row predication).  tab: the chunk's centroid table in LDS.
 // SM: 1 = one smoothing stage, table in LDS; 2 = S stages, all tables in LDS (tab);
 //     3 = S stages, tables read from global memory (cg).
-template <int T_, bool CHECK, int SM>
+// FMT: stored format (kFmt* bits).  4-bit levels: a lane's 8 channels of a round are one 32-bit
+// word (16 words per token and round, so the offsets below are the same in units of the word).
+template <int T_, bool CHECK, int SM, int FMT>
 __device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t n_left, uint32_t lane16,
                                             uint32_t G, uint32_t gidx, uint32_t kmax,
-                                            const uint8_t *ids_b, const uint16_t *codes_b,
-                                            const f16_t *scales_b, const bf16_t *tab, const bf16_t *cg,
+                                            const uint8_t *ids_b, const void *codes_v,
+                                            const void *scales_v, const bf16_t *tab, const bf16_t *cg,
                                             bf16_t *out_b, int64_t stride_token) {
     constexpr int TM = T_ > 0 ? T_ : kMaxStages;
+    constexpr bool FP8 = (FMT & kFmtE4M3) != 0, I4 = (FMT & kFmtInt4) != 0;
+    typedef typename std::conditional<I4, uint32_t, uint16_t>::type code_t;
+    typedef typename std::conditional<FP8, uint8_t, f16_t>::type scale_t;
+    const code_t *codes_b = static_cast<const code_t *>(codes_v);
+    const scale_t *scales_b = static_cast<const scale_t *>(scales_v);
+    auto hs = [](uint32_t bits) { return 0.5f * scale_bits_to_f32<FP8>(bits); };
     uint32_t idv[kDecUnroll];
     uint32_t code[kDecUnroll][TM];
     uint32_t sc[kDecUnroll][TM];
@@ -59,7 +69,7 @@ __device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t
                 idv[u] = 0u;
                 for (int st = 0; st < S; ++st) idv[u] |= (uint32_t)ids_b[ln * (uint32_t)S + st] << (8 * st);
             }
-            const uint32_t co = ln * (uint32_t)T * 16u + lane16;       // in uint16 units
+            const uint32_t co = ln * (uint32_t)T * 16u + lane16;       // in code words
             const uint32_t so = ln * (uint32_t)T * G + gidx;
 #pragma unroll
             for (int t = 0; t < TM; ++t)
@@ -90,26 +100,34 @@ __device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t
                 }
             }
         }
+        if (I4) {
 #pragma unroll
-        for (int t = 0; t + 1 < TM; t += 2) {
-            if (t + 1 < T) {
-                add_two_stages(accA, code[up][t] | (code[up][t + 1] << 16),
-                               half_scale(sc[up][t]), half_scale(sc[up][t + 1]));
-                add_two_stages(accB, code[up + 1][t] | (code[up + 1][t + 1] << 16),
-                               half_scale(sc[up + 1][t]), half_scale(sc[up + 1][t + 1]));
+            for (int t = 0; t < TM; ++t)
+                if (t < T) {
+                    add_stage_int4(accA, code[up][t], scale_bits_to_f32<FP8>(sc[up][t]));
+                    add_stage_int4(accB, code[up + 1][t], scale_bits_to_f32<FP8>(sc[up + 1][t]));
+                }
+        } else {
+#pragma unroll
+            for (int t = 0; t + 1 < TM; t += 2) {
+                if (t + 1 < T) {
+                    add_two_stages(accA, code[up][t] | (code[up][t + 1] << 16), hs(sc[up][t]), hs(sc[up][t + 1]));
+                    add_two_stages(accB, code[up + 1][t] | (code[up + 1][t + 1] << 16),
+                                   hs(sc[up + 1][t]), hs(sc[up + 1][t + 1]));
+                }
             }
-        }
-        if (T_ > 0) {
-            if (T_ & 1)
-                add_last_stage_of_two_rows(accA, accB, code[up][TM - 1] | (code[up + 1][TM - 1] << 16),
-                                           half_scale(sc[up][TM - 1]), half_scale(sc[up + 1][TM - 1]));
-        } else if (T & 1) {
-            // run-time stage count: the last odd stage sits at index T-1
+            if (T_ > 0) {
+                if (T_ & 1)
+                    add_last_stage_of_two_rows(accA, accB, code[up][TM - 1] | (code[up + 1][TM - 1] << 16),
+                                               hs(sc[up][TM - 1]), hs(sc[up + 1][TM - 1]));
+            } else if (T & 1) {
+                // run-time stage count: the last odd stage sits at index T-1
 #pragma unroll
-            for (int t = 0; t < TM; t += 2)
-                if (t == T - 1)
-                    add_last_stage_of_two_rows(accA, accB, code[up][t] | (code[up + 1][t] << 16),
-                                               half_scale(sc[up][t]), half_scale(sc[up + 1][t]));
+                for (int t = 0; t < TM; t += 2)
+                    if (t == T - 1)
+                        add_last_stage_of_two_rows(accA, accB, code[up][t] | (code[up + 1][t] << 16),
+                                                   hs(sc[up][t]), hs(sc[up + 1][t]));
+            }
         }
         if (ok[up])
             *reinterpret_cast<uint4 *>(out_b + ((int64_t)(ln0 + up * kDecRows) * stride_token + lane16 * 8)) =
@@ -122,7 +140,7 @@ __device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t
 
 // One workgroup = one slice of one chunk of one unit.  It stages the chunk's centroid table
 // in LDS once (the only shared operand) and then streams its tokens.
-template <int T_, int SM>   // T_ > 0: compile-time stage count; T_ == 0: run-time.  SM: see decode_pass
+template <int T_, int SM, int FMT>   // T_ > 0: compile-time stage count; T_ == 0: run-time.  SM, FMT: see decode_pass
 __global__ __launch_bounds__(kDecThreads)
 void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, int blocks_per_xcd) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -159,22 +177,22 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
     // per-block base pointers (uniform), per-lane 32-bit offsets
     const int64_t hn0 = (int64_t)h * a.n_tokens + tok0;
     const uint8_t *ids_b = a.ids + hn0 * S;
-    const uint16_t *codes_b = reinterpret_cast<const uint16_t *>(a.codes + hn0 * T * 32);
-    const f16_t *scales_b = a.scales + hn0 * T * G;
+    const void *codes_b = a.codes + hn0 * T * ((FMT & kFmtInt4) ? 64 : 32);
+    const void *scales_b = reinterpret_cast<const uint8_t *>(a.scales) + hn0 * T * G * ((FMT & kFmtE4M3) ? 1 : 2);
     bf16_t *out_b = a.out + (int64_t)h * a.stride_head + tok0 * a.stride_token;
     const uint32_t kmax = (uint32_t)a.K - 1u;
 
     for (uint32_t first = 0; first < n_left; first += kDecTokPerIter) {
         if (first + kDecTokPerIter <= n_left)
-            decode_pass<T_, false, SM>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
+            decode_pass<T_, false, SM, FMT>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
                                        tab, cg, out_b, a.stride_token);
         else
-            decode_pass<T_, true, SM>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
+            decode_pass<T_, true, SM, FMT>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
                                       tab, cg, out_b, a.stride_token);
     }
 }
 
-template <int T_, int SM>
+template <int T_, int SM, int FMT = 0>
 static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
     // slices per chunk: enough workgroups to fill 256 CUs x 2 twice over, but as few as possible
     // beyond that (every workgroup re-reads the chunk's table; measured flat from 512 to 4096)
@@ -191,16 +209,33 @@ static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
     if (nb > 0x7fffffff - kXcds) return hipErrorInvalidValue;
     const int bpx = (int)((nb + kXcds - 1) / kXcds);
     const size_t smem = (SM == 3) ? 16 : (size_t)(SM == 1 ? 1 : a.S) * a.K * kHeadDim * sizeof(bf16_t);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<T_, SM>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<T_, SM, FMT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((decode_kernel<T_, SM>), dim3((unsigned)(bpx * kXcds)), dim3(kDecThreads), smem, s, a,
+    hipLaunchKernelGGL((decode_kernel<T_, SM, FMT>), dim3((unsigned)(bpx * kXcds)), dim3(kDecThreads), smem, s, a,
                        (int)slices, (uint32_t)slice_len, (int)nb, bpx);
     return hipGetLastError();
 }
 
+// the other stored formats: run-time round count, except the paper's own 2-bit / E4M3 / one round
+template <int FMT>
+static hipError_t launch_decode_fmt(const DecodeArgs &a, hipStream_t s) {
+    if (a.S > 1) {
+        if ((size_t)a.S * a.K * kHeadDim * sizeof(bf16_t) <= 65536) return launch_decode_t<0, 2, FMT>(a, s);
+        return launch_decode_t<0, 3, FMT>(a, s);
+    }
+    if (FMT == kFmtE4M3 && a.T == 1) return launch_decode_t<(FMT == kFmtE4M3 ? 1 : 0), 1, FMT>(a, s);
+    return launch_decode_t<0, 1, FMT>(a, s);
+}
+
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s) {
     if (a.n_tokens == 0) return hipSuccess;
+    switch (a.fmt) {
+        case 0: break;
+        case kFmtE4M3: return launch_decode_fmt<kFmtE4M3>(a, s);
+        case kFmtInt4: return launch_decode_fmt<kFmtInt4>(a, s);
+        default: return launch_decode_fmt<kFmtInt4 | kFmtE4M3>(a, s);
+    }
     if (a.S > 1) {
         // several smoothing stages: every stage's table in LDS when they fit in 64 KB together
         if ((size_t)a.S * a.K * kHeadDim * sizeof(bf16_t) <= 65536) return launch_decode_t<0, 2>(a, s);

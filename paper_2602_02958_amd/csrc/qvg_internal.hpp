@@ -87,12 +87,46 @@ __device__ __forceinline__ void add_last_stage_of_two_rows(float *accA, float *a
     }
 }
 
+// ---- stored formats ---------------------------------------------------------
+// fmt bit 0: scales are FP8 E4M3 bytes (else binary16); bit 1: 4-bit levels (else 2-bit)
+constexpr int kFmtE4M3 = 1;
+constexpr int kFmtInt4 = 2;
+
+// E4M3 code of a non-negative scale (1 sign, 4 exponent bits with bias 7, 3 mantissa bits,
+// largest finite 448, subnormals m/8 * 2^-6) -> fp32, exact
+__device__ __forceinline__ float e4m3_bits_to_f32(uint32_t b) {
+    const float normal = __uint_as_float(((b & 0x7fu) << 20) + (120u << 23));
+    return (b & 0x78u) ? normal : (float)(b & 7u) * 0x1p-9f;
+}
+// non-negative finite fp32 -> E4M3 code, round to nearest even, saturating at 448
+__device__ __forceinline__ uint32_t f32_to_e4m3_bits(float a) {
+    a = fminf(a, 448.0f);
+    uint32_t u = __float_as_uint(a);
+    u += 0x7ffffu + ((u >> 20) & 1u);                 // nearest even at 3 mantissa bits
+    const uint32_t normal = (u >> 20) - (120u << 3);
+    // below 2^-6 the grid is uniform with step 2^-9; 8 steps are the smallest normal, code 8
+    return (a < 0x1p-6f) ? (uint32_t)__builtin_rintf(a * 512.0f) : normal;
+}
+template <bool FP8>
+__device__ __forceinline__ float scale_bits_to_f32(uint32_t bits) {
+    return FP8 ? e4m3_bits_to_f32(bits) : f16_bits_to_f32(bits);
+}
+// eight 4-bit two's complement levels of w (channel i in bits 4i..4i+3): acc += s * q
+__device__ __forceinline__ void add_stage_int4(float *acc, uint32_t w, float s) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int q = ((int)(w << (28 - 4 * i))) >> 28;          // v_bfe_i32
+        acc[i] = __builtin_fmaf(s, (float)q, acc[i]);
+    }
+}
+
 // ---- launchers (each returns a hipError_t from hipGetLastError) -----------
 struct DecodeArgs {
     const bf16_t *cent; const uint8_t *ids; const uint8_t *codes; const f16_t *scales;
     bf16_t *out; int64_t n_tokens; int64_t chunk_len; int n_chunks; int H; int K; int B; int T;
     int64_t stride_head, stride_token;
     int S;      // smoothing stages: cent [H][n_chunks][S][K][d], ids [H][N][S]
+    int fmt;    // kFmt* bits; scales then points at bytes, codes rows are 64 B per round with 4-bit levels
 };
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 
@@ -130,12 +164,24 @@ struct ResidualArgs {
 };
 hipError_t launch_residual(const ResidualArgs &a, hipStream_t s);
 
+// Eq. 5 and the T rounds of Eq. 2 for a given assignment, for every stored format (the fused
+// assignment kernel covers 2-bit levels with binary16 scales only).
+struct QuantArgs {
+    const bf16_t *x; int64_t stride_head, stride_token; int64_t n_tokens;
+    const bf16_t *cent;                    // [H][K][d]
+    const uint8_t *ids; int ids_step, ids_off;
+    uint8_t *codes; void *scales; int64_t out_stride;     // tokens between units in ids / codes / scales
+    int H; int K; int B; int T; int fmt;
+};
+hipError_t launch_quantize(const QuantArgs &a, hipStream_t s);
+
 struct AttnArgs {
     const bf16_t *q; bf16_t *out; float *lse; int64_t n_q; int64_t n_kv; int64_t chunk_len;
     int n_chunks; int H; int K; int B; int T; float scale;
     const bf16_t *k_cent; const uint8_t *k_ids; const uint8_t *k_codes; const f16_t *k_scales;
     const bf16_t *v_cent; const uint8_t *v_ids; const uint8_t *v_codes; const f16_t *v_scales;
     int S;      // smoothing stages, layouts as in DecodeArgs
+    int fmt;    // kFmt* bits, as in DecodeArgs
 };
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
 

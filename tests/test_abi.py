@@ -37,17 +37,33 @@ def test_compressed_bytes_matches_format():
     assert B.compressed_bytes(p, 4680) == 24 * (4680 * 73 + 256 * 128 * 2)
     p = B.make_params(1, 64, 32, 3)
     assert B.compressed_bytes(p, 10) == 10 * 121 + 64 * 256
+    # the paper's own formats (Sec. 5): one round, FP8 scales; INT2 B=64 -> 32 + 2 + 1 bytes per
+    # token, INT4 QVG-Pro (S = 4, B = 16) -> 64 + 8 + 4
+    p = B.make_params(1, 256, 64, 1, scale_format=B.SCALE_E4M3)
+    assert B.compressed_bytes(p, 1000) == 1000 * 35 + 256 * 256
+    p = B.make_params(1, 256, 16, 1, bits=4, n_smooth_stages=4, scale_format=B.SCALE_E4M3)
+    assert B.compressed_bytes(p, 1000) == 1000 * 76 + 4 * 256 * 256
+
+
+def test_params_struct_layout():
+    # nine consecutive int32 fields, in the order of include/qvg.h
+    text = open(os.path.join(ROOT, "include", "qvg.h")).read()
+    body = text[text.index("typedef struct qvg_params {"):text.index("} qvg_params;")]
+    names = re.findall(r"int32_t\s+([a-z_]+);", body)
+    assert names == [f[0] for f in B.QvgParams._fields_]
+    assert C.sizeof(B.QvgParams) == 4 * len(names)
 
 
 @pytest.mark.parametrize("kw,status", [
     (dict(n_heads=0), -2), (dict(n_clusters=0), -2), (dict(n_clusters=257), -2),
     (dict(n_stages=0), -2), (dict(n_stages=9), -2), (dict(group_size=48), -2),
-    (dict(head_dim=64), -3), (dict(bits=4), -3), (dict(bits=3), -2),
+    (dict(head_dim=64), -3), (dict(bits=4), 0), (dict(bits=3), -2), (dict(bits=8), -2),
+    (dict(scale_format=1), 0), (dict(scale_format=2), -2), (dict(scale_format=-1), -2),
     (dict(n_smooth_stages=5), -3), (dict(n_smooth_stages=0), -2), (dict(group_size=8), -3), (dict(kmeans_iters=-1), -2),
 ])
 def test_parameter_validation(kw, status):
     base = dict(n_heads=2, n_clusters=16, group_size=64, n_stages=2, kmeans_iters=0,
-                head_dim=128, bits=2, n_smooth_stages=1)
+                head_dim=128, bits=2, n_smooth_stages=1, scale_format=0)
     base.update(kw)
     p = B.make_params(**base)
     out = C.c_size_t(0)
