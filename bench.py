@@ -208,22 +208,39 @@ def warm_start_supplement(torch, B, synth, wl):
     return out
 
 
-def pro_supplement(torch, B, synth, CONFIGS, S=4, group_size=16, n_stages=1, n_clusters=256):
-    """The paper's QVG-Pro preset (S = 4 smoothing stages, B = 16, one 2-bit round) on the cfg2
-    window: 24 units, 8 chunks of 4680 tokens, 4680 queries."""
+# The paper's four presets (Sec. 5 "Implementation"): one quantization round, K = 256, FP8 E4M3
+# scales; QVG = one smoothing stage with B = 64, QVG-Pro = four with B = 16; INT2 and INT4.
+PAPER_PRESETS = {
+    "qvg_int2": dict(S=1, group_size=64, bits=2), "qvg_pro_int2": dict(S=4, group_size=16, bits=2),
+    "qvg_int4": dict(S=1, group_size=64, bits=4), "qvg_pro_int4": dict(S=4, group_size=16, bits=4),
+}
+TABLE1_CHUNK_TOKENS = 34800     # the chunk length at which the stored sizes give Table 1's ratios
+
+
+def preset_supplement(torch, B, synth, CONFIGS, S=4, group_size=16, n_stages=1, n_clusters=256, bits=2,
+                      scale_format=1):
+    """One of the paper's presets on the cfg2 window: 24 units, 8 chunks of 4680 tokens, 4680
+    queries."""
     wl = CONFIGS["cfg2_window21"]
     dev = "cuda"
     heads, units, L, n = wl.heads, 2 * wl.heads, wl.chunk, wl.tokens_per_layer
-    cache = B.alloc_cache(units, n, L, n_clusters, group_size, n_stages, wl.head_dim, dev, n_smooth=S)
+    cache = B.alloc_cache(units, n, L, n_clusters, group_size, n_stages, wl.head_dim, dev, n_smooth=S, bits=bits,
+                          scale_format=scale_format)
     sk, sv = synth.MixtureStream(wl, heads, 0, dev), synth.MixtureStream(wl, heads, 1, dev)
     x = init = None
     for c in range(wl.n_chunks):
         x = torch.cat([sk.next_chunk(L), sv.next_chunk(L)], 0)
-        init = (torch.stack([synth.cold_start_centroids(x, n_clusters, seed=st) for st in range(S)], 1)
-                if c == 0 else cache.centroids[:, c - 1].contiguous())
+        if c > 0:
+            init = cache.centroids[:, c - 1].contiguous()
+        elif S > 1:
+            init = torch.stack([synth.cold_start_centroids(x, n_clusters, seed=st) for st in range(S)], 1)
+        else:
+            init = synth.cold_start_centroids(x, n_clusters, seed=0)
         B.encode_chunk(x, init, group_size, n_stages, 10 if c == 0 else 3, cache=cache, chunk_index=c)
-    out = {"preset": f"S={S} B={group_size} T={n_stages} K={n_clusters}", "units": units, "tokens": n}
-    p = B.make_params(units, n_clusters, group_size, n_stages, 3, n_smooth_stages=S)
+    out = {"preset": f"S={S} B={group_size} T={n_stages} K={n_clusters} bits={bits} "
+                     f"scales={'e4m3' if scale_format else 'f16'}", "units": units, "tokens": n}
+    p = B.make_params(units, n_clusters, group_size, n_stages, 3, n_smooth_stages=S, bits=bits,
+                      scale_format=scale_format)
     ws = torch.empty(B.workspace_bytes(p, B.ENTRY_ENCODE, L), dtype=torch.uint8, device=dev)
     fn = lambda: B.encode_chunk(x, init, group_size, n_stages, 3, cache=cache, chunk_index=wl.n_chunks - 1, workspace=ws)
     fn(); torch.cuda.synchronize()
@@ -233,8 +250,7 @@ def pro_supplement(torch, B, synth, CONFIGS, S=4, group_size=16, n_stages=1, n_c
     fn = lambda: B.decode(cache, out=dec)
     fn(); torch.cuda.synchronize()
     ms = _event_ms(fn, 10)
-    per_tok = n_stages * (wl.head_dim // 4 + 2 * wl.head_dim // group_size) + S
-    alg = units * n * (256 + per_tok) + units * wl.n_chunks * S * n_clusters * wl.head_dim * 2
+    alg = units * n * 256 + B.compressed_bytes(p, L) * wl.n_chunks
     out["decode"] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(units * n * 256 / ms / 1e6, 1),
                      "hbm_GBps_algorithmic": round(alg / ms / 1e6, 1)}
     q = synth.queries(wl, heads, wl.n_queries, dev)
@@ -246,9 +262,16 @@ def pro_supplement(torch, B, synth, CONFIGS, S=4, group_size=16, n_stages=1, n_c
     ms = _event_ms(fn, 3)
     flops = 4.0 * wl.n_queries * n * wl.head_dim * heads
     out["attn"] = {"ms": round(ms, 4), "TFLOPs": round(flops / ms / 1e9, 1)}
-    out["compression_ratio"] = round(units * n * 256 / B.compressed_bytes(
-        B.make_params(units, n_clusters, group_size, n_stages, 0, n_smooth_stages=S), L) / wl.n_chunks, 3)
+    out["compression_ratio"] = round(units * L * 256 / B.compressed_bytes(p, L), 3)
+    out["compression_ratio_at_table1_chunk"] = round(
+        units * TABLE1_CHUNK_TOKENS * 256 / B.compressed_bytes(p, TABLE1_CHUNK_TOKENS), 3)
+    xhat = dec[:, (wl.n_chunks - 1) * L:].float()
+    out["rel_l2_error_last_chunk"] = round(float((xhat - x.float()).norm() / x.float().norm()), 4)
     return out
+
+
+def presets_supplement(torch, B, synth, CONFIGS):
+    return {name: preset_supplement(torch, B, synth, CONFIGS, **kw) for name, kw in PAPER_PRESETS.items()}
 
 
 def run_only(args, torch, B, synth, workload, CONFIGS):
@@ -313,7 +336,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large", action="store_true")
     ap.add_argument("--only", default=None,
-                    choices=["decode", "encode", "attn", "copy", "large_decode", "large_encode", "pro"],
+                    choices=["decode", "encode", "attn", "copy", "large_decode", "large_encode", "presets"],
                     help="profiling aid: run just this part --steps times and print a short JSON "
                          "(copy = a plain device copy of 1 GiB, the reference the HBM counters "
                          "are scaled by)")
@@ -331,8 +354,8 @@ def main():
     B.lib()                                    # fail loudly if the HIP library is missing
     wl = CONFIGS[args.workload]
     torch.cuda.set_device(0)
-    if args.only == "pro":
-        print(json.dumps(pro_supplement(torch, B, synth, CONFIGS)))
+    if args.only == "presets":
+        print(json.dumps(presets_supplement(torch, B, synth, CONFIGS)))
         print(json.dumps(warm_start_supplement(torch, B, synth, wl)))
         return
     if args.only:
@@ -416,7 +439,7 @@ def main():
         except torch.OutOfMemoryError as e:     # a smaller card than the one this is written for
             result["large"] = {"error": str(e)[:200]}
     if not args.no_large:
-        result["qvg_pro"] = pro_supplement(torch, B, synth, CONFIGS)
+        result["paper_presets"] = presets_supplement(torch, B, synth, CONFIGS)
         result["warm_start"] = warm_start_supplement(torch, B, synth, wl)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl)

@@ -754,7 +754,7 @@ static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
 // the other stored formats run on the general kernel
 template <int FMT>
 static hipError_t launch_attn_fmt(const AttnArgs &a, hipStream_t s) {
-    if (a.S > 1) return launch_attn_t<0, true, FMT>(a, s);
+    if (a.S > 1) return a.T == 1 ? launch_attn_t<1, true, FMT>(a, s) : launch_attn_t<0, true, FMT>(a, s);
     if (a.T == 1) return launch_attn_t<1, false, FMT>(a, s);       // the paper's single round
     return launch_attn_t<0, false, FMT>(a, s);
 }
@@ -769,7 +769,8 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     }
     // the staged kernel fetches scales in 16-byte pieces: every chunk must start on one
     const bool aligned = (a.chunk_len % 8 == 0) || a.n_chunks == 1;
-    if (a.S > 1) return launch_attn_t<0, true>(a, s);      // several smoothing stages: the general kernel
+    // several smoothing stages: the general kernel (the paper's presets have one round)
+    if (a.S > 1) return a.T == 1 ? launch_attn_t<1, true>(a, s) : launch_attn_t<0, true>(a, s);
     if (!aligned || a.T > kStMaxT) return launch_attn_t<0, false>(a, s);
     switch (a.T) {
         case 1: return launch_attn_staged<1>(a, s);
