@@ -446,6 +446,43 @@ void qvgo_attention(int64_t Nq, int64_t Nk, int d, const uint16_t *q, const uint
     free(p);
 }
 
+/* Rotary position embedding applied to decoded keys.  Sec. 5 "Implementation" caches keys
+ * BEFORE the rotary embedding (they quantize better), so the attention read has to rotate each
+ * decoded key by its position.  The paper does not print the rotation; reading: the usual
+ * complex form on interleaved channel pairs (2i, 2i+1), angle given per token and pair by the
+ * caller as a (cos, sin) table in binary16:
+ *     y[2i]   = x[2i] cos - x[2i+1] sin        y[2i+1] = x[2i] sin + x[2i+1] cos
+ * on the bf16 decoded key, each output one fp32 product and one fma, rounded to bf16 (the
+ * type the attention contraction reads).
+ * k [N][d] bf16, rope [N][d/2][2] binary16 (cos, sin), out [N][d] bf16. */
+void qvgo_rope_keys(int64_t N, int d, const uint16_t *k, const uint16_t *rope, uint16_t *out) {
+    for (int64_t n = 0; n < N; ++n)
+        for (int i = 0; i < d / 2; ++i) {
+            float x0 = qvgo_bf16_to_f32(k[n * d + 2 * i]), x1 = qvgo_bf16_to_f32(k[n * d + 2 * i + 1]);
+            float c = qvgo_f16_to_f32(rope[(n * (d / 2) + i) * 2]);
+            float sn = qvgo_f16_to_f32(rope[(n * (d / 2) + i) * 2 + 1]);
+            float t0 = x1 * sn, t1 = x1 * c;
+            out[n * d + 2 * i] = qvgo_f32_to_bf16(fmaf(x0, c, -t0));
+            out[n * d + 2 * i + 1] = qvgo_f32_to_bf16(fmaf(x0, sn, t1));
+        }
+}
+
+/* Two attention results over DISJOINT key sets A and B (the compressed cache and the current
+ * chunk's own bf16 keys, Sec. 3.1: a chunk attends to the cached chunks and to itself) merged
+ * into the attention over their union, from the outputs and the log-sum-exp of the scores:
+ *     w_a = exp(lse_a - lse), w_b = exp(lse_b - lse), lse = log(exp(lse_a) + exp(lse_b)),
+ *     o = w_a o_a + w_b o_b.
+ * rows x d outputs in fp64, lse per row. */
+void qvgo_attn_merge(int64_t rows, int d, const double *oa, const double *lsea,
+                     const double *ob, const double *lseb, double *out, double *lse) {
+    for (int64_t r = 0; r < rows; ++r) {
+        double m = lsea[r] > lseb[r] ? lsea[r] : lseb[r];
+        double wa = exp(lsea[r] - m), wb = exp(lseb[r] - m), z = wa + wb;
+        for (int ch = 0; ch < d; ++ch) out[r * d + ch] = (wa * oa[r * d + ch] + wb * ob[r * d + ch]) / z;
+        if (lse) lse[r] = m + log(z);
+    }
+}
+
 /* ------------------------------------------------------------------ */
 /* storage size (Sec. 5: compression ratio, memory breakdown)         */
 /* ------------------------------------------------------------------ */

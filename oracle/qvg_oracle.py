@@ -286,6 +286,29 @@ def attention(q, k, v, scale=None, want_lse=False):
     return (out, lse) if want_lse else out
 
 
+def rope_keys(k, rope):
+    """Rotary embedding of decoded keys (pre-RoPE key caching, Sec. 5 "Implementation").
+    k [N,d] bf16 bits, rope [N,d/2,2] binary16 bits (cos, sin). -> bf16 bits [N,d]."""
+    k = _c(k, np.uint16); rope = _c(rope, np.uint16)
+    N, d = k.shape
+    assert rope.shape == (N, d // 2, 2)
+    out = np.empty((N, d), np.uint16)
+    lib().qvgo_rope_keys(C.c_int64(N), d, _p(k, np.uint16), _p(rope, np.uint16), _p(out, np.uint16))
+    return out
+
+
+def attn_merge(oa, lsea, ob, lseb):
+    """Attention over the union of two disjoint key sets from the two partial results.
+    oa, ob float64 [R,d]; lsea, lseb float64 [R]. -> (o [R,d], lse [R])."""
+    oa = _c(oa, np.float64); ob = _c(ob, np.float64)
+    lsea = _c(lsea, np.float64); lseb = _c(lseb, np.float64)
+    R, d = oa.shape
+    out = np.empty((R, d), np.float64); lse = np.empty(R, np.float64)
+    lib().qvgo_attn_merge(C.c_int64(R), d, _p(oa, np.float64), _p(lsea, np.float64), _p(ob, np.float64),
+                          _p(lseb, np.float64), _p(out, np.float64), _p(lse, np.float64))
+    return out, lse
+
+
 # ---------------------------------------------------------------- batched (H independent units)
 def encode_batch(x, init, K, B, T, iters, S=1, bits=2, scale_fmt=0):
     """x [H,N,d] bf16 bits, init [H,S,K,d] (or [H,K,d] when S == 1)."""
