@@ -274,6 +274,33 @@ def presets_supplement(torch, B, synth, CONFIGS):
     return {name: preset_supplement(torch, B, synth, CONFIGS, **kw) for name, kw in PAPER_PRESETS.items()}
 
 
+def integration_supplement(torch, B, s):
+    """Attention-side pieces of a generation step on the benchmark's own state: the fused
+    attention with the rotary embedding applied to the decoded keys (pre-RoPE key caching, Sec. 5
+    "Implementation"), and the merge with the current chunk's own attention result (Sec. 3.1)."""
+    wl = s.wl
+    n_kv = s.cache.ids.shape[1]
+    pos = torch.arange(n_kv, dtype=torch.float64, device="cuda")
+    freq = 10000.0 ** (-torch.arange(wl.head_dim // 2, dtype=torch.float64, device="cuda") / (wl.head_dim // 2))
+    ang = pos[:, None] * freq[None]
+    rope = torch.stack([ang.cos(), ang.sin()], -1).to(torch.float16).contiguous()
+    out = {}
+    fn = lambda: B.attn_decode(s.q, s.k, s.v, out=s.attn_out, k_rope=rope)
+    fn(); torch.cuda.synchronize()
+    ms = _event_ms(fn, 5)
+    flops = 4.0 * wl.n_queries * n_kv * wl.head_dim * wl.heads
+    out["attn_with_rope"] = {"ms": round(ms, 4), "TFLOPs": round(flops / ms / 1e9, 1)}
+    oa, la = B.attn_decode(s.q, s.k, s.v, want_lse=True)
+    ob, lb = oa.flip(1).contiguous(), la.flip(1).contiguous()
+    res = torch.empty_like(oa)
+    fn = lambda: B.attn_merge(oa, la, ob, lb, out=res)
+    fn(); torch.cuda.synchronize()
+    ms = _event_ms(fn, 20)
+    nbytes = oa.numel() * 2 * 3 + la.numel() * 4 * 2
+    out["merge"] = {"ms": round(ms, 5), "rows": int(la.numel()), "GBps_algorithmic": round(nbytes / ms / 1e6, 1)}
+    return out
+
+
 def run_only(args, torch, B, synth, workload, CONFIGS):
     """One part of the path, repeated: what rocprofv3 is pointed at."""
     dev = "cuda"
@@ -441,6 +468,7 @@ def main():
     if not args.no_large:
         result["paper_presets"] = presets_supplement(torch, B, synth, CONFIGS)
         result["warm_start"] = warm_start_supplement(torch, B, synth, wl)
+        result["attn_integration"] = integration_supplement(torch, B, s)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(result))

@@ -158,6 +158,48 @@ int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q_bf16,
                     void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * qvg_attn_decode with what a generation step needs around it (Sec. 3.1: a chunk attends to the
+ * cached chunks and to itself; Sec. 5 "Implementation": keys are cached BEFORE the rotary
+ * position embedding):
+ *   kv_capacity_tokens  the caches may be allocated for more tokens than they hold: unit h starts
+ *                       kv_capacity_tokens tokens (ids, codes, scales) and
+ *                       ceil(kv_capacity_tokens / chunk_len) tables (centroids) after unit h-1;
+ *                       only the first n_kv_tokens tokens are read.  0 = n_kv_tokens.  Attention
+ *                       of an earlier chunk's queries over a prefix of the cache (chunk-causal
+ *                       order) is a call with a smaller n_kv_tokens.
+ *   k_rope_f16          NULL, or [n_kv_tokens][d/2][2] f16 = (cos, sin) of the rotation angle of
+ *                       token n and channel pair i, shared by all units: every decoded key,
+ *                       rounded to bf16 as qvg_decode returns it, is rotated on interleaved pairs,
+ *                       y[2i] = x[2i] cos - x[2i+1] sin, y[2i+1] = x[2i] sin + x[2i+1] cos (one
+ *                       fp32 product and one fma each, then bf16), before the scores are taken.
+ *                       The queries arrive already rotated.  V is not rotated.
+ * Everything else as in qvg_attn_decode.
+ */
+int qvg_attn_decode_ex(const qvg_params *p, int64_t n_q, const void *q_bf16,
+                       int64_t n_kv_tokens, int64_t chunk_len, int64_t kv_capacity_tokens,
+                       const void *k_centroids, const uint8_t *k_ids, const uint8_t *k_codes,
+                       const void *k_scales,
+                       const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
+                       const void *v_scales,
+                       const void *k_rope_f16,
+                       float softmax_scale, void *out_bf16, float *lse_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Merge two attention results over DISJOINT key sets (the compressed cache, from
+ * qvg_attn_decode with lse_out, and the current chunk's own bf16 keys, from the model's
+ * attention kernel) into the attention over their union (Sec. 3.1):
+ *   lse = log(exp(lse_a) + exp(lse_b)),  out = exp(lse_a - lse) out_a + exp(lse_b - lse) out_b.
+ *   out_a, out_b, out  [n_rows][head_dim] bf16 contiguous (out may be out_a or out_b)
+ *   lse_a, lse_b       [n_rows] fp32 natural-log sum of exp of the scaled scores; at least one
+ *                      of the two must be finite in every row
+ *   lse_out            [n_rows] fp32 or NULL
+ */
+int qvg_attn_merge(int64_t n_rows, int32_t head_dim, const void *out_a_bf16, const float *lse_a,
+                   const void *out_b_bf16, const float *lse_b, void *out_bf16, float *lse_out,
+                   void *stream);
+
+/*
  * The two k-means steps on their own (Sec. 4.1), as the encoder runs them.
  * assign: ids_out[h][n] = index of the nearest centroid of unit h; workspace
  *         qvg_workspace_bytes(p, QVG_ENTRY_KMEANS_ASSIGN, N, 0) bytes.

@@ -20,7 +20,8 @@ _lib = None
 ENTRY_ENCODE, ENTRY_DECODE, ENTRY_ATTN, ENTRY_KMEANS_UPDATE, ENTRY_KMEANS_ASSIGN = 0, 1, 2, 3, 4
 SCALE_F16, SCALE_E4M3 = 0, 1
 
-EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_attn_decode", "qvg_kmeans_assign",
+EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_attn_decode", "qvg_attn_decode_ex", "qvg_attn_merge",
+           "qvg_kmeans_assign",
            "qvg_kmeans_update", "qvg_workspace_bytes", "qvg_compressed_bytes",
            "qvg_status_string", "qvg_version"]
 
@@ -56,6 +57,11 @@ def lib():
         L.qvg_attn_decode.restype = C.c_int
         L.qvg_attn_decode.argtypes = [pp, i64, vp, i64, i64, vp, u8p, u8p, vp, vp, u8p, u8p, vp,
                                       C.c_float, vp, vp, vp, C.c_size_t, vp]
+        L.qvg_attn_decode_ex.restype = C.c_int
+        L.qvg_attn_decode_ex.argtypes = [pp, i64, vp, i64, i64, i64, vp, u8p, u8p, vp, vp, u8p, u8p, vp, vp,
+                                         C.c_float, vp, vp, vp, C.c_size_t, vp]
+        L.qvg_attn_merge.restype = C.c_int
+        L.qvg_attn_merge.argtypes = [i64, C.c_int32, vp, vp, vp, vp, vp, vp, vp]
         L.qvg_kmeans_assign.restype = C.c_int
         L.qvg_kmeans_assign.argtypes = [pp, i64, vp, i64, i64, vp, u8p, vp, C.c_size_t, vp]
         L.qvg_kmeans_update.restype = C.c_int
@@ -219,12 +225,22 @@ def decode(enc: Encoded, out=None) -> torch.Tensor:
     return out
 
 
-def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, out=None):
-    """qvg_attn_decode.  q [H, Nq, d] bf16 contiguous -> out bf16 [H, Nq, d] (and lse fp32 [H, Nq])."""
+def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, out=None, n_kv=None,
+                k_rope=None):
+    """qvg_attn_decode_ex.  q [H, Nq, d] bf16 contiguous -> out bf16 [H, Nq, d] (and lse fp32 [H, Nq]).
+    n_kv: read only the first n_kv tokens of the caches (they are allocated for more);
+    k_rope: [n_kv, d/2, 2] float16 (cos, sin), the rotary embedding of the decoded keys."""
     _check(q, torch.bfloat16, "q")
     q = q.contiguous()
     H, Nq, d = q.shape
-    Nk = k.ids.shape[1]
+    cap = k.ids.shape[1]
+    Nk = cap if n_kv is None else int(n_kv)
+    if not (1 <= Nk <= cap):
+        raise ValueError("n_kv must lie in 1 .. the caches' token capacity")
+    if k_rope is not None:
+        _check(k_rope, torch.float16, "k_rope")
+        if tuple(k_rope.shape) != (Nk, d // 2, 2) or not k_rope.is_contiguous():
+            raise ValueError("k_rope: need a contiguous [n_kv, d/2, 2] float16 tensor")
     K = k.centroids.shape[-2]
     T, G = k.codes.shape[2], k.scales.shape[3]
     if (v.ids.shape, v.codes.shape, v.scales.shape, v.scales.dtype, v.centroids.shape, v.chunk_len, v.n_smooth) != \
@@ -237,12 +253,34 @@ def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, o
     if out is None:
         out = torch.empty(H, Nq, d, dtype=torch.bfloat16, device=q.device)
     lse = torch.empty(H, Nq, dtype=torch.float32, device=q.device) if want_lse else None
-    st = lib().qvg_attn_decode(C.byref(p), Nq, _ptr(q), Nk, k.chunk_len,
-                               _ptr(k.centroids), _ptr(k.ids), _ptr(k.codes), _ptr(k.scales),
-                               _ptr(v.centroids), _ptr(v.ids), _ptr(v.codes), _ptr(v.scales),
-                               C.c_float(softmax_scale), _ptr(out), _ptr(lse), None, 0, _stream())
+    st = lib().qvg_attn_decode_ex(C.byref(p), Nq, _ptr(q), Nk, k.chunk_len, cap,
+                                  _ptr(k.centroids), _ptr(k.ids), _ptr(k.codes), _ptr(k.scales),
+                                  _ptr(v.centroids), _ptr(v.ids), _ptr(v.codes), _ptr(v.scales),
+                                  _ptr(k_rope), C.c_float(softmax_scale), _ptr(out), _ptr(lse), None, 0,
+                                  _stream())
     if st != 0:
-        raise QvgError(st, "qvg_attn_decode")
+        raise QvgError(st, "qvg_attn_decode_ex")
+    return (out, lse) if want_lse else out
+
+
+def attn_merge(out_a, lse_a, out_b, lse_b, out=None, want_lse=False):
+    """qvg_attn_merge.  out_* bf16 [..., d] contiguous, lse_* fp32 [...] -> merged bf16 (and lse)."""
+    for t, dt, nm in ((out_a, torch.bfloat16, "out_a"), (out_b, torch.bfloat16, "out_b"),
+                      (lse_a, torch.float32, "lse_a"), (lse_b, torch.float32, "lse_b")):
+        _check(t, dt, nm)
+        if not t.is_contiguous():
+            raise ValueError(f"{nm} must be contiguous")
+    d = out_a.shape[-1]
+    rows = out_a.numel() // d
+    if out_b.shape != out_a.shape or lse_a.numel() != rows or lse_b.numel() != rows:
+        raise ValueError("shapes of the two partial results differ")
+    if out is None:
+        out = torch.empty_like(out_a)
+    lse = torch.empty_like(lse_a) if want_lse else None
+    st = lib().qvg_attn_merge(rows, d, _ptr(out_a), _ptr(lse_a), _ptr(out_b), _ptr(lse_b), _ptr(out), _ptr(lse),
+                              _stream())
+    if st != 0:
+        raise QvgError(st, "qvg_attn_merge")
     return (out, lse) if want_lse else out
 
 

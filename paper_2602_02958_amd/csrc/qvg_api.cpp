@@ -308,6 +308,30 @@ int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q, int64_t n_k
                     const uint8_t *v_ids, const uint8_t *v_codes, const void *v_scales,
                     float softmax_scale, void *out, float *lse_out, void *workspace,
                     size_t workspace_bytes, void *stream) {
+    return qvg_attn_decode_ex(p, n_q, q, n_kv_tokens, chunk_len, 0, k_centroids, k_ids, k_codes, k_scales,
+                              v_centroids, v_ids, v_codes, v_scales, nullptr, softmax_scale, out, lse_out,
+                              workspace, workspace_bytes, stream);
+}
+
+int qvg_attn_merge(int64_t n_rows, int32_t head_dim, const void *out_a, const float *lse_a,
+                   const void *out_b, const float *lse_b, void *out, float *lse_out, void *stream) {
+    if (n_rows < 0) return QVG_ERR_BAD_PARAM;
+    if (head_dim != kHeadDim) return QVG_ERR_UNSUPPORTED;
+    if (n_rows == 0) return QVG_OK;
+    if (!out_a || !lse_a || !out_b || !lse_b || !out) return QVG_ERR_NULL;
+    if (!aligned16(out_a) || !aligned16(out_b) || !aligned16(out)) return QVG_ERR_ALIGN;
+    MergeArgs m{};
+    m.oa = static_cast<const bf16_t *>(out_a); m.lsea = lse_a; m.ob = static_cast<const bf16_t *>(out_b);
+    m.lseb = lse_b; m.out = static_cast<bf16_t *>(out); m.lse = lse_out; m.rows = n_rows;
+    return launch_attn_merge(m, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
+}
+
+int qvg_attn_decode_ex(const qvg_params *p, int64_t n_q, const void *q, int64_t n_kv_tokens,
+                       int64_t chunk_len, int64_t kv_capacity_tokens, const void *k_centroids,
+                       const uint8_t *k_ids, const uint8_t *k_codes, const void *k_scales,
+                       const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
+                       const void *v_scales, const void *k_rope, float softmax_scale, void *out,
+                       float *lse_out, void *workspace, size_t workspace_bytes, void *stream) {
     (void)workspace; (void)workspace_bytes;
     int st = check_params(p);
     if (st != QVG_OK) return st;
@@ -323,6 +347,11 @@ int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q, int64_t n_k
     const int64_t n_chunks = (n_kv_tokens + chunk_len - 1) / chunk_len;
     if (n_chunks > 0x7fffffff) return QVG_ERR_BAD_PARAM;
     if ((n_q + 127) / 128 > 0x7fffffff) return QVG_ERR_BAD_PARAM;
+    if (kv_capacity_tokens == 0) kv_capacity_tokens = n_kv_tokens;
+    if (kv_capacity_tokens < n_kv_tokens) return QVG_ERR_BAD_PARAM;
+    const int64_t cap_chunks = (kv_capacity_tokens + chunk_len - 1) / chunk_len;
+    if (cap_chunks > 0x7fffffff) return QVG_ERR_BAD_PARAM;
+    if (k_rope && !aligned16(k_rope)) return QVG_ERR_ALIGN;
     AttnArgs a{};
     a.q = static_cast<const bf16_t *>(q); a.out = static_cast<bf16_t *>(out); a.lse = lse_out;
     a.n_q = n_q; a.n_kv = n_kv_tokens; a.chunk_len = chunk_len; a.n_chunks = (int)n_chunks;
@@ -333,6 +362,8 @@ int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q, int64_t n_k
     a.v_cent = static_cast<const bf16_t *>(v_centroids); a.v_ids = v_ids; a.v_codes = v_codes;
     a.v_scales = static_cast<const f16_t *>(v_scales);
     a.S = p->n_smooth_stages; a.fmt = format_of(p);
+    a.kv_stride = kv_capacity_tokens; a.chunk_stride = (int)cap_chunks;
+    a.rope = static_cast<const f16_t *>(k_rope);
     return launch_attn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
 }
 

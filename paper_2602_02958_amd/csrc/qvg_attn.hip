@@ -181,9 +181,22 @@ __device__ __forceinline__ void dequant2x8(const Raw<TM> &r, int T, float *accA,
 // memory (many small loads).  Used for more than 4 quantization rounds (their staging area would
 // not fit in LDS), for chunks whose scale records do not start on 16-byte boundaries, and for
 // several smoothing stages (the rows of all stages are added as they arrive).
-template <int T_, bool MULTI, int FMT>   // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages).
+// the (cos, sin) pairs of this thread's 8 channels of its two tokens of a tile (zero for tokens
+// that do not exist: their decoded value is zero as well)
+__device__ __forceinline__ void load_rope(const f16_t *rope, const Tile &t, int tp, int c8, uint4 rp[2]) {
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int n = t.t0 + 2 * tp + e;
+        rp[e] = (t.valid && n < t.cend)
+                    ? *reinterpret_cast<const uint4 *>(rope + (int64_t)n * kHeadDim + c8 * 8)
+                    : make_uint4(0u, 0u, 0u, 0u);
+    }
+}
+
+template <int T_, bool MULTI, int FMT, bool ROPE>   // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages).
                                 // MULTI: more than one smoothing stage (a.S tables and id bytes)
                                 // FMT: stored format (kFmt* bits)
+                                // ROPE: rotate the decoded keys by a.rope
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_kernel_direct(AttnArgs a) {
     constexpr int TM = T_ > 0 ? T_ : kMaxStages;
@@ -203,12 +216,12 @@ void attn_kernel_direct(AttnArgs a) {
 
     CacheSide ks, vs;
     constexpr int kCodeBytes = (FMT & kFmtInt4) ? 64 : 32, kScaleBytes = (FMT & kFmtE4M3) ? 1 : 2;
-    ks.ids = a.k_ids + (int64_t)h * a.n_kv * S;  ks.codes = a.k_codes + (int64_t)h * a.n_kv * T * kCodeBytes;
-    ks.scales = reinterpret_cast<const uint8_t *>(a.k_scales) + (int64_t)h * a.n_kv * T * G * kScaleBytes;
-    ks.cent = a.k_cent + (int64_t)h * a.n_chunks * S * K * kHeadDim;
-    vs.ids = a.v_ids + (int64_t)h * a.n_kv * S;  vs.codes = a.v_codes + (int64_t)h * a.n_kv * T * kCodeBytes;
-    vs.scales = reinterpret_cast<const uint8_t *>(a.v_scales) + (int64_t)h * a.n_kv * T * G * kScaleBytes;
-    vs.cent = a.v_cent + (int64_t)h * a.n_chunks * S * K * kHeadDim;
+    ks.ids = a.k_ids + (int64_t)h * a.kv_stride * S;  ks.codes = a.k_codes + (int64_t)h * a.kv_stride * T * kCodeBytes;
+    ks.scales = reinterpret_cast<const uint8_t *>(a.k_scales) + (int64_t)h * a.kv_stride * T * G * kScaleBytes;
+    ks.cent = a.k_cent + (int64_t)h * a.chunk_stride * S * K * kHeadDim;
+    vs.ids = a.v_ids + (int64_t)h * a.kv_stride * S;  vs.codes = a.v_codes + (int64_t)h * a.kv_stride * T * kCodeBytes;
+    vs.scales = reinterpret_cast<const uint8_t *>(a.v_scales) + (int64_t)h * a.kv_stride * T * G * kScaleBytes;
+    vs.cent = a.v_cent + (int64_t)h * a.chunk_stride * S * K * kHeadDim;
 
     // decode mapping: 16 adjacent lanes cover the 16 channel chunks of a token pair (coalesced)
     const int c8 = tid & 15, tp = tid >> 4;            // tp 0..31: tokens 2*tp, 2*tp+1 of the tile
@@ -236,9 +249,11 @@ void attn_kernel_direct(AttnArgs a) {
     float m = -INFINITY, l = 0.0f;
     const float scale2 = a.scale * 1.4426950408889634f;
 
+    uint4 rp[2];                      // (cos, sin) of the tile held in rk (ROPE only)
     auto decode_to_lds = [&](const Raw<TM> &rk, const Raw<TM> &rv, int buf) {
         float accA[8], accB[8];
         dequant2x8<T_, TM, MULTI, FMT>(rk, T, accA, accB);
+        if (ROPE) { rope_rotate8(accA, rp[0]); rope_rotate8(accB, rp[1]); }
         uint16_t *kt = Kt + buf * kKtElems;
         *reinterpret_cast<uint4 *>(kt + (tok + 0) * kKtPitch + c8 * 8) = pack_bf16x8(accA);
         *reinterpret_cast<uint4 *>(kt + (tok + 1) * kKtPitch + c8 * 8) = pack_bf16x8(accB);
@@ -264,6 +279,7 @@ void attn_kernel_direct(AttnArgs a) {
     load_ids(vs, cur, tp, kmax, S, idv);
     load_raw<T_, TM, MULTI, FMT>(ks, cur, tp, c8, T, G, g, K, S, idk, rk);
     load_raw<T_, TM, MULTI, FMT>(vs, cur, tp, c8, T, G, g, K, S, idv, rv);
+    if (ROPE) load_rope(a.rope, cur, tp, c8, rp);
     load_ids(ks, nxt, tp, kmax, S, idk);
     load_ids(vs, nxt, tp, kmax, S, idv);
     decode_to_lds(rk, rv, 0);
@@ -275,6 +291,7 @@ void attn_kernel_direct(AttnArgs a) {
         if (nxt.valid) {
             load_raw<T_, TM, MULTI, FMT>(ks, nxt, tp, c8, T, G, g, K, S, idk, rk);
             load_raw<T_, TM, MULTI, FMT>(vs, nxt, tp, c8, T, G, g, K, S, idv, rv);
+            if (ROPE) load_rope(a.rope, nxt, tp, c8, rp);
             load_ids(ks, nn, tp, kmax, S, idk);
             load_ids(vs, nn, tp, kmax, S, idv);
         }
@@ -391,7 +408,7 @@ constexpr size_t kAtSmemStaged = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint
 
 template <bool V> struct BoolC { static constexpr bool value = V; };
 
-template <int T_>
+template <int T_, bool ROPE>      // ROPE: rotate the decoded keys by a.rope
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_xcd) {
     constexpr int T = T_;
@@ -418,12 +435,12 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     const int G = kHeadDim / B;
     const uint32_t kmax = (uint32_t)K - 1u;
 
-    const uint8_t *k_ids = a.k_ids + (int64_t)h * a.n_kv, *v_ids = a.v_ids + (int64_t)h * a.n_kv;
-    const uint8_t *k_codes = a.k_codes + (int64_t)h * a.n_kv * T * 32, *v_codes = a.v_codes + (int64_t)h * a.n_kv * T * 32;
-    const unsigned char *k_scales = reinterpret_cast<const unsigned char *>(a.k_scales + (int64_t)h * a.n_kv * T * G);
-    const unsigned char *v_scales = reinterpret_cast<const unsigned char *>(a.v_scales + (int64_t)h * a.n_kv * T * G);
-    const bf16_t *k_cent = a.k_cent + (int64_t)h * a.n_chunks * K * kHeadDim;
-    const bf16_t *v_cent = a.v_cent + (int64_t)h * a.n_chunks * K * kHeadDim;
+    const uint8_t *k_ids = a.k_ids + (int64_t)h * a.kv_stride, *v_ids = a.v_ids + (int64_t)h * a.kv_stride;
+    const uint8_t *k_codes = a.k_codes + (int64_t)h * a.kv_stride * T * 32, *v_codes = a.v_codes + (int64_t)h * a.kv_stride * T * 32;
+    const unsigned char *k_scales = reinterpret_cast<const unsigned char *>(a.k_scales + (int64_t)h * a.kv_stride * T * G);
+    const unsigned char *v_scales = reinterpret_cast<const unsigned char *>(a.v_scales + (int64_t)h * a.kv_stride * T * G);
+    const bf16_t *k_cent = a.k_cent + (int64_t)h * a.chunk_stride * K * kHeadDim;
+    const bf16_t *v_cent = a.v_cent + (int64_t)h * a.chunk_stride * K * kHeadDim;
 
     const int c8 = tid & 15, tp = tid >> 4;            // tp 0..31: tokens 2*tp, 2*tp+1 of the tile
     const int g = (c8 * 8) / B;
@@ -529,7 +546,9 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     };
     // centroid rows of this thread's two tokens, both sides, using the parked ids (the id of a
     // token that does not exist is parked as 0)
+    uint4 rp[2];                      // ROPE: (cos, sin) pairs of the tile whose rows are in cen
     auto gather_rows = [&](const Tile &t, int ordinal, uint4 cen[2][2]) {
+        if (ROPE) load_rope(a.rope, t, tp, c8, rp);
         const unsigned char *st = idring + (ordinal & 3) * 2 * kAtKv;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -563,6 +582,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
             float accA[8], accB[8];
             dequant2x8<T, T>(r, T, accA, accB);
             if (s == 0) {
+                if (ROPE) { rope_rotate8(accA, rp[0]); rope_rotate8(accB, rp[1]); }
                 uint16_t *kt = Kt + buf * kKtElems;
                 *reinterpret_cast<uint4 *>(kt + (tok + 0) * kKtPitch + c8 * 8) = pack_bf16x8(accA);
                 *reinterpret_cast<uint4 *>(kt + (tok + 1) * kKtPitch + c8 * 8) = pack_bf16x8(accB);
@@ -723,11 +743,11 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     }
 }
 
-template <int T_>
-static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
+template <int T_, bool ROPE>
+static hipError_t launch_attn_staged_r(const AttnArgs &a, hipStream_t s) {
     static bool configured = false;          // the attribute is per function, set once per process
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmemStaged);
         if (e != hipSuccess) return e;
         configured = true;
@@ -736,19 +756,27 @@ static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
     const int64_t nb = nqb * a.H;
     if (nb > 0x7fffffff - 8) return hipErrorInvalidValue;
     const int bpx = (int)((nb + 7) / 8);
-    hipLaunchKernelGGL((attn_kernel_staged<T_>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmemStaged, s, a,
+    hipLaunchKernelGGL((attn_kernel_staged<T_, ROPE>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmemStaged, s, a,
                        (int)nqb, (int)nb, bpx);
     return hipGetLastError();
 }
+template <int T_>
+static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
+    return a.rope ? launch_attn_staged_r<T_, true>(a, s) : launch_attn_staged_r<T_, false>(a, s);
+}
 
-template <int T_, bool MULTI, int FMT = 0>
-static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_, MULTI, FMT>),
+template <int T_, bool MULTI, int FMT, bool ROPE>
+static hipError_t launch_attn_tr(const AttnArgs &a, hipStream_t s) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_, MULTI, FMT, ROPE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmem);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
-    hipLaunchKernelGGL((attn_kernel_direct<T_, MULTI, FMT>), grid, dim3(kAtThreads), kAtSmem, s, a);
+    hipLaunchKernelGGL((attn_kernel_direct<T_, MULTI, FMT, ROPE>), grid, dim3(kAtThreads), kAtSmem, s, a);
     return hipGetLastError();
+}
+template <int T_, bool MULTI, int FMT = 0>
+static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
+    return a.rope ? launch_attn_tr<T_, MULTI, FMT, true>(a, s) : launch_attn_tr<T_, MULTI, FMT, false>(a, s);
 }
 
 // the other stored formats run on the general kernel
@@ -778,6 +806,39 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
         case 3: return launch_attn_staged<3>(a, s);
         default: return launch_attn_staged<4>(a, s);
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Merge of two partial attention results over disjoint key sets (the compressed cache and the
+// current chunk's own keys) into the attention over their union, from the outputs and the
+// log-sum-exps: w_a = exp(lse_a - m), w_b = exp(lse_b - m), m = max; o = (w_a o_a + w_b o_b) /
+// (w_a + w_b); lse = m + log(w_a + w_b).  16 lanes per row, 8 channels each: a streaming pass.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256)
+void attn_merge_kernel(MergeArgs a) {
+    const int64_t r = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int c8 = threadIdx.x & 15;
+    if (r >= a.rows) return;
+    const float la = a.lsea[r], lb = a.lseb[r];
+    const float m = fmaxf(la, lb);
+    const float wa = __builtin_amdgcn_exp2f((la - m) * 1.4426950408889634f);
+    const float wb = __builtin_amdgcn_exp2f((lb - m) * 1.4426950408889634f);
+    const float z = wa + wb, inv = 1.0f / z;
+    float xa[8], xb[8], o[8];
+    unpack_bf16x8(*reinterpret_cast<const uint4 *>(a.oa + r * kHeadDim + c8 * 8), xa);
+    unpack_bf16x8(*reinterpret_cast<const uint4 *>(a.ob + r * kHeadDim + c8 * 8), xb);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (wa * xa[i] + wb * xb[i]) * inv;
+    *reinterpret_cast<uint4 *>(a.out + r * kHeadDim + c8 * 8) = pack_bf16x8(o);
+    if (a.lse && c8 == 0) a.lse[r] = m + __builtin_log2f(z) * 0.6931471805599453f;
+}
+
+hipError_t launch_attn_merge(const MergeArgs &a, hipStream_t s) {
+    if (a.rows == 0) return hipSuccess;
+    const int64_t nb = (a.rows + 15) / 16;
+    if (nb > 0x7fffffff) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attn_merge_kernel, dim3((unsigned)nb), dim3(256), 0, s, a);
+    return hipGetLastError();
 }
 
 }  // namespace qvg

@@ -182,7 +182,35 @@ struct AttnArgs {
     const bf16_t *v_cent; const uint8_t *v_ids; const uint8_t *v_codes; const f16_t *v_scales;
     int S;      // smoothing stages, layouts as in DecodeArgs
     int fmt;    // kFmt* bits, as in DecodeArgs
+    int64_t kv_stride;     // tokens between consecutive units in ids / codes / scales (>= n_kv)
+    int chunk_stride;      // chunk tables between consecutive units in the centroid arrays (>= n_chunks)
+    const f16_t *rope;     // [n_kv][d/2][2] (cos, sin) applied to the decoded keys, or nullptr
 };
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
+
+// Rotary embedding of one lane's 8 decoded key channels (4 interleaved pairs): the values are
+// first rounded to bf16 (what the stand-alone decoder stores), then each pair (x0, x1) becomes
+// (x0 cos - x1 sin, x0 sin + x1 cos), one fp32 product and one fma per output.
+// rp: the lane's 4 (cos, sin) binary16 pairs.
+__device__ __forceinline__ void rope_rotate8(float *acc, const uint4 &rp) {
+    const uint32_t w[4] = {rp.x, rp.y, rp.z, rp.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t pk = pack_bf16x2(acc[2 * i], acc[2 * i + 1]);
+        const float x0 = bf16_lo(pk), x1 = bf16_hi(pk);
+        const halfx2_t cs = __builtin_bit_cast(halfx2_t, w[i]);
+        const float c = (float)cs[0], sn = (float)cs[1];
+        const float t0 = x1 * sn, t1 = x1 * c;
+        acc[2 * i] = __builtin_fmaf(x0, c, -t0);
+        acc[2 * i + 1] = __builtin_fmaf(x0, sn, t1);
+    }
+}
+
+// Merge of two partial attention results over disjoint key sets (rows of d = 128 channels)
+struct MergeArgs {
+    const bf16_t *oa; const float *lsea; const bf16_t *ob; const float *lseb;
+    bf16_t *out; float *lse; int64_t rows;
+};
+hipError_t launch_attn_merge(const MergeArgs &a, hipStream_t s);
 
 }  // namespace qvg

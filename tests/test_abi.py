@@ -105,6 +105,17 @@ def test_null_and_alignment_errors_are_reported_before_any_launch():
     for bad in (0.0, -0.5, float("inf")):
         assert L.qvg_attn_decode(C.byref(p), 4, fake, 10, 10, fake, fake, fake, fake, fake, fake, fake,
                                  fake, C.c_float(bad), fake, None, None, 0, None) == -2
+    # extended attention: capacity below the fill, misaligned rotary table
+    ex = lambda cap, rope: L.qvg_attn_decode_ex(C.byref(p), 4, fake, 10, 10, cap, fake, fake, fake, fake, fake, fake,
+                                                fake, fake, rope, C.c_float(0.1), fake, None, None, 0, None)
+    assert ex(5, None) == -2
+    assert ex(0, C.c_void_p(0x1004)) == -5
+    # merge
+    assert L.qvg_attn_merge(4, 64, fake, fake, fake, fake, fake, None, None) == -3
+    assert L.qvg_attn_merge(-1, 128, fake, fake, fake, fake, fake, None, None) == -2
+    assert L.qvg_attn_merge(4, 128, fake, None, fake, fake, fake, None, None) == -1
+    assert L.qvg_attn_merge(4, 128, odd, fake, fake, fake, fake, None, None) == -5
+    assert L.qvg_attn_merge(0, 128, None, None, None, None, None, None, None) == 0
     # zero-size calls succeed without touching the device
     assert L.qvg_decode(C.byref(p), 0, 10, None, None, None, None, None, 0, 0, None) == 0
     assert L.qvg_attn_decode(C.byref(p), 0, None, 10, 10, None, None, None, None, None, None, None,

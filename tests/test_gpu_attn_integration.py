@@ -1,0 +1,141 @@
+"""What a generation step needs around the fused attention (Sec. 3.1: a chunk attends to the
+cached chunks and to itself; Sec. 5 "Implementation": keys are cached before the rotary
+embedding): reading a prefix of a cache allocated for more tokens, rotating the decoded keys,
+and merging with a second partial attention - each against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qvg_oracle as O
+from paper_2602_02958_amd import binding as B
+from paper_2602_02958_amd import synth
+from paper_2602_02958_amd.configs import CONFIGS
+from conftest import bf16_bits, bits_to_f32
+import parity_util as P
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _filled_caches(H, L, capacity_chunks, filled, K, Bg, T, S=1, bits=2, fmt=B.SCALE_F16):
+    """K and V caches with room for capacity_chunks chunks of L tokens, the first `filled` tokens
+    encoded (the rest zero bytes)."""
+    wl = CONFIGS["cfg2_window21"]
+    caches = []
+    for kv in (0, 1):
+        st = synth.MixtureStream(wl, H, kv, DEV)
+        cache = B.alloc_cache(H, L * capacity_chunks, L, K, Bg, T, 128, DEV, n_smooth=S, bits=bits, scale_format=fmt)
+        for t in (cache.centroids, cache.ids, cache.codes, cache.scales):
+            t.zero_()
+        c = 0
+        while c * L < filled:
+            n = min(L, filled - c * L)
+            x = st.next_chunk(n)
+            init = torch.stack([synth.cold_start_centroids(x, K, seed=s) for s in range(S)], 1)
+            B.encode_chunk(x, init if S > 1 else init[:, 0], Bg, T, 2, cache=cache, chunk_index=c)
+            c += 1
+        caches.append(cache)
+    return caches
+
+
+def _rope_table(n, d=128, theta=10000.0, offset=0):
+    pos = torch.arange(offset, offset + n, dtype=torch.float64)
+    freq = theta ** (-torch.arange(d // 2, dtype=torch.float64) / (d // 2))
+    ang = pos[:, None] * freq[None]
+    return torch.stack([ang.cos(), ang.sin()], -1).to(torch.float16).contiguous()      # [n, d/2, 2]
+
+
+def _check_against_oracle(q, out, lse, khat_bits, vhat_bits, h):
+    want, lse_w = O.attention(bf16_bits(q[h]), khat_bits, vhat_bits, want_lse=True)
+    ok, max_abs, worst = P.attn_tolerance_ok(P.to_np_u16(out[h]), want)
+    assert ok, f"head {h}: max abs err {max_abs}, worst err/tol {worst}"
+    assert np.abs(lse[h].cpu().numpy() - lse_w).max() < 2e-3
+
+
+@pytest.mark.parametrize("L,T,Bg,bits,fmt", [(520, 2, 32, 2, B.SCALE_F16),      # staged kernel
+                                             (516, 3, 64, 2, B.SCALE_F16),      # general kernel (chunks not on 16-byte scale boundaries)
+                                             (520, 1, 64, 4, B.SCALE_E4M3)])
+def test_attention_over_a_prefix_of_a_larger_cache(L, T, Bg, bits, fmt):
+    H, K, Nq = 2, 64, 300
+    filled = 2 * L + 133
+    kc, vc = _filled_caches(H, L, 4, filled, K, Bg, T, bits=bits, fmt=fmt)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    khat, vhat = B.decode(kc), B.decode(vc)
+    for n_kv in (filled, 2 * L, L + 7, 64, 1):
+        out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=n_kv)
+        torch.cuda.synchronize()
+        for h in range(H):
+            _check_against_oracle(q, out, lse, P.to_np_u16(khat[h, :n_kv]), P.to_np_u16(vhat[h, :n_kv]), h)
+
+
+@pytest.mark.parametrize("L,T,Bg,S,bits,fmt", [(520, 2, 32, 1, 2, B.SCALE_F16),     # staged kernel
+                                               (520, 4, 64, 1, 2, B.SCALE_F16),
+                                               (516, 3, 64, 1, 2, B.SCALE_F16),     # general kernel
+                                               (520, 1, 64, 1, 2, B.SCALE_E4M3),    # the paper's QVG format
+                                               (520, 1, 16, 2, 4, B.SCALE_E4M3)])
+def test_attention_with_rotary_embedding_of_decoded_keys(L, T, Bg, S, bits, fmt):
+    H, K, Nq = 2, 64, 300
+    filled = 2 * L + 133
+    kc, vc = _filled_caches(H, L, 3, filled, K, Bg, T, S=S, bits=bits, fmt=fmt)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    rope = _rope_table(filled, offset=3)
+    out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled, k_rope=rope.to(DEV))
+    plain = B.attn_decode(q, kc, vc, n_kv=filled)
+    khat, vhat = B.decode(kc), B.decode(vc)
+    torch.cuda.synchronize()
+    rope_bits = rope.view(torch.int16).numpy().view(np.uint16)
+    for h in range(H):
+        krot = O.rope_keys(P.to_np_u16(khat[h, :filled]), rope_bits)
+        _check_against_oracle(q, out, lse, krot, P.to_np_u16(vhat[h, :filled]), h)
+    assert (out.float() - plain.float()).abs().max() > 0.05          # the rotation is not a no-op
+    # the identity rotation (cos 1, sin 0) reproduces the plain call bit for bit
+    ident = torch.zeros(filled, 64, 2, dtype=torch.float16); ident[..., 0] = 1.0
+    same = B.attn_decode(q, kc, vc, n_kv=filled, k_rope=ident.to(DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(same, plain)
+
+
+def test_merge_with_the_current_chunks_own_attention():
+    """Cache part from the fused kernel, the current chunk's bf16 part from the oracle (standing in
+    for the model's own attention kernel), merged on the GPU: equals attention over the union."""
+    H, L, K, Bg, T, Nq, Ntail = 2, 520, 64, 32, 2, 333, 200
+    filled = 2 * L + 50
+    kc, vc = _filled_caches(H, L, 3, filled, K, Bg, T)
+    wl = CONFIGS["cfg2_window21"]
+    q = synth.queries(wl, H, Nq, DEV)
+    tail_k = synth.MixtureStream(wl, H, 0, "cpu").next_chunk(Ntail)
+    tail_v = synth.MixtureStream(wl, H, 1, "cpu").next_chunk(Ntail)
+    out_a, lse_a = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled)
+    khat, vhat = B.decode(kc), B.decode(vc)
+    torch.cuda.synchronize()
+    ob = np.empty((H, Nq, 128)); lb = np.empty((H, Nq))
+    for h in range(H):
+        ob[h], lb[h] = O.attention(bf16_bits(q[h]), bf16_bits(tail_k[h]), bf16_bits(tail_v[h]), want_lse=True)
+    out_b = torch.from_numpy(ob).to(torch.bfloat16).to(DEV)
+    lse_b = torch.from_numpy(lb).float().to(DEV)
+    out, lse = B.attn_merge(out_a, lse_a, out_b, lse_b, want_lse=True)
+    torch.cuda.synchronize()
+    for h in range(H):
+        ku = np.concatenate([P.to_np_u16(khat[h, :filled]), bf16_bits(tail_k[h])])
+        vu = np.concatenate([P.to_np_u16(vhat[h, :filled]), bf16_bits(tail_v[h])])
+        want, lse_w = O.attention(bf16_bits(q[h]), ku, vu, want_lse=True)
+        # each partial result carries its own bf16 rounding (2^-9 relative) into the convex
+        # combination, the merged row is rounded once more: 2e-3 + 2^-7 max(|o_a|, |o_b|, |o|)
+        got = bits_to_f32(P.to_np_u16(out[h])).astype(np.float64)
+        mag = np.maximum(np.maximum(np.abs(bits_to_f32(P.to_np_u16(out_a[h]))), np.abs(ob[h])), np.abs(want))
+        assert (np.abs(got - want) <= 2e-3 + 2.0 ** -7 * mag).all()
+        assert np.abs(lse[h].cpu().numpy() - lse_w).max() < 2e-3
+        # against the oracle's merge of the very same partial results: only fp32 arithmetic and
+        # the final bf16 rounding remain
+        om, lm = O.attn_merge(bits_to_f32(P.to_np_u16(out_a[h])).astype(np.float64), lse_a[h].cpu().double().numpy(),
+                              bits_to_f32(P.to_np_u16(out_b[h])).astype(np.float64), lse_b[h].cpu().double().numpy())
+        assert (np.abs(got - om) <= 2.0 ** -8 * np.abs(om) + 1e-5).all()
+        assert np.abs(lse[h].cpu().numpy() - lm).max() < 1e-4
+    # in place, and with a second set that carries no weight
+    out2 = B.attn_merge(out_a.clone(), lse_a, out_b, lse_b - 200.0)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, out_a)
+    buf = out_a.clone()
+    B.attn_merge(buf, lse_a, out_b, lse_b, out=buf)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, out)
