@@ -138,6 +138,20 @@ int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len,
                int64_t stride_token, void *stream);
 
 /*
+ * qvg_decode of a token range of caches that are allocated for more tokens than are decoded:
+ * tokens first_token .. first_token + n_tokens - 1 of every unit, first_token a multiple of
+ * chunk_len; unit h starts kv_capacity_tokens tokens (ids, codes, scales) and
+ * ceil(kv_capacity_tokens / chunk_len) tables after unit h-1 (0 = first_token + n_tokens).
+ * The array pointers are those of the whole cache (token 0 of unit 0); x_bf16_out receives
+ * the range only, [H][n_tokens][d] in the view convention of qvg_decode.
+ */
+int qvg_decode_ex(const qvg_params *p, int64_t n_tokens, int64_t chunk_len,
+                  int64_t kv_capacity_tokens, int64_t first_token,
+                  const void *centroids_bf16, const uint8_t *ids, const uint8_t *codes,
+                  const void *scales, void *x_bf16_out, int64_t stride_head,
+                  int64_t stride_token, void *stream);
+
+/*
  * Attention over the compressed cache: O = softmax(softmax_scale * Q K_hat^T) V_hat
  * per unit, no mask, where K_hat and V_hat are what qvg_decode would return (bf16),
  * produced tile by tile in LDS and never written to memory.

@@ -20,7 +20,7 @@ _lib = None
 ENTRY_ENCODE, ENTRY_DECODE, ENTRY_ATTN, ENTRY_KMEANS_UPDATE, ENTRY_KMEANS_ASSIGN = 0, 1, 2, 3, 4
 SCALE_F16, SCALE_E4M3 = 0, 1
 
-EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_attn_decode", "qvg_attn_decode_ex", "qvg_attn_merge",
+EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_decode_ex", "qvg_attn_decode", "qvg_attn_decode_ex", "qvg_attn_merge",
            "qvg_kmeans_assign",
            "qvg_kmeans_update", "qvg_workspace_bytes", "qvg_compressed_bytes",
            "qvg_status_string", "qvg_version"]
@@ -54,6 +54,8 @@ def lib():
                                        C.c_size_t, vp]
         L.qvg_decode.restype = C.c_int
         L.qvg_decode.argtypes = [pp, i64, i64, vp, u8p, u8p, vp, vp, i64, i64, vp]
+        L.qvg_decode_ex.restype = C.c_int
+        L.qvg_decode_ex.argtypes = [pp, i64, i64, i64, i64, vp, u8p, u8p, vp, vp, i64, i64, vp]
         L.qvg_attn_decode.restype = C.c_int
         L.qvg_attn_decode.argtypes = [pp, i64, vp, i64, i64, vp, u8p, u8p, vp, vp, u8p, u8p, vp,
                                       C.c_float, vp, vp, vp, C.c_size_t, vp]
@@ -203,9 +205,13 @@ def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: E
     return cache
 
 
-def decode(enc: Encoded, out=None) -> torch.Tensor:
-    """qvg_decode -> bf16 [H, N, d]."""
-    H, N = enc.ids.shape[:2]
+def decode(enc: Encoded, out=None, n_tokens=None, first_token=0) -> torch.Tensor:
+    """qvg_decode_ex -> bf16 [H, n_tokens, d]: the whole cache, or n_tokens tokens starting at
+    first_token (a multiple of the chunk length)."""
+    H, cap = enc.ids.shape[:2]
+    N = cap - first_token if n_tokens is None else int(n_tokens)
+    if first_token < 0 or N < 0 or first_token + N > cap:
+        raise ValueError("token range outside the cache")
     K, d = enc.centroids.shape[-2:]
     T, G = enc.codes.shape[2], enc.scales.shape[3]
     p = make_params(H, K, d // G, T, 0, head_dim=d, n_smooth_stages=enc.n_smooth, bits=enc.bits,
@@ -218,10 +224,10 @@ def decode(enc: Encoded, out=None) -> torch.Tensor:
         _check(t, dt, nm)
         if not t.is_contiguous():
             raise ValueError(f"{nm} must be contiguous")
-    st = lib().qvg_decode(C.byref(p), N, enc.chunk_len, _ptr(enc.centroids), _ptr(enc.ids),
-                          _ptr(enc.codes), _ptr(enc.scales), _ptr(out), sh, st_, _stream())
+    st = lib().qvg_decode_ex(C.byref(p), N, enc.chunk_len, cap, first_token, _ptr(enc.centroids), _ptr(enc.ids),
+                             _ptr(enc.codes), _ptr(enc.scales), _ptr(out), sh, st_, _stream())
     if st != 0:
-        raise QvgError(st, "qvg_decode")
+        raise QvgError(st, "qvg_decode_ex")
     return out
 
 

@@ -284,9 +284,22 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
 int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, const void *centroids,
                const uint8_t *ids, const uint8_t *codes, const void *scales, void *x_out,
                int64_t stride_head, int64_t stride_token, void *stream) {
+    return qvg_decode_ex(p, n_tokens, chunk_len, 0, 0, centroids, ids, codes, scales, x_out, stride_head,
+                         stride_token, stream);
+}
+
+int qvg_decode_ex(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, int64_t kv_capacity_tokens,
+                  int64_t first_token, const void *centroids, const uint8_t *ids, const uint8_t *codes,
+                  const void *scales, void *x_out, int64_t stride_head, int64_t stride_token,
+                  void *stream) {
     int st = check_params(p);
     if (st != QVG_OK) return st;
     if (n_tokens < 0 || n_tokens > 0x7fffffff || chunk_len < 1) return QVG_ERR_BAD_PARAM;
+    if (first_token < 0 || first_token % chunk_len != 0) return QVG_ERR_BAD_PARAM;
+    if (kv_capacity_tokens == 0) kv_capacity_tokens = first_token + n_tokens;
+    if (kv_capacity_tokens < first_token + n_tokens) return QVG_ERR_BAD_PARAM;
+    const int64_t cap_chunks = (kv_capacity_tokens + chunk_len - 1) / chunk_len;
+    if (cap_chunks > 0x7fffffff) return QVG_ERR_BAD_PARAM;
     if (n_tokens == 0) return QVG_OK;
     if (!centroids || !ids || !codes || !scales || !x_out) return QVG_ERR_NULL;
     if ((st = check_view(x_out, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
@@ -294,8 +307,15 @@ int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, const v
     const int64_t n_chunks = (n_tokens + chunk_len - 1) / chunk_len;
     if (n_chunks > 0x7fffffff) return QVG_ERR_BAD_PARAM;
     DecodeArgs a{};
-    a.cent = static_cast<const bf16_t *>(centroids); a.ids = ids; a.codes = codes;
-    a.scales = static_cast<const f16_t *>(scales); a.out = static_cast<bf16_t *>(x_out);
+    // the range starts on a chunk boundary: move the unit-0 pointers to it, keep the unit strides
+    const int64_t S_ = p->n_smooth_stages, T_ = p->n_stages, G_ = p->head_dim / p->group_size;
+    a.cent = static_cast<const bf16_t *>(centroids) + (first_token / chunk_len) * S_ * p->n_clusters * kHeadDim;
+    a.ids = ids + first_token * S_;
+    a.codes = codes + first_token * T_ * (kHeadDim * p->bits / 8);
+    a.scales = reinterpret_cast<const f16_t *>(static_cast<const uint8_t *>(scales) +
+                                               first_token * T_ * G_ * (p->scale_format == QVG_SCALE_E4M3 ? 1 : 2));
+    a.out = static_cast<bf16_t *>(x_out);
+    a.kv_stride = kv_capacity_tokens; a.chunk_stride = (int)cap_chunks;
     a.n_tokens = n_tokens; a.chunk_len = chunk_len; a.n_chunks = (int)n_chunks;
     a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size; a.T = p->n_stages;
     a.stride_head = stride_head; a.stride_token = stride_token; a.S = p->n_smooth_stages; a.fmt = format_of(p);

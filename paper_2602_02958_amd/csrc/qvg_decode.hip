@@ -167,7 +167,7 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
     const uint32_t gidx = (lane16 * 8) / a.B;     // scale group of this lane's 8 channels
 
     const int S = (SM == 1) ? 1 : a.S;
-    const bf16_t *cg = a.cent + ((int64_t)h * a.n_chunks + c) * S * a.K * kHeadDim;    // [S][K][128] of this chunk
+    const bf16_t *cg = a.cent + ((int64_t)h * a.chunk_stride + c) * S * a.K * kHeadDim;    // [S][K][128] of this chunk
     if (SM != 3) {   // stage the tables: S*K rows of 256 B, 16 B per thread and step
         for (int i = threadIdx.x; i < S * a.K * 16; i += kDecThreads)
             *reinterpret_cast<uint4 *>(tab + i * 8) = *reinterpret_cast<const uint4 *>(cg + i * 8);
@@ -175,7 +175,7 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
     __syncthreads();
 
     // per-block base pointers (uniform), per-lane 32-bit offsets
-    const int64_t hn0 = (int64_t)h * a.n_tokens + tok0;
+    const int64_t hn0 = (int64_t)h * a.kv_stride + tok0;
     const uint8_t *ids_b = a.ids + hn0 * S;
     const void *codes_b = a.codes + hn0 * T * ((FMT & kFmtInt4) ? 64 : 32);
     const void *scales_b = reinterpret_cast<const uint8_t *>(a.scales) + hn0 * T * G * ((FMT & kFmtE4M3) ? 1 : 2);

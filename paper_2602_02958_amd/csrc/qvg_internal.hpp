@@ -127,6 +127,8 @@ struct DecodeArgs {
     int64_t stride_head, stride_token;
     int S;      // smoothing stages: cent [H][n_chunks][S][K][d], ids [H][N][S]
     int fmt;    // kFmt* bits; scales then points at bytes, codes rows are 64 B per round with 4-bit levels
+    int64_t kv_stride;     // tokens between consecutive units in ids / codes / scales (>= n_tokens)
+    int chunk_stride;      // chunk tables between consecutive units in cent (>= n_chunks)
 };
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 

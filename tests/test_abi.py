@@ -105,6 +105,9 @@ def test_null_and_alignment_errors_are_reported_before_any_launch():
     for bad in (0.0, -0.5, float("inf")):
         assert L.qvg_attn_decode(C.byref(p), 4, fake, 10, 10, fake, fake, fake, fake, fake, fake, fake,
                                  fake, C.c_float(bad), fake, None, None, 0, None) == -2
+    # decode of a range: start off a chunk boundary, capacity below the range's end
+    assert L.qvg_decode_ex(C.byref(p), 10, 10, 0, 5, fake, fake, fake, fake, fake, 1280, 128, None) == -2
+    assert L.qvg_decode_ex(C.byref(p), 10, 10, 15, 10, fake, fake, fake, fake, fake, 1280, 128, None) == -2
     # extended attention: capacity below the fill, misaligned rotary table
     ex = lambda cap, rope: L.qvg_attn_decode_ex(C.byref(p), 4, fake, 10, 10, cap, fake, fake, fake, fake, fake, fake,
                                                 fake, fake, rope, C.c_float(0.1), fake, None, None, 0, None)

@@ -139,3 +139,26 @@ def test_merge_with_the_current_chunks_own_attention():
     B.attn_merge(buf, lse_a, out_b, lse_b, out=buf)
     torch.cuda.synchronize()
     assert torch.equal(buf, out)
+
+
+@pytest.mark.parametrize("T,Bg,S,bits,fmt", [(2, 32, 1, 2, B.SCALE_F16), (1, 16, 2, 4, B.SCALE_E4M3)])
+def test_decode_of_a_token_range_of_a_larger_cache(T, Bg, S, bits, fmt):
+    H, L, K = 3, 520, 64
+    filled = 3 * L + 77
+    kc, _ = _filled_caches(H, L, 5, filled, K, Bg, T, S=S, bits=bits, fmt=fmt)
+    whole = B.decode(kc)                                     # all 5 chunk slots (the unfilled ones hold zero bytes)
+    torch.cuda.synchronize()
+    sc = P.to_np_u8(kc.scales).astype(np.uint16) if fmt == B.SCALE_E4M3 else P.to_np_u16(kc.scales)
+    for h in range(H):                                       # the filled part is the oracle's decode
+        for c in range(4):
+            sl = slice(c * L, min((c + 1) * L, filled))
+            want = O.decode_unit(P.to_np_u16(kc.centroids[h, c]).reshape(S, K, 128),
+                                 P.to_np_u8(kc.ids[h, sl]).reshape(-1, S).T, P.to_np_u8(kc.codes[h, sl]), sc[h, sl],
+                                 Bg, bits=bits, scale_fmt=fmt)
+            assert np.array_equal(P.to_np_u16(whole[h, sl]), want)
+    for first, n in ((0, filled), (L, 2 * L + 77), (2 * L, 100), (3 * L, 77), (L, 0)):
+        part = B.decode(kc, n_tokens=n, first_token=first)
+        torch.cuda.synchronize()
+        assert part.shape == (H, n, 128) and torch.equal(part, whole[:, first:first + n])
+    with pytest.raises(B.QvgError):
+        B.decode(kc, n_tokens=10, first_token=7)             # not on a chunk boundary
