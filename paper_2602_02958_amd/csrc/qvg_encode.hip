@@ -197,25 +197,37 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
     bf16_t *scr = lscr + wave * kHeadDim;
     // token operand of the extra MFMA step: three ones against (hi, mid, lo), lanes 0..31 only
     const uint32_t tagmask = vgpr_const(kTagMask);
+    // +inf kept in a register the compiler cannot see through: med3(a, b, +inf) then stays one
+    // instruction (as a constant it is rewritten into max(a, b) plus a NaN-quieting copy)
+    const float pinf = __uint_as_float(vgpr_const(0x7f800000u));
     const uint4 ones = half ? make_uint4(0u, 0u, 0u, 0u) : make_uint4(0x3F803F80u, 0x00003F80u, 0u, 0u);
 
     const int64_t blk0 = (int64_t)blockIdx.y * tiles_per_wave * (kAsgWaves * kAsgTile);
     const bf16_t *xh = a.x + (int64_t)h * a.stride_head + half * 64;
-    for (int k = 0; k < tiles_per_wave; ++k) {
-        const int64_t n0 = blk0 + (int64_t)(k * kAsgWaves + wave) * kAsgTile;
-        if (n0 >= N) break;                                  // uniform per wavefront
-        // this lane's 64 channels of its two tokens of the step (the MFMA B operands); a token
-        // past the end of the chunk reads as zero.  (Fetching the next step's tokens ahead was
-        // measured: no gain, and the registers are needed elsewhere.)
-        uint4 xa[2][8];
+    // this lane's 64 channels of its two tokens of a step (the MFMA B operands); a token past the
+    // end of the chunk reads as zero
+    auto load_x = [&](int64_t n0_, uint4 (&dst)[2][8]) {
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
-            const int64_t nn = n0 + tb * 32 + col;
+            const int64_t nn = n0_ + tb * 32 + col;
             const bf16_t *xp = xh + nn * a.stride_token;
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk)
-                xa[tb][kk] = (nn < N) ? *reinterpret_cast<const uint4 *>(xp + kk * 8) : make_uint4(0u, 0u, 0u, 0u);
+                dst[tb][kk] = (nn < N) ? *reinterpret_cast<const uint4 *>(xp + kk * 8) : make_uint4(0u, 0u, 0u, 0u);
         }
+    };
+    auto step_start = [&](int k) {
+        return k < tiles_per_wave ? blk0 + (int64_t)(k * kAsgWaves + wave) * kAsgTile : N;
+    };
+    // One step: 64 tokens.  Measured and left out, each without effect on the time of the pass:
+    // requesting the next step's tokens a step ahead into a second register set; fetching the
+    // tokens with whole rows per instruction through a staging area in LDS (each lane below reads
+    // 16 bytes out of 64 different cache lines per instruction); more or fewer steps per workgroup.
+    uint4 xa[2][8];
+    for (int k = 0; k < tiles_per_wave; ++k) {
+        const int64_t n0 = step_start(k);
+        if (n0 >= N) break;                                  // uniform per wavefront
+        load_x(n0, xa);
         int64_t n[2];
         bool valid[2];
         float xn[2];
@@ -260,7 +272,8 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[1], 0, 0, 0);
         };
         auto rank_block = [&](int jb, const floatx16_t (&acc)[2]) {
-            const uint32_t tag0 = (uint32_t)jb << 4;
+            uint32_t tag0 = (uint32_t)jb << 4;
+            asm volatile("" : "+s"(tag0));      // opaque: tag0 + r stays scalar arithmetic, the tag insert one v_and_or_b32
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
@@ -270,34 +283,88 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                     const float v = __uint_as_float((__float_as_uint(acc[tb][r]) & tagmask) | (tag0 + r));
                     b3[tb] = __builtin_amdgcn_fmed3f(b2[tb], b3[tb], v);
                     b2[tb] = __builtin_amdgcn_fmed3f(b1[tb], b2[tb], v);
-                    b1[tb] = __builtin_amdgcn_fmed3f(b1[tb], v, INFINITY);
+                    b1[tb] = __builtin_amdgcn_fmed3f(b1[tb], v, pinf);
                 }
-        };
-        // issue order of one pipelined pair: operand reads run two MFMAs ahead
-        auto interleave = [&]() {
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-#pragma unroll
-            for (int i = 0; i < 9; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
-                if (i < 7) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
         };
         if (FUSED) {
             // the fused pass has no registers for a second set of accumulators
             floatx16_t acc[2];
             for (int jb = 0; jb < (Kpad >> 5); ++jb) { score_block(jb, acc); rank_block(jb, acc); }
         } else {
+            // Software pipeline over groups of three k-steps (a block of 32 centroids is three
+            // groups: 8 channel steps and the norm step).  The centroid operands of the NEXT group
+            // are requested before the six MFMAs of the current one, whose issue slots are shared
+            // with a third of the ranking of the PREVIOUS block; scheduling barriers keep each
+            // part where it is written (left alone, the compiler reads every operand right
+            // before its use and the LDS latency is exposed once per k-step).
             const int nb = Kpad >> 5;                    // even: Kpad is a multiple of 64
             floatx16_t accA[2], accB[2];
-            score_block(0, accA);
-            for (int jb = 0; jb + 2 < nb; jb += 2) {
-                score_block(jb + 1, accB);  rank_block(jb, accA);      interleave();
-                score_block(jb + 2, accA);  rank_block(jb + 1, accB);  interleave();
+            bf16x8_t av[2][3];
+            const bf16x8_t bones = __builtin_bit_cast(bf16x8_t, ones);
+            auto load_group = [&](int jb, int g, bf16x8_t (&dst)[3]) {
+                const bf16_t *arow = lc + (jb * 32 + col) * kCPitch;
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    const int kk = g * 3 + i;
+                    dst[i] = *reinterpret_cast<const bf16x8_t *>(kk < 8 ? arow + half * 64 + kk * 8 : arow + kHeadDim);
+                }
+            };
+            auto mfma_group = [&](int g, const bf16x8_t (&src)[3], floatx16_t (&acc)[2]) {
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    const int kk = g * 3 + i;
+                    if (kk == 0) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) { acc[0][r] = 0.0f; acc[1][r] = 0.0f; }
+                    }
+                    const bf16x8_t b0 = kk < 8 ? __builtin_bit_cast(bf16x8_t, xa[0][kk < 8 ? kk : 0]) : bones;
+                    const bf16x8_t b1 = kk < 8 ? __builtin_bit_cast(bf16x8_t, xa[1][kk < 8 ? kk : 0]) : bones;
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(src[i], b0, acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(src[i], b1, acc[1], 0, 0, 0);
+                }
+            };
+            // scores 11 c .. 11 c + 10 (of 32: 16 per token block) of a finished block
+            auto rank_part = [&](int jb, const floatx16_t (&acc)[2], int c) {
+                uint32_t tag0 = (uint32_t)jb << 4;
+                asm volatile("" : "+s"(tag0));  // opaque, see rank_block
+#pragma unroll
+                for (int sidx = 11 * c; sidx < (c == 2 ? 32 : 11 * c + 11); ++sidx) {
+                    const int tb = sidx >> 4, r = sidx & 15;
+                    const float v = __uint_as_float((__float_as_uint(acc[tb][r]) & tagmask) | (tag0 + r));
+                    b3[tb] = __builtin_amdgcn_fmed3f(b2[tb], b3[tb], v);
+                    b2[tb] = __builtin_amdgcn_fmed3f(b1[tb], b2[tb], v);
+                    b1[tb] = __builtin_amdgcn_fmed3f(b1[tb], v, pinf);
+                }
+            };
+            auto interleave6 = [&]() {
+#pragma unroll
+                for (int i = 0; i < 6; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
+                }
+            };
+            // one block: its three groups; `prev` (if any) is ranked in their shadow; the operands
+            // of the group after the current one are requested first (next_jb < 0: none)
+            auto block_step = [&](int jb, floatx16_t (&acc)[2], int prev_jb, const floatx16_t (&prev)[2],
+                                  int parity, bool more) {
+#pragma unroll
+                for (int g = 0; g < 3; ++g) {
+                    const int cur = (parity + g) & 1;
+                    if (g < 2) load_group(jb, g + 1, av[cur ^ 1]);
+                    else if (more) load_group(jb + 1, 0, av[cur ^ 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mfma_group(g, av[cur], acc);
+                    if (prev_jb >= 0) { rank_part(prev_jb, prev, g); interleave6(); }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            load_group(0, 0, av[0]);
+            block_step(0, accA, -1, accB, 0, true);                 // groups 0..2: parities 0, 1, 0
+            for (int jb = 1; jb + 1 < nb; jb += 2) {
+                block_step(jb, accB, jb - 1, accA, 1, true);        // groups 3..5: parities 1, 0, 1
+                block_step(jb + 1, accA, jb, accB, 0, true);
             }
-            score_block(nb - 1, accB);  rank_block(nb - 2, accA);  interleave();
+            block_step(nb - 1, accB, nb - 2, accA, 1, false);
             rank_block(nb - 1, accB);
         }
         // tag -> centroid index: row 8*(r/4) + 4*half + r%4 of block jb
