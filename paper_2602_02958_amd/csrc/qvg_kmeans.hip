@@ -5,9 +5,10 @@
 //   rank:  a stable counting sort of the token indices of one unit by cluster id
 //          (16 wavefronts, each histogramming and then placing its own contiguous range
 //          of tokens, ballot-built peer masks keeping equal ids in token order);
-//   mean:  one wavefront per centroid walks its members in that order, two channels
-//          per lane (a 256-byte coalesced row per member), up to 128 rows in flight,
-//          adds in fp64, divides by the count, rounds to fp32 and then to bf16.
+//   mean:  one wavefront per centroid adds its members in fp64, divides by the count, rounds
+//          to fp32 and then to bf16: in token order for short lists, in four interleaved
+//          partial sums for long ones when a test on the members' exponents shows that no
+//          addition can round (then every order gives the same bits).
 //          A group without members keeps its previous centroid.
 // Also here: the residual pass that turns one smoothing stage's output into the next one's
 // input (Eq. 5 on whole tensors, result rounded to bf16).
@@ -126,9 +127,21 @@ void kmeans_rank_kernel(UpdateArgs a) {
 }
 
 constexpr int kMeanThreads = 256;           // 4 wavefronts = 4 centroids per block
+constexpr int kMeanParallelMin = 96;        // member lists at least this long try the order-free path
 
-// WIDE: many members per centroid (few, long waves): see the comments inside
-template <bool WIDE>
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+
+// One wavefront per centroid.  The defined result is the fp64 sum of the members in token order.
+// Short lists are summed exactly like that (two channels per lane, 16 rows in flight).  A long list
+// is latency-bound that way (one dependent fp64 add per member), so it is first summed in FOUR
+// interleaved partial sums (lane = member slot x 8 channels, 16-byte row pieces), which is the same
+// number whenever no addition rounds: every member is an integer multiple of 2^(emin-134) and every
+// partial sum is below n * 256 * 2^(emax-134), with emin / emax the smallest / largest exponent
+// field among the non-zero members of the channel, so if
+//     ceil(log2 n) + 8 + emax - emin <= 53
+// all partial sums of any order are exact in fp64.  The exponents are tracked alongside (packed
+// 16-bit min / max of the magnitudes' bit patterns); a centroid with a channel that fails the
+// test is summed again in token order.
 __global__ __launch_bounds__(kMeanThreads)
 void kmeans_mean_kernel(UpdateArgs a) {
     const int h = blockIdx.y, lane = threadIdx.x & 63;
@@ -139,76 +152,111 @@ void kmeans_mean_kernel(UpdateArgs a) {
     const int32_t *offs = a.offsets + (int64_t)h * (K + 1);
     const int32_t *perm = a.perm + (int64_t)h * N;
     const int beg = offs[j], end = offs[j + 1];
-    const int64_t co = ((int64_t)h * K + j) * kHeadDim + lane * 2;
+    const int64_t co = ((int64_t)h * K + j) * kHeadDim;
     if (end == beg) {
-        *reinterpret_cast<uint32_t *>(a.cent_out + co) = *reinterpret_cast<const uint32_t *>(a.cent_prev + co);
+        *reinterpret_cast<uint32_t *>(a.cent_out + co + lane * 2) = *reinterpret_cast<const uint32_t *>(a.cent_prev + co + lane * 2);
         return;
     }
-    double s0 = 0.0, s1 = 0.0;
-    if (!WIDE) {
-        // few members per centroid (many small waves): 16 rows in flight, few registers
-        const bf16_t *xb = a.x + (int64_t)h * a.stride_head + lane * 2;
-        for (int base = beg; base < end; base += 64) {
-            // 64 member indices with one coalesced load, then broadcast lane by lane
-            const int mine = (base + lane < end) ? perm[base + lane] : 0;
-            const int cntm = (end - base < 64) ? end - base : 64;
-            for (int u0 = 0; u0 < cntm; u0 += 16) {
-                uint32_t wv[16];
+    const double c = (double)(end - beg);
+    const bf16_t *xu = a.x + (int64_t)h * a.stride_head;
+
+    if (end - beg >= kMeanParallelMin) {
+        const int slot = lane >> 4, c8 = lane & 15;
+        double s[8];
 #pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    const int idx = __shfl(mine, u0 + u, 64);
-                    wv[u] = (u0 + u < cntm)
-                        ? *reinterpret_cast<const uint32_t *>(xb + (int64_t)idx * a.stride_token) : 0u;
+        for (int i = 0; i < 8; ++i) s[i] = 0.0;
+        uint32_t amax[4] = {0u, 0u, 0u, 0u};                       // per 16-bit half: largest |bits|
+        uint32_t amin[4] = {~0u, ~0u, ~0u, ~0u};                   // per half: smallest non-zero |bits|, minus 1
+        const bf16_t *xb = xu + c8 * 8;
+        for (int base = beg; base < end; base += 64) {
+            const int mine = (base + lane < end) ? perm[base + lane] : 0;     // 64 member indices, one coalesced load
+            const int cntm = (end - base < 64) ? end - base : 64;
+            // slot s takes members s, s + 4, s + 8, .. of the group; 8 rows in flight per lane
+            for (int i0 = 0; 4 * i0 < cntm; i0 += 8) {
+                uint4 row[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int u = 4 * (i0 + i) + slot;
+                    const int idx = __shfl(mine, u & 63, 64);
+                    row[i] = (u < cntm) ? *reinterpret_cast<const uint4 *>(xb + (int64_t)idx * a.stride_token)
+                                        : make_uint4(0u, 0u, 0u, 0u);
                 }
 #pragma unroll
-                for (int u = 0; u < 16; ++u)
-                    if (u0 + u < cntm) { s0 += (double)bf16_lo(wv[u]); s1 += (double)bf16_hi(wv[u]); }
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t w[4] = {row[i].x, row[i].y, row[i].z, row[i].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        s[2 * e] += (double)bf16_lo(w[e]);
+                        s[2 * e + 1] += (double)bf16_hi(w[e]);
+                        const uint32_t mag = w[e] & 0x7fff7fffu;
+                        const ushort2_t m2 = __builtin_bit_cast(ushort2_t, mag);
+                        amax[e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, amax[e]), m2));
+                        const ushort2_t one = {1, 1};
+                        amin[e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(ushort2_t, amin[e]),
+                                                                                         (ushort2_t)(m2 - one)));   // zero -> 0xffff
+                    }
+                }
             }
         }
-    } else {
-        // Members are walked 64 at a time: one coalesced load brings their indices (one group
-        // ahead), a constant-lane read moves each index into a scalar register, so the row address is
-        // scalar arithmetic, and all 64 rows of the NEXT group are requested before the current
-        // group is added.  The additions are strictly ordered (fp64, token order); with two groups
-        // in flight they run in the shadow of the loads.
-        const bf16_t *xu = a.x + (int64_t)h * a.stride_head;
-        auto load64 = [&](int mine, int cntm, uint32_t (&wv)[64]) {
+        // the four slots hold partial results of the same channels: lanes l, l^16, l^32, l^48
+        bool ok = true;
+        int lg = 0;
+        while ((1 << lg) < end - beg) ++lg;                          // ceil(log2 n)
 #pragma unroll
-            for (int u = 0; u < 64; ++u) {
-                const int idx = __builtin_amdgcn_readlane(mine, u);
-                const bf16_t *row = xu + (int64_t)idx * a.stride_token;
-                wv[u] = (u < cntm) ? *reinterpret_cast<const uint32_t *>(row + lane * 2) : 0u;   // uniform condition
+        for (int e = 0; e < 4; ++e) {
+            uint32_t mx = amax[e], mn = amin[e];
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) {
+                const uint32_t omx = __shfl_xor(mx, off, 64), omn = __shfl_xor(mn, off, 64);
+                mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx), __builtin_bit_cast(ushort2_t, omx)));
+                mn = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(ushort2_t, mn), __builtin_bit_cast(ushort2_t, omn)));
             }
-        };
-        auto add64 = [&](int cntm, const uint32_t (&wv)[64]) {
-            if (cntm == 64) {
 #pragma unroll
-                for (int u = 0; u < 64; ++u) { s0 += (double)bf16_lo(wv[u]); s1 += (double)bf16_hi(wv[u]); }
-            } else {
-#pragma unroll
-                for (int u = 0; u < 64; ++u)
-                    if (u < cntm) { s0 += (double)bf16_lo(wv[u]); s1 += (double)bf16_hi(wv[u]); }
+            for (int hf = 0; hf < 2; ++hf) {
+                const uint32_t big = (mx >> (16 * hf)) & 0xffffu, small1 = (mn >> (16 * hf)) & 0xffffu;
+                if (small1 == 0xffffu) continue;                     // no non-zero member in this channel: the sum is zero
+                const int eb = (int)(big >> 7) > 1 ? (int)(big >> 7) : 1;
+                const int es = (int)((small1 + 1u) >> 7) > 1 ? (int)((small1 + 1u) >> 7) : 1;
+                if (lg + 8 + eb - es > 53) ok = false;
             }
-        };
-        auto count_at = [&](int base) { return (end - base < 64) ? end - base : 64; };
-        auto indices_at = [&](int base) { return (base + lane < end) ? perm[base + lane] : 0; };
-        uint32_t wa[64], wb[64];
-        int mine_b = indices_at(beg + 64);
-        load64(indices_at(beg), count_at(beg), wa);
-        for (int base = beg; base < end; base += 128) {
-            // group B = [base + 64, base + 128), group A' = [base + 128, base + 192)
-            const int mine_a = indices_at(base + 128);
-            if (base + 64 < end) load64(mine_b, count_at(base + 64), wb);
-            add64(count_at(base), wa);
-            if (base + 64 >= end) break;
-            mine_b = indices_at(base + 192);
-            if (base + 128 < end) load64(mine_a, count_at(base + 128), wa);
-            add64(count_at(base + 64), wb);
+        }
+        if (__all(ok)) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                s[i] += __shfl_xor(s[i], 16, 64);
+                s[i] += __shfl_xor(s[i], 32, 64);
+            }
+            if (slot == 0) {
+                float m[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) m[i] = (float)(s[i] / c);
+                *reinterpret_cast<uint4 *>(a.cent_out + co + c8 * 8) = pack_bf16x8(m);
+            }
+            return;
         }
     }
-    const double c = (double)(end - beg);
+    // token order: two channels per lane, 16 rows in flight
+    double s0 = 0.0, s1 = 0.0;
+    const bf16_t *xb = xu + lane * 2;
+    for (int base = beg; base < end; base += 64) {
+        // 64 member indices with one coalesced load, then broadcast lane by lane
+        const int mine = (base + lane < end) ? perm[base + lane] : 0;
+        const int cntm = (end - base < 64) ? end - base : 64;
+        for (int u0 = 0; u0 < cntm; u0 += 16) {
+            uint32_t wv[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int idx = __shfl(mine, u0 + u, 64);
+                wv[u] = (u0 + u < cntm)
+                    ? *reinterpret_cast<const uint32_t *>(xb + (int64_t)idx * a.stride_token) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (u0 + u < cntm) { s0 += (double)bf16_lo(wv[u]); s1 += (double)bf16_hi(wv[u]); }
+        }
+    }
     const float m0 = (float)(s0 / c), m1 = (float)(s1 / c);
-    *reinterpret_cast<uint32_t *>(a.cent_out + co) = pack_bf16x2(m0, m1);
+    *reinterpret_cast<uint32_t *>(a.cent_out + co + lane * 2) = pack_bf16x2(m0, m1);
 }
 
 // Residual for the next smoothing stage: 16 lanes per token, 8 channels each.
@@ -242,9 +290,7 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.K + 3) / 4), (unsigned)a.H);
-    // long member lists are latency-bound on their ordered sums: more rows in flight pays there
-    if (a.n_tokens / a.K >= 48) hipLaunchKernelGGL(kmeans_mean_kernel<true>, grid, dim3(kMeanThreads), 0, s, a);
-    else hipLaunchKernelGGL(kmeans_mean_kernel<false>, grid, dim3(kMeanThreads), 0, s, a);
+    hipLaunchKernelGGL(kmeans_mean_kernel, grid, dim3(kMeanThreads), 0, s, a);
     return hipGetLastError();
 }
 

