@@ -408,7 +408,7 @@ constexpr size_t kAtSmemStaged = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint
 
 template <bool V> struct BoolC { static constexpr bool value = V; };
 
-template <int T_, bool ROPE>      // ROPE: rotate the decoded keys by a.rope
+template <int T_, bool ROPE, bool FP8>      // ROPE: rotate the decoded keys by a.rope; FP8: E4M3 scale bytes
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_xcd) {
     constexpr int T = T_;
@@ -437,8 +437,9 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
 
     const uint8_t *k_ids = a.k_ids + (int64_t)h * a.kv_stride, *v_ids = a.v_ids + (int64_t)h * a.kv_stride;
     const uint8_t *k_codes = a.k_codes + (int64_t)h * a.kv_stride * T * 32, *v_codes = a.v_codes + (int64_t)h * a.kv_stride * T * 32;
-    const unsigned char *k_scales = reinterpret_cast<const unsigned char *>(a.k_scales + (int64_t)h * a.kv_stride * T * G);
-    const unsigned char *v_scales = reinterpret_cast<const unsigned char *>(a.v_scales + (int64_t)h * a.kv_stride * T * G);
+    constexpr int SZ = FP8 ? 1 : 2;                                     // bytes of a stored scale
+    const unsigned char *k_scales = reinterpret_cast<const unsigned char *>(a.k_scales) + (int64_t)h * a.kv_stride * T * G * SZ;
+    const unsigned char *v_scales = reinterpret_cast<const unsigned char *>(a.v_scales) + (int64_t)h * a.kv_stride * T * G * SZ;
     const bf16_t *k_cent = a.k_cent + (int64_t)h * a.chunk_stride * K * kHeadDim;
     const bf16_t *v_cent = a.v_cent + (int64_t)h * a.chunk_stride * K * kHeadDim;
 
@@ -471,8 +472,8 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     // predicates at all, the common case) and the general one.
     constexpr int kPieces = 2 * kAtKv * T * 2;                       // code pieces, both sides
     constexpr int kPiecesPerThread = (kPieces + kAtThreads - 1) / kAtThreads;
-    const int scPiecesSide = kAtKv * T * G / 8;                      // scale pieces per side (<= 256)
-    const int scBytesTok = T * G * 2;
+    const int scPiecesSide = kAtKv * T * G * SZ / 16;                // scale pieces per side (<= 256)
+    const int scBytesTok = T * G * SZ;                               // even (the host sees to it)
     struct Fetch { uint4 code[kPiecesPerThread]; uint4 sc; uint32_t id; };
 
     auto fetch_tile = [&](auto full, const Tile &t, Fetch &f) {
@@ -569,7 +570,8 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         for (int s = 0; s < 2; ++s) {
             Raw<T> r;
             const uint16_t *cp = reinterpret_cast<const uint16_t *>(st + s * kStCodes) + tok * T * 16 + c8;
-            const uint16_t *sp = reinterpret_cast<const uint16_t *>(st + 2 * kStCodes + s * kStScales) + tok * T * G + g;
+            typedef typename std::conditional<FP8, uint8_t, uint16_t>::type scale_t;
+            const scale_t *sp = reinterpret_cast<const scale_t *>(st + 2 * kStCodes + s * kStScales) + tok * T * G + g;
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
 #pragma unroll
@@ -580,7 +582,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
                 r.cen[e] = (FULL || tok + e < nvalid) ? cen[s][e] : make_uint4(0u, 0u, 0u, 0u);
             }
             float accA[8], accB[8];
-            dequant2x8<T, T>(r, T, accA, accB);
+            dequant2x8<T, T, false, FP8 ? kFmtE4M3 : 0>(r, T, accA, accB);
             if (s == 0) {
                 if (ROPE) { rope_rotate8(accA, rp[0]); rope_rotate8(accB, rp[1]); }
                 uint16_t *kt = Kt + buf * kKtElems;
@@ -743,11 +745,11 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     }
 }
 
-template <int T_, bool ROPE>
+template <int T_, bool ROPE, bool FP8>
 static hipError_t launch_attn_staged_r(const AttnArgs &a, hipStream_t s) {
     static bool configured = false;          // the attribute is per function, set once per process
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE, FP8>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmemStaged);
         if (e != hipSuccess) return e;
         configured = true;
@@ -756,13 +758,13 @@ static hipError_t launch_attn_staged_r(const AttnArgs &a, hipStream_t s) {
     const int64_t nb = nqb * a.H;
     if (nb > 0x7fffffff - 8) return hipErrorInvalidValue;
     const int bpx = (int)((nb + 7) / 8);
-    hipLaunchKernelGGL((attn_kernel_staged<T_, ROPE>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmemStaged, s, a,
+    hipLaunchKernelGGL((attn_kernel_staged<T_, ROPE, FP8>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmemStaged, s, a,
                        (int)nqb, (int)nb, bpx);
     return hipGetLastError();
 }
-template <int T_>
+template <int T_, bool FP8 = false>
 static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
-    return a.rope ? launch_attn_staged_r<T_, true>(a, s) : launch_attn_staged_r<T_, false>(a, s);
+    return a.rope ? launch_attn_staged_r<T_, true, FP8>(a, s) : launch_attn_staged_r<T_, false, FP8>(a, s);
 }
 
 template <int T_, bool MULTI, int FMT, bool ROPE>
@@ -789,14 +791,28 @@ static hipError_t launch_attn_fmt(const AttnArgs &a, hipStream_t s) {
 
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     if (a.n_q == 0) return hipSuccess;
+    // the staged kernel fetches scales in 16-byte pieces: every chunk must start on one
+    const bool aligned = (a.chunk_len % 8 == 0) || a.n_chunks == 1;
     switch (a.fmt) {
         case 0: break;
-        case kFmtE4M3: return launch_attn_fmt<kFmtE4M3>(a, s);
+        case kFmtE4M3:
+            // 2-bit levels with E4M3 scales (the paper's own format): the staged kernel when a token's
+            // scale record has an even number of bytes (its tail handling moves two at a time)
+            // and every unit's scale array starts on a 16-byte boundary
+            if (a.S == 1 && aligned && a.T <= kStMaxT && ((a.T * (kHeadDim / a.B)) & 1) == 0 &&
+                ((reinterpret_cast<uintptr_t>(a.k_scales) | reinterpret_cast<uintptr_t>(a.v_scales)) & 15u) == 0 &&
+                (a.H == 1 || (a.kv_stride * a.T * (kHeadDim / a.B)) % 16 == 0)) {
+                switch (a.T) {
+                    case 1: return launch_attn_staged<1, true>(a, s);
+                    case 2: return launch_attn_staged<2, true>(a, s);
+                    case 3: return launch_attn_staged<3, true>(a, s);
+                    default: return launch_attn_staged<4, true>(a, s);
+                }
+            }
+            return launch_attn_fmt<kFmtE4M3>(a, s);
         case kFmtInt4: return launch_attn_fmt<kFmtInt4>(a, s);
         default: return launch_attn_fmt<kFmtInt4 | kFmtE4M3>(a, s);
     }
-    // the staged kernel fetches scales in 16-byte pieces: every chunk must start on one
-    const bool aligned = (a.chunk_len % 8 == 0) || a.n_chunks == 1;
     // several smoothing stages: the general kernel (the paper's presets have one round)
     if (a.S > 1) return a.T == 1 ? launch_attn_t<1, true>(a, s) : launch_attn_t<0, true>(a, s);
     if (!aligned || a.T > kStMaxT) return launch_attn_t<0, false>(a, s);
