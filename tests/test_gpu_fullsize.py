@@ -228,3 +228,66 @@ def test_cfg5_drifting_stream_four_rounds():
     assert np.array_equal(P.to_np_u16(cache.scales[u, sl]), ref["scales"][0])
     want = O.decode_batch(ref["cent"], ref["ids"], ref["codes"], ref["scales"], wl.group_size)
     assert np.array_equal(P.to_np_u16(dec[u, sl]), want[0])
+
+
+@pytest.mark.parametrize("S,Bg,bits,with_rope", [(1, 64, 2, True), (4, 16, 4, False)])
+def test_paper_presets_on_the_cfg2_window_sampled(S, Bg, bits, with_rope):
+    """The paper's presets (one round, K = 256, E4M3 scales; QVG INT2 and QVG-Pro INT4) at the size
+    and in the launches bench.py's `paper_presets` times: 24 units, 8 chunks of 4680 tokens, 4680
+    queries.  Sampled: the last chunk's encode on two units (whole Lloyd fit), the decode of two
+    units, the attention of 24 queries of two heads over the full cache (with the rotary embedding
+    of the decoded keys for the first preset)."""
+    from paper_2602_02958_amd import synth
+    wl = CONFIGS["cfg2_window21"]
+    heads, units, L, n, K = wl.heads, 2 * wl.heads, wl.chunk, wl.tokens_per_layer, 256
+    cache = B.alloc_cache(units, n, L, K, Bg, 1, 128, "cuda", n_smooth=S, bits=bits, scale_format=B.SCALE_E4M3)
+    sk, sv = synth.MixtureStream(wl, heads, 0, "cuda"), synth.MixtureStream(wl, heads, 1, "cuda")
+    x = init = None
+    for c in range(wl.n_chunks):
+        x = torch.cat([sk.next_chunk(L), sv.next_chunk(L)], 0)
+        if c > 0:
+            init = cache.centroids[:, c - 1].contiguous()
+        elif S > 1:
+            init = torch.stack([synth.cold_start_centroids(x, K, seed=st) for st in range(S)], 1)
+        else:
+            init = synth.cold_start_centroids(x, K, seed=0)
+        B.encode_chunk(x, init, Bg, 1, 10 if c == 0 else 3, cache=cache, chunk_index=c)
+    dec = B.decode(cache)
+    q = synth.queries(wl, heads, wl.n_queries, "cuda")
+    rope = bench_rope(n) if with_rope else None
+    k = B.Encoded(cache.centroids[:heads], cache.ids[:heads], cache.codes[:heads], cache.scales[:heads], L, S)
+    v = B.Encoded(cache.centroids[heads:], cache.ids[heads:], cache.codes[heads:], cache.scales[heads:], L, S)
+    out = B.attn_decode(q, k, v, k_rope=rope)
+    torch.cuda.synchronize()
+    c = wl.n_chunks - 1
+    lo = c * L
+    sel = [3, 20]
+    ref = O.encode_batch(bf16_bits(x[sel]), P.to_np_u16(init[sel]), K, Bg, 1, 3, S=S, bits=bits, scale_fmt=1)
+    assert np.array_equal(P.to_np_u16(cache.centroids[sel, c]).reshape(2, S, K, 128), ref["cent"])
+    assert np.array_equal(P.to_np_u8(cache.ids[sel, lo:]).reshape(2, L, S).transpose(0, 2, 1), ref["ids"])
+    assert np.array_equal(P.to_np_u8(cache.codes[sel, lo:]), ref["codes"])
+    assert np.array_equal(P.to_np_u8(cache.scales[sel, lo:]).astype(np.uint16), ref["scales"])
+    for u in (0, heads):                                     # K of head 0, V of head 0: the whole cache
+        want = np.concatenate([
+            O.decode_unit(P.to_np_u16(cache.centroids[u, cc]).reshape(S, K, 128),
+                          P.to_np_u8(cache.ids[u, cc * L:(cc + 1) * L]).reshape(L, S).T,
+                          P.to_np_u8(cache.codes[u, cc * L:(cc + 1) * L]),
+                          P.to_np_u8(cache.scales[u, cc * L:(cc + 1) * L]).astype(np.uint16), Bg, bits=bits, scale_fmt=1)
+            for cc in range(wl.n_chunks)])
+        assert np.array_equal(P.to_np_u16(dec[u]), want)
+    rng = np.random.default_rng(4)
+    qi = np.sort(rng.choice(wl.n_queries, 24, replace=False))
+    qi[0], qi[-1] = 0, wl.n_queries - 1
+    k_hat = P.to_np_u16(dec[0])
+    if with_rope:
+        k_hat = O.rope_keys(k_hat, rope.cpu().view(torch.int16).numpy().view(np.uint16))
+    want = O.attention(bf16_bits(q[0])[qi], k_hat, P.to_np_u16(dec[heads]))
+    ok, max_abs, worst = P.attn_tolerance_ok(P.to_np_u16(out[0])[qi], want)
+    assert ok, f"max abs err {max_abs}, worst err/tol {worst}"
+
+
+def bench_rope(n, d=128):
+    pos = torch.arange(n, dtype=torch.float64, device="cuda")
+    freq = 10000.0 ** (-torch.arange(d // 2, dtype=torch.float64, device="cuda") / (d // 2))
+    ang = pos[:, None] * freq[None]
+    return torch.stack([ang.cos(), ang.sin()], -1).to(torch.float16).contiguous()
