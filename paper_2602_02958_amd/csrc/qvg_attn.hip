@@ -18,9 +18,12 @@
 //      other LDS buffer, from data that was requested one or two tiles earlier.
 // The decode work is amortised over 256 queries; only the two contractions use the matrix
 // cores, the unpack / fma / soft-max work is VALU and is what bounds the kernel.
-// Two kernels: attn_kernel_staged (one smoothing stage, 1..4 quantization rounds, chunks that
-// start on 16-byte boundaries of the scale array: the measured path) and attn_kernel_direct
-// (everything else).
+// Two kernels: attn_kernel_staged (one smoothing stage, 1..4 rounds of 2-bit levels with binary16
+// or E4M3 scales, chunks that start on 16-byte boundaries of the scale array: the measured path)
+// and attn_kernel_direct (everything else: more rounds, several smoothing stages, 4-bit levels).
+// Both can rotate the decoded keys by a caller-supplied (cos, sin) table (keys are cached before
+// the rotary embedding, Sec. 5 "Implementation") and read a prefix of caches allocated for more
+// tokens.  A small third kernel merges two partial results by their log-sum-exps.
 #include <type_traits>
 
 #include "qvg_internal.hpp"

@@ -15,6 +15,9 @@
 // With S > 1 smoothing stages a token has S ids and S centroid rows, added in stage order in fp32
 // before the rounds; the S tables of a chunk sit in LDS together when they fit in 64 KB, else the
 // rows are read from global memory (a general, slower variant of the same kernel).
+// The other stored formats (FP8 E4M3 scale bytes, 4-bit levels; Sec. 5 "Implementation") are
+// template variants of the same kernel: only the scale conversion and the field extraction differ.
+// The caches may be allocated for more tokens than are decoded (unit strides in the arguments).
 //
 // Mapping: 16 lanes per token, 8 channels (one 16-byte store) per lane, so that a
 // wavefront's store instruction covers 4 whole token rows = 1 KB contiguous.  A workgroup of
