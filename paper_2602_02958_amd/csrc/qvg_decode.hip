@@ -132,12 +132,18 @@ __device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t
                                                    hs(sc[up][t]), hs(sc[up + 1][t]));
             }
         }
-        if (ok[up])
-            *reinterpret_cast<uint4 *>(out_b + ((int64_t)(ln0 + up * kDecRows) * stride_token + lane16 * 8)) =
-                pack_bf16x8(accA);
-        if (ok[up + 1])
-            *reinterpret_cast<uint4 *>(out_b + ((int64_t)(ln0 + (up + 1) * kDecRows) * stride_token + lane16 * 8)) =
-                pack_bf16x8(accB);
+        // the output is written once and not read again by this kernel: streaming stores
+        typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+        if (ok[up]) {
+            const uint4 o = pack_bf16x8(accA);
+            __builtin_nontemporal_store(u32x4_t{o.x, o.y, o.z, o.w},
+                reinterpret_cast<u32x4_t *>(out_b + ((int64_t)(ln0 + up * kDecRows) * stride_token + lane16 * 8)));
+        }
+        if (ok[up + 1]) {
+            const uint4 o = pack_bf16x8(accB);
+            __builtin_nontemporal_store(u32x4_t{o.x, o.y, o.z, o.w},
+                reinterpret_cast<u32x4_t *>(out_b + ((int64_t)(ln0 + (up + 1) * kDecRows) * stride_token + lane16 * 8)));
+        }
     }
 }
 
