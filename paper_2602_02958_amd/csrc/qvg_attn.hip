@@ -40,6 +40,16 @@ constexpr int kKtElems = kAtKv * kKtPitch;
 constexpr int kVtElems = kHeadDim * kVtPitch;
 constexpr size_t kAtSmem = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint16_t);
 
+// acc + the eight f16 values of v, accumulated in fp32 (v_dot2_f32_f16 against ones)
+__device__ __forceinline__ float sum_f16_pairs(const uint4 &v, float acc) {
+    const halfx2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(halfx2_t, v.x), ones, acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(halfx2_t, v.y), ones, acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(halfx2_t, v.z), ones, acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(halfx2_t, v.w), ones, acc, false);
+    return acc;
+}
+
 struct CacheSide {                 // one of K / V, already offset to this unit
     const bf16_t *cent;            // [n_chunks][K][d]
     const uint8_t *ids; const uint8_t *codes;
@@ -347,12 +357,13 @@ void attn_kernel_direct(AttnArgs a) {
         for (int st = 0; st < 4; ++st) {
             float p[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
+            for (int e = 0; e < 8; ++e)
                 p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[st >> 1][(st & 1) * 8 + e], scale2, -m));
-                l += p[e];
-            }
             pb[st] = make_uint4(pack_f16x2_rtz(p[0], p[1]), pack_f16x2_rtz(p[2], p[3]),
                                 pack_f16x2_rtz(p[4], p[5]), pack_f16x2_rtz(p[6], p[7]));
+            // the normaliser is the sum of the f16 probabilities the PV contraction uses (their
+            // rounding toward zero would otherwise bias every output by up to 2^-10 of |V|)
+            l = sum_f16_pairs(pb[st], l);
         }
         // ---- O^T += V_tile^T . P --------------------------------------------
 #pragma unroll
@@ -674,12 +685,13 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         for (int st = 0; st < 4; ++st) {
             float p[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
+            for (int e = 0; e < 8; ++e)
                 p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[st >> 1][(st & 1) * 8 + e], scale2, -m));
-                l += p[e];
-            }
             pb[st] = make_uint4(pack_f16x2_rtz(p[0], p[1]), pack_f16x2_rtz(p[2], p[3]),
                                 pack_f16x2_rtz(p[4], p[5]), pack_f16x2_rtz(p[6], p[7]));
+            // the normaliser is the sum of the f16 probabilities the PV contraction uses (their
+            // rounding toward zero would otherwise bias every output by up to 2^-10 of |V|)
+            l = sum_f16_pairs(pb[st], l);
         }
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {

@@ -171,3 +171,60 @@ def test_more_levels_and_more_rounds_reconstruct_better():
             assert err[bits, fmt, 2] < 0.5 * err[bits, fmt, 1]
     for bits in (2, 4):
         assert err[bits, E4M3, 1] < 1.25 * err[bits, F16, 1]
+
+
+def test_seeded_sweep_over_parameter_combinations():
+    """Forty seeded draws of (H, N, chunk length, K, B, T, S, bits, scale format, Lloyd iterations):
+    a cache filled chunk by chunk, every stored array and the decode bit-equal to the oracle, the
+    fused attention over a random prefix within tolerance.  Small sizes, many shapes: ragged
+    chunks, K not a multiple of 32, N < K, single tokens."""
+    rng = np.random.default_rng(77)
+    wl = CONFIGS["cfg1_tiny"]
+    for draw in range(40):
+        H = int(rng.integers(1, 4))
+        K = int(rng.choice([1, 3, 16, 33, 64, 100, 256]))
+        Bg = int(rng.choice([16, 32, 64, 128]))
+        T = int(rng.integers(1, 5)) if draw % 5 else int(rng.integers(5, 9))
+        S = int(rng.choice([1, 1, 1, 2, 3]))
+        bits = int(rng.choice([2, 4]))
+        fmt = int(rng.choice([F16, E4M3]))
+        I = int(rng.integers(0, 3))
+        n_chunks = int(rng.integers(1, 4))
+        # f16 scale arrays are written with 16-byte stores: chunks must start on such a boundary
+        step = 8 if fmt == F16 else 1
+        L = int(rng.integers(1, 40)) * step
+        last = int(rng.integers(1, L + 1))
+        N = L * (n_chunks - 1) + last
+        tag = dict(draw=draw, H=H, K=K, B=Bg, T=T, S=S, bits=bits, fmt=fmt, I=I, L=L, N=N)
+        caches, xs = [], []
+        for kv in (0, 1):
+            st = synth.MixtureStream(wl, H, kv, DEV)
+            cache = B.alloc_cache(H, N, L, K, Bg, T, 128, DEV, n_smooth=S, bits=bits, scale_format=fmt)
+            for c in range(n_chunks):
+                n = min(L, N - c * L)
+                x = st.next_chunk(n)
+                init = torch.randn(H, S, K, 128, device=DEV).to(torch.bfloat16)
+                B.encode_chunk(x, init if S > 1 else init[:, 0].contiguous(), Bg, T, I, cache=cache, chunk_index=c)
+                ref = O.encode_batch(bf16_bits(x), bf16_bits(init), K, Bg, T, I, S=S, bits=bits, scale_fmt=fmt)
+                sl = slice(c * L, c * L + n)
+                assert np.array_equal(P.to_np_u16(cache.centroids[:, c]).reshape(H, S, K, 128), ref["cent"]), tag
+                assert np.array_equal(P.to_np_u8(cache.ids[:, sl]).reshape(H, n, S).transpose(0, 2, 1), ref["ids"]), tag
+                assert np.array_equal(P.to_np_u8(cache.codes[:, sl]), ref["codes"]), tag
+                assert np.array_equal(_scales_np(cache)[:, sl], ref["scales"]), tag
+                want = O.decode_batch(ref["cent"], ref["ids"], ref["codes"], ref["scales"], Bg, bits=bits, scale_fmt=fmt)
+                got = B.decode(cache, n_tokens=n, first_token=c * L)
+                assert np.array_equal(P.to_np_u16(got), want), tag
+            caches.append(cache)
+        n_kv = int(rng.integers(1, N + 1))
+        Nq = int(rng.integers(1, 70))
+        q = synth.queries(wl, H, Nq, DEV)
+        out, lse = B.attn_decode(q, caches[0], caches[1], want_lse=True, n_kv=n_kv)
+        khat, vhat = B.decode(caches[0]), B.decode(caches[1])
+        torch.cuda.synchronize()
+        for h in range(H):
+            want, lse_w = O.attention(bf16_bits(q[h]), P.to_np_u16(khat[h, :n_kv]), P.to_np_u16(vhat[h, :n_kv]), want_lse=True)
+            # this workload has channels scaled x8: the tolerance with the f16-probability term
+            ok, max_abs, worst = P.attn_tolerance_wide_range_ok(P.to_np_u16(out[h]), want, bf16_bits(q[h]),
+                                                                P.to_np_u16(khat[h, :n_kv]), P.to_np_u16(vhat[h, :n_kv]))
+            assert ok, (tag, h, max_abs, worst)
+            assert np.abs(lse[h].cpu().numpy() - lse_w).max() < 2e-3, tag
