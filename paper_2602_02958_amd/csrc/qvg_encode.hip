@@ -167,9 +167,10 @@ __device__ __forceinline__ void quantize_token(float *r, int T, bool valid, int 
 
 // grid: x = unit, y = block of 256 * tiles_per_wave tokens.  With the unit as the fastest grid
 // index and H a multiple of 8, all blocks of a unit run on one XCD and share its table in L2.
-template <int B_, bool FUSED>
+template <int B_, bool FUSED, bool NORMS_GIVEN>
 __global__ __launch_bounds__(kAsgThreads, 2)
 void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
+    constexpr bool norms_given = NORMS_GIVEN;
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t *lc = reinterpret_cast<bf16_t *>(smem);                       // [Kpad][kCPitch]
     bf16_t *lscr = lc + (size_t)Kpad * kCPitch;                          // [waves][128]
@@ -180,20 +181,53 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
     const int K = a.K;
     const int64_t N = a.n_tokens;
 
-    // ---- stage the centroid table (rows K.. are zero) and the split -||c||^2/2 ----
+    // ---- stage the centroid table (rows K.. are zero).  The norms either come from the
+    // preparation kernel (norms_given: many workgroups per unit would each repeat the fp64 sums)
+    // or are taken here while a row passes through (few workgroups per unit: one launch less): nh = fp32(-||c||^2 / 2) from an fp64 sum, split into three bf16 pieces by truncation
+    // (8 significant bits each, so hi + mid + lo == nh exactly) that go into the row's padding;
+    // rows K..Kpad-1 get a huge negative value so that they never win.  The largest ||c||^2 of the
+    // unit (one ulp up) is needed for the error band of the certification.
+    __shared__ uint32_t smax;
+    if (tid == 0) smax = 0u;
+    __syncthreads();
     const bf16_t *cg = a.cent + (int64_t)h * K * kHeadDim;
-    for (int i = tid; i < Kpad * 16; i += kAsgThreads) {
+    for (int i = tid; i < Kpad * 16; i += kAsgThreads) {           // Kpad*16 is a multiple of the block: whole waves
         const int row = i >> 4, c16 = i & 15;
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (row < K) v = *reinterpret_cast<const uint4 *>(cg + (int64_t)row * kHeadDim + c16 * 8);
         *reinterpret_cast<uint4 *>(lc + row * kCPitch + c16 * 8) = v;
+        if (norms_given) continue;                                  // uniform
+        double sq = 0.0;
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double lo = (double)bf16_lo(w[e]), hi = (double)bf16_hi(w[e]);
+            sq += lo * lo; sq += hi * hi;
+        }
+        sq += shfl_xor_f64(sq, 1); sq += shfl_xor_f64(sq, 2);
+        sq += shfl_xor_f64(sq, 4); sq += shfl_xor_f64(sq, 8);
+        if (c16 == 0) {
+            float nh = -3.0e38f;
+            if (row < K) {
+                nh = (float)(-0.5 * sq);
+                const float up = (float)sq * (1.0f + 0x1p-22f);      // upper bound of ||c||^2 in fp32, as its bit pattern
+                atomicMax(&smax, __float_as_uint(up));
+            }
+            const float hi = __uint_as_float(__float_as_uint(nh) & 0xffff0000u);
+            const float r1 = nh - hi;
+            const float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
+            const float lo = __uint_as_float(__float_as_uint(r1 - mid) & 0xffff0000u);
+            *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) =
+                make_uint4((__float_as_uint(hi) >> 16) | (__float_as_uint(mid) & 0xffff0000u), __float_as_uint(lo) >> 16, 0u, 0u);
+        }
     }
-    for (int row = tid; row < Kpad; row += kAsgThreads) {
-        const uint2 p = a.nh3[(int64_t)h * Kpad + row];
-        *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) = make_uint4(p.x, p.y, 0u, 0u);
-    }
-    const float cmax = a.cmax[h];
+    if (norms_given)
+        for (int row = tid; row < Kpad; row += kAsgThreads) {
+            const uint2 p = a.nh3[(int64_t)h * Kpad + row];
+            *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) = make_uint4(p.x, p.y, 0u, 0u);
+        }
     __syncthreads();
+    const float cmax = norms_given ? a.cmax[h] : __uint_as_float(smax);
     bf16_t *scr = lscr + wave * kHeadDim;
     // token operand of the extra MFMA step: three ones against (hi, mid, lo), lanes 0..31 only
     const uint32_t tagmask = vgpr_const(kTagMask);
@@ -477,8 +511,11 @@ template <int B_, bool FUSED>
 static hipError_t launch_assign_t(const AssignArgs &a, hipStream_t s) {
     const int Kpad = (a.K + 63) & ~63;
     const size_t smem = assign_smem_bytes(Kpad);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED, true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     // tokens per workgroup: 256 per step; more steps per workgroup amortise the table staging
     // once there are enough workgroups to fill the chip several times over
@@ -487,12 +524,22 @@ static hipError_t launch_assign_t(const AssignArgs &a, hipStream_t s) {
     while (tpw < 4 && (steps / (2 * tpw)) * a.H >= 2048) tpw *= 2;
     const int64_t gy = (steps + tpw - 1) / tpw;
     if (gy > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(centroid_prep_kernel, dim3((unsigned)a.H), dim3(kPrepThreads), 0, s, a.cent, a.K, Kpad,
-                       a.nh3, a.cmax);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((assign_kernel<B_, FUSED>), dim3((unsigned)a.H, (unsigned)gy), dim3(kAsgThreads), smem, s, a,
-                       Kpad, tpw);
+    // the centroid norms: by a kernel of their own when there are many workgroups (each would
+    // repeat the fp64 sums of its unit's table); inside the assignment kernel when there are few
+    // (the extra launch then costs more than the repeated sums: 0.165 -> 0.154 ms per cfg2 encode)
+    const bool norms_given = (int64_t)a.H * gy > 2048;
+    if (norms_given) {
+        hipLaunchKernelGGL(centroid_prep_kernel, dim3((unsigned)a.H), dim3(kPrepThreads), 0, s, a.cent, a.K, Kpad,
+                           a.nh3, a.cmax);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (norms_given)
+        hipLaunchKernelGGL((assign_kernel<B_, FUSED, true>), dim3((unsigned)a.H, (unsigned)gy), dim3(kAsgThreads), smem, s, a,
+                           Kpad, tpw);
+    else
+        hipLaunchKernelGGL((assign_kernel<B_, FUSED, false>), dim3((unsigned)a.H, (unsigned)gy), dim3(kAsgThreads), smem, s, a,
+                           Kpad, tpw);
     return hipGetLastError();
 }
 
