@@ -274,6 +274,60 @@ def presets_supplement(torch, B, synth, CONFIGS):
     return {name: preset_supplement(torch, B, synth, CONFIGS, **kw) for name, kw in PAPER_PRESETS.items()}
 
 
+def long_supplement(torch, B, synth, CONFIGS):
+    """One layer of the long-horizon configuration at full size (cfg5: 12 heads, 160 chunks of 4680
+    tokens = 748800 cached tokens per head, K = 256, T = 4, centres drifting from chunk to chunk):
+    the cache is filled chunk by chunk through the rollout object with centroid caching
+    (Sec. 4.3), then decoded and attended over as a whole."""
+    wl = CONFIGS["cfg5_long"]
+    dev = "cuda"
+    heads, L, n = wl.heads, wl.chunk, wl.tokens_per_layer
+    sc = B.StreamingCache(heads, n, L, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev,
+                          warm_iters=wl.kmeans_iters_warm, cold_iters=wl.kmeans_iters_cold)
+    sk, sv = synth.MixtureStream(wl, heads, 0, dev), synth.MixtureStream(wl, heads, 1, dev)
+    ev = []
+    x = None
+    for c in range(wl.n_chunks):
+        x = torch.cat([sk.next_chunk(L), sv.next_chunk(L)], 0)
+        init = synth.cold_start_centroids(x, wl.n_clusters) if c == 0 else None
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); sc.append(x, init=init); e1.record()
+        ev.append((e0, e1))
+    torch.cuda.synchronize()
+    ms = [a.elapsed_time(b) for a, b in ev]
+    out = {"workload": wl.name, "units": 2 * heads, "tokens": n, "chunks": wl.n_chunks,
+           "fill": {"first_chunk_cold_ms": round(ms[0], 4), "warm_chunk_ms_avg": round(sum(ms[1:]) / (len(ms) - 1), 4),
+                    "total_ms": round(sum(ms), 2)}}
+    # the last chunk again, cold (seeded token picks, 10 iterations), for the saving of Sec. 4.3
+    cold = B.alloc_cache(2 * heads, L, L, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
+    init = synth.cold_start_centroids(x, wl.n_clusters)
+    fn = lambda: B.encode_chunk(x, init, wl.group_size, wl.n_stages, wl.kmeans_iters_cold, cache=cold)
+    fn(); torch.cuda.synchronize()
+    out["fill"]["cold_chunk_ms"] = round(_event_ms(fn, 5), 4)
+    out["fill"]["speedup_warm_vs_cold"] = round(out["fill"]["cold_chunk_ms"] / out["fill"]["warm_chunk_ms_avg"], 2)
+    stored = sc.stored_bytes()
+    out["stored_GB"] = round(stored / 1e9, 3)
+    out["compression_ratio"] = round(2 * heads * n * 256 / stored, 3)
+    dec = torch.empty(2 * heads, n, wl.head_dim, dtype=torch.bfloat16, device=dev)
+    fn = lambda: sc.decode(out=dec)
+    fn(); torch.cuda.synchronize()
+    ms_d = _event_ms(fn, 3)
+    alg = 2 * heads * n * 256 + stored
+    out["decode"] = {"ms": round(ms_d, 3), "GBps_bf16_equiv": round(2 * heads * n * 256 / ms_d / 1e6, 1),
+                     "hbm_GBps_algorithmic": round(alg / ms_d / 1e6, 1), "hbm_frac": round(alg / ms_d / 1e6 / HBM_PEAK_GBPS, 4)}
+    del dec
+    q = synth.queries(wl, heads, wl.n_queries, dev)
+    o = torch.empty(heads, wl.n_queries, wl.head_dim, dtype=torch.bfloat16, device=dev)
+    fn = lambda: sc.attend(q, out=o)
+    fn(); torch.cuda.synchronize()
+    ms_a = _event_ms(fn, 2)
+    flops = 4.0 * wl.n_queries * n * wl.head_dim * heads
+    out["attn"] = {"ms": round(ms_a, 3), "TFLOPs": round(flops / ms_a / 1e9, 1),
+                   "mfma_frac": round(flops / ms_a / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                   "cache_tokens_per_s": round(n * heads / ms_a * 1e3, 1)}
+    return out
+
+
 def integration_supplement(torch, B, s):
     """Attention-side pieces of a generation step on the benchmark's own state: the fused
     attention with the rotary embedding applied to the decoded keys (pre-RoPE key caching, Sec. 5
@@ -363,7 +417,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large", action="store_true")
     ap.add_argument("--only", default=None,
-                    choices=["decode", "encode", "attn", "copy", "large_decode", "large_encode", "presets"],
+                    choices=["decode", "encode", "attn", "copy", "large_decode", "large_encode", "presets", "long"],
                     help="profiling aid: run just this part --steps times and print a short JSON "
                          "(copy = a plain device copy of 1 GiB, the reference the HBM counters "
                          "are scaled by)")
@@ -381,6 +435,9 @@ def main():
     B.lib()                                    # fail loudly if the HIP library is missing
     wl = CONFIGS[args.workload]
     torch.cuda.set_device(0)
+    if args.only == "long":
+        print(json.dumps(long_supplement(torch, B, synth, CONFIGS)))
+        return
     if args.only == "presets":
         print(json.dumps(presets_supplement(torch, B, synth, CONFIGS)))
         print(json.dumps(warm_start_supplement(torch, B, synth, wl)))
@@ -469,6 +526,9 @@ def main():
         result["paper_presets"] = presets_supplement(torch, B, synth, CONFIGS)
         result["warm_start"] = warm_start_supplement(torch, B, synth, wl)
         result["attn_integration"] = integration_supplement(torch, B, s)
+        del s
+        torch.cuda.empty_cache()
+        result["long_horizon"] = long_supplement(torch, B, synth, CONFIGS)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(result))

@@ -322,3 +322,89 @@ def kmeans_update(x, ids, centroids_prev):
     if st != 0:
         raise QvgError(st, "qvg_kmeans_update")
     return cent, counts
+
+
+class StreamingCache:
+    """The compressed K and V cache of one layer during a chunk-by-chunk rollout (paper Sec. 3.1,
+    4.3): allocated once for `capacity_tokens`, filled by `append`, read by `attend` / `decode`.
+    K heads and V heads are stacked as 2 * heads independent units so that one library call
+    encodes both.  Every chunk but the last appended one must be full (chunk_len tokens).
+    Argument marshalling only: every step runs in the library's kernels.
+
+    A chunk's k-means starts from the previous chunk's centroids (Sec. 4.3: centroid caching) and
+    runs `warm_iters` Lloyd iterations; the first chunk starts from `init` ([2 * heads, K, d], or
+    [2 * heads, S, K, d] with S smoothing stages) and runs `cold_iters`."""
+
+    def __init__(self, heads, capacity_tokens, chunk_len, n_clusters, group_size, n_stages, head_dim=128,
+                 device="cuda", n_smooth=1, bits=2, scale_format=SCALE_F16, warm_iters=3, cold_iters=10):
+        self.heads, self.chunk_len = heads, chunk_len
+        self.group_size, self.n_stages = group_size, n_stages
+        self.warm_iters, self.cold_iters = warm_iters, cold_iters
+        self.cache = alloc_cache(2 * heads, capacity_tokens, chunk_len, n_clusters, group_size, n_stages, head_dim,
+                                 device, n_smooth=n_smooth, bits=bits, scale_format=scale_format)
+        self.n_tokens = 0
+        p = make_params(2 * heads, n_clusters, group_size, n_stages, max(warm_iters, cold_iters), head_dim=head_dim,
+                        bits=bits, n_smooth_stages=n_smooth, scale_format=scale_format)
+        need = workspace_bytes(p, ENTRY_ENCODE, chunk_len)
+        self._ws = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
+
+    @property
+    def capacity(self) -> int:
+        return self.cache.ids.shape[1]
+
+    def _side(self, lo, hi) -> Encoded:
+        c = self.cache
+        return Encoded(c.centroids[lo:hi], c.ids[lo:hi], c.codes[lo:hi], c.scales[lo:hi], c.chunk_len, c.n_smooth)
+
+    @property
+    def k(self) -> Encoded:
+        return self._side(0, self.heads)
+
+    @property
+    def v(self) -> Encoded:
+        return self._side(self.heads, 2 * self.heads)
+
+    def append(self, kv_chunk, init=None, iters=None) -> int:
+        """Encode one chunk, kv_chunk [2 * heads, n, d] bf16 (K heads first), n <= chunk_len, at the
+        end of the cache.  Returns the chunk's index."""
+        if self.n_tokens % self.chunk_len != 0:
+            raise ValueError("the previous chunk was not full: nothing can be appended after it")
+        n = kv_chunk.shape[1]
+        if n < 1 or n > self.chunk_len or self.n_tokens + n > self.capacity:
+            raise ValueError("chunk does not fit")
+        c = self.n_tokens // self.chunk_len
+        if c > 0 and init is None:
+            init = self.cache.centroids[:, c - 1]
+            iters = self.warm_iters if iters is None else iters
+        elif init is None:
+            raise ValueError("the first chunk needs start centroids")
+        else:
+            iters = (self.cold_iters if c == 0 else self.warm_iters) if iters is None else iters
+        encode_chunk(kv_chunk, init, self.group_size, self.n_stages, iters, cache=self.cache, chunk_index=c,
+                     workspace=self._ws)
+        self.n_tokens += n
+        return c
+
+    def attend(self, q, k_rope=None, softmax_scale=None, want_lse=False, out=None):
+        """Attention of q [heads, n_q, d] over the tokens appended so far (decode fused in)."""
+        if self.n_tokens == 0:
+            raise ValueError("the cache is empty")
+        return attn_decode(q, self.k, self.v, softmax_scale=softmax_scale, want_lse=want_lse, out=out,
+                           n_kv=self.n_tokens, k_rope=k_rope)
+
+    def decode(self, out=None, first_chunk=0, n_tokens=None) -> torch.Tensor:
+        """bf16 [2 * heads, n, d] of the tokens appended so far, from chunk `first_chunk` on."""
+        first = first_chunk * self.chunk_len
+        n = self.n_tokens - first if n_tokens is None else n_tokens
+        if first + n > self.n_tokens:
+            raise ValueError("range beyond the tokens appended so far")
+        return decode(self.cache, out=out, n_tokens=n, first_token=first)
+
+    def stored_bytes(self) -> int:
+        """Bytes the appended tokens occupy (codes, scales, ids and the chunks' tables)."""
+        c = self.cache
+        per_tok = c.codes.shape[2] * c.codes.shape[3] + c.scales.shape[2] * c.scales.shape[3] * c.scales.element_size() \
+            + c.n_smooth
+        chunks = -(-self.n_tokens // self.chunk_len)
+        table = c.n_smooth * c.centroids.shape[-2] * c.centroids.shape[-1] * 2
+        return 2 * self.heads * (self.n_tokens * per_tok + chunks * table)

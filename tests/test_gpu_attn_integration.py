@@ -162,3 +162,38 @@ def test_decode_of_a_token_range_of_a_larger_cache(T, Bg, S, bits, fmt):
         assert part.shape == (H, n, 128) and torch.equal(part, whole[:, first:first + n])
     with pytest.raises(B.QvgError):
         B.decode(kc, n_tokens=10, first_token=7)             # not on a chunk boundary
+
+
+def test_streaming_cache_append_attend_decode():
+    """The rollout object: a cache allocated for five chunks, three and a bit appended with
+    centroid caching; every appended chunk equals a stand-alone encode from the same start, the
+    attention over what has been appended so far equals the oracle's over the decoded prefix."""
+    wl = CONFIGS["cfg2_window21"]
+    heads, L, K, Bg, T = 2, 520, 64, 32, 2
+    sc = B.StreamingCache(heads, 5 * L, L, K, Bg, T, warm_iters=2, cold_iters=4)
+    sk, sv = synth.MixtureStream(wl, heads, 0, DEV), synth.MixtureStream(wl, heads, 1, DEV)
+    q = synth.queries(wl, heads, 200, DEV)
+    prev = None
+    for c, n in enumerate((L, L, L, 133)):
+        x = torch.cat([sk.next_chunk(n), sv.next_chunk(n)], 0)
+        init = synth.cold_start_centroids(x, K) if c == 0 else None
+        assert sc.append(x, init=init) == c
+        start = init if c == 0 else prev
+        alone = B.encode_chunk(x, start, Bg, T, 4 if c == 0 else 2)
+        lo = c * L
+        assert torch.equal(sc.cache.centroids[:, c], alone.centroids[:, 0])
+        assert torch.equal(sc.cache.ids[:, lo:lo + n], alone.ids) and torch.equal(sc.cache.codes[:, lo:lo + n], alone.codes)
+        assert torch.equal(sc.cache.scales[:, lo:lo + n], alone.scales)
+        prev = sc.cache.centroids[:, c].clone()
+        out, lse = sc.attend(q, want_lse=True)
+        dec = sc.decode()
+        torch.cuda.synchronize()
+        assert dec.shape == (2 * heads, sc.n_tokens, 128)
+        for h in range(heads):
+            _check_against_oracle(q, out, lse, P.to_np_u16(dec[h]), P.to_np_u16(dec[heads + h]), h)
+    assert sc.n_tokens == 3 * L + 133
+    assert sc.stored_bytes() == B.compressed_bytes(B.make_params(2 * heads, K, Bg, T), L) * 3 + \
+        B.compressed_bytes(B.make_params(2 * heads, K, Bg, T), 133)
+    with pytest.raises(ValueError):
+        sc.append(torch.zeros(2 * heads, 10, 128, dtype=torch.bfloat16, device=DEV))      # after a partial chunk
+    assert torch.equal(sc.decode(first_chunk=2), sc.decode()[:, 2 * L:])
