@@ -274,12 +274,13 @@ def presets_supplement(torch, B, synth, CONFIGS):
     return {name: preset_supplement(torch, B, synth, CONFIGS, **kw) for name, kw in PAPER_PRESETS.items()}
 
 
-def long_supplement(torch, B, synth, CONFIGS):
-    """One layer of the long-horizon configuration at full size (cfg5: 12 heads, 160 chunks of 4680
-    tokens = 748800 cached tokens per head, K = 256, T = 4, centres drifting from chunk to chunk):
+def long_supplement(torch, B, synth, CONFIGS, name="cfg5_long"):
+    """One layer of a configuration at full size (default cfg5, the long-horizon one: 12 heads, 160
+    chunks of 4680 tokens = 748800 cached tokens per head, K = 256, T = 4, centres drifting from
+    chunk to chunk; also run for cfg4: 40 heads, 10 chunks of 10800 tokens, K = 128, T = 3, B = 32):
     the cache is filled chunk by chunk through the rollout object with centroid caching
     (Sec. 4.3), then decoded and attended over as a whole."""
-    wl = CONFIGS["cfg5_long"]
+    wl = CONFIGS[name]
     dev = "cuda"
     heads, L, n = wl.heads, wl.chunk, wl.tokens_per_layer
     sc = B.StreamingCache(heads, n, L, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev,
@@ -437,6 +438,8 @@ def main():
     torch.cuda.set_device(0)
     if args.only == "long":
         print(json.dumps(long_supplement(torch, B, synth, CONFIGS)))
+        torch.cuda.empty_cache()
+        print(json.dumps(long_supplement(torch, B, synth, CONFIGS, "cfg4_dit_large")))
         return
     if args.only == "presets":
         print(json.dumps(presets_supplement(torch, B, synth, CONFIGS)))
@@ -529,6 +532,8 @@ def main():
         del s
         torch.cuda.empty_cache()
         result["long_horizon"] = long_supplement(torch, B, synth, CONFIGS)
+        torch.cuda.empty_cache()
+        result["cfg4_layer"] = long_supplement(torch, B, synth, CONFIGS, "cfg4_dit_large")
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(result))
