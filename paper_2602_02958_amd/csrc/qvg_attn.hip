@@ -79,11 +79,16 @@ __device__ __forceinline__ Tile next_tile(const AttnArgs &a, Tile t) {
     return t;
 }
 
-template <int TM>
+// SM: how the smoothing stages are handled.  1: a single stage; 0: several, their number known at
+// run time only (the rows are added as they arrive, which waits for every load where it is
+// issued); 2..kMaxSmooth: that many stages, fixed at compile time (the rows stay packed in
+// registers while the loads are in flight and are added, in stage order, when the tile is decoded).
+template <int TM, int SM = 1>
 struct Raw {                       // what one thread loads for its 2 tokens x 8 channels of one side
     uint32_t code[2][TM], sc[2][TM];
     uint4 cen[2];                  // one smoothing stage: the centroid row (8 bf16)
-    float ci[2][8];                // several stages: their rows added in stage order (fp32)
+    float ci[2][8];                // SM == 0: the rows added in stage order (fp32)
+    uint4 rows[2][SM > 1 ? SM : 1];     // SM > 1: the stages' rows
 };
 
 // ids of this thread's two tokens of a tile (0 for tokens past the chunk end / an invalid tile);
@@ -102,9 +107,9 @@ __device__ __forceinline__ void load_ids(const CacheSide &s, const Tile &t, int 
 
 // FMT: stored format (kFmt* bits); with 4-bit levels a thread's 8 channels of a round are one
 // 32-bit word, else one 16-bit word
-template <int T_, int TM, bool MULTI, int FMT>
+template <int T_, int TM, int SM, int FMT>
 __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int tp, int c8, int T,
-                                         int G, int g, int K, int S, const uint32_t id[2], Raw<TM> &r) {
+                                         int G, int g, int K, int S, const uint32_t id[2], Raw<TM, SM> &r) {
     const bf16_t *cent = s.cent + (int64_t)t.chunk * S * K * kHeadDim;      // [S][K][d] of this chunk
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
@@ -113,9 +118,13 @@ __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int 
 #pragma unroll
         for (int k = 0; k < TM; ++k) { r.code[e][k] = 0u; r.sc[e][k] = 0u; }
         r.cen[e] = make_uint4(0u, 0u, 0u, 0u);
-        if (MULTI) {
+        if (SM == 0) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) r.ci[e][i] = 0.0f;
+        }
+        if (SM > 1) {
+#pragma unroll
+            for (int st = 0; st < SM; ++st) r.rows[e][st] = make_uint4(0u, 0u, 0u, 0u);
         }
         if (ok) {
             constexpr bool FP8 = (FMT & kFmtE4M3) != 0, I4 = (FMT & kFmtInt4) != 0;
@@ -126,8 +135,13 @@ __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int 
 #pragma unroll
             for (int k = 0; k < TM; ++k)
                 if (k < T) { r.code[e][k] = cp[k * 16]; r.sc[e][k] = sp[k * G]; }
-            if (!MULTI) {
+            if (SM == 1) {
                 r.cen[e] = *reinterpret_cast<const uint4 *>(cent + (int64_t)id[e] * kHeadDim + c8 * 8);
+            } else if (SM > 1) {
+#pragma unroll
+                for (int st = 0; st < SM; ++st)
+                    r.rows[e][st] = *reinterpret_cast<const uint4 *>(
+                        cent + ((int64_t)st * K + ((id[e] >> (8 * st)) & 0xffu)) * kHeadDim + c8 * 8);
             } else {
                 for (int st = 0; st < S; ++st) {
                     float row[8];
@@ -143,11 +157,22 @@ __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int 
 
 // fp32 decoded values of the thread's two tokens (tokens that do not exist decode to zero
 // because their codes, scales and centroid were loaded as zero)
-template <int T_, int TM, bool MULTI = false, int FMT = 0>
-__device__ __forceinline__ void dequant2x8(const Raw<TM> &r, int T, float *accA, float *accB) {
-    if (MULTI) {
+template <int T_, int TM, int SM = 1, int FMT = 0>
+__device__ __forceinline__ void dequant2x8(const Raw<TM, SM> &r, int T, float *accA, float *accB) {
+    if (SM == 0) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) { accA[i] = r.ci[0][i]; accB[i] = r.ci[1][i]; }
+    } else if (SM > 1) {
+        unpack_bf16x8(r.rows[0][0], accA);
+        unpack_bf16x8(r.rows[1][0], accB);
+#pragma unroll
+        for (int st = 1; st < SM; ++st) {
+            float ra[8], rb[8];
+            unpack_bf16x8(r.rows[0][st], ra);
+            unpack_bf16x8(r.rows[1][st], rb);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { accA[i] += ra[i]; accB[i] += rb[i]; }
+        }
     } else {
         unpack_bf16x8(r.cen[0], accA);
         unpack_bf16x8(r.cen[1], accB);
@@ -206,8 +231,8 @@ __device__ __forceinline__ void load_rope(const f16_t *rope, const Tile &t, int 
     }
 }
 
-template <int T_, bool MULTI, int FMT, bool ROPE>   // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages).
-                                // MULTI: more than one smoothing stage (a.S tables and id bytes)
+template <int T_, int SM, int FMT, bool ROPE>   // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages).
+                                // SM: smoothing stages (a.S tables and id bytes): 1, 2..4, or 0 = a.S
                                 // FMT: stored format (kFmt* bits)
                                 // ROPE: rotate the decoded keys by a.rope
 __global__ __launch_bounds__(kAtThreads, 2)
@@ -223,7 +248,7 @@ void attn_kernel_direct(AttnArgs a) {
     const int64_t qrow = (int64_t)blockIdx.x * kAtQPerBlock + wave * 32 + col;
     const bool qvalid = qrow < a.n_q;
     const int T = T_ > 0 ? T_ : a.T, B = a.B, K = a.K;
-    const int S = MULTI ? a.S : 1;
+    const int S = SM > 0 ? SM : a.S;
     const int G = kHeadDim / B;
     const uint32_t kmax = (uint32_t)K - 1u;
 
@@ -263,14 +288,14 @@ void attn_kernel_direct(AttnArgs a) {
     const float scale2 = a.scale * 1.4426950408889634f;
 
     uint4 rp[2];                      // (cos, sin) of the tile held in rk (ROPE only)
-    auto decode_to_lds = [&](const Raw<TM> &rk, const Raw<TM> &rv, int buf) {
+    auto decode_to_lds = [&](const Raw<TM, SM> &rk, const Raw<TM, SM> &rv, int buf) {
         float accA[8], accB[8];
-        dequant2x8<T_, TM, MULTI, FMT>(rk, T, accA, accB);
+        dequant2x8<T_, TM, SM, FMT>(rk, T, accA, accB);
         if (ROPE) { rope_rotate8(accA, rp[0]); rope_rotate8(accB, rp[1]); }
         uint16_t *kt = Kt + buf * kKtElems;
         *reinterpret_cast<uint4 *>(kt + (tok + 0) * kKtPitch + c8 * 8) = pack_bf16x8(accA);
         *reinterpret_cast<uint4 *>(kt + (tok + 1) * kKtPitch + c8 * 8) = pack_bf16x8(accB);
-        dequant2x8<T_, TM, MULTI, FMT>(rv, T, accA, accB);
+        dequant2x8<T_, TM, SM, FMT>(rv, T, accA, accB);
         uint16_t *vt = Vt + buf * kVtElems + v_off;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
@@ -287,11 +312,11 @@ void attn_kernel_direct(AttnArgs a) {
     Tile nxt = next_tile(a, cur);
     Tile nn = nxt.valid ? next_tile(a, nxt) : nxt;
     uint32_t idk[2], idv[2];
-    Raw<TM> rk, rv;
+    Raw<TM, SM> rk, rv;
     load_ids(ks, cur, tp, kmax, S, idk);
     load_ids(vs, cur, tp, kmax, S, idv);
-    load_raw<T_, TM, MULTI, FMT>(ks, cur, tp, c8, T, G, g, K, S, idk, rk);
-    load_raw<T_, TM, MULTI, FMT>(vs, cur, tp, c8, T, G, g, K, S, idv, rv);
+    load_raw<T_, TM, SM, FMT>(ks, cur, tp, c8, T, G, g, K, S, idk, rk);
+    load_raw<T_, TM, SM, FMT>(vs, cur, tp, c8, T, G, g, K, S, idv, rv);
     if (ROPE) load_rope(a.rope, cur, tp, c8, rp);
     load_ids(ks, nxt, tp, kmax, S, idk);
     load_ids(vs, nxt, tp, kmax, S, idv);
@@ -302,8 +327,8 @@ void attn_kernel_direct(AttnArgs a) {
     while (true) {
         // raw data of the next tile (consumed at the end of this iteration), ids of the one after
         if (nxt.valid) {
-            load_raw<T_, TM, MULTI, FMT>(ks, nxt, tp, c8, T, G, g, K, S, idk, rk);
-            load_raw<T_, TM, MULTI, FMT>(vs, nxt, tp, c8, T, G, g, K, S, idv, rv);
+            load_raw<T_, TM, SM, FMT>(ks, nxt, tp, c8, T, G, g, K, S, idk, rk);
+            load_raw<T_, TM, SM, FMT>(vs, nxt, tp, c8, T, G, g, K, S, idv, rv);
             if (ROPE) load_rope(a.rope, nxt, tp, c8, rp);
             load_ids(ks, nn, tp, kmax, S, idk);
             load_ids(vs, nn, tp, kmax, S, idv);
@@ -596,7 +621,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
                 r.cen[e] = (FULL || tok + e < nvalid) ? cen[s][e] : make_uint4(0u, 0u, 0u, 0u);
             }
             float accA[8], accB[8];
-            dequant2x8<T, T, false, FP8 ? kFmtE4M3 : 0>(r, T, accA, accB);
+            dequant2x8<T, T, 1, FP8 ? kFmtE4M3 : 0>(r, T, accA, accB);
             if (s == 0) {
                 if (ROPE) { rope_rotate8(accA, rp[0]); rope_rotate8(accB, rp[1]); }
                 uint16_t *kt = Kt + buf * kKtElems;
@@ -782,26 +807,34 @@ static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
     return a.rope ? launch_attn_staged_r<T_, true, FP8>(a, s) : launch_attn_staged_r<T_, false, FP8>(a, s);
 }
 
-template <int T_, bool MULTI, int FMT, bool ROPE>
+template <int T_, int SM, int FMT, bool ROPE>
 static hipError_t launch_attn_tr(const AttnArgs &a, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_, MULTI, FMT, ROPE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_, SM, FMT, ROPE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmem);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
-    hipLaunchKernelGGL((attn_kernel_direct<T_, MULTI, FMT, ROPE>), grid, dim3(kAtThreads), kAtSmem, s, a);
+    hipLaunchKernelGGL((attn_kernel_direct<T_, SM, FMT, ROPE>), grid, dim3(kAtThreads), kAtSmem, s, a);
     return hipGetLastError();
 }
-template <int T_, bool MULTI, int FMT = 0>
+template <int T_, int SM, int FMT = 0>
 static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
-    return a.rope ? launch_attn_tr<T_, MULTI, FMT, true>(a, s) : launch_attn_tr<T_, MULTI, FMT, false>(a, s);
+    return a.rope ? launch_attn_tr<T_, SM, FMT, true>(a, s) : launch_attn_tr<T_, SM, FMT, false>(a, s);
+}
+// several smoothing stages: the paper's form (two or four stages, one round) with the stage count
+// fixed at compile time, anything else with run-time counts
+template <int FMT>
+static hipError_t launch_attn_multi(const AttnArgs &a, hipStream_t s) {
+    if (a.T == 1 && a.S == 4) return launch_attn_t<1, 4, FMT>(a, s);
+    if (a.T == 1 && a.S == 2) return launch_attn_t<1, 2, FMT>(a, s);
+    return a.T == 1 ? launch_attn_t<1, 0, FMT>(a, s) : launch_attn_t<0, 0, FMT>(a, s);
 }
 
 // the other stored formats run on the general kernel
 template <int FMT>
 static hipError_t launch_attn_fmt(const AttnArgs &a, hipStream_t s) {
-    if (a.S > 1) return a.T == 1 ? launch_attn_t<1, true, FMT>(a, s) : launch_attn_t<0, true, FMT>(a, s);
-    if (a.T == 1) return launch_attn_t<1, false, FMT>(a, s);       // the paper's single round
-    return launch_attn_t<0, false, FMT>(a, s);
+    if (a.S > 1) return launch_attn_multi<FMT>(a, s);
+    if (a.T == 1) return launch_attn_t<1, 1, FMT>(a, s);       // the paper's single round
+    return launch_attn_t<0, 1, FMT>(a, s);
 }
 
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
@@ -829,8 +862,8 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
         default: return launch_attn_fmt<kFmtInt4 | kFmtE4M3>(a, s);
     }
     // several smoothing stages: the general kernel (the paper's presets have one round)
-    if (a.S > 1) return a.T == 1 ? launch_attn_t<1, true>(a, s) : launch_attn_t<0, true>(a, s);
-    if (!aligned || a.T > kStMaxT) return launch_attn_t<0, false>(a, s);
+    if (a.S > 1) return launch_attn_multi<0>(a, s);
+    if (!aligned || a.T > kStMaxT) return launch_attn_t<0, 1>(a, s);
     switch (a.T) {
         case 1: return launch_attn_staged<1>(a, s);
         case 2: return launch_attn_staged<2>(a, s);
