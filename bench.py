@@ -217,6 +217,25 @@ PAPER_PRESETS = {
 TABLE1_CHUNK_TOKENS = 34800     # the chunk length at which the stored sizes give Table 1's ratios
 
 
+def staged_cold_start(torch, B, synth, x, n_clusters, S, group_size, n_stages, iters, bits, scale_format):
+    """Start centroids of S smoothing stages for a first chunk: stage s starts from seeded picks
+    among the tokens of ITS input, the residual that the library's own fit of the stages before it
+    leaves (rebuilt here from that fit's centroids and ids, rounded to bf16 like the library's
+    stage input).  Picks among the original tokens would start every later stage far from its
+    data: nearly all of its clusters stay empty.  [units, S, K, d] bf16."""
+    inits, r = [], x
+    for s in range(S):
+        inits.append(synth.cold_start_centroids(r, n_clusters, seed=s))
+        if s + 1 < S:
+            enc = B.encode_chunk(x, torch.stack(inits, 1) if s else inits[0], group_size, n_stages, iters,
+                                 bits=bits, scale_format=scale_format)
+            cent = enc.centroids[:, 0] if s else enc.centroids[:, 0, None]      # [units, s+1, K, d]
+            ids = enc.ids if s else enc.ids[:, :, None]
+            idx = ids[:, :, s].long()[:, :, None].expand(-1, -1, x.shape[-1])
+            r = (r.float() - torch.gather(cent[:, s], 1, idx).float()).to(torch.bfloat16)
+    return torch.stack(inits, 1)
+
+
 def preset_supplement(torch, B, synth, CONFIGS, S=4, group_size=16, n_stages=1, n_clusters=256, bits=2,
                       scale_format=1):
     """One of the paper's presets on the cfg2 window: 24 units, 8 chunks of 4680 tokens, 4680
@@ -233,7 +252,7 @@ def preset_supplement(torch, B, synth, CONFIGS, S=4, group_size=16, n_stages=1, 
         if c > 0:
             init = cache.centroids[:, c - 1].contiguous()
         elif S > 1:
-            init = torch.stack([synth.cold_start_centroids(x, n_clusters, seed=st) for st in range(S)], 1)
+            init = staged_cold_start(torch, B, synth, x, n_clusters, S, group_size, n_stages, 10, bits, scale_format)
         else:
             init = synth.cold_start_centroids(x, n_clusters, seed=0)
         B.encode_chunk(x, init, group_size, n_stages, 10 if c == 0 else 3, cache=cache, chunk_index=c)

@@ -6,8 +6,9 @@
 //          (16 wavefronts, each histogramming and then placing its own contiguous range
 //          of tokens, ballot-built peer masks keeping equal ids in token order);
 //   mean:  one wavefront per centroid adds its members in fp64, divides by the count, rounds
-//          to fp32 and then to bf16: in token order for short lists, in four interleaved
-//          partial sums for long ones when a test on the members' exponents shows that no
+//          to fp32 and then to bf16: in token order for short lists, in interleaved partial
+//          sums for long ones (four per wavefront; the longest lists are spread over the
+//          wavefronts of the block) when a test on the members' exponents shows that no
 //          addition can round (then every order gives the same bits).
 //          A group without members keeps its previous centroid.
 // Also here: the residual pass that turns one smoothing stage's output into the next one's
@@ -127,115 +128,76 @@ void kmeans_rank_kernel(UpdateArgs a) {
 }
 
 constexpr int kMeanThreads = 256;           // 4 wavefronts = 4 centroids per block
+constexpr int kMeanWaves = kMeanThreads / 64;
 constexpr int kMeanParallelMin = 96;        // member lists at least this long try the order-free path
+constexpr int kMeanCoopMin = 192;           // lists at least this long are summed by the whole block
 
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 
-// One wavefront per centroid.  The defined result is the fp64 sum of the members in token order.
-// Short lists are summed exactly like that (two channels per lane, 16 rows in flight).  A long list
-// is latency-bound that way (one dependent fp64 add per member), so it is first summed in FOUR
-// interleaved partial sums (lane = member slot x 8 channels, 16-byte row pieces), which is the same
-// number whenever no addition rounds: every member is an integer multiple of 2^(emin-134) and every
-// partial sum is below n * 256 * 2^(emax-134), with emin / emax the smallest / largest exponent
-// field among the non-zero members of the channel, so if
-//     ceil(log2 n) + 8 + emax - emin <= 53
-// all partial sums of any order are exact in fp64.  The exponents are tracked alongside (packed
-// 16-bit min / max of the magnitudes' bit patterns); a centroid with a channel that fails the
-// test is summed again in token order.
-__global__ __launch_bounds__(kMeanThreads)
-void kmeans_mean_kernel(UpdateArgs a) {
-    const int h = blockIdx.y, lane = threadIdx.x & 63;
-    const int j = blockIdx.x * (kMeanThreads / 64) + (threadIdx.x >> 6);
-    const int K = a.K;
-    if (j >= K) return;
-    const int64_t N = a.n_tokens;
-    const int32_t *offs = a.offsets + (int64_t)h * (K + 1);
-    const int32_t *perm = a.perm + (int64_t)h * N;
-    const int beg = offs[j], end = offs[j + 1];
-    const int64_t co = ((int64_t)h * K + j) * kHeadDim;
-    if (end == beg) {
-        *reinterpret_cast<uint32_t *>(a.cent_out + co + lane * 2) = *reinterpret_cast<const uint32_t *>(a.cent_prev + co + lane * 2);
-        return;
-    }
-    const double c = (double)(end - beg);
-    const bf16_t *xu = a.x + (int64_t)h * a.stride_head;
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a), __builtin_bit_cast(ushort2_t, b)));
+}
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(ushort2_t, a), __builtin_bit_cast(ushort2_t, b)));
+}
 
-    if (end - beg >= kMeanParallelMin) {
-        const int slot = lane >> 4, c8 = lane & 15;
-        double s[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) s[i] = 0.0;
-        uint32_t amax[4] = {0u, 0u, 0u, 0u};                       // per 16-bit half: largest |bits|
-        uint32_t amin[4] = {~0u, ~0u, ~0u, ~0u};                   // per half: smallest non-zero |bits|, minus 1
-        const bf16_t *xb = xu + c8 * 8;
-        for (int base = beg; base < end; base += 64) {
-            const int mine = (base + lane < end) ? perm[base + lane] : 0;     // 64 member indices, one coalesced load
-            const int cntm = (end - base < 64) ? end - base : 64;
-            // slot s takes members s, s + 4, s + 8, .. of the group; 8 rows in flight per lane
-            for (int i0 = 0; 4 * i0 < cntm; i0 += 8) {
-                uint4 row[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int u = 4 * (i0 + i) + slot;
-                    const int idx = __shfl(mine, u & 63, 64);
-                    row[i] = (u < cntm) ? *reinterpret_cast<const uint4 *>(xb + (int64_t)idx * a.stride_token)
-                                        : make_uint4(0u, 0u, 0u, 0u);
-                }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const uint32_t w[4] = {row[i].x, row[i].y, row[i].z, row[i].w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        s[2 * e] += (double)bf16_lo(w[e]);
-                        s[2 * e + 1] += (double)bf16_hi(w[e]);
-                        const uint32_t mag = w[e] & 0x7fff7fffu;
-                        const ushort2_t m2 = __builtin_bit_cast(ushort2_t, mag);
-                        amax[e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, amax[e]), m2));
-                        const ushort2_t one = {1, 1};
-                        amin[e] = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(ushort2_t, amin[e]),
-                                                                                         (ushort2_t)(m2 - one)));   // zero -> 0xffff
-                    }
-                }
-            }
-        }
-        // the four slots hold partial results of the same channels: lanes l, l^16, l^32, l^48
-        bool ok = true;
-        int lg = 0;
-        while ((1 << lg) < end - beg) ++lg;                          // ceil(log2 n)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            uint32_t mx = amax[e], mn = amin[e];
-#pragma unroll
-            for (int off = 16; off <= 32; off <<= 1) {
-                const uint32_t omx = __shfl_xor(mx, off, 64), omn = __shfl_xor(mn, off, 64);
-                mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx), __builtin_bit_cast(ushort2_t, omx)));
-                mn = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(ushort2_t, mn), __builtin_bit_cast(ushort2_t, omn)));
-            }
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const uint32_t big = (mx >> (16 * hf)) & 0xffffu, small1 = (mn >> (16 * hf)) & 0xffffu;
-                if (small1 == 0xffffu) continue;                     // no non-zero member in this channel: the sum is zero
-                const int eb = (int)(big >> 7) > 1 ? (int)(big >> 7) : 1;
-                const int es = (int)((small1 + 1u) >> 7) > 1 ? (int)((small1 + 1u) >> 7) : 1;
-                if (lg + 8 + eb - es > 53) ok = false;
-            }
-        }
-        if (__all(ok)) {
+// Order-free partial sums of a member list: the wavefront takes the groups of 64 members
+// first, first + step, .. of perm[beg .. end); lane = member slot (4) x 8 channels, 8 rows in
+// flight per lane.  s: the lane's partial sums of its 8 channels; amax / amin: per 16-bit half the
+// largest magnitude bits and the smallest non-zero magnitude bits minus one (0xffff: none).
+__device__ __forceinline__ void mean_partial(const bf16_t *xb, int64_t stride_token, const int32_t *perm, int beg,
+                                             int end, int first, int step, int lane, double s[8], uint32_t amax[4],
+                                             uint32_t amin[4]) {
+    const int slot = lane >> 4;
+    for (int base = beg + 64 * first; base < end; base += 64 * step) {
+        const int mine = (base + lane < end) ? perm[base + lane] : 0;    // 64 member indices, one coalesced load
+        const int cntm = (end - base < 64) ? end - base : 64;
+        // slot s takes members s, s + 4, s + 8, .. of the group: 8 rows in flight per lane (more
+        // would cost the occupancy that the short lists of other blocks live on)
+        for (int i0 = 0; 4 * i0 < cntm; i0 += 8) {
+            uint4 row[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                s[i] += __shfl_xor(s[i], 16, 64);
-                s[i] += __shfl_xor(s[i], 32, 64);
+                const int u = 4 * (i0 + i) + slot;
+                const int idx = __shfl(mine, u & 63, 64);
+                row[i] = (u < cntm) ? *reinterpret_cast<const uint4 *>(xb + (int64_t)idx * stride_token)
+                                    : make_uint4(0u, 0u, 0u, 0u);
             }
-            if (slot == 0) {
-                float m[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) m[i] = (float)(s[i] / c);
-                *reinterpret_cast<uint4 *>(a.cent_out + co + c8 * 8) = pack_bf16x8(m);
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t w[4] = {row[i].x, row[i].y, row[i].z, row[i].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    s[2 * e] += (double)bf16_lo(w[e]);
+                    s[2 * e + 1] += (double)bf16_hi(w[e]);
+                    const uint32_t mag = w[e] & 0x7fff7fffu;
+                    const ushort2_t one = {1, 1};
+                    amax[e] = pk_max_u16(amax[e], mag);
+                    amin[e] = pk_min_u16(amin[e], __builtin_bit_cast(uint32_t, (ushort2_t)(__builtin_bit_cast(ushort2_t, mag) - one)));   // zero -> 0xffff
+                }
             }
-            return;
         }
     }
-    // token order: two channels per lane, 16 rows in flight
+}
+
+// no partial sum of n members can round in fp64 when ceil(log2 n) + 8 + emax - emin <= 53; mx /
+// mn: the packed largest / smallest-non-zero-minus-one magnitude bits of two channels
+__device__ __forceinline__ bool mean_exact(uint32_t mx, uint32_t mn, int lg) {
+    bool ok = true;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+        const uint32_t big = (mx >> (16 * hf)) & 0xffffu, small1 = (mn >> (16 * hf)) & 0xffffu;
+        if (small1 == 0xffffu) continue;                     // no non-zero member in this channel: the sum is zero
+        const int eb = (int)(big >> 7) > 1 ? (int)(big >> 7) : 1;
+        const int es = (int)((small1 + 1u) >> 7) > 1 ? (int)((small1 + 1u) >> 7) : 1;
+        if (lg + 8 + eb - es > 53) ok = false;
+    }
+    return ok;
+}
+
+// the defining order: members in token order, two channels per lane, 16 rows in flight
+__device__ __forceinline__ void mean_token_order(const bf16_t *xu, int64_t stride_token, const int32_t *perm, int beg,
+                                                 int end, int lane, bf16_t *out) {
     double s0 = 0.0, s1 = 0.0;
     const bf16_t *xb = xu + lane * 2;
     for (int base = beg; base < end; base += 64) {
@@ -248,15 +210,156 @@ void kmeans_mean_kernel(UpdateArgs a) {
             for (int u = 0; u < 16; ++u) {
                 const int idx = __shfl(mine, u0 + u, 64);
                 wv[u] = (u0 + u < cntm)
-                    ? *reinterpret_cast<const uint32_t *>(xb + (int64_t)idx * a.stride_token) : 0u;
+                    ? *reinterpret_cast<const uint32_t *>(xb + (int64_t)idx * stride_token) : 0u;
             }
 #pragma unroll
             for (int u = 0; u < 16; ++u)
                 if (u0 + u < cntm) { s0 += (double)bf16_lo(wv[u]); s1 += (double)bf16_hi(wv[u]); }
         }
     }
+    const double c = (double)(end - beg);
     const float m0 = (float)(s0 / c), m1 = (float)(s1 / c);
-    *reinterpret_cast<uint32_t *>(a.cent_out + co + lane * 2) = pack_bf16x2(m0, m1);
+    *reinterpret_cast<uint32_t *>(out + lane * 2) = pack_bf16x2(m0, m1);
+}
+
+// One wavefront per centroid, four centroids per block.  The defined result is the fp64 sum of
+// the members in token order.  Short lists are summed exactly like that.  A long list is
+// latency-bound that way (one dependent fp64 add per member), so it is first summed in
+// interleaved partial sums, which give the same number whenever no addition rounds: every member
+// is an integer multiple of 2^(emin-134) and every partial sum is below n * 256 * 2^(emax-134),
+// with emin / emax the smallest / largest exponent field among the non-zero members of the
+// channel, so if
+//     ceil(log2 n) + 8 + emax - emin <= 53
+// all partial sums of any order are exact in fp64.  The exponents are tracked alongside (packed
+// 16-bit min / max of the magnitudes' bit patterns); a centroid with a channel that fails the
+// test is summed again in token order.  Lists of medium length use the four member slots of their
+// own wavefront; the longest ones (one cluster can hold a large share of a unit's tokens, e.g.
+// in the later smoothing stages) are split over all wavefronts of the block, whose partial
+// results meet in LDS.  Four wavefronts per block and at most 80 registers (the few values that
+// spill are touched once per block-wide list) keep six wavefronts per SIMD resident, which is what
+// the common case of many short lists lives on; eight wavefronts per block sum the longest lists
+// faster and everything else slower.
+__global__ __launch_bounds__(kMeanThreads, 6)
+void kmeans_mean_kernel(UpdateArgs a) {
+    __shared__ double part[kMeanWaves][kHeadDim];
+    __shared__ uint32_t pmx[kMeanWaves][kHeadDim / 2], pmn[kMeanWaves][kHeadDim / 2];
+    const int h = blockIdx.y, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int j0 = blockIdx.x * kMeanWaves;
+    const int j = j0 + wave;
+    const int K = a.K;
+    const int64_t N = a.n_tokens;
+    const int32_t *offs = a.offsets + (int64_t)h * (K + 1);
+    const int32_t *perm = a.perm + (int64_t)h * N;
+    const bf16_t *xu = a.x + (int64_t)h * a.stride_head;
+    const int slot = lane >> 4, c8 = lane & 15;
+    // the block's list boundaries with one load per wavefront (lane i: start of centroid j0 + i);
+    // used after the wavefront's own list
+    const int myoff = (lane <= kMeanWaves && j0 + lane <= K) ? offs[j0 + lane] : 0;
+
+    // ---- the wavefront's own centroid, unless its list is left to the whole block ----
+    if (j < K) {
+        const int beg = offs[j], end = offs[j + 1];                      // wave-uniform: scalar loads
+        const int64_t co = ((int64_t)h * K + j) * kHeadDim;
+        if (end == beg) {
+            *reinterpret_cast<uint32_t *>(a.cent_out + co + lane * 2) = *reinterpret_cast<const uint32_t *>(a.cent_prev + co + lane * 2);
+        } else if (end - beg < kMeanCoopMin) {
+            bool done = false;
+            if (end - beg >= kMeanParallelMin) {
+                double s[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) s[i] = 0.0;
+                uint32_t amax[4] = {0u, 0u, 0u, 0u}, amin[4] = {~0u, ~0u, ~0u, ~0u};
+                mean_partial(xu + c8 * 8, a.stride_token, perm, beg, end, 0, 1, lane, s, amax, amin);
+                // the four slots hold partial results of the same channels: lanes l, l^16, l^32, l^48
+                int lg = 0;
+                while ((1 << lg) < end - beg) ++lg;                          // ceil(log2 n)
+                bool ok = true;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    uint32_t mx = amax[e], mn = amin[e];
+#pragma unroll
+                    for (int off = 16; off <= 32; off <<= 1) {
+                        mx = pk_max_u16(mx, __shfl_xor(mx, off, 64));
+                        mn = pk_min_u16(mn, __shfl_xor(mn, off, 64));
+                    }
+                    ok = ok && mean_exact(mx, mn, lg);
+                }
+                if (__all(ok)) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        s[i] += __shfl_xor(s[i], 16, 64);
+                        s[i] += __shfl_xor(s[i], 32, 64);
+                    }
+                    if (slot == 0) {
+                        const double c = (double)(end - beg);
+                        float m[8];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) m[i] = (float)(s[i] / c);
+                        *reinterpret_cast<uint4 *>(a.cent_out + co + c8 * 8) = pack_bf16x8(m);
+                    }
+                    done = true;
+                }
+            }
+            if (!done) mean_token_order(xu, a.stride_token, perm, beg, end, lane, a.cent_out + co);
+        }
+    }
+
+    // ---- the block's longest lists, one after the other, by all wavefronts (every wavefront of
+    // the block takes the same branches: the list lengths are read by all of them) ----
+    const int mylen = __shfl_down(myoff, 1, 64) - myoff;                 // all lanes take part in the exchange
+    const uint64_t coop = __ballot(lane < kMeanWaves && j0 + lane < K && mylen >= kMeanCoopMin);   // the same in every wavefront
+    for (uint64_t todo = coop; todo; todo &= todo - 1) {
+        const int t = __builtin_ctzll(todo);
+        const int jt = j0 + t;
+        const int beg = __shfl(myoff, t, 64), end = __shfl(myoff, t + 1, 64);
+        double s[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s[i] = 0.0;
+        uint32_t amax[4] = {0u, 0u, 0u, 0u}, amin[4] = {~0u, ~0u, ~0u, ~0u};
+        mean_partial(xu + c8 * 8, a.stride_token, perm, beg, end, wave, kMeanWaves, lane, s, amax, amin);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {          // harmless if an addition rounds: then the result is discarded
+            s[i] += __shfl_xor(s[i], 16, 64);
+            s[i] += __shfl_xor(s[i], 32, 64);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) {
+                amax[e] = pk_max_u16(amax[e], __shfl_xor(amax[e], off, 64));
+                amin[e] = pk_min_u16(amin[e], __shfl_xor(amin[e], off, 64));
+            }
+        }
+        if (slot == 0) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) part[wave][c8 * 8 + i] = s[i];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { pmx[wave][c8 * 4 + e] = amax[e]; pmn[wave][c8 * 4 + e] = amin[e]; }
+        }
+        __syncthreads();
+        if (wave == t) {                      // the centroid's own wavefront: channels 2*lane, 2*lane+1
+            double s0 = 0.0, s1 = 0.0;
+            uint32_t mx = 0u, mn = ~0u;
+#pragma unroll
+            for (int w = 0; w < kMeanWaves; ++w) {
+                s0 += part[w][2 * lane];
+                s1 += part[w][2 * lane + 1];
+                mx = pk_max_u16(mx, pmx[w][lane]);
+                mn = pk_min_u16(mn, pmn[w][lane]);
+            }
+            int lg = 0;
+            while ((1 << lg) < end - beg) ++lg;
+            const int64_t co = ((int64_t)h * K + jt) * kHeadDim;
+            if (__all(mean_exact(mx, mn, lg))) {
+                const double c = (double)(end - beg);
+                *reinterpret_cast<uint32_t *>(a.cent_out + co + lane * 2) = pack_bf16x2((float)(s0 / c), (float)(s1 / c));
+            } else {
+                mean_token_order(xu, a.stride_token, perm, beg, end, lane, a.cent_out + co);
+            }
+        }
+        __syncthreads();                      // the partial results are overwritten by the next list
+    }
 }
 
 // Residual for the next smoothing stage: 16 lanes per token, 8 channels each.
@@ -289,7 +392,7 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     hipLaunchKernelGGL(kmeans_rank_kernel, dim3((unsigned)a.H), dim3(kRankThreads), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    dim3 grid((unsigned)((a.K + 3) / 4), (unsigned)a.H);
+    dim3 grid((unsigned)((a.K + kMeanWaves - 1) / kMeanWaves), (unsigned)a.H);
     hipLaunchKernelGGL(kmeans_mean_kernel, grid, dim3(kMeanThreads), 0, s, a);
     return hipGetLastError();
 }

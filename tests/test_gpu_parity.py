@@ -81,7 +81,8 @@ def test_decode_multi_chunk_strided_output():
 # ------------------------------------------------------------------ assignment and update steps
 @pytest.mark.parametrize("cfg,N,K", [("cfg1_tiny", 4096, 16), ("cfg2_window21", 1500, 64),
                                      ("cfg3_dit_small", 2000, 256), ("cfg4_dit_large", 777, 128),
-                                     ("cfg2_window21", 31, 5), ("cfg2_window21", 20, 64)])
+                                     ("cfg2_window21", 31, 5), ("cfg2_window21", 20, 64),
+                                     ("cfg2_window21", 3000, 5)])
 def test_kmeans_steps_match_oracle(cfg, N, K):
     """Step parity: the oracle's state after each iteration is fed to the GPU assign and update."""
     H = 2
@@ -146,15 +147,20 @@ def test_encode_single_pass_matches_oracle(cfg, N, K, Bg, T):
 
 
 def test_update_long_lists_exact_and_rounding_cases():
-    """Long member lists are summed in four interleaved partial sums when a test on the members'
-    exponents shows that no fp64 addition can round, and in token order otherwise.  Both must give
+    """Long member lists are summed in interleaved partial sums (four per wavefront; the longest
+    lists by all wavefronts of a block) when a test on the members' exponents shows that no fp64
+    addition can round, and in token order otherwise.  Both must give
     the oracle's token-order sum: ordinary data (the test passes, every order is exact), a channel
     whose members span more than 2^45 (the order matters: token order is taken), zeros and
     subnormals, list lengths around the thresholds, and everything in one cluster."""
     g = torch.Generator().manual_seed(5)
-    H, N, K = 2, 3000, 8
+    H, N, K = 3, 3000, 8
     x = torch.randn(H, N, 128, generator=g)
     ids = torch.randint(0, K, (H, N), generator=g, dtype=torch.uint8)
+    # unit 2: ordinary data; lists long enough to be split over the wavefronts of a block (several
+    # of them in one block, lengths around that threshold too), the test passes
+    ids[2, :1000] = 1; ids[2, 1000:1383] = 2; ids[2, 1383:1767] = 4
+    ids[2, 1767:] = torch.randint(5, 8, (N - 1767,), generator=g, dtype=torch.uint8)
     ids[0, :1500] = 3                                        # a list of > 1500 members
     ids[1, :] = 5                                            # one cluster holds everything
     ids[0, 1500:1595] = 6; ids[0, 1595:1691] = 7             # about 95 and 96 more members (the threshold)
