@@ -40,8 +40,10 @@ constexpr int kXcds = 8;                         // MI355X: 8 XCDs, each with it
 //     3 = S stages, tables read from global memory (cg).
 // FMT: stored format (kFmt* bits).  4-bit levels: a lane's 8 channels of a round are one 32-bit
 // word (16 words per token and round, so the offsets below are the same in units of the word).
-template <int T_, bool CHECK, int SM, int FMT>
-__device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t n_left, uint32_t lane16,
+// SC: number of smoothing stages when known at compile time (the loops over the stages unroll and
+// their loads are issued together), 0 = run-time S.
+template <int T_, bool CHECK, int SM, int FMT, int SC>
+__device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_t n_left, uint32_t lane16,
                                             uint32_t G, uint32_t gidx, uint32_t kmax,
                                             const uint8_t *ids_b, const void *codes_v,
                                             const void *scales_v, const bf16_t *tab, const bf16_t *cg,
@@ -53,6 +55,7 @@ __device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t
     const code_t *codes_b = static_cast<const code_t *>(codes_v);
     const scale_t *scales_b = static_cast<const scale_t *>(scales_v);
     auto hs = [](uint32_t bits) { return 0.5f * scale_bits_to_f32<FP8>(bits); };
+    const int S = SC > 0 ? SC : S_;
     uint32_t idv[kDecUnroll];
     uint32_t code[kDecUnroll][TM];
     uint32_t sc[kDecUnroll][TM];
@@ -70,7 +73,9 @@ __device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t
             if (SM == 1) idv[u] = ids_b[ln];
             else {                                   // up to four id bytes of the token, stage s in byte s
                 idv[u] = 0u;
-                for (int st = 0; st < S; ++st) idv[u] |= (uint32_t)ids_b[ln * (uint32_t)S + st] << (8 * st);
+#pragma unroll
+                for (int st = 0; st < (SC > 0 ? SC : kMaxSmooth); ++st)
+                    if (st < S) idv[u] |= (uint32_t)ids_b[ln * (uint32_t)S + st] << (8 * st);
             }
             const uint32_t co = ln * (uint32_t)T * 16u + lane16;       // in code words
             const uint32_t so = ln * (uint32_t)T * G + gidx;
@@ -90,16 +95,38 @@ __device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t
         } else {
             // Eq. 7 with S tables: the rows are added in stage order in fp32
             const bf16_t *tb = (SM == 2) ? tab : cg;
-            for (int st = 0; st < S; ++st) {
-                const uint32_t ia = min((idv[up] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
-                const uint32_t ib = min((idv[up + 1] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
-                float ra[8], rb[8];
-                unpack_bf16x8(*reinterpret_cast<const uint4 *>(tb + ia * kHeadDim + lane16 * 8), ra);
-                unpack_bf16x8(*reinterpret_cast<const uint4 *>(tb + ib * kHeadDim + lane16 * 8), rb);
+            if (SC > 0) {
+                uint4 wa[SC > 0 ? SC : 1], wb[SC > 0 ? SC : 1];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    accA[i] = st ? accA[i] + ra[i] : ra[i];
-                    accB[i] = st ? accB[i] + rb[i] : rb[i];
+                for (int st = 0; st < SC; ++st) {
+                    const uint32_t ia = min((idv[up] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
+                    const uint32_t ib = min((idv[up + 1] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
+                    wa[st] = *reinterpret_cast<const uint4 *>(tb + ia * kHeadDim + lane16 * 8);
+                    wb[st] = *reinterpret_cast<const uint4 *>(tb + ib * kHeadDim + lane16 * 8);
+                }
+#pragma unroll
+                for (int st = 0; st < SC; ++st) {
+                    float ra[8], rb[8];
+                    unpack_bf16x8(wa[st], ra);
+                    unpack_bf16x8(wb[st], rb);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        accA[i] = st ? accA[i] + ra[i] : ra[i];
+                        accB[i] = st ? accB[i] + rb[i] : rb[i];
+                    }
+                }
+            } else {
+                for (int st = 0; st < S; ++st) {
+                    const uint32_t ia = min((idv[up] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
+                    const uint32_t ib = min((idv[up + 1] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
+                    float ra[8], rb[8];
+                    unpack_bf16x8(*reinterpret_cast<const uint4 *>(tb + ia * kHeadDim + lane16 * 8), ra);
+                    unpack_bf16x8(*reinterpret_cast<const uint4 *>(tb + ib * kHeadDim + lane16 * 8), rb);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        accA[i] = st ? accA[i] + ra[i] : ra[i];
+                        accB[i] = st ? accB[i] + rb[i] : rb[i];
+                    }
                 }
             }
         }
@@ -149,7 +176,7 @@ __device__ __forceinline__ void decode_pass(int T, int S, uint32_t ln0, uint32_t
 
 // One workgroup = one slice of one chunk of one unit.  It stages the chunk's centroid table
 // in LDS once (the only shared operand) and then streams its tokens.
-template <int T_, int SM, int FMT>   // T_ > 0: compile-time stage count; T_ == 0: run-time.  SM, FMT: see decode_pass
+template <int T_, int SM, int FMT, int SC>   // T_ > 0: compile-time stage count; T_ == 0: run-time.  SM, FMT, SC: see decode_pass
 __global__ __launch_bounds__(kDecThreads)
 void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, int blocks_per_xcd) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -175,7 +202,7 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
     const uint32_t G = kHeadDim / a.B;
     const uint32_t gidx = (lane16 * 8) / a.B;     // scale group of this lane's 8 channels
 
-    const int S = (SM == 1) ? 1 : a.S;
+    const int S = (SM == 1) ? 1 : (SC > 0 ? SC : a.S);
     const bf16_t *cg = a.cent + ((int64_t)h * a.chunk_stride + c) * S * a.K * kHeadDim;    // [S][K][128] of this chunk
     if (SM != 3) {   // stage the tables: S*K rows of 256 B, 16 B per thread and step
         for (int i = threadIdx.x; i < S * a.K * 16; i += kDecThreads)
@@ -193,15 +220,15 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
 
     for (uint32_t first = 0; first < n_left; first += kDecTokPerIter) {
         if (first + kDecTokPerIter <= n_left)
-            decode_pass<T_, false, SM, FMT>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
+            decode_pass<T_, false, SM, FMT, SC>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
                                        tab, cg, out_b, a.stride_token);
         else
-            decode_pass<T_, true, SM, FMT>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
+            decode_pass<T_, true, SM, FMT, SC>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
                                       tab, cg, out_b, a.stride_token);
     }
 }
 
-template <int T_, int SM, int FMT = 0>
+template <int T_, int SM, int FMT = 0, int SC = 0>
 static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
     // slices per chunk: enough workgroups to fill 256 CUs x 2 twice over, but as few as possible
     // beyond that (every workgroup re-reads the chunk's table; measured flat from 512 to 4096)
@@ -218,10 +245,10 @@ static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
     if (nb > 0x7fffffff - kXcds) return hipErrorInvalidValue;
     const int bpx = (int)((nb + kXcds - 1) / kXcds);
     const size_t smem = (SM == 3) ? 16 : (size_t)(SM == 1 ? 1 : a.S) * a.K * kHeadDim * sizeof(bf16_t);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<T_, SM, FMT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<T_, SM, FMT, SC>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((decode_kernel<T_, SM, FMT>), dim3((unsigned)(bpx * kXcds)), dim3(kDecThreads), smem, s, a,
+    hipLaunchKernelGGL((decode_kernel<T_, SM, FMT, SC>), dim3((unsigned)(bpx * kXcds)), dim3(kDecThreads), smem, s, a,
                        (int)slices, (uint32_t)slice_len, (int)nb, bpx);
     return hipGetLastError();
 }
@@ -231,6 +258,8 @@ template <int FMT>
 static hipError_t launch_decode_fmt(const DecodeArgs &a, hipStream_t s) {
     if (a.S > 1) {
         if ((size_t)a.S * a.K * kHeadDim * sizeof(bf16_t) <= 65536) return launch_decode_t<0, 2, FMT>(a, s);
+        // the paper's form with large tables (four stages, one round): counts fixed at compile time
+        if ((FMT & kFmtE4M3) && a.S == 4 && a.T == 1) return launch_decode_t<1, 3, FMT, 4>(a, s);
         return launch_decode_t<0, 3, FMT>(a, s);
     }
     if (FMT == kFmtE4M3 && a.T == 1) return launch_decode_t<(FMT == kFmtE4M3 ? 1 : 0), 1, FMT>(a, s);
