@@ -507,7 +507,10 @@ def main():
         "decode": {"ms": round(ms_dec, 4), "GBps_bf16_equiv": round(vec["decode"] * 256 / ms_dec / 1e6, 1),
                    "hbm_GBps_algorithmic": round(dec_alg / ms_dec / 1e6, 1),
                    "hbm_frac": round(dec_alg / ms_dec / 1e6 / HBM_PEAK_GBPS, 4),
-                   "note": "cache-resident size (compressed + bf16 < 256 MB Infinity Cache)" if dec_alg < 2.6e8 else ""},
+                   "note": ("cache-resident size (compressed + bf16 < 256 MB Infinity Cache)" if dec_alg < 2.6e8 else
+                            "the compressed cache (%d MB) fits the 256 MB Infinity Cache and is re-read from it by "
+                            "every repetition; the HBM-bound figure is large.decode" % (_format_bytes(wl, units, n_tok, wl.chunk) >> 20)
+                            if _format_bytes(wl, units, n_tok, wl.chunk) < 2.6e8 else "")},
         "attn": {"ms": round(ms_att, 4), "q_tokens_per_s": round(wl.n_queries * wl.heads / ms_att * 1e3, 1),
                  "cache_tokens_per_s": round(n_tok * wl.heads / ms_att * 1e3, 1),
                  "TFLOPs": round(att_flops / ms_att / 1e9, 2),

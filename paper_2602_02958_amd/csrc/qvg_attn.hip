@@ -18,9 +18,10 @@
 //      other LDS buffer, from data that was requested one or two tiles earlier.
 // The decode work is amortised over 256 queries; only the two contractions use the matrix
 // cores, the unpack / fma / soft-max work is VALU and is what bounds the kernel.
-// Two kernels: attn_kernel_staged (one smoothing stage, 1..4 rounds of 2-bit levels with binary16
-// or E4M3 scales, chunks that start on 16-byte boundaries of the scale array: the measured path)
-// and attn_kernel_direct (everything else: more rounds, several smoothing stages, 4-bit levels).
+// Two kernels: attn_kernel_staged (one smoothing stage; 1..4 rounds of 2-bit levels with binary16
+// or E4M3 scales, or one round of 4-bit levels with E4M3 scales; chunks that start on 16-byte
+// boundaries of the scale array: the measured path) and attn_kernel_direct (everything else: more
+// rounds, several smoothing stages, the other 4-bit forms).
 // Both can rotate the decoded keys by a caller-supplied (cos, sin) table (keys are cached before
 // the rotary embedding, Sec. 5 "Implementation") and read a prefix of caches allocated for more
 // tokens.  A small third kernel merges two partial results by their log-sum-exps.
@@ -447,10 +448,13 @@ constexpr size_t kAtSmemStaged = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint
 
 template <bool V> struct BoolC { static constexpr bool value = V; };
 
-template <int T_, bool ROPE, bool FP8>      // ROPE: rotate the decoded keys by a.rope; FP8: E4M3 scale bytes
+template <int T_, bool ROPE, bool FP8, bool I4>   // ROPE: rotate the decoded keys by a.rope; FP8: E4M3 scale bytes;
+                                                  // I4: 4-bit levels (64 code bytes per token and round, T_ <= 2)
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_xcd) {
     constexpr int T = T_;
+    constexpr int CB = I4 ? 64 : 32;                                    // code bytes per token and round
+    static_assert(kAtKv * T * CB <= kStCodes, "the codes of a tile must fit their staging area");
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t *Kt = reinterpret_cast<uint16_t *>(smem);                  // [2][64][136] bf16
     uint16_t *Vt = Kt + 2 * kKtElems;                                   // [2][128][72] f16, transposed
@@ -475,7 +479,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     const uint32_t kmax = (uint32_t)K - 1u;
 
     const uint8_t *k_ids = a.k_ids + (int64_t)h * a.kv_stride, *v_ids = a.v_ids + (int64_t)h * a.kv_stride;
-    const uint8_t *k_codes = a.k_codes + (int64_t)h * a.kv_stride * T * 32, *v_codes = a.v_codes + (int64_t)h * a.kv_stride * T * 32;
+    const uint8_t *k_codes = a.k_codes + (int64_t)h * a.kv_stride * T * CB, *v_codes = a.v_codes + (int64_t)h * a.kv_stride * T * CB;
     constexpr int SZ = FP8 ? 1 : 2;                                     // bytes of a stored scale
     const unsigned char *k_scales = reinterpret_cast<const unsigned char *>(a.k_scales) + (int64_t)h * a.kv_stride * T * G * SZ;
     const unsigned char *v_scales = reinterpret_cast<const unsigned char *>(a.v_scales) + (int64_t)h * a.kv_stride * T * G * SZ;
@@ -504,12 +508,13 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     const float scale2 = a.scale * 1.4426950408889634f;
 
     // ---- staging: what a thread fetches for a tile ------------------------------------------
-    // 16-byte pieces, both sides: codes (a token-stage record is 32 B, always 16-byte aligned;
-    // piece p of a side belongs to token p / (2T)) and scales (T*G*2 bytes per token, contiguous
+    // 16-byte pieces, both sides: codes (a token-stage record is 32 B, or 64 B with 4-bit levels,
+    // always 16-byte aligned; piece p of a side belongs to token p / (T * CB / 16)) and scales (T*G*2 bytes per token, contiguous
     // over the tile; the host picks this kernel only when chunks start 16-byte aligned).
     // Every step below comes in two forms: FULL (the tile has all 64 tokens: no per-token
     // predicates at all, the common case) and the general one.
-    constexpr int kPieces = 2 * kAtKv * T * 2;                       // code pieces, both sides
+    constexpr int kTokPieces = T * CB / 16;                          // code pieces of one token
+    constexpr int kPieces = 2 * kAtKv * kTokPieces;                  // code pieces, both sides
     constexpr int kPiecesPerThread = (kPieces + kAtThreads - 1) / kAtThreads;
     const int scPiecesSide = kAtKv * T * G * SZ / 16;                // scale pieces per side (<= 256)
     const int scBytesTok = T * G * SZ;                               // even (the host sees to it)
@@ -525,9 +530,9 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
             if (p < kPieces) {
                 const bool vside = p >= kPieces / 2;
                 const int ps = p - (vside ? kPieces / 2 : 0);
-                if (FULL || ps / (2 * T) < nvalid)
+                if (FULL || ps / kTokPieces < nvalid)
                     f.code[i] = *reinterpret_cast<const uint4 *>((vside ? v_codes : k_codes) +
-                                                                 ((int64_t)t.t0 * T * 32 + (int64_t)ps * 16));
+                                                                 ((int64_t)t.t0 * T * CB + (int64_t)ps * 16));
             }
         }
         if (!FULL) f.sc = make_uint4(0u, 0u, 0u, 0u);
@@ -608,7 +613,8 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             Raw<T> r;
-            const uint16_t *cp = reinterpret_cast<const uint16_t *>(st + s * kStCodes) + tok * T * 16 + c8;
+            typedef typename std::conditional<I4, uint32_t, uint16_t>::type code_t;   // a thread's 8 channels of a round
+            const code_t *cp = reinterpret_cast<const code_t *>(st + s * kStCodes) + tok * T * 16 + c8;
             typedef typename std::conditional<FP8, uint8_t, uint16_t>::type scale_t;
             const scale_t *sp = reinterpret_cast<const scale_t *>(st + 2 * kStCodes + s * kStScales) + tok * T * G + g;
 #pragma unroll
@@ -621,7 +627,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
                 r.cen[e] = (FULL || tok + e < nvalid) ? cen[s][e] : make_uint4(0u, 0u, 0u, 0u);
             }
             float accA[8], accB[8];
-            dequant2x8<T, T, 1, FP8 ? kFmtE4M3 : 0>(r, T, accA, accB);
+            dequant2x8<T, T, 1, (FP8 ? kFmtE4M3 : 0) | (I4 ? kFmtInt4 : 0)>(r, T, accA, accB);
             if (s == 0) {
                 if (ROPE) { rope_rotate8(accA, rp[0]); rope_rotate8(accB, rp[1]); }
                 uint16_t *kt = Kt + buf * kKtElems;
@@ -785,11 +791,11 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     }
 }
 
-template <int T_, bool ROPE, bool FP8>
+template <int T_, bool ROPE, bool FP8, bool I4>
 static hipError_t launch_attn_staged_r(const AttnArgs &a, hipStream_t s) {
     static bool configured = false;          // the attribute is per function, set once per process
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE, FP8>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE, FP8, I4>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmemStaged);
         if (e != hipSuccess) return e;
         configured = true;
@@ -798,13 +804,13 @@ static hipError_t launch_attn_staged_r(const AttnArgs &a, hipStream_t s) {
     const int64_t nb = nqb * a.H;
     if (nb > 0x7fffffff - 8) return hipErrorInvalidValue;
     const int bpx = (int)((nb + 7) / 8);
-    hipLaunchKernelGGL((attn_kernel_staged<T_, ROPE, FP8>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmemStaged, s, a,
+    hipLaunchKernelGGL((attn_kernel_staged<T_, ROPE, FP8, I4>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmemStaged, s, a,
                        (int)nqb, (int)nb, bpx);
     return hipGetLastError();
 }
-template <int T_, bool FP8 = false>
+template <int T_, bool FP8 = false, bool I4 = false>
 static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
-    return a.rope ? launch_attn_staged_r<T_, true, FP8>(a, s) : launch_attn_staged_r<T_, false, FP8>(a, s);
+    return a.rope ? launch_attn_staged_r<T_, true, FP8, I4>(a, s) : launch_attn_staged_r<T_, false, FP8, I4>(a, s);
 }
 
 template <int T_, int SM, int FMT, bool ROPE>
@@ -841,15 +847,17 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     if (a.n_q == 0) return hipSuccess;
     // the staged kernel fetches scales in 16-byte pieces: every chunk must start on one
     const bool aligned = (a.chunk_len % 8 == 0) || a.n_chunks == 1;
+    // E4M3 scales on the staged kernel: a token's scale record must have an even number of bytes
+    // (the tail handling moves two at a time) and every unit's scale array must start on a
+    // 16-byte boundary
+    const bool fp8_staged = a.S == 1 && aligned && ((a.T * (kHeadDim / a.B)) & 1) == 0 &&
+        ((reinterpret_cast<uintptr_t>(a.k_scales) | reinterpret_cast<uintptr_t>(a.v_scales)) & 15u) == 0 &&
+        (a.H == 1 || (a.kv_stride * a.T * (kHeadDim / a.B)) % 16 == 0);
     switch (a.fmt) {
         case 0: break;
         case kFmtE4M3:
-            // 2-bit levels with E4M3 scales (the paper's own format): the staged kernel when a token's
-            // scale record has an even number of bytes (its tail handling moves two at a time)
-            // and every unit's scale array starts on a 16-byte boundary
-            if (a.S == 1 && aligned && a.T <= kStMaxT && ((a.T * (kHeadDim / a.B)) & 1) == 0 &&
-                ((reinterpret_cast<uintptr_t>(a.k_scales) | reinterpret_cast<uintptr_t>(a.v_scales)) & 15u) == 0 &&
-                (a.H == 1 || (a.kv_stride * a.T * (kHeadDim / a.B)) % 16 == 0)) {
+            // 2-bit levels with E4M3 scales (the paper's own format)
+            if (fp8_staged && a.T <= kStMaxT) {
                 switch (a.T) {
                     case 1: return launch_attn_staged<1, true>(a, s);
                     case 2: return launch_attn_staged<2, true>(a, s);
@@ -859,7 +867,10 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
             }
             return launch_attn_fmt<kFmtE4M3>(a, s);
         case kFmtInt4: return launch_attn_fmt<kFmtInt4>(a, s);
-        default: return launch_attn_fmt<kFmtInt4 | kFmtE4M3>(a, s);
+        default:
+            // 4-bit levels with E4M3 scales, one round (the paper's INT4 format)
+            if (fp8_staged && a.T == 1) return launch_attn_staged<1, true, true>(a, s);
+            return launch_attn_fmt<kFmtInt4 | kFmtE4M3>(a, s);
     }
     // several smoothing stages: the general kernel (the paper's presets have one round)
     if (a.S > 1) return launch_attn_multi<0>(a, s);
