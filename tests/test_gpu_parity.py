@@ -82,7 +82,7 @@ def test_decode_multi_chunk_strided_output():
 @pytest.mark.parametrize("cfg,N,K", [("cfg1_tiny", 4096, 16), ("cfg2_window21", 1500, 64),
                                      ("cfg3_dit_small", 2000, 256), ("cfg4_dit_large", 777, 128),
                                      ("cfg2_window21", 31, 5), ("cfg2_window21", 20, 64),
-                                     ("cfg2_window21", 3000, 5)])
+                                     ("cfg2_window21", 3000, 5), ("cfg1_tiny", 1200, 1), ("cfg1_tiny", 900, 3)])
 def test_kmeans_steps_match_oracle(cfg, N, K):
     """Step parity: the oracle's state after each iteration is fed to the GPU assign and update."""
     H = 2
