@@ -127,10 +127,12 @@ void kmeans_rank_kernel(UpdateArgs a) {
     }
 }
 
-constexpr int kMeanThreads = 256;           // 4 wavefronts = 4 centroids per block
+constexpr int kMeanThreads = 256;           // 4 wavefronts
 constexpr int kMeanWaves = kMeanThreads / 64;
 constexpr int kMeanParallelMin = 96;        // member lists at least this long try the order-free path
 constexpr int kMeanCoopMin = 192;           // lists at least this long are summed by the whole block
+                                            // (with one centroid per block: every order-free list)
+constexpr int kMeanSmallGrid = 2048;        // up to this many centroids in a launch: one block each
 
 typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 
@@ -143,28 +145,38 @@ __device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
 
 // Order-free partial sums of a member list: the wavefront takes the groups of 64 members
 // first, first + step, .. of perm[beg .. end); lane = member slot (4) x 8 channels, 8 rows in
-// flight per lane.  s: the lane's partial sums of its 8 channels; amax / amin: per 16-bit half the
+// flight per lane (ROWS = 16 where registers do not matter).  s: the lane's partial sums of its 8 channels; amax / amin: per 16-bit half the
 // largest magnitude bits and the smallest non-zero magnitude bits minus one (0xffff: none).
+template <int ROWS>
 __device__ __forceinline__ void mean_partial(const bf16_t *xb, int64_t stride_token, const int32_t *perm, int beg,
                                              int end, int first, int step, int lane, double s[8], uint32_t amax[4],
                                              uint32_t amin[4]) {
     const int slot = lane >> 4;
-    for (int base = beg + 64 * first; base < end; base += 64 * step) {
-        const int mine = (base + lane < end) ? perm[base + lane] : 0;    // 64 member indices, one coalesced load
+    constexpr bool AHEAD = ROWS > 8;       // member indices requested a group ahead (two more registers)
+    int base = beg + 64 * first;
+    int nxt = (AHEAD && base + lane < end) ? perm[base + lane] : 0;
+    for (; base < end; base += 64 * step) {
+        int mine;                                                        // 64 member indices, one coalesced load
+        if (AHEAD) {
+            mine = nxt;
+            const int nb = base + 64 * step;
+            nxt = (nb + lane < end) ? perm[nb + lane] : 0;
+        } else {
+            mine = (base + lane < end) ? perm[base + lane] : 0;
+        }
         const int cntm = (end - base < 64) ? end - base : 64;
-        // slot s takes members s, s + 4, s + 8, .. of the group: 8 rows in flight per lane (more
-        // would cost the occupancy that the short lists of other blocks live on)
-        for (int i0 = 0; 4 * i0 < cntm; i0 += 8) {
-            uint4 row[8];
+        // slot s takes members s, s + 4, s + 8, .. of the group: ROWS rows in flight per lane
+        for (int i0 = 0; 4 * i0 < cntm; i0 += ROWS) {
+            uint4 row[ROWS];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < ROWS; ++i) {
                 const int u = 4 * (i0 + i) + slot;
                 const int idx = __shfl(mine, u & 63, 64);
                 row[i] = (u < cntm) ? *reinterpret_cast<const uint4 *>(xb + (int64_t)idx * stride_token)
                                     : make_uint4(0u, 0u, 0u, 0u);
             }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
+            for (int i = 0; i < ROWS; ++i) {
                 const uint32_t w[4] = {row[i].x, row[i].y, row[i].z, row[i].w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -222,7 +234,7 @@ __device__ __forceinline__ void mean_token_order(const bf16_t *xu, int64_t strid
     *reinterpret_cast<uint32_t *>(out + lane * 2) = pack_bf16x2(m0, m1);
 }
 
-// One wavefront per centroid, four centroids per block.  The defined result is the fp64 sum of
+// One wavefront per centroid, CPB = four centroids per block (or CPB = 1, see below).  The defined result is the fp64 sum of
 // the members in token order.  Short lists are summed exactly like that.  A long list is
 // latency-bound that way (one dependent fp64 add per member), so it is first summed in
 // interleaved partial sums, which give the same number whenever no addition rounds: every member
@@ -238,14 +250,19 @@ __device__ __forceinline__ void mean_token_order(const bf16_t *xu, int64_t strid
 // results meet in LDS.  Four wavefronts per block and at most 80 registers (the few values that
 // spill are touched once per block-wide list) keep six wavefronts per SIMD resident, which is what
 // the common case of many short lists lives on; eight wavefronts per block sum the longest lists
-// faster and everything else slower.
-__global__ __launch_bounds__(kMeanThreads, 6)
+// faster and everything else slower.  A launch with few centroids (one chunk of a few heads) cannot
+// fill the chip anyway and is a chain of dependent loads: there a block has ONE centroid (CPB = 1),
+// every list long enough for the order-free path is spread over the block's four wavefronts, and
+// 16 rows are in flight per lane (ROWS = 16: no occupancy to protect).
+template <int CPB, int ROWS>
+__global__ __launch_bounds__(kMeanThreads, CPB == 1 ? 2 : 6)
 void kmeans_mean_kernel(UpdateArgs a) {
+    constexpr int kCoopMin = CPB == 1 ? kMeanParallelMin : kMeanCoopMin;
     __shared__ double part[kMeanWaves][kHeadDim];
     __shared__ uint32_t pmx[kMeanWaves][kHeadDim / 2], pmn[kMeanWaves][kHeadDim / 2];
     const int h = blockIdx.y, lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int j0 = blockIdx.x * kMeanWaves;
+    const int j0 = blockIdx.x * CPB;
     const int j = j0 + wave;
     const int K = a.K;
     const int64_t N = a.n_tokens;
@@ -255,22 +272,22 @@ void kmeans_mean_kernel(UpdateArgs a) {
     const int slot = lane >> 4, c8 = lane & 15;
     // the block's list boundaries with one load per wavefront (lane i: start of centroid j0 + i);
     // used after the wavefront's own list
-    const int myoff = (lane <= kMeanWaves && j0 + lane <= K) ? offs[j0 + lane] : 0;
+    const int myoff = (lane <= CPB && j0 + lane <= K) ? offs[j0 + lane] : 0;
 
     // ---- the wavefront's own centroid, unless its list is left to the whole block ----
-    if (j < K) {
+    if (wave < CPB && j < K) {
         const int beg = offs[j], end = offs[j + 1];                      // wave-uniform: scalar loads
         const int64_t co = ((int64_t)h * K + j) * kHeadDim;
         if (end == beg) {
             *reinterpret_cast<uint32_t *>(a.cent_out + co + lane * 2) = *reinterpret_cast<const uint32_t *>(a.cent_prev + co + lane * 2);
-        } else if (end - beg < kMeanCoopMin) {
+        } else if (end - beg < kCoopMin) {
             bool done = false;
-            if (end - beg >= kMeanParallelMin) {
+            if (CPB > 1 && end - beg >= kMeanParallelMin) {
                 double s[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) s[i] = 0.0;
                 uint32_t amax[4] = {0u, 0u, 0u, 0u}, amin[4] = {~0u, ~0u, ~0u, ~0u};
-                mean_partial(xu + c8 * 8, a.stride_token, perm, beg, end, 0, 1, lane, s, amax, amin);
+                mean_partial<ROWS>(xu + c8 * 8, a.stride_token, perm, beg, end, 0, 1, lane, s, amax, amin);
                 // the four slots hold partial results of the same channels: lanes l, l^16, l^32, l^48
                 int lg = 0;
                 while ((1 << lg) < end - beg) ++lg;                          // ceil(log2 n)
@@ -308,7 +325,7 @@ void kmeans_mean_kernel(UpdateArgs a) {
     // ---- the block's longest lists, one after the other, by all wavefronts (every wavefront of
     // the block takes the same branches: the list lengths are read by all of them) ----
     const int mylen = __shfl_down(myoff, 1, 64) - myoff;                 // all lanes take part in the exchange
-    const uint64_t coop = __ballot(lane < kMeanWaves && j0 + lane < K && mylen >= kMeanCoopMin);   // the same in every wavefront
+    const uint64_t coop = __ballot(lane < CPB && j0 + lane < K && mylen >= kCoopMin);   // the same in every wavefront
     for (uint64_t todo = coop; todo; todo &= todo - 1) {
         const int t = __builtin_ctzll(todo);
         const int jt = j0 + t;
@@ -317,7 +334,7 @@ void kmeans_mean_kernel(UpdateArgs a) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) s[i] = 0.0;
         uint32_t amax[4] = {0u, 0u, 0u, 0u}, amin[4] = {~0u, ~0u, ~0u, ~0u};
-        mean_partial(xu + c8 * 8, a.stride_token, perm, beg, end, wave, kMeanWaves, lane, s, amax, amin);
+        mean_partial<ROWS>(xu + c8 * 8, a.stride_token, perm, beg, end, wave, kMeanWaves, lane, s, amax, amin);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {          // harmless if an addition rounds: then the result is discarded
             s[i] += __shfl_xor(s[i], 16, 64);
@@ -338,7 +355,7 @@ void kmeans_mean_kernel(UpdateArgs a) {
             for (int e = 0; e < 4; ++e) { pmx[wave][c8 * 4 + e] = amax[e]; pmn[wave][c8 * 4 + e] = amin[e]; }
         }
         __syncthreads();
-        if (wave == t) {                      // the centroid's own wavefront: channels 2*lane, 2*lane+1
+        if (wave == t) {                      // the centroid's own wavefront (t < CPB): channels 2*lane, 2*lane+1
             double s0 = 0.0, s1 = 0.0;
             uint32_t mx = 0u, mn = ~0u;
 #pragma unroll
@@ -392,8 +409,12 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
     hipLaunchKernelGGL(kmeans_rank_kernel, dim3((unsigned)a.H), dim3(kRankThreads), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    dim3 grid((unsigned)((a.K + kMeanWaves - 1) / kMeanWaves), (unsigned)a.H);
-    hipLaunchKernelGGL(kmeans_mean_kernel, grid, dim3(kMeanThreads), 0, s, a);
+    if ((int64_t)a.K * a.H <= kMeanSmallGrid) {
+        hipLaunchKernelGGL((kmeans_mean_kernel<1, 16>), dim3((unsigned)a.K, (unsigned)a.H), dim3(kMeanThreads), 0, s, a);
+    } else {
+        dim3 grid((unsigned)((a.K + kMeanWaves - 1) / kMeanWaves), (unsigned)a.H);
+        hipLaunchKernelGGL((kmeans_mean_kernel<kMeanWaves, 8>), grid, dim3(kMeanThreads), 0, s, a);
+    }
     return hipGetLastError();
 }
 
