@@ -122,10 +122,14 @@ def test_decode_random_storage_all_table_placements(bits, fmt):
 
 @pytest.mark.parametrize("bits,fmt,S,T,Bg", [(2, E4M3, 1, 1, 64), (2, E4M3, 1, 3, 32), (4, E4M3, 1, 1, 64),
                                              (4, F16, 1, 2, 16), (2, E4M3, 2, 1, 16), (4, E4M3, 2, 2, 64)])
-def test_attention_over_cache_in_other_formats(bits, fmt, S, T, Bg):
+@pytest.mark.parametrize("trim", [37, 40])
+def test_attention_over_cache_in_other_formats(bits, fmt, S, T, Bg, trim):
+    """trim = 40: every unit's scale array starts on a 16-byte boundary, so the formats the staged
+    kernel knows (E4M3 scales with one smoothing stage: 2-bit levels, or 4-bit levels in one round)
+    run there; trim = 37: the general kernel."""
     wl = CONFIGS["cfg2_window21"]
     H, L, n_chunks, K, Nq = 2, 520, 3, 64, 300
-    N = L * n_chunks - 37                                   # ragged last chunk
+    N = L * n_chunks - trim                                 # ragged last chunk
     caches = []
     for kv in (0, 1):
         st = synth.MixtureStream(wl, H, kv, DEV)
