@@ -246,12 +246,11 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
                 cur = buf[it & 1];
             }
         }
-        // this stage's table goes out as H rows of K*d bf16 with the caller's pitch
+        // this stage's table goes out as H rows of K*d bf16 with the caller's pitch: the stage's
+        // last assignment writes them while it stages the table (no copy of its own)
         bf16_t *cdst = static_cast<bf16_t *>(centroids_out) + (size_t)stage * p->n_clusters * kHeadDim;
         if (!(cur == cdst && cent_out_stride_head == (int64_t)p->n_clusters * kHeadDim)) {
-            if (hipMemcpy2DAsync(cdst, (size_t)cent_out_stride_head * sizeof(bf16_t), cur, row, row,
-                                 (size_t)p->n_heads, hipMemcpyDeviceToDevice, s) != hipSuccess)
-                return QVG_ERR_LAUNCH;
+            a.cent_copy = cdst; a.cent_copy_stride = cent_out_stride_head;
         }
         if (stage + 1 < S) {
             // final assignment of this stage, then the bf16 residual becomes the next input

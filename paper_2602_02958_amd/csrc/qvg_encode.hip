@@ -194,7 +194,11 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
     for (int i = tid; i < Kpad * 16; i += kAsgThreads) {           // Kpad*16 is a multiple of the block: whole waves
         const int row = i >> 4, c16 = i & 15;
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (row < K) v = *reinterpret_cast<const uint4 *>(cg + (int64_t)row * kHeadDim + c16 * 8);
+        if (row < K) {
+            v = *reinterpret_cast<const uint4 *>(cg + (int64_t)row * kHeadDim + c16 * 8);
+            if (a.cent_copy && blockIdx.y == 0)                     // the table's way out to the caller, for free
+                *reinterpret_cast<uint4 *>(a.cent_copy + (int64_t)h * a.cent_copy_stride + (int64_t)row * kHeadDim + c16 * 8) = v;
+        }
         *reinterpret_cast<uint4 *>(lc + row * kCPitch + c16 * 8) = v;
         if (norms_given) continue;                                  // uniform
         double sq = 0.0;

@@ -141,6 +141,8 @@ struct AssignArgs {
     int ids_step, ids_off;   // a token has ids_step id bytes; this pass writes byte ids_off (smoothing stage)
     int fused;
     uint2 *nh3; float *cmax; // scratch of assign_workspace_bytes(H, K): split -||c||^2/2 per row, max ||c||^2 per unit
+    bf16_t *cent_copy; int64_t cent_copy_stride;   // optional: the table also goes here, unit h at h * stride elements
+                                                   // (written by the unit's first workgroup while it stages the table)
 };
 // launches the centroid preparation and the assignment (fused with quantization when a.fused)
 hipError_t launch_assign(const AssignArgs &a, hipStream_t s);
