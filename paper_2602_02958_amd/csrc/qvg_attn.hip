@@ -267,10 +267,15 @@ void attn_kernel_direct(AttnArgs a) {
     const int g = (c8 * 8) / B;
     // position of the token pair in a transposed V row: token 16*st + 8*a + 4*hh + e sits at
     // 16*st + 8*hh + 4*a + e (the order in which a lane's soft-max values feed the PV MFMA);
-    // the 16-byte group index is XOR-ed with the channel chunk to spread the banks
+    // the 16-byte group index of a row is XOR-ed with a key, 2 * (row / 32), to spread the banks of
+    // these transposing 4-byte stores.  The key must not change inside the 32 consecutive rows
+    // that half a wavefront reads with one ds_read_b128 (measured: with 144-byte rows such a read
+    // takes 5.3 cycles of LDS time when the 32 lanes use the same key, 8.5 when lanes 16..31 use
+    // another one and 12.6 with a key per 8 rows, although every 16 lanes hit 16 different
+    // groups in all three cases)
     const int tok = 2 * tp;
     const int v_pos = 16 * (tok >> 4) + 8 * ((tok >> 2) & 1) + 4 * ((tok >> 3) & 1) + (tok & 3);
-    const int v_off = ((v_pos >> 3) ^ (c8 & 7)) * 8 + (v_pos & 7);      // in f16 units
+    const int v_off = ((v_pos >> 3) ^ ((c8 >> 2) * 2)) * 8 + (v_pos & 7);      // in f16 units; rows 8*c8 .. 8*c8+7 have key 2*(row/32)
 
     // Q as the B operand of S^T = K Q^T: lane (col, half) holds Q[q][16*kk + 8*half .. +7].
     uint4 qa[8];
@@ -394,7 +399,7 @@ void attn_kernel_direct(AttnArgs a) {
         // ---- O^T += V_tile^T . P --------------------------------------------
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
-            const int key = (mb * 4 + (col >> 3)) & 7;            // swizzle key of row 32*mb + col
+            const int key = mb * 2;                               // swizzle key of rows 32*mb .. 32*mb + 31
             const uint16_t *vrow = vt + (mb * 32 + col) * kVtPitch;
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
@@ -490,7 +495,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     const int g = (c8 * 8) / B;
     const int tok = 2 * tp;
     const int v_pos = 16 * (tok >> 4) + 8 * ((tok >> 2) & 1) + 4 * ((tok >> 3) & 1) + (tok & 3);
-    const int v_off = ((v_pos >> 3) ^ (c8 & 7)) * 8 + (v_pos & 7);      // in f16 units
+    const int v_off = ((v_pos >> 3) ^ ((c8 >> 2) * 2)) * 8 + (v_pos & 7);      // in f16 units; rows 8*c8 .. 8*c8+7 have key 2*(row/32)
 
     uint4 qa[8];
     {
@@ -726,7 +731,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         }
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
-            const int key = (mb * 4 + (col >> 3)) & 7;            // swizzle key of row 32*mb + col
+            const int key = mb * 2;                               // swizzle key of rows 32*mb .. 32*mb + 31
             const uint16_t *vrow = vt + (mb * 32 + col) * kVtPitch;
 #pragma unroll
             for (int st = 0; st < 4; ++st) {
