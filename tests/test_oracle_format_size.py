@@ -1,5 +1,7 @@
 """Pins the storage-size arithmetic against the compression ratios the paper prints
-(tests/golden/paper_compression_ratios.txt; Tables 1 and 4)."""
+(tests/golden/paper_compression_ratios.txt: Tables 1 and 4; paper_table5_codebook_size.txt:
+Table 5)."""
+import math
 import os
 
 from oracle import qvg_oracle as O
@@ -70,3 +72,33 @@ def test_this_builds_format_bytes_per_vector():
                                (128, 3, 32, 10800, 121), (256, 4, 64, 4680, 145)):
         total = O.chunk_bytes(N, D, K, B, 1, T, 2, 2.0, 8.0)
         assert total == N * want + K * D * 2
+
+
+def test_table5_codebook_size_sweep():
+    """Table 5 (ratio against K = 64 .. 512, 4-bit and 2-bit levels): all eight printed ratios follow
+    from ONE chunk length when a token costs its levels plus log2(K) id bits and a chunk its K x d
+    bf16 table (scales are not in these figures: with a byte per group no chunk length comes
+    within 0.2 of them).  This fixes how the size arithmetic counts ids (bits, not whole bytes)
+    and tables (2 bytes per entry), and that 512 centroids cost 9 bits per token."""
+    rows = [tuple(float(v) for v in line.split()) for line in
+            open(os.path.join(os.path.dirname(__file__), "golden", "paper_table5_codebook_size.txt"))
+            if line.strip() and not line.startswith("#")]
+    assert [int(r[0]) for r in rows] == [512, 256, 128, 64]
+
+    def ratio(N, K, bits, scale_bytes=0.0):
+        return N * D * 2 / O.chunk_bytes(N, D, int(K), 64, 1, 1, bits, scale_bytes, math.log2(K))
+
+    # the chunk length the (K = 256, 2-bit) entry implies
+    lo, hi = 1000, 10_000_000
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        lo, hi = (mid, hi) if ratio(mid, 256, 2) < 7.539 else (lo, mid)
+    N = hi
+    assert 20_000 < N < 200_000
+    for K, r4, r2 in rows:
+        assert abs(ratio(N, K, 4) - r4) <= 0.01, (K, ratio(N, K, 4))
+        assert abs(ratio(N, K, 2) - r2) <= 0.01, (K, ratio(N, K, 2))
+    # a dropped table term, whole-byte ids at K = 512 or a byte of scale per group would all miss
+    assert abs(N * D * 2 / (N * (32 + 9 / 8)) - 7.307) > 0.2
+    assert abs(N * D * 2 / O.chunk_bytes(N, D, 512, 64, 1, 1, 2, 0.0, 16.0) - 7.307) > 0.1
+    assert min(abs(ratio(n, 256, 2, 1.0) - 7.539) for n in (N // 2, N, 2 * N, 100 * N)) > 0.2
