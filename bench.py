@@ -293,6 +293,13 @@ def presets_supplement(torch, B, synth, CONFIGS):
     return {name: preset_supplement(torch, B, synth, CONFIGS, **kw) for name, kw in PAPER_PRESETS.items()}
 
 
+def codebook_supplement(torch, B, synth, CONFIGS):
+    """The codebook-size study of Sec. 5 (Table 5) on the cfg2 window: QVG INT2 with K = 64 .. 512
+    centroids (512: 16-bit ids, the general attention kernel)."""
+    return {f"K{K}": preset_supplement(torch, B, synth, CONFIGS, S=1, group_size=64, bits=2, n_clusters=K)
+            for K in (64, 128, 256, 512)}
+
+
 def long_supplement(torch, B, synth, CONFIGS, name="cfg5_long"):
     """One layer of a configuration at full size (default cfg5, the long-horizon one: 12 heads, 160
     chunks of 4680 tokens = 748800 cached tokens per head, K = 256, T = 4, centres drifting from
@@ -462,6 +469,7 @@ def main():
         return
     if args.only == "presets":
         print(json.dumps(presets_supplement(torch, B, synth, CONFIGS)))
+        print(json.dumps(codebook_supplement(torch, B, synth, CONFIGS)))
         print(json.dumps(warm_start_supplement(torch, B, synth, wl)))
         return
     if args.only:
@@ -549,6 +557,7 @@ def main():
             result["large"] = {"error": str(e)[:200]}
     if not args.no_large:
         result["paper_presets"] = presets_supplement(torch, B, synth, CONFIGS)
+        result["codebook_size"] = codebook_supplement(torch, B, synth, CONFIGS)
         result["warm_start"] = warm_start_supplement(torch, B, synth, wl)
         result["attn_integration"] = integration_supplement(torch, B, s)
         del s

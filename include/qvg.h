@@ -37,6 +37,9 @@
  * exponent bits with bias 7, 3 mantissa bits; largest finite value 448, no infinity, subnormals
  * m/8 * 2^-6), scales [N][T][d/B] uint8; the encoder never writes the NaN code 0x7F, and a
  * decoder that meets it reads 480.  E4M3 scale arrays need no alignment.
+ * With more than 256 centroids (the codebook-size study of Sec. 5, Table 5, goes to K = 512) an id
+ * is a 16-bit word: every "uint8_t *ids" argument then points at uint16 data, 2-byte aligned;
+ * this form has one smoothing stage only (QVG_ERR_UNSUPPORTED otherwise).
  * A cache of several chunks concatenates ids/codes/scales along N and keeps one
  * centroid table per chunk: centroids [n_chunks][K][d].
  *
@@ -70,7 +73,7 @@ typedef enum qvg_status {
 typedef struct qvg_params {
     int32_t n_heads;         /* H >= 1: independent units handled by one call           */
     int32_t head_dim;        /* d: 128                                                  */
-    int32_t n_clusters;      /* K: 1..256, ids are uint8 (Sec. 5: K = 256)              */
+    int32_t n_clusters;      /* K: 1..512; ids are uint8 up to 256 (Sec. 5: K = 256), uint16 beyond */
     int32_t group_size;      /* B: 16, 32, 64 or 128 consecutive channels of one token  */
     int32_t n_stages;        /* T: 1..8 rounds of b-bit quantization of the residual    */
     int32_t bits;            /* b: 2 or 4 bits per level (Sec. 5: INT2 / INT4)          */

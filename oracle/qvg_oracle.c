@@ -21,7 +21,9 @@
  * Pins (tests/test_oracle_*.py): brute-force numpy argmin, member-mean and
  * scipy/sklearn Lloyd, Eq. 3 error bound, exact-on-grid round trip, monotone
  * error in T, torch SDPA, numpy float16/bfloat16 conversions, and the paper's
- * printed compression ratios (Tables 1, 4).
+ * printed compression ratios (Tables 1, 4, 5).
+ * Cluster ids are 16-bit words here whatever K is (the codebook-size study of Sec. 5 goes to
+ * K = 512); the Python wrapper hands them out as bytes when K <= 256, as a stored cache has them.
  * Parity unpinned: reconstruction quality on real model KV (Sec. 5 MSE gains)
  * cannot be checked here; no model weights exist in this build.
  */
@@ -29,6 +31,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+
+/* cluster index of a token: 16 bits in memory here, whatever width a stored format gives it */
+typedef uint16_t qid_t;
 
 /* ------------------------------------------------------------------ */
 /* number formats                                                     */
@@ -132,7 +137,7 @@ static double sqdist(int d, const float *r, const uint16_t *c) {
  * centroid is nearest; equal distances go to the lowest index.
  * best_dist (nullable) receives the winning squared distance. */
 void qvgo_assign(int64_t N, int d, int K, const float *r, const uint16_t *cent,
-                 uint8_t *ids, double *best_dist) {
+                 qid_t *ids, double *best_dist) {
     for (int64_t n = 0; n < N; ++n) {
         int best = 0;
         double bd = sqdist(d, r + n * d, cent);
@@ -140,7 +145,7 @@ void qvgo_assign(int64_t N, int d, int K, const float *r, const uint16_t *cent,
             double dj = sqdist(d, r + n * d, cent + (int64_t)j * d);
             if (dj < bd) { bd = dj; best = j; }
         }
-        ids[n] = (uint8_t)best;
+        ids[n] = (qid_t)best;
         if (best_dist) best_dist[n] = bd;
     }
 }
@@ -148,7 +153,7 @@ void qvgo_assign(int64_t N, int d, int K, const float *r, const uint16_t *cent,
 /* Squared distance of each token to a GIVEN centroid index (for the tie
  * classification in the parity tests). */
 void qvgo_dist_to(int64_t N, int d, const float *r, const uint16_t *cent,
-                  const uint8_t *ids, double *out) {
+                  const qid_t *ids, double *out) {
     for (int64_t n = 0; n < N; ++n)
         out[n] = sqdist(d, r + n * d, cent + (int64_t)ids[n] * d);
 }
@@ -157,7 +162,7 @@ void qvgo_dist_to(int64_t N, int d, const float *r, const uint16_t *cent,
  * Sum of the members in token order in fp64, divided by the member count,
  * rounded to binary32 and then to bf16 (the stored precision).  A group
  * without members keeps its previous centroid. */
-void qvgo_update(int64_t N, int d, int K, const float *r, const uint8_t *ids,
+void qvgo_update(int64_t N, int d, int K, const float *r, const qid_t *ids,
                  const uint16_t *cent_prev, uint16_t *cent_out, int32_t *counts) {
     double *sum = (double *)calloc((size_t)K * d, sizeof(double));
     int32_t *cnt = (int32_t *)calloc((size_t)K, sizeof(int32_t));
@@ -183,7 +188,7 @@ void qvgo_update(int64_t N, int d, int K, const float *r, const uint8_t *ids,
  * inertia (nullable, I+1 entries) receives the summed winning distance of
  * each assign pass. */
 void qvgo_lloyd(int64_t N, int d, int K, int I, const float *r, const uint16_t *init,
-                uint16_t *cent_out, uint8_t *ids_out, double *inertia) {
+                uint16_t *cent_out, qid_t *ids_out, double *inertia) {
     size_t tb = (size_t)K * d * sizeof(uint16_t);
     uint16_t *cur = (uint16_t *)malloc(tb), *nxt = (uint16_t *)malloc(tb);
     double *bd = (double *)malloc((size_t)(N > 0 ? N : 1) * sizeof(double));
@@ -201,7 +206,7 @@ void qvgo_lloyd(int64_t N, int d, int K, int I, const float *r, const uint16_t *
 
 /* Eq. 5: residual = token minus the centroid of its group (one fp32 subtract). */
 void qvgo_residual(int64_t N, int d, const float *r_in, const uint16_t *cent,
-                   const uint8_t *ids, float *r_out) {
+                   const qid_t *ids, float *r_out) {
     for (int64_t n = 0; n < N; ++n)
         for (int ch = 0; ch < d; ++ch)
             r_out[n * d + ch] = r_in[n * d + ch] - qvgo_bf16_to_f32(cent[(int64_t)ids[n] * d + ch]);
@@ -307,7 +312,7 @@ void qvgo_unpack(int64_t n_elems, int bits, const uint8_t *packed, int8_t *q) {
  * resid_out (nullable) [N][d] fp32: what remains after all rounds */
 void qvgo_encode_unit(int64_t N, int d, int K, int B, int S, int T, int bits, int scale_fmt, int I,
                       const uint16_t *x, const uint16_t *init, const int32_t *init_idx,
-                      uint16_t *cent_out, uint8_t *ids_out,
+                      uint16_t *cent_out, qid_t *ids_out,
                       uint8_t *codes_out, uint16_t *scales_out, float *resid_out) {
     const int G = d / B, cb = d * bits / 8;
     size_t nd = (size_t)(N > 0 ? N : 1) * d;
@@ -324,7 +329,7 @@ void qvgo_encode_unit(int64_t N, int d, int K, int B, int S, int T, int bits, in
             for (int ch = 0; ch < d; ++ch)
                 start[j * d + ch] = qvgo_f32_to_bf16(r[(int64_t)init_idx[j] * d + ch]);
         uint16_t *cs = cent_out + (int64_t)s * K * d;
-        uint8_t *is = ids_out + (int64_t)s * N;
+        qid_t *is = ids_out + (int64_t)s * N;
         qvgo_lloyd(N, d, K, I, r, start, cs, is, NULL);
         qvgo_residual(N, d, r, cs, is, r2);
         /* A residual that feeds another smoothing stage is a tensor of the input's type
@@ -348,7 +353,7 @@ void qvgo_encode_unit(int64_t N, int d, int K, int B, int S, int T, int bits, in
  * assignment, residual, quantization rounds.  S = 1 only. */
 void qvgo_encode_given_centroids(int64_t N, int d, int K, int B, int T, int bits, int scale_fmt,
                                  const uint16_t *x, const uint16_t *cent,
-                                 uint8_t *ids_out, uint8_t *codes_out, uint16_t *scales_out) {
+                                 qid_t *ids_out, uint8_t *codes_out, uint16_t *scales_out) {
     uint16_t *cdump = (uint16_t *)malloc((size_t)K * d * 2);
     qvgo_encode_unit(N, d, K, B, 1, T, bits, scale_fmt, 0, x, cent, NULL, cdump, ids_out,
                      codes_out, scales_out, NULL);
@@ -357,7 +362,7 @@ void qvgo_encode_given_centroids(int64_t N, int d, int K, int B, int T, int bits
 
 /* Same, with the assignment given too: residual and quantization rounds. */
 void qvgo_encode_given_ids(int64_t N, int d, int B, int T, int bits, int scale_fmt,
-                           const uint16_t *x, const uint16_t *cent, const uint8_t *ids,
+                           const uint16_t *x, const uint16_t *cent, const qid_t *ids,
                            uint8_t *codes_out, uint16_t *scales_out) {
     const int G = d / B, cb = d * bits / 8;
     size_t nd = (size_t)(N > 0 ? N : 1) * d;
@@ -386,7 +391,7 @@ void qvgo_encode_given_ids(int64_t N, int d, int B, int T, int bits, int scale_f
  * cent [S][K][d], ids [S][N], codes [N][T][d*b/8], scales [N][T][d/B].
  * out_bf16 [N][d]; out_f32 (nullable) the value before the final rounding. */
 void qvgo_decode_unit(int64_t N, int d, int K, int B, int S, int T, int bits, int scale_fmt,
-                      const uint16_t *cent, const uint8_t *ids, const uint8_t *codes,
+                      const uint16_t *cent, const qid_t *ids, const uint8_t *codes,
                       const uint16_t *scales, uint16_t *out_bf16, float *out_f32) {
     const int G = d / B, cb = d * bits / 8;
     int8_t *q = (int8_t *)malloc((size_t)d);
@@ -507,7 +512,7 @@ double qvgo_chunk_bytes(int64_t N, int d, int K, int B, int S, int T, int bits,
 
 void qvgo_encode_batch(int H, int64_t N, int d, int K, int B, int S, int T, int bits, int scale_fmt, int I,
                        const uint16_t *x, const uint16_t *init,
-                       uint16_t *cent_out, uint8_t *ids_out,
+                       uint16_t *cent_out, qid_t *ids_out,
                        uint8_t *codes_out, uint16_t *scales_out) {
     const int G = d / B, cb = d * bits / 8;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -519,7 +524,7 @@ void qvgo_encode_batch(int H, int64_t N, int d, int K, int B, int S, int T, int 
 }
 
 void qvgo_decode_batch(int H, int64_t N, int d, int K, int B, int S, int T, int bits, int scale_fmt,
-                       const uint16_t *cent, const uint8_t *ids, const uint8_t *codes,
+                       const uint16_t *cent, const qid_t *ids, const uint8_t *codes,
                        const uint16_t *scales, uint16_t *out_bf16) {
     const int G = d / B, cb = d * bits / 8;
 #pragma omp parallel for schedule(dynamic, 1)

@@ -67,6 +67,11 @@ def _c(a, dtype):
     return np.ascontiguousarray(a, dtype=dtype)
 
 
+def _stored_ids(ids, K):
+    """ids as the stored format keeps them: one byte per id up to 256 centroids, two beyond."""
+    return ids.astype(np.uint8) if K <= 256 else ids
+
+
 # ---------------------------------------------------------------- formats
 def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
     """bf16 bit patterns (uint16) -> float32 (exact)."""
@@ -133,29 +138,30 @@ def assign(r, cent, want_dist=False):
     """Nearest-centroid assignment; r [N,d] float32, cent [K,d] bf16 bits."""
     r = _c(r, np.float32); cent = _c(cent, np.uint16)
     N, d = r.shape; K = cent.shape[0]
-    ids = np.empty(N, np.uint8)
+    ids = np.empty(N, np.uint16)
     bd = np.empty(N, np.float64) if want_dist else None
     lib().qvgo_assign(C.c_int64(N), d, K, _p(r, np.float32), _p(cent, np.uint16),
-                      _p(ids, np.uint8), _p(bd, np.float64))
+                      _p(ids, np.uint16), _p(bd, np.float64))
+    ids = _stored_ids(ids, K)
     return (ids, bd) if want_dist else ids
 
 
 def dist_to(r, cent, ids):
     """fp64 squared distance of every token to the centroid ids[n]."""
-    r = _c(r, np.float32); cent = _c(cent, np.uint16); ids = _c(ids, np.uint8)
+    r = _c(r, np.float32); cent = _c(cent, np.uint16); ids = _c(ids, np.uint16)
     N, d = r.shape
     out = np.empty(N, np.float64)
     lib().qvgo_dist_to(C.c_int64(N), d, _p(r, np.float32), _p(cent, np.uint16),
-                       _p(ids, np.uint8), _p(out, np.float64))
+                       _p(ids, np.uint16), _p(out, np.float64))
     return out
 
 
 def update(r, ids, cent_prev):
     """Centroid = mean of its members; empty groups keep cent_prev. -> (cent, counts)."""
-    r = _c(r, np.float32); ids = _c(ids, np.uint8); cent_prev = _c(cent_prev, np.uint16)
+    r = _c(r, np.float32); ids = _c(ids, np.uint16); cent_prev = _c(cent_prev, np.uint16)
     N, d = r.shape; K = cent_prev.shape[0]
     out = np.empty((K, d), np.uint16); cnt = np.empty(K, np.int32)
-    lib().qvgo_update(C.c_int64(N), d, K, _p(r, np.float32), _p(ids, np.uint8),
+    lib().qvgo_update(C.c_int64(N), d, K, _p(r, np.float32), _p(ids, np.uint16),
                       _p(cent_prev, np.uint16), _p(out, np.uint16), _p(cnt, np.int32))
     return out, cnt
 
@@ -164,20 +170,20 @@ def lloyd(r, init, iters):
     """iters x (assign, update) + final assign. -> (cent, ids, inertia[iters+1])."""
     r = _c(r, np.float32); init = _c(init, np.uint16)
     N, d = r.shape; K = init.shape[0]
-    cent = np.empty((K, d), np.uint16); ids = np.empty(N, np.uint8)
+    cent = np.empty((K, d), np.uint16); ids = np.empty(N, np.uint16)
     inertia = np.empty(iters + 1, np.float64)
     lib().qvgo_lloyd(C.c_int64(N), d, K, iters, _p(r, np.float32), _p(init, np.uint16),
-                     _p(cent, np.uint16), _p(ids, np.uint8), _p(inertia, np.float64))
-    return cent, ids, inertia
+                     _p(cent, np.uint16), _p(ids, np.uint16), _p(inertia, np.float64))
+    return cent, _stored_ids(ids, K), inertia
 
 
 def residual(r, cent, ids):
     """Eq. 5."""
-    r = _c(r, np.float32); cent = _c(cent, np.uint16); ids = _c(ids, np.uint8)
+    r = _c(r, np.float32); cent = _c(cent, np.uint16); ids = _c(ids, np.uint16)
     N, d = r.shape
     out = np.empty((N, d), np.float32)
     lib().qvgo_residual(C.c_int64(N), d, _p(r, np.float32), _p(cent, np.uint16),
-                        _p(ids, np.uint8), _p(out, np.float32))
+                        _p(ids, np.uint16), _p(out, np.float32))
     return out
 
 
@@ -220,14 +226,14 @@ def encode_unit(x, K, B, S, T, iters, init=None, init_idx=None, bits=2, want_res
     else:
         init_idx = _c(init_idx, np.int32)
         assert init_idx.shape == (K,)
-    cent = np.empty((S, K, d), np.uint16); ids = np.empty((S, N), np.uint8)
+    cent = np.empty((S, K, d), np.uint16); ids = np.empty((S, N), np.uint16)
     codes = np.empty((N, T, d * bits // 8), np.uint8); sc = np.empty((N, T, d // B), np.uint16)
     resid = np.empty((N, d), np.float32) if want_resid else None
     lib().qvgo_encode_unit(C.c_int64(N), d, K, B, S, T, bits, scale_fmt, iters, _p(x, np.uint16),
                            _p(init, np.uint16), _p(init_idx, np.int32), _p(cent, np.uint16),
-                           _p(ids, np.uint8), _p(codes, np.uint8), _p(sc, np.uint16),
+                           _p(ids, np.uint16), _p(codes, np.uint8), _p(sc, np.uint16),
                            _p(resid, np.float32))
-    out = dict(cent=cent, ids=ids, codes=codes, scales=sc)
+    out = dict(cent=cent, ids=_stored_ids(ids, K), codes=codes, scales=sc)
     if want_resid:
         out["resid"] = resid
     return out
@@ -236,27 +242,27 @@ def encode_unit(x, K, B, S, T, iters, init=None, init_idx=None, bits=2, want_res
 def encode_given_centroids(x, cent, B, T, bits=2, scale_fmt=0):
     x = _c(x, np.uint16); cent = _c(cent, np.uint16)
     N, d = x.shape; K = cent.shape[0]
-    ids = np.empty(N, np.uint8)
+    ids = np.empty(N, np.uint16)
     codes = np.empty((N, T, d * bits // 8), np.uint8); sc = np.empty((N, T, d // B), np.uint16)
     lib().qvgo_encode_given_centroids(C.c_int64(N), d, K, B, T, bits, scale_fmt, _p(x, np.uint16),
-                                      _p(cent, np.uint16), _p(ids, np.uint8),
+                                      _p(cent, np.uint16), _p(ids, np.uint16),
                                       _p(codes, np.uint8), _p(sc, np.uint16))
-    return dict(ids=ids, codes=codes, scales=sc)
+    return dict(ids=_stored_ids(ids, K), codes=codes, scales=sc)
 
 
 def encode_given_ids(x, cent, ids, B, T, bits=2, scale_fmt=0):
-    x = _c(x, np.uint16); cent = _c(cent, np.uint16); ids = _c(ids, np.uint8)
+    x = _c(x, np.uint16); cent = _c(cent, np.uint16); ids = _c(ids, np.uint16)
     N, d = x.shape
     codes = np.empty((N, T, d * bits // 8), np.uint8); sc = np.empty((N, T, d // B), np.uint16)
     lib().qvgo_encode_given_ids(C.c_int64(N), d, B, T, bits, scale_fmt, _p(x, np.uint16),
-                                _p(cent, np.uint16), _p(ids, np.uint8),
+                                _p(cent, np.uint16), _p(ids, np.uint16),
                                 _p(codes, np.uint8), _p(sc, np.uint16))
     return dict(codes=codes, scales=sc)
 
 
 def decode_unit(cent, ids, codes, scales, B, bits=2, want_f32=False, scale_fmt=0):
     """Eq. 7 replay.  cent [S,K,d] (or [K,d]), ids [S,N] (or [N]). -> bf16 bits [N,d]."""
-    cent = _c(cent, np.uint16); ids = _c(ids, np.uint8)
+    cent = _c(cent, np.uint16); ids = _c(ids, np.uint16)
     codes = _c(codes, np.uint8); scales = _c(scales, np.uint16)
     if cent.ndim == 2:
         cent = cent[None]
@@ -267,7 +273,7 @@ def decode_unit(cent, ids, codes, scales, B, bits=2, want_f32=False, scale_fmt=0
     out = np.empty((N, d), np.uint16)
     f32 = np.empty((N, d), np.float32) if want_f32 else None
     lib().qvgo_decode_unit(C.c_int64(N), d, K, B, S, T, bits, scale_fmt, _p(cent, np.uint16),
-                           _p(ids, np.uint8), _p(codes, np.uint8), _p(scales, np.uint16),
+                           _p(ids, np.uint16), _p(codes, np.uint8), _p(scales, np.uint16),
                            _p(out, np.uint16), _p(f32, np.float32))
     return (out, f32) if want_f32 else out
 
@@ -315,22 +321,22 @@ def encode_batch(x, init, K, B, T, iters, S=1, bits=2, scale_fmt=0):
     x = _c(x, np.uint16); init = _c(init, np.uint16)
     H, N, d = x.shape
     init = init.reshape(H, S, K, d)
-    cent = np.empty((H, S, K, d), np.uint16); ids = np.empty((H, S, N), np.uint8)
+    cent = np.empty((H, S, K, d), np.uint16); ids = np.empty((H, S, N), np.uint16)
     codes = np.empty((H, N, T, d * bits // 8), np.uint8); sc = np.empty((H, N, T, d // B), np.uint16)
     lib().qvgo_encode_batch(H, C.c_int64(N), d, K, B, S, T, bits, scale_fmt, iters, _p(x, np.uint16),
-                            _p(init, np.uint16), _p(cent, np.uint16), _p(ids, np.uint8),
+                            _p(init, np.uint16), _p(cent, np.uint16), _p(ids, np.uint16),
                             _p(codes, np.uint8), _p(sc, np.uint16))
-    return dict(cent=cent, ids=ids, codes=codes, scales=sc)
+    return dict(cent=cent, ids=_stored_ids(ids, K), codes=codes, scales=sc)
 
 
 def decode_batch(cent, ids, codes, scales, B, bits=2, scale_fmt=0):
-    cent = _c(cent, np.uint16); ids = _c(ids, np.uint8)
+    cent = _c(cent, np.uint16); ids = _c(ids, np.uint16)
     codes = _c(codes, np.uint8); scales = _c(scales, np.uint16)
     H, S, K, d = cent.shape
     N, T = codes.shape[1], codes.shape[2]
     out = np.empty((H, N, d), np.uint16)
     lib().qvgo_decode_batch(H, C.c_int64(N), d, K, B, S, T, bits, scale_fmt, _p(cent, np.uint16),
-                            _p(ids, np.uint8), _p(codes, np.uint8), _p(scales, np.uint16),
+                            _p(ids, np.uint16), _p(codes, np.uint8), _p(scales, np.uint16),
                             _p(out, np.uint16))
     return out
 

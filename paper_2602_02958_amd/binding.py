@@ -132,7 +132,7 @@ class Encoded:
     The formats are read off the tensors: 4-bit levels have d/2 code bytes per round, FP8 E4M3
     scales are a uint8 tensor."""
     centroids: torch.Tensor   # [H, n_chunks, K, d] bf16
-    ids: torch.Tensor         # [H, N] uint8
+    ids: torch.Tensor         # [H, N] uint8 (int16 with more than 256 centroids)
     codes: torch.Tensor       # [H, N, T, d*bits/8] uint8
     scales: torch.Tensor      # [H, N, T, d/B] float16, or uint8 (E4M3)
     chunk_len: int
@@ -147,6 +147,12 @@ class Encoded:
         return SCALE_E4M3 if self.scales.dtype == torch.uint8 else SCALE_F16
 
 
+def id_dtype(n_clusters):
+    """Cluster ids are bytes up to 256 centroids and 16-bit words beyond (int16 tensors here: the
+    values stay below 512)."""
+    return torch.uint8 if n_clusters <= 256 else torch.int16
+
+
 def alloc_cache(n_heads, n_tokens, chunk_len, n_clusters, group_size, n_stages, head_dim=128,
                 device="cuda", n_smooth=1, bits=2, scale_format=SCALE_F16) -> Encoded:
     """Uninitialised storage for a cache of n_tokens tokens per unit in chunks of chunk_len."""
@@ -156,7 +162,7 @@ def alloc_cache(n_heads, n_tokens, chunk_len, n_clusters, group_size, n_stages, 
     ishape = (n_heads, n_tokens) if S == 1 else (n_heads, n_tokens, S)
     return Encoded(
         torch.empty(cshape, dtype=torch.bfloat16, device=device),
-        torch.empty(ishape, dtype=torch.uint8, device=device),
+        torch.empty(ishape, dtype=id_dtype(n_clusters), device=device),
         torch.empty(n_heads, n_tokens, n_stages, head_dim * bits // 8, dtype=torch.uint8, device=device),
         torch.empty(n_heads, n_tokens, n_stages, head_dim // group_size,
                     dtype=torch.uint8 if scale_format == SCALE_E4M3 else torch.float16, device=device),
@@ -185,7 +191,8 @@ def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: E
     if not (0 <= chunk_index < n_chunks) or off + N > n_total or (N > cache.chunk_len):
         raise ValueError("chunk does not fit the cache")
     if cache.codes.shape[2] != n_stages or cache.scales.shape[3] != d // group_size or \
-            cache.centroids.shape[-2] != K or cache.ids.shape[0] != H or cache.n_smooth != S:
+            cache.centroids.shape[-2] != K or cache.ids.shape[0] != H or cache.n_smooth != S or \
+            cache.ids.dtype != id_dtype(K):
         raise ValueError("cache was allocated for other parameters")
     p = make_params(H, K, group_size, n_stages, kmeans_iters, head_dim=d, n_smooth_stages=S, bits=bits,
                     scale_format=scale_format)
@@ -196,7 +203,7 @@ def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: E
     st = lib().qvg_encode_chunk(
         C.byref(p), N, _ptr(x), sh, st_, _ptr(init_centroids),
         C.c_void_p(cache.centroids.data_ptr() + chunk_index * S * K * d * 2), n_chunks * S * K * d,
-        C.c_void_p(cache.ids.data_ptr() + off * S),
+        C.c_void_p(cache.ids.data_ptr() + off * S * cache.ids.element_size()),
         C.c_void_p(cache.codes.data_ptr() + off * T * (d * bits // 8)),
         C.c_void_p(cache.scales.data_ptr() + off * T * G * cache.scales.element_size()), n_total,
         _ptr(workspace) if need else None, need, _stream())
@@ -219,7 +226,7 @@ def decode(enc: Encoded, out=None, n_tokens=None, first_token=0) -> torch.Tensor
     if out is None:
         out = torch.empty(H, N, d, dtype=torch.bfloat16, device=enc.ids.device)
     sh, st_ = _view3(out, "out")
-    for t, dt, nm in ((enc.centroids, torch.bfloat16, "centroids"), (enc.ids, torch.uint8, "ids"),
+    for t, dt, nm in ((enc.centroids, torch.bfloat16, "centroids"), (enc.ids, id_dtype(K), "ids"),
                       (enc.codes, torch.uint8, "codes"), (enc.scales, enc.scales.dtype, "scales")):
         _check(t, dt, nm)
         if not t.is_contiguous():
@@ -249,6 +256,8 @@ def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, o
             raise ValueError("k_rope: need a contiguous [n_kv, d/2, 2] float16 tensor")
     K = k.centroids.shape[-2]
     T, G = k.codes.shape[2], k.scales.shape[3]
+    _check(k.ids, id_dtype(K), "k.ids")
+    _check(v.ids, id_dtype(K), "v.ids")
     if (v.ids.shape, v.codes.shape, v.scales.shape, v.scales.dtype, v.centroids.shape, v.chunk_len, v.n_smooth) != \
             (k.ids.shape, k.codes.shape, k.scales.shape, k.scales.dtype, k.centroids.shape, k.chunk_len, k.n_smooth):
         raise ValueError("K and V caches must share shapes and parameters")
@@ -291,12 +300,12 @@ def attn_merge(out_a, lse_a, out_b, lse_b, out=None, want_lse=False):
 
 
 def kmeans_assign(x, centroids) -> torch.Tensor:
-    """qvg_kmeans_assign -> ids uint8 [H, N]."""
+    """qvg_kmeans_assign -> ids [H, N], uint8 (int16 with more than 256 centroids)."""
     sh, st_ = _view3(x, "x")
     H, N, d = x.shape
     centroids = centroids.contiguous()
     p = make_params(H, centroids.shape[-2], 64, 1, 0, head_dim=d)
-    ids = torch.empty(H, N, dtype=torch.uint8, device=x.device)
+    ids = torch.empty(H, N, dtype=id_dtype(centroids.shape[-2]), device=x.device)
     need = workspace_bytes(p, ENTRY_KMEANS_ASSIGN, N)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
     st = lib().qvg_kmeans_assign(C.byref(p), N, _ptr(x), sh, st_, _ptr(centroids), _ptr(ids), _ptr(ws), need,
@@ -312,6 +321,7 @@ def kmeans_update(x, ids, centroids_prev):
     H, N, d = x.shape
     centroids_prev = centroids_prev.contiguous()
     K = centroids_prev.shape[-2]
+    _check(ids, id_dtype(K), "ids")
     p = make_params(H, K, 64, 1, 0, head_dim=d)
     cent = torch.empty(H, K, d, dtype=torch.bfloat16, device=x.device)
     counts = torch.empty(H, K, dtype=torch.int32, device=x.device)

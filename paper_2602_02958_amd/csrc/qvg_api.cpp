@@ -16,7 +16,7 @@ inline size_t round256(size_t v) { return (v + 255u) & ~(size_t)255u; }
 int check_params(const qvg_params *p) {
     if (!p) return QVG_ERR_NULL;
     if (p->n_heads < 1 || p->n_heads > 65535) return QVG_ERR_BAD_PARAM;
-    if (p->n_clusters < 1 || p->n_clusters > 256) return QVG_ERR_BAD_PARAM;
+    if (p->n_clusters < 1 || p->n_clusters > kMaxClusters) return QVG_ERR_BAD_PARAM;
     if (p->n_stages < 1 || p->n_stages > kMaxStages) return QVG_ERR_BAD_PARAM;
     if (p->kmeans_iters < 0) return QVG_ERR_BAD_PARAM;
     if (p->head_dim < 1 || p->n_smooth_stages < 1) return QVG_ERR_BAD_PARAM;
@@ -26,11 +26,17 @@ int check_params(const qvg_params *p) {
     // valid in the paper, not built here
     if (p->head_dim != kHeadDim) return QVG_ERR_UNSUPPORTED;
     if (p->n_smooth_stages > kMaxSmooth) return QVG_ERR_UNSUPPORTED;
+    if (p->n_clusters > 256 && p->n_smooth_stages > 1) return QVG_ERR_UNSUPPORTED;    // 16-bit ids: one stage
     const int B = p->group_size;
     if (B != 16 && B != 32 && B != 64 && B != 128) return QVG_ERR_UNSUPPORTED;
     return QVG_OK;
 }
 
+// more than 256 centroids: an id is a 16-bit word (2-byte aligned arrays)
+inline int id_wide(const qvg_params *p) { return p->n_clusters > 256 ? 1 : 0; }
+inline bool ids_aligned(const qvg_params *p, const void *ids) {
+    return !id_wide(p) || (reinterpret_cast<uintptr_t>(ids) & 1u) == 0;
+}
 inline int format_of(const qvg_params *p) {
     return (p->bits == 4 ? kFmtInt4 : 0) | (p->scale_format == QVG_SCALE_E4M3 ? kFmtE4M3 : 0);
 }
@@ -122,7 +128,7 @@ int64_t qvg_compressed_bytes(const qvg_params *p, int64_t n_tokens) {
     const int64_t d = p->head_dim, T = p->n_stages;
     const int64_t S = p->n_smooth_stages;
     const int64_t scale_bytes = p->scale_format == QVG_SCALE_E4M3 ? 1 : 2;
-    const int64_t per_token = T * (d * p->bits / 8 + scale_bytes * (d / p->group_size)) + S;
+    const int64_t per_token = T * (d * p->bits / 8 + scale_bytes * (d / p->group_size)) + S * (id_wide(p) ? 2 : 1);
     return (int64_t)p->n_heads * (n_tokens * per_token + S * (int64_t)p->n_clusters * d * 2);
 }
 
@@ -135,7 +141,7 @@ int qvg_kmeans_assign(const qvg_params *p, int64_t n_tokens, const void *x, int6
     if (n_tokens == 0) return QVG_OK;
     if (!x || !centroids || !ids_out) return QVG_ERR_NULL;
     if ((st = check_view(x, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
-    if (!aligned16(centroids)) return QVG_ERR_ALIGN;
+    if (!aligned16(centroids) || !ids_aligned(p, ids_out)) return QVG_ERR_ALIGN;
     const EncodeWs w = encode_ws(p, n_tokens, true, false, false);
     if (!workspace || workspace_bytes < w.total) return QVG_ERR_WORKSPACE;
     if (!aligned16(workspace)) return QVG_ERR_ALIGN;
@@ -145,7 +151,7 @@ int qvg_kmeans_assign(const qvg_params *p, int64_t n_tokens, const void *x, int6
     a.n_tokens = n_tokens; a.cent = static_cast<const bf16_t *>(centroids);
     a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size; a.T = p->n_stages;
     a.ids = ids_out; a.codes = nullptr; a.scales = nullptr; a.out_stride = n_tokens; a.fused = 0;
-    a.ids_step = 1; a.ids_off = 0;
+    a.ids_step = 1; a.ids_off = 0; a.id_wide = id_wide(p);
     return launch_assign(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
 }
 
@@ -159,7 +165,7 @@ int qvg_kmeans_update(const qvg_params *p, int64_t n_tokens, const void *x, int6
     if (!cent_prev || !cent_out) return QVG_ERR_NULL;
     if (n_tokens > 0 && (!x || !ids)) return QVG_ERR_NULL;
     if (n_tokens > 0 && (st = check_view(x, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
-    if (!aligned16(cent_prev) || !aligned16(cent_out)) return QVG_ERR_ALIGN;
+    if (!aligned16(cent_prev) || !aligned16(cent_out) || !ids_aligned(p, ids)) return QVG_ERR_ALIGN;
     const EncodeWs w = encode_ws(p, n_tokens, false, false);
     if (!workspace || workspace_bytes < w.total) return QVG_ERR_WORKSPACE;
     if (!aligned16(workspace)) return QVG_ERR_ALIGN;
@@ -167,6 +173,7 @@ int qvg_kmeans_update(const qvg_params *p, int64_t n_tokens, const void *x, int6
     UpdateArgs u{};
     u.x = static_cast<const bf16_t *>(x); u.stride_head = stride_head; u.stride_token = stride_token;
     u.n_tokens = n_tokens; u.ids = ids; u.ids_stride = n_tokens; u.ids_step = 1; u.ids_off = 0;
+    u.id_wide = id_wide(p);
     u.cent_prev = static_cast<const bf16_t *>(cent_prev);
     u.cent_out = static_cast<bf16_t *>(cent_out); u.counts_out = counts_out;
     u.perm = reinterpret_cast<int32_t *>(ws + w.perm); u.offsets = reinterpret_cast<int32_t *>(ws + w.offs);
@@ -202,7 +209,7 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
     if (n_tokens == 0) return copy_out(init_centroids);
     if (!x || !ids_out || !codes_out || !scales_out) return QVG_ERR_NULL;
     if ((st = check_view(x, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
-    if (!aligned16(codes_out) || !scales_aligned(p, scales_out)) return QVG_ERR_ALIGN;
+    if (!aligned16(codes_out) || !scales_aligned(p, scales_out) || !ids_aligned(p, ids_out)) return QVG_ERR_ALIGN;
     const int I = p->kmeans_iters;
     const int fmt = format_of(p);
     const int S = p->n_smooth_stages;
@@ -222,7 +229,7 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
         a.x = xin; a.stride_head = sh; a.stride_token = stt;
         a.n_tokens = n_tokens; a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size;
         a.T = p->n_stages; a.ids = ids_out; a.out_stride = out_stride_head_tokens; a.fused = 0;
-        a.ids_step = S; a.ids_off = stage; a.nh3 = nh3; a.cmax = cmax;
+        a.ids_step = S; a.ids_off = stage; a.nh3 = nh3; a.cmax = cmax; a.id_wide = id_wide(p);
         bf16_t *buf[2] = {reinterpret_cast<bf16_t *>(ws + w.cent[0]), reinterpret_cast<bf16_t *>(ws + w.cent[1])};
         if (S > 1) {
             // the kernels want a dense [H][K][d] table; the caller's start tables are [H][S][K][d]
@@ -235,7 +242,7 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
             UpdateArgs u{};
             u.x = a.x; u.stride_head = sh; u.stride_token = stt; u.n_tokens = n_tokens;
             u.ids = ids_out; u.ids_stride = out_stride_head_tokens; u.ids_step = S; u.ids_off = stage;
-            u.counts_out = nullptr;
+            u.counts_out = nullptr; u.id_wide = id_wide(p);
             u.perm = reinterpret_cast<int32_t *>(ws + w.perm); u.offsets = reinterpret_cast<int32_t *>(ws + w.offs);
             u.H = p->n_heads; u.K = p->n_clusters;
             for (int it = 0; it < I; ++it) {
@@ -260,6 +267,7 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
             r.x = xin; r.stride_head = sh; r.stride_token = stt; r.n_tokens = n_tokens;
             r.cent = cur; r.ids = ids_out; r.ids_stride = out_stride_head_tokens; r.ids_step = S; r.ids_off = stage;
             r.out = reinterpret_cast<bf16_t *>(ws + w.resid[stage & 1]); r.H = p->n_heads; r.K = p->n_clusters;
+            r.id_wide = id_wide(p);
             if (launch_residual(r, s) != hipSuccess) return QVG_ERR_LAUNCH;
             xin = r.out; sh = n_tokens * kHeadDim; stt = kHeadDim;
         } else if (fmt == 0) {
@@ -273,7 +281,7 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
             q.x = xin; q.stride_head = sh; q.stride_token = stt; q.n_tokens = n_tokens; q.cent = cur;
             q.ids = ids_out; q.ids_step = S; q.ids_off = stage; q.codes = codes_out; q.scales = scales_out;
             q.out_stride = out_stride_head_tokens; q.H = p->n_heads; q.K = p->n_clusters; q.B = p->group_size;
-            q.T = p->n_stages; q.fmt = fmt;
+            q.T = p->n_stages; q.fmt = fmt; q.id_wide = id_wide(p);
             if (launch_quantize(q, s) != hipSuccess) return QVG_ERR_LAUNCH;
         }
     }
@@ -302,14 +310,15 @@ int qvg_decode_ex(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, int6
     if (n_tokens == 0) return QVG_OK;
     if (!centroids || !ids || !codes || !scales || !x_out) return QVG_ERR_NULL;
     if ((st = check_view(x_out, stride_head, stride_token, n_tokens)) != QVG_OK) return st;
-    if (!aligned16(centroids) || !aligned16(codes) || !scales_aligned(p, scales)) return QVG_ERR_ALIGN;
+    if (!aligned16(centroids) || !aligned16(codes) || !scales_aligned(p, scales) || !ids_aligned(p, ids)) return QVG_ERR_ALIGN;
     const int64_t n_chunks = (n_tokens + chunk_len - 1) / chunk_len;
     if (n_chunks > 0x7fffffff) return QVG_ERR_BAD_PARAM;
     DecodeArgs a{};
     // the range starts on a chunk boundary: move the unit-0 pointers to it, keep the unit strides
     const int64_t S_ = p->n_smooth_stages, T_ = p->n_stages, G_ = p->head_dim / p->group_size;
     a.cent = static_cast<const bf16_t *>(centroids) + (first_token / chunk_len) * S_ * p->n_clusters * kHeadDim;
-    a.ids = ids + first_token * S_;
+    a.ids = ids + first_token * S_ * (id_wide(p) ? 2 : 1);
+    a.id_wide = id_wide(p);
     a.codes = codes + first_token * T_ * (kHeadDim * p->bits / 8);
     a.scales = reinterpret_cast<const f16_t *>(static_cast<const uint8_t *>(scales) +
                                                first_token * T_ * G_ * (p->scale_format == QVG_SCALE_E4M3 ? 1 : 2));
@@ -383,6 +392,8 @@ int qvg_attn_decode_ex(const qvg_params *p, int64_t n_q, const void *q, int64_t 
     a.S = p->n_smooth_stages; a.fmt = format_of(p);
     a.kv_stride = kv_capacity_tokens; a.chunk_stride = (int)cap_chunks;
     a.rope = static_cast<const f16_t *>(k_rope);
+    a.id_wide = id_wide(p);
+    if (!ids_aligned(p, k_ids) || !ids_aligned(p, v_ids)) return QVG_ERR_ALIGN;
     return launch_attn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
 }
 

@@ -94,15 +94,19 @@ struct Raw {                       // what one thread loads for its 2 tokens x 8
 
 // ids of this thread's two tokens of a tile (0 for tokens past the chunk end / an invalid tile);
 // with S smoothing stages a token has S id bytes, stage s in byte s of the result
+// (ids of 16 bits, for tables of more than 256 rows, come with one stage only)
 __device__ __forceinline__ void load_ids(const CacheSide &s, const Tile &t, int tp, uint32_t kmax, int S,
-                                         uint32_t id[2]) {
+                                         int wide, uint32_t id[2]) {
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
         const int n = t.t0 + 2 * tp + e;
         id[e] = 0u;
-        if (t.valid && n < t.cend)
-            for (int st = 0; st < S; ++st)
-                id[e] |= min((uint32_t)s.ids[(int64_t)n * S + st], kmax) << (8 * st);
+        if (t.valid && n < t.cend) {
+            if (wide) id[e] = min(load_id(s.ids, n, 1), kmax);
+            else
+                for (int st = 0; st < S; ++st)
+                    id[e] |= min((uint32_t)s.ids[(int64_t)n * S + st], kmax) << (8 * st);
+        }
     }
 }
 
@@ -255,10 +259,10 @@ void attn_kernel_direct(AttnArgs a) {
 
     CacheSide ks, vs;
     constexpr int kCodeBytes = (FMT & kFmtInt4) ? 64 : 32, kScaleBytes = (FMT & kFmtE4M3) ? 1 : 2;
-    ks.ids = a.k_ids + (int64_t)h * a.kv_stride * S;  ks.codes = a.k_codes + (int64_t)h * a.kv_stride * T * kCodeBytes;
+    ks.ids = a.k_ids + (int64_t)h * a.kv_stride * S * (a.id_wide ? 2 : 1);  ks.codes = a.k_codes + (int64_t)h * a.kv_stride * T * kCodeBytes;
     ks.scales = reinterpret_cast<const uint8_t *>(a.k_scales) + (int64_t)h * a.kv_stride * T * G * kScaleBytes;
     ks.cent = a.k_cent + (int64_t)h * a.chunk_stride * S * K * kHeadDim;
-    vs.ids = a.v_ids + (int64_t)h * a.kv_stride * S;  vs.codes = a.v_codes + (int64_t)h * a.kv_stride * T * kCodeBytes;
+    vs.ids = a.v_ids + (int64_t)h * a.kv_stride * S * (a.id_wide ? 2 : 1);  vs.codes = a.v_codes + (int64_t)h * a.kv_stride * T * kCodeBytes;
     vs.scales = reinterpret_cast<const uint8_t *>(a.v_scales) + (int64_t)h * a.kv_stride * T * G * kScaleBytes;
     vs.cent = a.v_cent + (int64_t)h * a.chunk_stride * S * K * kHeadDim;
 
@@ -319,13 +323,13 @@ void attn_kernel_direct(AttnArgs a) {
     Tile nn = nxt.valid ? next_tile(a, nxt) : nxt;
     uint32_t idk[2], idv[2];
     Raw<TM, SM> rk, rv;
-    load_ids(ks, cur, tp, kmax, S, idk);
-    load_ids(vs, cur, tp, kmax, S, idv);
+    load_ids(ks, cur, tp, kmax, S, a.id_wide, idk);
+    load_ids(vs, cur, tp, kmax, S, a.id_wide, idv);
     load_raw<T_, TM, SM, FMT>(ks, cur, tp, c8, T, G, g, K, S, idk, rk);
     load_raw<T_, TM, SM, FMT>(vs, cur, tp, c8, T, G, g, K, S, idv, rv);
     if (ROPE) load_rope(a.rope, cur, tp, c8, rp);
-    load_ids(ks, nxt, tp, kmax, S, idk);
-    load_ids(vs, nxt, tp, kmax, S, idv);
+    load_ids(ks, nxt, tp, kmax, S, a.id_wide, idk);
+    load_ids(vs, nxt, tp, kmax, S, a.id_wide, idv);
     decode_to_lds(rk, rv, 0);
     __syncthreads();
 
@@ -336,8 +340,8 @@ void attn_kernel_direct(AttnArgs a) {
             load_raw<T_, TM, SM, FMT>(ks, nxt, tp, c8, T, G, g, K, S, idk, rk);
             load_raw<T_, TM, SM, FMT>(vs, nxt, tp, c8, T, G, g, K, S, idv, rv);
             if (ROPE) load_rope(a.rope, nxt, tp, c8, rp);
-            load_ids(ks, nn, tp, kmax, S, idk);
-            load_ids(vs, nn, tp, kmax, S, idv);
+            load_ids(ks, nn, tp, kmax, S, a.id_wide, idk);
+            load_ids(vs, nn, tp, kmax, S, a.id_wide, idv);
         }
         const uint16_t *kt = Kt + buf * kKtElems;
         const uint16_t *vt = Vt + buf * kVtElems;
@@ -855,6 +859,14 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     // E4M3 scales on the staged kernel: a token's scale record must have an even number of bytes
     // (the tail handling moves two at a time) and every unit's scale array must start on a
     // 16-byte boundary
+    if (a.id_wide) {               // 16-bit ids (more than 256 centroids): the general kernel, one smoothing stage
+        switch (a.fmt) {
+            case 0: return launch_attn_t<0, 1>(a, s);
+            case kFmtE4M3: return launch_attn_fmt<kFmtE4M3>(a, s);
+            case kFmtInt4: return launch_attn_fmt<kFmtInt4>(a, s);
+            default: return launch_attn_fmt<kFmtInt4 | kFmtE4M3>(a, s);
+        }
+    }
     const bool fp8_staged = a.S == 1 && aligned && ((a.T * (kHeadDim / a.B)) & 1) == 0 &&
         ((reinterpret_cast<uintptr_t>(a.k_scales) | reinterpret_cast<uintptr_t>(a.v_scales)) & 15u) == 0 &&
         (a.H == 1 || (a.kv_stride * a.T * (kHeadDim / a.B)) % 16 == 0);

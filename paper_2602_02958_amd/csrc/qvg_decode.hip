@@ -45,7 +45,7 @@ constexpr int kXcds = 8;                         // MI355X: 8 XCDs, each with it
 template <int T_, bool CHECK, int SM, int FMT, int SC>
 __device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_t n_left, uint32_t lane16,
                                             uint32_t G, uint32_t gidx, uint32_t kmax,
-                                            const uint8_t *ids_b, const void *codes_v,
+                                            const uint8_t *ids_b, int id_wide, const void *codes_v,
                                             const void *scales_v, const bf16_t *tab, const bf16_t *cg,
                                             bf16_t *out_b, int64_t stride_token) {
     constexpr int TM = T_ > 0 ? T_ : kMaxStages;
@@ -70,7 +70,7 @@ __device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_
             for (int t = 0; t < TM; ++t) { code[u][t] = 0u; sc[u][t] = 0u; }
         }
         if (ok[u]) {
-            if (SM == 1) idv[u] = ids_b[ln];
+            if (SM == 1) idv[u] = load_id(ids_b, ln, id_wide);
             else {                                   // up to four id bytes of the token, stage s in byte s
                 idv[u] = 0u;
 #pragma unroll
@@ -212,7 +212,7 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
 
     // per-block base pointers (uniform), per-lane 32-bit offsets
     const int64_t hn0 = (int64_t)h * a.kv_stride + tok0;
-    const uint8_t *ids_b = a.ids + hn0 * S;
+    const uint8_t *ids_b = a.ids + hn0 * S * (a.id_wide ? 2 : 1);
     const void *codes_b = a.codes + hn0 * T * ((FMT & kFmtInt4) ? 64 : 32);
     const void *scales_b = reinterpret_cast<const uint8_t *>(a.scales) + hn0 * T * G * ((FMT & kFmtE4M3) ? 1 : 2);
     bf16_t *out_b = a.out + (int64_t)h * a.stride_head + tok0 * a.stride_token;
@@ -220,10 +220,10 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
 
     for (uint32_t first = 0; first < n_left; first += kDecTokPerIter) {
         if (first + kDecTokPerIter <= n_left)
-            decode_pass<T_, false, SM, FMT, SC>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
+            decode_pass<T_, false, SM, FMT, SC>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, a.id_wide, codes_b, scales_b,
                                        tab, cg, out_b, a.stride_token);
         else
-            decode_pass<T_, true, SM, FMT, SC>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
+            decode_pass<T_, true, SM, FMT, SC>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, a.id_wide, codes_b, scales_b,
                                       tab, cg, out_b, a.stride_token);
     }
 }

@@ -19,8 +19,8 @@
 // (cluster index carried in the 7 low mantissa bits) and certifies the winner only
 // when it leads by more than a bound on that error,
 //     thr = 2^-14 * (||x||^2 / 2 + max_j ||c_j||^2),
-// which covers the 131 accumulation roundings of one ulp each plus the index tag for both
-// scores.  Otherwise the candidates are re-evaluated in fp64: the two leaders
+// which covers the 131 accumulation roundings of half an ulp each plus the index tag for both
+// scores (with more than 256 centroids the tag has 8 bits and the factor is 1.5 * 2^-14).  Otherwise the candidates are re-evaluated in fp64: the two leaders
 // cooperatively by the wavefront, or, if the third score is inside the band as well,
 // all K centroids with the channels summed in index order (the reference order).
 // Equal fp64 distances go to the lower index.
@@ -32,7 +32,6 @@ constexpr int kAsgThreads = 256;
 constexpr int kAsgWaves = kAsgThreads / 64;
 constexpr int kAsgTile = 64;                    // tokens per wavefront step (two MFMA column blocks)
 constexpr int kCPitch = 136;                    // bf16 elements per LDS centroid row (272 B): 128 + (hi, mid, lo of -||c||^2/2) + 5 zeros
-constexpr uint32_t kTagMask = 0xFFFFFF80u;
 constexpr int kPrepThreads = 256;
 
 __device__ __forceinline__ void insert3(float v, int idx, float &b1, float &b2, float &b3,
@@ -234,7 +233,9 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
     const float cmax = norms_given ? a.cmax[h] : __uint_as_float(smax);
     bf16_t *scr = lscr + wave * kHeadDim;
     // token operand of the extra MFMA step: three ones against (hi, mid, lo), lanes 0..31 only
-    const uint32_t tagmask = vgpr_const(kTagMask);
+    // 7 tag bits name a row among 256; with more rows the tag takes 8 (and the band below widens)
+    const uint32_t tagbits = K > 256 ? 0xFFu : 0x7Fu;
+    const uint32_t tagmask = vgpr_const(~tagbits);
     // +inf kept in a register the compiler cannot see through: med3(a, b, +inf) then stays one
     // instruction (as a constant it is rewritten into max(a, b) plus a NaN-quieting copy)
     const float pinf = __uint_as_float(vgpr_const(0x7f800000u));
@@ -407,7 +408,7 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
         }
         // tag -> centroid index: row 8*(r/4) + 4*half + r%4 of block jb
         auto tag_to_idx = [&](float v) {
-            const uint32_t t = __float_as_uint(v) & 0x7Fu;
+            const uint32_t t = __float_as_uint(v) & tagbits;
             return (int)((t >> 4) * 32 + ((t >> 2) & 3) * 8 + half * 4 + (t & 3));
         };
 #pragma unroll
@@ -423,7 +424,7 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                 insert3(p2, q2, c1, c2, c3, i1, i2);
                 insert3(p3, 0, c1, c2, c3, i1, i2);
             }
-            const float thr = 0x1p-14f * (0.5f * xn[tb] + cmax);
+            const float thr = (K > 256 ? 0x1.8p-14f : 0x1p-14f) * (0.5f * xn[tb] + cmax);
             int id = i1;
             const bool amb = valid[tb] && (i2 < K) && !(c1 - c2 > thr);
             const bool full = !(c1 - c3 > thr);
@@ -483,7 +484,7 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             }
 
             const int64_t hn = (int64_t)h * a.out_stride + n[tb];
-            if (valid[tb] && half == 0) a.ids[hn * a.ids_step + a.ids_off] = (uint8_t)id;
+            if (valid[tb] && half == 0) store_id(a.ids, hn * a.ids_step + a.ids_off, a.id_wide, (uint32_t)id);
             if (!FUSED) continue;
 
             // ---- Eq. 5: residual against the assigned centroid, then the T rounds ----

@@ -13,6 +13,7 @@ constexpr int kHeadDim = 128;      // only head_dim the kernels are written for
 constexpr int kMaxStages = 8;
 constexpr int kMaxSmooth = 4;       // smoothing stages (k-means rounds on the residual)
 constexpr int kMaxTokensPerChunk = 1 << 20;
+constexpr int kMaxClusters = 512;   // up to 256: one id byte per token; beyond: two (one smoothing stage only)
 
 typedef uint16_t bf16_t;           // bit pattern of a bfloat16
 typedef uint16_t f16_t;            // bit pattern of an IEEE binary16
@@ -87,6 +88,15 @@ __device__ __forceinline__ void add_last_stage_of_two_rows(float *accA, float *a
     }
 }
 
+// ---- cluster ids: bytes, or 16-bit words when the table has more than 256 rows ("wide") ----
+__device__ __forceinline__ uint32_t load_id(const uint8_t *ids, int64_t i, int wide) {
+    return wide ? (uint32_t)reinterpret_cast<const uint16_t *>(ids)[i] : (uint32_t)ids[i];
+}
+__device__ __forceinline__ void store_id(uint8_t *ids, int64_t i, int wide, uint32_t id) {
+    if (wide) reinterpret_cast<uint16_t *>(ids)[i] = (uint16_t)id;
+    else ids[i] = (uint8_t)id;
+}
+
 // ---- stored formats ---------------------------------------------------------
 // fmt bit 0: scales are FP8 E4M3 bytes (else binary16); bit 1: 4-bit levels (else 2-bit)
 constexpr int kFmtE4M3 = 1;
@@ -129,6 +139,7 @@ struct DecodeArgs {
     int fmt;    // kFmt* bits; scales then points at bytes, codes rows are 64 B per round with 4-bit levels
     int64_t kv_stride;     // tokens between consecutive units in ids / codes / scales (>= n_tokens)
     int chunk_stride;      // chunk tables between consecutive units in cent (>= n_chunks)
+    int id_wide;           // ids are 16-bit words (K > 256, S == 1)
 };
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 
@@ -143,6 +154,7 @@ struct AssignArgs {
     uint2 *nh3; float *cmax; // scratch of assign_workspace_bytes(H, K): split -||c||^2/2 per row, max ||c||^2 per unit
     bf16_t *cent_copy; int64_t cent_copy_stride;   // optional: the table also goes here, unit h at h * stride elements
                                                    // (written by the unit's first workgroup while it stages the table)
+    int id_wide;             // ids are 16-bit words (K > 256)
 };
 // launches the centroid preparation and the assignment (fused with quantization when a.fused)
 hipError_t launch_assign(const AssignArgs &a, hipStream_t s);
@@ -156,6 +168,7 @@ struct UpdateArgs {
     const bf16_t *cent_prev; bf16_t *cent_out; int32_t *counts_out;
     int32_t *perm; int32_t *offsets;     // workspace: [H][N] and [H][K+1]
     int H; int K;
+    int id_wide;                         // ids are 16-bit words (K > 256)
 };
 hipError_t launch_update(const UpdateArgs &a, hipStream_t s);
 
@@ -164,7 +177,7 @@ hipError_t launch_update(const UpdateArgs &a, hipStream_t s);
 struct ResidualArgs {
     const bf16_t *x; int64_t stride_head, stride_token; int64_t n_tokens;
     const bf16_t *cent; const uint8_t *ids; int64_t ids_stride; int ids_step, ids_off;
-    bf16_t *out; int H; int K;
+    bf16_t *out; int H; int K; int id_wide;
 };
 hipError_t launch_residual(const ResidualArgs &a, hipStream_t s);
 
@@ -175,7 +188,7 @@ struct QuantArgs {
     const bf16_t *cent;                    // [H][K][d]
     const uint8_t *ids; int ids_step, ids_off;
     uint8_t *codes; void *scales; int64_t out_stride;     // tokens between units in ids / codes / scales
-    int H; int K; int B; int T; int fmt;
+    int H; int K; int B; int T; int fmt; int id_wide;
 };
 hipError_t launch_quantize(const QuantArgs &a, hipStream_t s);
 
@@ -189,6 +202,7 @@ struct AttnArgs {
     int64_t kv_stride;     // tokens between consecutive units in ids / codes / scales (>= n_kv)
     int chunk_stride;      // chunk tables between consecutive units in the centroid arrays (>= n_chunks)
     const f16_t *rope;     // [n_kv][d/2][2] (cos, sin) applied to the decoded keys, or nullptr
+    int id_wide;           // ids are 16-bit words (K > 256, S == 1)
 };
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
 

@@ -20,6 +20,7 @@ namespace qvg {
 constexpr int kRankThreads = 1024;
 constexpr int kRankWaves = kRankThreads / 64;      // the tokens of a unit are split into 16 ranges
 constexpr int kRankKeep = 8;                        // ids a lane keeps in registers between passes
+constexpr int kRankK = kMaxClusters;                // histogram width
 
 // Stable counting sort of token indices by cluster id, one workgroup per unit.
 // Wavefront w owns the w-th contiguous range of tokens: it histograms the range, and after
@@ -28,17 +29,19 @@ constexpr int kRankKeep = 8;                        // ids a lane keeps in regis
 // lane number (ballot-built peer masks), so equal ids keep their token order.
 __global__ __launch_bounds__(kRankThreads)
 void kmeans_rank_kernel(UpdateArgs a) {
-    __shared__ int cnt[kRankWaves][256];      // histogram per range, then running cursor
-    __shared__ int total[256];
+    __shared__ int cnt[kRankWaves][kRankK];   // histogram per range, then running cursor
+    __shared__ int total[kRankK];
     const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int K = a.K;
     const int64_t N = a.n_tokens;
-    const uint8_t *ids = a.ids + (int64_t)h * a.ids_stride * a.ids_step + a.ids_off;   // token n at ids[n * step]
+    const int wide = a.id_wide;
+    const int64_t id0 = (int64_t)h * a.ids_stride * a.ids_step + a.ids_off;   // token n at element id0 + n * step
     const int64_t step = a.ids_step;
+    auto id_of = [&](int64_t n) { return (int)load_id(a.ids, id0 + n * step, wide); };
     int32_t *perm = a.perm + (int64_t)h * N;
     int32_t *offs = a.offsets + (int64_t)h * (K + 1);
 
-    for (int i = tid; i < kRankWaves * 256; i += kRankThreads) (&cnt[0][0])[i] = 0;
+    for (int i = tid; i < kRankWaves * kRankK; i += kRankThreads) (&cnt[0][0])[i] = 0;
     __syncthreads();
     // range of this wavefront, a multiple of 64 tokens long
     const int64_t per = ((N + kRankWaves * 64 - 1) / (kRankWaves * 64)) * 64;
@@ -53,25 +56,26 @@ void kmeans_rank_kernel(UpdateArgs a) {
         for (int i = 0; i < kRankKeep; ++i) {
             const int64_t n = beg + (int64_t)i * 64 + lane;
             int id = -1;
-            if (i < steps && n < end) { id = ids[n * step]; if (id >= K) id = -1; }
+            if (i < steps && n < end) { id = id_of(n); if (id >= K) id = -1; }
             kept[i] = id;
         }
 #pragma unroll
         for (int i = 0; i < kRankKeep; ++i) if (kept[i] >= 0) atomicAdd(&cnt[w][kept[i]], 1);
     } else {
-        for (int64_t n = beg + lane; n < end; n += 64) { const int id = ids[n * step]; if (id < K) atomicAdd(&cnt[w][id], 1); }
+        for (int64_t n = beg + lane; n < end; n += 64) { const int id = id_of(n); if (id < K) atomicAdd(&cnt[w][id], 1); }
     }
     __syncthreads();
-    if (tid < 256) {
+    if (tid < kRankK) {
         int t = 0;
         for (int r = 0; r < kRankWaves; ++r) t += cnt[r][tid];
         total[tid] = (tid < K) ? t : 0;
     }
     __syncthreads();
-    if (tid < 64) {                       // exclusive scan of total[0..255] by one wavefront
-        int v[4], run = 0;
+    constexpr int kPerLane = kRankK / 64;
+    if (tid < 64) {                       // exclusive scan of total[0..kRankK-1] by one wavefront
+        int v[kPerLane], run = 0;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { v[i] = total[lane * 4 + i]; run += v[i]; }
+        for (int i = 0; i < kPerLane; ++i) { v[i] = total[lane * kPerLane + i]; run += v[i]; }
         int incl = run;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -80,10 +84,10 @@ void kmeans_rank_kernel(UpdateArgs a) {
         }
         int start = incl - run;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { total[lane * 4 + i] = start; start += v[i]; }
+        for (int i = 0; i < kPerLane; ++i) { total[lane * kPerLane + i] = start; start += v[i]; }
     }
     __syncthreads();
-    if (tid < 256) {
+    if (tid < kRankK) {
         // cursor of (range r, cluster tid) = start of the cluster + members in earlier ranges
         int run = total[tid], c = 0;
         for (int r = 0; r < kRankWaves; ++r) { const int t = cnt[r][tid]; cnt[r][tid] = run; run += t; c += t; }
@@ -96,7 +100,7 @@ void kmeans_rank_kernel(UpdateArgs a) {
     __syncthreads();
 
     int nxt = -1;
-    if (!keep && beg + lane < end) { nxt = ids[(beg + lane) * step]; if (nxt >= K) nxt = -1; }
+    if (!keep && beg + lane < end) { nxt = id_of(beg + lane); if (nxt >= K) nxt = -1; }
     for (int i = 0; i < steps; ++i) {
         const int64_t n = beg + (int64_t)i * 64 + lane;
         int id;
@@ -108,12 +112,12 @@ void kmeans_rank_kernel(UpdateArgs a) {
             id = nxt;
             const int64_t nn = n + 64;
             nxt = -1;
-            if (nn < end) { nxt = ids[nn * step]; if (nxt >= K) nxt = -1; }
+            if (nn < end) { nxt = id_of(nn); if (nxt >= K) nxt = -1; }
         }
         const bool valid = id >= 0;
         uint64_t peers = __ballot(valid);
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
+        for (int b = 0; b < 9; ++b) {
             const uint64_t m = __ballot((id >> b) & 1);
             peers &= ((id >> b) & 1) ? m : ~m;
         }
@@ -386,7 +390,7 @@ void residual_kernel(ResidualArgs a) {
     const int64_t n = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
     const int c8 = threadIdx.x & 15;
     if (n >= a.n_tokens) return;
-    int id = a.ids[((int64_t)h * a.ids_stride + n) * a.ids_step + a.ids_off];
+    int id = (int)load_id(a.ids, ((int64_t)h * a.ids_stride + n) * a.ids_step + a.ids_off, a.id_wide);
     if (id >= a.K) id = a.K - 1;
     const uint4 xv = *reinterpret_cast<const uint4 *>(a.x + (int64_t)h * a.stride_head + n * a.stride_token + c8 * 8);
     const uint4 cv = *reinterpret_cast<const uint4 *>(a.cent + ((int64_t)h * a.K + id) * kHeadDim + c8 * 8);

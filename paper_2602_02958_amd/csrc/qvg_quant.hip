@@ -39,7 +39,7 @@ void quantize_kernel(QuantArgs a, int passes) {
         for (int i = 0; i < 8; ++i) r[i] = 0.0f;
         const int64_t hn = (int64_t)h * a.out_stride + n;
         if (valid) {
-            const uint32_t id = min((uint32_t)a.ids[hn * a.ids_step + a.ids_off], kmax);
+            const uint32_t id = min(load_id(a.ids, hn * a.ids_step + a.ids_off, a.id_wide), kmax);
             const uint4 xv = *reinterpret_cast<const uint4 *>(a.x + (int64_t)h * a.stride_head + n * a.stride_token + lane16 * 8);
             const uint4 cv = *reinterpret_cast<const uint4 *>(cent + (int64_t)id * kHeadDim + lane16 * 8);
             const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w}, cw[4] = {cv.x, cv.y, cv.z, cv.w};

@@ -43,6 +43,9 @@ def test_compressed_bytes_matches_format():
     assert B.compressed_bytes(p, 1000) == 1000 * 35 + 256 * 256
     p = B.make_params(1, 256, 16, 1, bits=4, n_smooth_stages=4, scale_format=B.SCALE_E4M3)
     assert B.compressed_bytes(p, 1000) == 1000 * 76 + 4 * 256 * 256
+    # more than 256 centroids: two id bytes per token
+    p = B.make_params(1, 512, 64, 1, scale_format=B.SCALE_E4M3)
+    assert B.compressed_bytes(p, 1000) == 1000 * 36 + 512 * 256
 
 
 def test_params_struct_layout():
@@ -55,7 +58,8 @@ def test_params_struct_layout():
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(n_heads=0), -2), (dict(n_clusters=0), -2), (dict(n_clusters=257), -2),
+    (dict(n_heads=0), -2), (dict(n_clusters=0), -2), (dict(n_clusters=257), 0), (dict(n_clusters=512), 0),
+    (dict(n_clusters=513), -2), (dict(n_clusters=512, n_smooth_stages=2), -3),
     (dict(n_stages=0), -2), (dict(n_stages=9), -2), (dict(group_size=48), -2),
     (dict(head_dim=64), -3), (dict(bits=4), 0), (dict(bits=3), -2), (dict(bits=8), -2),
     (dict(scale_format=1), 0), (dict(scale_format=2), -2), (dict(scale_format=-1), -2),
@@ -124,6 +128,10 @@ def test_null_and_alignment_errors_are_reported_before_any_launch():
     assert L.qvg_attn_decode(C.byref(p), 0, None, 10, 10, None, None, None, None, None, None, None,
                              None, C.c_float(0.1), None, None, None, 0, None) == 0
     assert L.qvg_kmeans_assign(C.byref(p), 0, None, 0, 0, None, None, None, 0, None) == 0
+    # 16-bit ids (more than 256 centroids) must be 2-byte aligned
+    pw = B.make_params(2, 512, 64, 2)
+    assert L.qvg_decode(C.byref(pw), 10, 10, fake, C.c_void_p(0x1001), fake, fake, fake, 1280, 128, None) == -5
+    assert L.qvg_decode(C.byref(p), 10, 0, fake, C.c_void_p(0x1001), fake, fake, fake, 1280, 128, None) == -2
 
 
 def test_workspace_sizes():

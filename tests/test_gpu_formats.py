@@ -41,6 +41,8 @@ def _inputs(cfg, H, N, K, S=1):
     ("cfg1_tiny", 1, 300, 16, 128, 3, 2, 1, 4, F16),
     ("cfg3_dit_small", 2, 1000, 256, 16, 1, 4, 1, 4, E4M3),   # QVG-Pro INT4
     ("cfg1_tiny", 2, 17, 16, 64, 8, 1, 1, 4, E4M3),           # fewer tokens than a pass, 8 rounds
+    ("cfg3_dit_small", 2, 1200, 512, 64, 1, 1, 2, 2, E4M3),   # the codebook-size study's K = 512: 16-bit ids
+    ("cfg3_dit_small", 2, 1200, 512, 64, 1, 1, 2, 4, E4M3),
 ])
 def test_encode_decode_in_other_formats(cfg, H, N, K, Bg, T, S, I, bits, fmt):
     x, init = _inputs(cfg, H, N, K, S)
@@ -58,7 +60,8 @@ def test_encode_decode_in_other_formats(cfg, H, N, K, Bg, T, S, I, bits, fmt):
     want = O.decode_batch(ref["cent"], ref["ids"], ref["codes"], ref["scales"], Bg, bits=bits, scale_fmt=fmt)
     assert np.array_equal(P.to_np_u16(dec), want)
     assert B.compressed_bytes(B.make_params(H, K, Bg, T, I, n_smooth_stages=S, bits=bits, scale_format=fmt), N) == \
-        enc.codes.numel() + enc.scales.numel() * enc.scales.element_size() + enc.ids.numel() + enc.centroids.numel() * 2
+        enc.codes.numel() + enc.scales.numel() * enc.scales.element_size() + enc.ids.numel() * enc.ids.element_size() + \
+        enc.centroids.numel() * 2
 
 
 def test_e4m3_scale_of_every_bf16_magnitude():

@@ -30,12 +30,18 @@ def _oracle_cache(x, init, K, Bg, T, iters):
     return dict(cent=enc["cent"][:, 0], ids=enc["ids"][:, 0], codes=enc["codes"], scales=enc["scales"])
 
 
+def _ids_tensor(ids):
+    """oracle ids -> tensor of the binding's id type (uint8, or int16 beyond 256 centroids)"""
+    ids = np.ascontiguousarray(ids)
+    return torch.from_numpy(ids.view(np.int16).copy() if ids.dtype == np.uint16 else ids.copy())
+
+
 def _to_encoded(oc, chunk_len=None):
     H, N = oc["ids"].shape
     cent = oc["cent"] if oc["cent"].ndim == 4 else oc["cent"][:, None]
     return B.Encoded(
         torch.from_numpy(cent.view(np.int16).copy()).view(torch.bfloat16).to(DEV),
-        torch.from_numpy(oc["ids"].copy()).to(DEV),
+        _ids_tensor(oc["ids"]).to(DEV),
         torch.from_numpy(oc["codes"].copy()).to(DEV),
         torch.from_numpy(oc["scales"].view(np.int16).copy()).view(torch.float16).to(DEV),
         chunk_len or max(N, 1))
@@ -43,7 +49,8 @@ def _to_encoded(oc, chunk_len=None):
 
 # ------------------------------------------------------------------ decode
 @pytest.mark.parametrize("N,K,Bg,T", [(4096, 16, 64, 2), (1000, 64, 32, 3), (333, 256, 64, 4),
-                                      (65, 7, 16, 1), (1, 1, 128, 2), (700, 33, 128, 5)])
+                                      (65, 7, 16, 1), (1, 1, 128, 2), (700, 33, 128, 5),
+                                      (900, 512, 64, 2), (300, 300, 32, 3)])      # 16-bit ids
 def test_decode_bit_exact(N, K, Bg, T):
     x, init = _inputs("cfg2_window21", 3, N, K)
     oc = _oracle_cache(x, init, K, Bg, T, iters=1)
@@ -82,7 +89,8 @@ def test_decode_multi_chunk_strided_output():
 @pytest.mark.parametrize("cfg,N,K", [("cfg1_tiny", 4096, 16), ("cfg2_window21", 1500, 64),
                                      ("cfg3_dit_small", 2000, 256), ("cfg4_dit_large", 777, 128),
                                      ("cfg2_window21", 31, 5), ("cfg2_window21", 20, 64),
-                                     ("cfg2_window21", 3000, 5), ("cfg1_tiny", 1200, 1), ("cfg1_tiny", 900, 3)])
+                                     ("cfg2_window21", 3000, 5), ("cfg1_tiny", 1200, 1), ("cfg1_tiny", 900, 3),
+                                     ("cfg3_dit_small", 2000, 512), ("cfg3_dit_small", 700, 300)])   # 16-bit ids
 def test_kmeans_steps_match_oracle(cfg, N, K):
     """Step parity: the oracle's state after each iteration is fed to the GPU assign and update."""
     H = 2
@@ -102,7 +110,7 @@ def test_kmeans_steps_match_oracle(cfg, N, K):
             c_o, n_o = O.update(r, ids_o, cur[h])
             nxt[h] = c_o
         # update from the ORACLE's ids so that the two steps are checked independently
-        ids_od = torch.from_numpy(np.stack([O.assign(bits_to_f32(xb[h]), cur[h]) for h in range(H)])).to(DEV)
+        ids_od = _ids_tensor(np.stack([O.assign(bits_to_f32(xb[h]), cur[h]) for h in range(H)])).to(DEV)
         c_g, n_g = B.kmeans_update(xd, ids_od, cd)
         torch.cuda.synchronize()
         assert np.array_equal(P.to_np_u16(c_g), nxt), f"centroids differ at iteration {it}"
@@ -133,7 +141,8 @@ def test_assign_forced_ties_and_duplicates():
 @pytest.mark.parametrize("cfg,N,K,Bg,T", [("cfg1_tiny", 4096, 16, 64, 2), ("cfg2_window21", 2000, 64, 32, 3),
                                           ("cfg3_dit_small", 1111, 256, 64, 2), ("cfg4_dit_large", 900, 128, 32, 3),
                                           ("cfg5_long", 513, 256, 64, 4), ("cfg2_window21", 257, 20, 16, 1),
-                                          ("cfg2_window21", 300, 9, 128, 2), ("cfg3_dit_small", 40, 64, 64, 6)])
+                                          ("cfg2_window21", 300, 9, 128, 2), ("cfg3_dit_small", 40, 64, 64, 6),
+                                          ("cfg3_dit_small", 1111, 512, 64, 2), ("cfg5_long", 600, 384, 32, 3)])
 def test_encode_single_pass_matches_oracle(cfg, N, K, Bg, T):
     """I = 0: assignment against given centroids, residual, T quantization rounds, packing."""
     H = 3
@@ -190,7 +199,8 @@ def test_update_long_lists_exact_and_rounding_cases():
 
 
 @pytest.mark.parametrize("cfg,N,K,Bg,T,I", [("cfg1_tiny", 4096, 16, 64, 2, 10), ("cfg2_window21", 3000, 64, 32, 3, 3),
-                                            ("cfg3_dit_small", 2500, 256, 64, 2, 4)])
+                                            ("cfg3_dit_small", 2500, 256, 64, 2, 4),
+                                            ("cfg3_dit_small", 2500, 512, 64, 2, 3)])       # 16-bit ids
 def test_encode_with_lloyd_end_to_end(cfg, N, K, Bg, T, I):
     """Full encode against the full oracle from the same start.  The stored ids and codes must be
     the oracle's for the GPU's own final centroids (self-consistency); the centroids themselves
@@ -316,6 +326,7 @@ def _attn_case(cfg, H, Nq, Ns, L, K, Bg, T, scale=None):
     ("cfg5_long", 1, 33, [64, 64, 1], 64, 256, 64, 4),
     ("cfg4_dit_large", 1, 70, [500], 500, 128, 16, 1),
     ("cfg2_window21", 1, 5, [100], 100, 8, 128, 5),
+    ("cfg3_dit_small", 2, 129, [600, 257], 600, 512, 64, 2),      # 16-bit ids
 ])
 def test_attention_matches_oracle(cfg, H, Nq, Ns, L, K, Bg, T):
     _attn_case(cfg, H, Nq, Ns, L, K, Bg, T)
