@@ -454,11 +454,13 @@ constexpr int kStCodes = kAtKv * kStMaxT * 32;            // bytes of one side's
 constexpr int kStScales = kAtKv * kStMaxT * kStMaxG * 2;  // bytes of one side's scales
 constexpr int kStBytes = 2 * kStCodes + 2 * kStScales;   // K and V: codes, scales
 constexpr size_t kAtSmemStaged = (size_t)2 * (kKtElems + kVtElems) * sizeof(uint16_t) + 2 * kStBytes + 4 * 2 * kAtKv;
+constexpr size_t kAtSmemStagedWide = kAtSmemStaged + 4 * 2 * kAtKv;      // the id ring holds 16-bit words
 
 template <bool V> struct BoolC { static constexpr bool value = V; };
 
-template <int T_, bool ROPE, bool FP8, bool I4>   // ROPE: rotate the decoded keys by a.rope; FP8: E4M3 scale bytes;
-                                                  // I4: 4-bit levels (64 code bytes per token and round, T_ <= 2)
+template <int T_, bool ROPE, bool FP8, bool I4, bool WIDE>   // ROPE: rotate the decoded keys by a.rope; FP8: E4M3 scale bytes;
+                                                  // I4: 4-bit levels (64 code bytes per token and round, T_ <= 2);
+                                                  // WIDE: 16-bit ids (more than 256 centroids)
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_xcd) {
     constexpr int T = T_;
@@ -468,7 +470,8 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     uint16_t *Kt = reinterpret_cast<uint16_t *>(smem);                  // [2][64][136] bf16
     uint16_t *Vt = Kt + 2 * kKtElems;                                   // [2][128][72] f16, transposed
     unsigned char *stage = reinterpret_cast<unsigned char *>(Vt + 2 * kVtElems);   // [2][kStBytes]
-    unsigned char *idring = stage + 2 * kStBytes;                       // [4][2][64]: ids run one tile further ahead
+    typedef typename std::conditional<WIDE, uint16_t, unsigned char>::type id_t;
+    id_t *idring = reinterpret_cast<id_t *>(stage + 2 * kStBytes);      // [4][2][64]: ids run one tile further ahead
 
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id; re-number them so that
     // the query blocks of one unit run on one XCD (two at a boundary) and the unit's compressed
@@ -487,7 +490,8 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     const int G = kHeadDim / B;
     const uint32_t kmax = (uint32_t)K - 1u;
 
-    const uint8_t *k_ids = a.k_ids + (int64_t)h * a.kv_stride, *v_ids = a.v_ids + (int64_t)h * a.kv_stride;
+    const id_t *k_ids = reinterpret_cast<const id_t *>(a.k_ids) + (int64_t)h * a.kv_stride;
+    const id_t *v_ids = reinterpret_cast<const id_t *>(a.v_ids) + (int64_t)h * a.kv_stride;
     const uint8_t *k_codes = a.k_codes + (int64_t)h * a.kv_stride * T * CB, *v_codes = a.v_codes + (int64_t)h * a.kv_stride * T * CB;
     constexpr int SZ = FP8 ? 1 : 2;                                     // bytes of a stored scale
     const unsigned char *k_scales = reinterpret_cast<const unsigned char *>(a.k_scales) + (int64_t)h * a.kv_stride * T * G * SZ;
@@ -579,7 +583,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         }
     };
     auto park_ids = [&](const Fetch &f, int ordinal) {
-        if (tid < 2 * kAtKv) idring[(ordinal & 3) * 2 * kAtKv + tid] = (unsigned char)f.id;
+        if (tid < 2 * kAtKv) idring[(ordinal & 3) * 2 * kAtKv + tid] = (id_t)f.id;
     };
     auto park_tile = [&](const Fetch &f, int sb) {
         unsigned char *st = stage + sb * kStBytes;
@@ -603,7 +607,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     uint4 rp[2];                      // ROPE: (cos, sin) pairs of the tile whose rows are in cen
     auto gather_rows = [&](const Tile &t, int ordinal, uint4 cen[2][2]) {
         if (ROPE) load_rope(a.rope, t, tp, c8, rp);
-        const unsigned char *st = idring + (ordinal & 3) * 2 * kAtKv;
+        const id_t *st = idring + (ordinal & 3) * 2 * kAtKv;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const bf16_t *cent = (s ? v_cent : k_cent) + (int64_t)t.chunk * K * kHeadDim + c8 * 8;
@@ -800,12 +804,13 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     }
 }
 
-template <int T_, bool ROPE, bool FP8, bool I4>
+template <int T_, bool ROPE, bool FP8, bool I4, bool WIDE>
 static hipError_t launch_attn_staged_r(const AttnArgs &a, hipStream_t s) {
+    constexpr size_t kSmem = WIDE ? kAtSmemStagedWide : kAtSmemStaged;
     static bool configured = false;          // the attribute is per function, set once per process
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE, FP8, I4>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmemStaged);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE, FP8, I4, WIDE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmem);
         if (e != hipSuccess) return e;
         configured = true;
     }
@@ -813,13 +818,13 @@ static hipError_t launch_attn_staged_r(const AttnArgs &a, hipStream_t s) {
     const int64_t nb = nqb * a.H;
     if (nb > 0x7fffffff - 8) return hipErrorInvalidValue;
     const int bpx = (int)((nb + 7) / 8);
-    hipLaunchKernelGGL((attn_kernel_staged<T_, ROPE, FP8, I4>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmemStaged, s, a,
+    hipLaunchKernelGGL((attn_kernel_staged<T_, ROPE, FP8, I4, WIDE>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kSmem, s, a,
                        (int)nqb, (int)nb, bpx);
     return hipGetLastError();
 }
-template <int T_, bool FP8 = false, bool I4 = false>
+template <int T_, bool FP8 = false, bool I4 = false, bool WIDE = false>
 static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
-    return a.rope ? launch_attn_staged_r<T_, true, FP8, I4>(a, s) : launch_attn_staged_r<T_, false, FP8, I4>(a, s);
+    return a.rope ? launch_attn_staged_r<T_, true, FP8, I4, WIDE>(a, s) : launch_attn_staged_r<T_, false, FP8, I4, WIDE>(a, s);
 }
 
 template <int T_, int SM, int FMT, bool ROPE>
@@ -859,7 +864,13 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     // E4M3 scales on the staged kernel: a token's scale record must have an even number of bytes
     // (the tail handling moves two at a time) and every unit's scale array must start on a
     // 16-byte boundary
-    if (a.id_wide) {               // 16-bit ids (more than 256 centroids): the general kernel, one smoothing stage
+    const bool fp8_staged_any = a.S == 1 && aligned && ((a.T * (kHeadDim / a.B)) & 1) == 0 &&
+        ((reinterpret_cast<uintptr_t>(a.k_scales) | reinterpret_cast<uintptr_t>(a.v_scales)) & 15u) == 0 &&
+        (a.H == 1 || (a.kv_stride * a.T * (kHeadDim / a.B)) % 16 == 0);
+    if (a.id_wide) {
+        // 16-bit ids (more than 256 centroids): the form of the paper's codebook-size study (2-bit
+        // levels, E4M3 scales, one round) has a staged instance, everything else runs on the general kernel
+        if (a.fmt == kFmtE4M3 && fp8_staged_any && a.T == 1) return launch_attn_staged<1, true, false, true>(a, s);
         switch (a.fmt) {
             case 0: return launch_attn_t<0, 1>(a, s);
             case kFmtE4M3: return launch_attn_fmt<kFmtE4M3>(a, s);
@@ -867,9 +878,7 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
             default: return launch_attn_fmt<kFmtInt4 | kFmtE4M3>(a, s);
         }
     }
-    const bool fp8_staged = a.S == 1 && aligned && ((a.T * (kHeadDim / a.B)) & 1) == 0 &&
-        ((reinterpret_cast<uintptr_t>(a.k_scales) | reinterpret_cast<uintptr_t>(a.v_scales)) & 15u) == 0 &&
-        (a.H == 1 || (a.kv_stride * a.T * (kHeadDim / a.B)) % 16 == 0);
+    const bool fp8_staged = fp8_staged_any;
     switch (a.fmt) {
         case 0: break;
         case kFmtE4M3:
