@@ -73,12 +73,9 @@ def cpu_baseline(wl, budget_s=12.0):
     t0 = time.perf_counter()
     enc = O.encode_batch(xb, ib, wl.n_clusters, wl.group_size, wl.n_stages, wl.kmeans_iters_warm)
     t_enc = time.perf_counter() - t0
-    cent = np.repeat(enc["cent"], n_chunks, axis=1)
-    ids = np.tile(enc["ids"].reshape(units, 1, n_enc), (1, n_chunks, 1))
-    codes = np.tile(enc["codes"], (1, n_chunks, 1, 1))
-    scales = np.tile(enc["scales"], (1, n_chunks, 1, 1))
     t0 = time.perf_counter()
-    dec = O.decode_batch(cent, ids, codes, scales, wl.group_size)
+    dec = np.concatenate([O.decode_batch(enc["cent"], enc["ids"], enc["codes"], enc["scales"], wl.group_size)
+                          for _ in range(n_chunks)], 1)           # chunk by chunk, each with its own table
     t_dec = time.perf_counter() - t0
     n_tok = dec.shape[1]
     qall = synth.queries(wl, heads, wl.n_queries).view(torch.int16).numpy().view(np.uint16)

@@ -270,6 +270,7 @@ def decode_unit(cent, ids, codes, scales, B, bits=2, want_f32=False, scale_fmt=0
         ids = ids[None]
     S, K, d = cent.shape
     N, T = codes.shape[0], codes.shape[1]
+    assert ids.shape == (S, N) and scales.shape[:2] == (N, T), (cent.shape, ids.shape, codes.shape, scales.shape)
     out = np.empty((N, d), np.uint16)
     f32 = np.empty((N, d), np.float32) if want_f32 else None
     lib().qvgo_decode_unit(C.c_int64(N), d, K, B, S, T, bits, scale_fmt, _p(cent, np.uint16),
@@ -334,6 +335,8 @@ def decode_batch(cent, ids, codes, scales, B, bits=2, scale_fmt=0):
     codes = _c(codes, np.uint8); scales = _c(scales, np.uint16)
     H, S, K, d = cent.shape
     N, T = codes.shape[1], codes.shape[2]
+    assert ids.shape == (H, S, N) and codes.shape[0] == H and scales.shape[:3] == (H, N, T), \
+        (cent.shape, ids.shape, codes.shape, scales.shape)
     out = np.empty((H, N, d), np.uint16)
     lib().qvgo_decode_batch(H, C.c_int64(N), d, K, B, S, T, bits, scale_fmt, _p(cent, np.uint16),
                             _p(ids, np.uint16), _p(codes, np.uint8), _p(scales, np.uint16),
