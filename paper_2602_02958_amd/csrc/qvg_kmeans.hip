@@ -41,7 +41,8 @@ void kmeans_rank_kernel(UpdateArgs a) {
     int32_t *perm = a.perm + (int64_t)h * N;
     int32_t *offs = a.offsets + (int64_t)h * (K + 1);
 
-    for (int i = tid; i < kRankWaves * kRankK; i += kRankThreads) (&cnt[0][0])[i] = 0;
+    const int Kp = (K + 63) & ~63;            // only the first Kp columns of the histograms are used
+    for (int k = lane; k < Kp; k += 64) cnt[w][k] = 0;
     __syncthreads();
     // range of this wavefront, a multiple of 64 tokens long
     const int64_t per = ((N + kRankWaves * 64 - 1) / (kRankWaves * 64)) * 64;
@@ -67,8 +68,8 @@ void kmeans_rank_kernel(UpdateArgs a) {
     __syncthreads();
     if (tid < kRankK) {
         int t = 0;
-        for (int r = 0; r < kRankWaves; ++r) t += cnt[r][tid];
-        total[tid] = (tid < K) ? t : 0;
+        if (tid < K) for (int r = 0; r < kRankWaves; ++r) t += cnt[r][tid];
+        total[tid] = t;
     }
     __syncthreads();
     constexpr int kPerLane = kRankK / 64;
@@ -87,7 +88,7 @@ void kmeans_rank_kernel(UpdateArgs a) {
         for (int i = 0; i < kPerLane; ++i) { total[lane * kPerLane + i] = start; start += v[i]; }
     }
     __syncthreads();
-    if (tid < kRankK) {
+    if (tid < Kp) {
         // cursor of (range r, cluster tid) = start of the cluster + members in earlier ranges
         int run = total[tid], c = 0;
         for (int r = 0; r < kRankWaves; ++r) { const int t = cnt[r][tid]; cnt[r][tid] = run; run += t; c += t; }
@@ -118,6 +119,7 @@ void kmeans_rank_kernel(UpdateArgs a) {
         uint64_t peers = __ballot(valid);
 #pragma unroll
         for (int b = 0; b < 9; ++b) {
+            if (b == 8 && K <= 256) break;                          // uniform: the ninth bit only with 16-bit ids
             const uint64_t m = __ballot((id >> b) & 1);
             peers &= ((id >> b) & 1) ? m : ~m;
         }
