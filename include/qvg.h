@@ -203,6 +203,27 @@ int qvg_attn_decode_ex(const qvg_params *p, int64_t n_q, const void *q_bf16,
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * qvg_attn_decode_ex with a prefix length per query: query i (of every unit) sees the cached
+ * tokens 0 .. q_kv_len[i]-1 only.  With lengths that are multiples of chunk_len this is the
+ * chunk-causal order of Sec. 3.1 for the queries of SEVERAL chunks in one call (each chunk
+ * attends to the chunks before it; its own keys are not in the compressed cache: see
+ * qvg_attn_merge).
+ *   q_kv_len   [n_q] int32, device; values are clamped to 1 .. n_kv_tokens.  NULL = every query
+ *              sees all n_kv_tokens tokens (the call is then qvg_attn_decode_ex).
+ * A workgroup stops at the longest prefix among its 256 queries, so queries sorted by length
+ * cost what their prefixes cost.  Runs on the general attention kernel.
+ */
+int qvg_attn_decode_causal(const qvg_params *p, int64_t n_q, const void *q_bf16,
+                           int64_t n_kv_tokens, int64_t chunk_len, int64_t kv_capacity_tokens,
+                           const void *k_centroids, const uint8_t *k_ids, const uint8_t *k_codes,
+                           const void *k_scales,
+                           const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
+                           const void *v_scales,
+                           const void *k_rope_f16, const int32_t *q_kv_len,
+                           float softmax_scale, void *out_bf16, float *lse_out,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Merge two attention results over DISJOINT key sets (the compressed cache, from
  * qvg_attn_decode with lse_out, and the current chunk's own bf16 keys, from the model's
  * attention kernel) into the attention over their union (Sec. 3.1):

@@ -20,7 +20,8 @@ _lib = None
 ENTRY_ENCODE, ENTRY_DECODE, ENTRY_ATTN, ENTRY_KMEANS_UPDATE, ENTRY_KMEANS_ASSIGN = 0, 1, 2, 3, 4
 SCALE_F16, SCALE_E4M3 = 0, 1
 
-EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_decode_ex", "qvg_attn_decode", "qvg_attn_decode_ex", "qvg_attn_merge",
+EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_decode_ex", "qvg_attn_decode", "qvg_attn_decode_ex",
+           "qvg_attn_decode_causal", "qvg_attn_merge",
            "qvg_kmeans_assign",
            "qvg_kmeans_update", "qvg_workspace_bytes", "qvg_compressed_bytes",
            "qvg_status_string", "qvg_version"]
@@ -62,6 +63,9 @@ def lib():
         L.qvg_attn_decode_ex.restype = C.c_int
         L.qvg_attn_decode_ex.argtypes = [pp, i64, vp, i64, i64, i64, vp, u8p, u8p, vp, vp, u8p, u8p, vp, vp,
                                          C.c_float, vp, vp, vp, C.c_size_t, vp]
+        L.qvg_attn_decode_causal.restype = C.c_int
+        L.qvg_attn_decode_causal.argtypes = [pp, i64, vp, i64, i64, i64, vp, u8p, u8p, vp, vp, u8p, u8p, vp, vp, vp,
+                                             C.c_float, vp, vp, vp, C.c_size_t, vp]
         L.qvg_attn_merge.restype = C.c_int
         L.qvg_attn_merge.argtypes = [i64, C.c_int32, vp, vp, vp, vp, vp, vp, vp]
         L.qvg_kmeans_assign.restype = C.c_int
@@ -239,10 +243,11 @@ def decode(enc: Encoded, out=None, n_tokens=None, first_token=0) -> torch.Tensor
 
 
 def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, out=None, n_kv=None,
-                k_rope=None):
+                k_rope=None, q_kv_len=None):
     """qvg_attn_decode_ex.  q [H, Nq, d] bf16 contiguous -> out bf16 [H, Nq, d] (and lse fp32 [H, Nq]).
     n_kv: read only the first n_kv tokens of the caches (they are allocated for more);
-    k_rope: [n_kv, d/2, 2] float16 (cos, sin), the rotary embedding of the decoded keys."""
+    k_rope: [n_kv, d/2, 2] float16 (cos, sin), the rotary embedding of the decoded keys;
+    q_kv_len: [Nq] int32, query i sees the first q_kv_len[i] tokens only (qvg_attn_decode_causal)."""
     _check(q, torch.bfloat16, "q")
     q = q.contiguous()
     H, Nq, d = q.shape
@@ -268,6 +273,18 @@ def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, o
     if out is None:
         out = torch.empty(H, Nq, d, dtype=torch.bfloat16, device=q.device)
     lse = torch.empty(H, Nq, dtype=torch.float32, device=q.device) if want_lse else None
+    if q_kv_len is not None:
+        _check(q_kv_len, torch.int32, "q_kv_len")
+        if tuple(q_kv_len.shape) != (Nq,) or not q_kv_len.is_contiguous():
+            raise ValueError("q_kv_len: need a contiguous [n_q] int32 tensor")
+        st = lib().qvg_attn_decode_causal(C.byref(p), Nq, _ptr(q), Nk, k.chunk_len, cap,
+                                          _ptr(k.centroids), _ptr(k.ids), _ptr(k.codes), _ptr(k.scales),
+                                          _ptr(v.centroids), _ptr(v.ids), _ptr(v.codes), _ptr(v.scales),
+                                          _ptr(k_rope), _ptr(q_kv_len), C.c_float(softmax_scale), _ptr(out),
+                                          _ptr(lse), None, 0, _stream())
+        if st != 0:
+            raise QvgError(st, "qvg_attn_decode_causal")
+        return (out, lse) if want_lse else out
     st = lib().qvg_attn_decode_ex(C.byref(p), Nq, _ptr(q), Nk, k.chunk_len, cap,
                                   _ptr(k.centroids), _ptr(k.ids), _ptr(k.codes), _ptr(k.scales),
                                   _ptr(v.centroids), _ptr(v.ids), _ptr(v.codes), _ptr(v.scales),

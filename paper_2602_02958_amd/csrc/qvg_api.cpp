@@ -360,6 +360,18 @@ int qvg_attn_decode_ex(const qvg_params *p, int64_t n_q, const void *q, int64_t 
                        const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
                        const void *v_scales, const void *k_rope, float softmax_scale, void *out,
                        float *lse_out, void *workspace, size_t workspace_bytes, void *stream) {
+    return qvg_attn_decode_causal(p, n_q, q, n_kv_tokens, chunk_len, kv_capacity_tokens, k_centroids, k_ids, k_codes,
+                                  k_scales, v_centroids, v_ids, v_codes, v_scales, k_rope, nullptr, softmax_scale, out,
+                                  lse_out, workspace, workspace_bytes, stream);
+}
+
+int qvg_attn_decode_causal(const qvg_params *p, int64_t n_q, const void *q, int64_t n_kv_tokens,
+                           int64_t chunk_len, int64_t kv_capacity_tokens, const void *k_centroids,
+                           const uint8_t *k_ids, const uint8_t *k_codes, const void *k_scales,
+                           const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
+                           const void *v_scales, const void *k_rope, const int32_t *q_kv_len,
+                           float softmax_scale, void *out, float *lse_out, void *workspace,
+                           size_t workspace_bytes, void *stream) {
     (void)workspace; (void)workspace_bytes;
     int st = check_params(p);
     if (st != QVG_OK) return st;
@@ -394,6 +406,8 @@ int qvg_attn_decode_ex(const qvg_params *p, int64_t n_q, const void *q, int64_t 
     a.rope = static_cast<const f16_t *>(k_rope);
     a.id_wide = id_wide(p);
     if (!ids_aligned(p, k_ids) || !ids_aligned(p, v_ids)) return QVG_ERR_ALIGN;
+    if (q_kv_len && (reinterpret_cast<uintptr_t>(q_kv_len) & 3u)) return QVG_ERR_ALIGN;
+    a.q_len = q_kv_len;
     return launch_attn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
 }
 

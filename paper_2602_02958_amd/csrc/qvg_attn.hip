@@ -61,12 +61,19 @@ struct Tile {                      // one 64-token tile; tiles never straddle a 
     int chunk; int t0, cend; bool valid;     // token indices fit 31 bits (checked by the caller)
 };
 
-__device__ __forceinline__ Tile first_tile(const AttnArgs &a) {
+struct Span {                      // the part of the cache a workgroup walks
+    int64_t chunk_len, n_kv; int n_chunks;
+};
+__device__ __forceinline__ Span span_of(const AttnArgs &a) {
+    Span s; s.chunk_len = a.chunk_len; s.n_kv = a.n_kv; s.n_chunks = a.n_chunks;
+    return s;
+}
+__device__ __forceinline__ Tile first_tile(const Span &a) {
     Tile t;
     t.chunk = 0; t.t0 = 0; t.cend = (int)(a.chunk_len < a.n_kv ? a.chunk_len : a.n_kv); t.valid = true;
     return t;
 }
-__device__ __forceinline__ Tile next_tile(const AttnArgs &a, Tile t) {
+__device__ __forceinline__ Tile next_tile(const Span &a, Tile t) {
     t.t0 += kAtKv;
     if (t.t0 >= t.cend) {
         t.chunk += 1;
@@ -236,8 +243,9 @@ __device__ __forceinline__ void load_rope(const f16_t *rope, const Tile &t, int 
     }
 }
 
-template <int T_, int SM, int FMT, bool ROPE>   // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages).
+template <int T_, int SM, int FMT, bool ROPE, bool QL>   // T_ > 0: compile-time stage count; 0: run-time (up to kMaxStages).
                                 // SM: smoothing stages (a.S tables and id bytes): 1, 2..4, or 0 = a.S
+                                // QL: a prefix length per query (a.q_len)
                                 // FMT: stored format (kFmt* bits)
                                 // ROPE: rotate the decoded keys by a.rope
 __global__ __launch_bounds__(kAtThreads, 2)
@@ -252,6 +260,30 @@ void attn_kernel_direct(AttnArgs a) {
     const int h = blockIdx.y;
     const int64_t qrow = (int64_t)blockIdx.x * kAtQPerBlock + wave * 32 + col;
     const bool qvalid = qrow < a.n_q;
+    // Prefix length per query (chunk-causal order for the queries of several chunks): the lane's
+    // query sees tokens 0 .. qlen-1; wmin = the shortest prefix in the wavefront (tiles below it
+    // need no mask); the workgroup walks the cache only up to its longest prefix.
+    int qlen = 0x7fffffff, wmin = 0x7fffffff;
+    Span sp = span_of(a);
+    if (QL) {
+        __shared__ int bmax;
+        if (tid == 0) bmax = 1;
+        __syncthreads();
+        const int nk = (int)a.n_kv;
+        int mx = 1;
+        if (qvalid) { const int v = a.q_len[qrow]; qlen = v < 1 ? 1 : (v > nk ? nk : v); mx = qlen; }
+        wmin = qlen;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const int o = __shfl_xor(wmin, off, 64); wmin = o < wmin ? o : wmin;
+            const int p = __shfl_xor(mx, off, 64); mx = p > mx ? p : mx;
+        }
+        if (lane == 0) atomicMax(&bmax, mx);
+        __syncthreads();
+        sp.n_kv = bmax;
+        sp.n_chunks = (int)((sp.n_kv + sp.chunk_len - 1) / sp.chunk_len);
+        wmin = __builtin_amdgcn_readfirstlane(wmin);
+    }
     const int T = T_ > 0 ? T_ : a.T, B = a.B, K = a.K;
     const int S = SM > 0 ? SM : a.S;
     const int G = kHeadDim / B;
@@ -318,9 +350,9 @@ void attn_kernel_direct(AttnArgs a) {
     };
 
     // ---- prologue: tile 0 into buffer 0, raw data of tile 1 in flight -------------------
-    Tile cur = first_tile(a);
-    Tile nxt = next_tile(a, cur);
-    Tile nn = nxt.valid ? next_tile(a, nxt) : nxt;
+    Tile cur = first_tile(sp);
+    Tile nxt = next_tile(sp, cur);
+    Tile nn = nxt.valid ? next_tile(sp, nxt) : nxt;
     uint32_t idk[2], idv[2];
     Raw<TM, SM> rk, rv;
     load_ids(ks, cur, tp, kmax, S, a.id_wide, idk);
@@ -371,6 +403,16 @@ void attn_kernel_direct(AttnArgs a) {
                     if (kv >= ntile) S[nb][r] = -INFINITY;
                 }
         }
+        if (QL && cur.t0 + kAtKv > wmin) {                     // uniform: some query of the wavefront ends in or before this tile
+            const int left = qlen - cur.t0;                    // tokens of this tile the lane's query sees (may be <= 0)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kv = nb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                    if (kv >= left) S[nb][r] = -INFINITY;
+                }
+        }
         float tmax = -INFINITY;
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb)
@@ -418,7 +460,7 @@ void attn_kernel_direct(AttnArgs a) {
         __syncthreads();
         buf ^= 1;
         cur = nxt; nxt = nn;
-        nn = nn.valid ? next_tile(a, nn) : nn;
+        nn = nn.valid ? next_tile(sp, nn) : nn;
     }
     // ---- normalise and store: lane holds channels 32*mb + 8*g + 4*half + 0..3 of its query ----
     const float ltot = l + __shfl_xor(l, 32, 64);
@@ -661,10 +703,11 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     auto is_full = [&](const Tile &t) { return t.valid && t.cend - t.t0 >= kAtKv; };
 
     // ---- prologue: tile 0 decoded into buffer 0, tile 1 parked, ids of tiles 0..2 parked ------
-    Tile cur = first_tile(a);
-    Tile nxt = next_tile(a, cur);
-    Tile nn = nxt.valid ? next_tile(a, nxt) : nxt;
-    Tile n3 = nn.valid ? next_tile(a, nn) : nn;
+    const Span sp = span_of(a);
+    Tile cur = first_tile(sp);
+    Tile nxt = next_tile(sp, cur);
+    Tile nn = nxt.valid ? next_tile(sp, nxt) : nxt;
+    Tile n3 = nn.valid ? next_tile(sp, nn) : nn;
     Fetch f;
     uint4 cen[2][2];
     fetch_tile(BoolC<false>{}, cur, f);  fetch_ids(cur, f);  park_tile(f, 0);  park_ids(f, 0);
@@ -776,7 +819,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         buf ^= 1;
         jt += 1;
         cur = nxt; nxt = nn; nn = n3;
-        n3 = n3.valid ? next_tile(a, n3) : n3;
+        n3 = n3.valid ? next_tile(sp, n3) : n3;
         return true;
     };
     // wavefronts w and w + 4 share a SIMD: the first four decode first (measured: 3 % over all
@@ -827,13 +870,13 @@ static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
     return a.rope ? launch_attn_staged_r<T_, true, FP8, I4, WIDE>(a, s) : launch_attn_staged_r<T_, false, FP8, I4, WIDE>(a, s);
 }
 
-template <int T_, int SM, int FMT, bool ROPE>
+template <int T_, int SM, int FMT, bool ROPE, bool QL = false>
 static hipError_t launch_attn_tr(const AttnArgs &a, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_, SM, FMT, ROPE>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_, SM, FMT, ROPE, QL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmem);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
-    hipLaunchKernelGGL((attn_kernel_direct<T_, SM, FMT, ROPE>), grid, dim3(kAtThreads), kAtSmem, s, a);
+    hipLaunchKernelGGL((attn_kernel_direct<T_, SM, FMT, ROPE, QL>), grid, dim3(kAtThreads), kAtSmem, s, a);
     return hipGetLastError();
 }
 template <int T_, int SM, int FMT = 0>
@@ -857,8 +900,22 @@ static hipError_t launch_attn_fmt(const AttnArgs &a, hipStream_t s) {
     return launch_attn_t<0, 1, FMT>(a, s);
 }
 
+template <int FMT>
+static hipError_t launch_attn_qlen(const AttnArgs &a, hipStream_t s) {
+    if (a.S > 1) return a.rope ? launch_attn_tr<0, 0, FMT, true, true>(a, s) : launch_attn_tr<0, 0, FMT, false, true>(a, s);
+    return a.rope ? launch_attn_tr<0, 1, FMT, true, true>(a, s) : launch_attn_tr<0, 1, FMT, false, true>(a, s);
+}
+
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     if (a.n_q == 0) return hipSuccess;
+    if (a.q_len) {                 // a prefix per query: instances of the general kernel with run-time counts
+        switch (a.fmt) {
+            case 0: return launch_attn_qlen<0>(a, s);
+            case kFmtE4M3: return launch_attn_qlen<kFmtE4M3>(a, s);
+            case kFmtInt4: return launch_attn_qlen<kFmtInt4>(a, s);
+            default: return launch_attn_qlen<kFmtInt4 | kFmtE4M3>(a, s);
+        }
+    }
     // the staged kernel fetches scales in 16-byte pieces: every chunk must start on one
     const bool aligned = (a.chunk_len % 8 == 0) || a.n_chunks == 1;
     // E4M3 scales on the staged kernel: a token's scale record must have an even number of bytes

@@ -203,6 +203,7 @@ struct AttnArgs {
     int chunk_stride;      // chunk tables between consecutive units in the centroid arrays (>= n_chunks)
     const f16_t *rope;     // [n_kv][d/2][2] (cos, sin) applied to the decoded keys, or nullptr
     int id_wide;           // ids are 16-bit words (K > 256, S == 1)
+    const int32_t *q_len;  // [n_q] prefix length per query (clamped to 1 .. n_kv), or nullptr: all n_kv tokens
 };
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
 

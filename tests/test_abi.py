@@ -117,6 +117,11 @@ def test_null_and_alignment_errors_are_reported_before_any_launch():
                                                 fake, fake, rope, C.c_float(0.1), fake, None, None, 0, None)
     assert ex(5, None) == -2
     assert ex(0, C.c_void_p(0x1004)) == -5
+    # prefix length per query: a misaligned length array
+    assert L.qvg_attn_decode_causal(C.byref(p), 4, fake, 10, 10, 0, fake, fake, fake, fake, fake, fake, fake, fake,
+                                    None, C.c_void_p(0x1002), C.c_float(0.1), fake, None, None, 0, None) == -5
+    assert L.qvg_attn_decode_causal(C.byref(p), 0, None, 10, 10, 0, None, None, None, None, None, None, None, None,
+                                    None, None, C.c_float(0.1), None, None, None, 0, None) == 0
     # merge
     assert L.qvg_attn_merge(4, 64, fake, fake, fake, fake, fake, None, None) == -3
     assert L.qvg_attn_merge(-1, 128, fake, fake, fake, fake, fake, None, None) == -2

@@ -197,3 +197,54 @@ def test_streaming_cache_append_attend_decode():
     with pytest.raises(ValueError):
         sc.append(torch.zeros(2 * heads, 10, 128, dtype=torch.bfloat16, device=DEV))      # after a partial chunk
     assert torch.equal(sc.decode(first_chunk=2), sc.decode()[:, 2 * L:])
+
+
+@pytest.mark.parametrize("L,T,Bg,S,bits,fmt,rope", [(520, 2, 32, 1, 2, B.SCALE_F16, False), (260, 1, 16, 4, 2, B.SCALE_E4M3, False),
+                                                    (516, 3, 64, 1, 4, B.SCALE_F16, True), (520, 1, 64, 2, 4, B.SCALE_E4M3, True)])
+def test_attention_with_a_prefix_length_per_query(L, T, Bg, S, bits, fmt, rope):
+    """qvg_attn_decode_causal: the queries of several chunks in one call, each seeing the chunks
+    before its own (lengths on chunk boundaries), plus lengths inside a chunk, the whole cache,
+    a single token and out-of-range values (clamped).  Every query is checked against the oracle's
+    attention over its own prefix.  Query blocks with short prefixes stop early: more than 256
+    queries, sorted and unsorted."""
+    H, K = 2, 64
+    n_chunks, filled = 4, 3 * L + 77
+    kc, vc = _filled_caches(H, L, n_chunks, filled, K, Bg, T, S, bits, fmt)
+    wl = CONFIGS["cfg2_window21"]
+    Nq = 300
+    q = synth.queries(wl, H, Nq, DEV)
+    g = torch.Generator().manual_seed(3)
+    lens = torch.empty(Nq, dtype=torch.int64)
+    lens[:100] = L                                   # queries of chunk 1 see chunk 0
+    lens[100:200] = 2 * L                            # queries of chunk 2 see chunks 0-1
+    lens[200:260] = torch.randint(1, filled + 1, (60,), generator=g)
+    lens[260:] = torch.tensor([1, 2, 63, 64, 65, L - 1, L + 1, filled, filled - 1, filled + 50, 0, -5] + [3 * L] * 28)
+    if T == 3:
+        lens = lens[torch.randperm(Nq, generator=g)]              # unsorted: every block walks to its longest prefix
+    table = _rope_table(filled).to(DEV) if rope else None
+    out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled, k_rope=table,
+                             q_kv_len=lens.to(torch.int32).to(DEV))
+    khat, vhat = B.decode(kc, n_tokens=filled), B.decode(vc, n_tokens=filled)
+    torch.cuda.synchronize()
+    eff = lens.clamp(1, filled).numpy()
+    for h in range(H):
+        kb = P.to_np_u16(khat[h])
+        if rope:
+            kb = O.rope_keys(kb, table.cpu().numpy().view(np.uint16))
+        vb = P.to_np_u16(vhat[h])
+        qb = bf16_bits(q[h])
+        og, lg = P.to_np_u16(out[h]), lse[h].cpu().numpy()
+        for n in np.unique(eff):
+            rows = np.flatnonzero(eff == n)
+            want, lse_w = O.attention(qb[rows], kb[:n], vb[:n], want_lse=True)
+            ok, max_abs, worst = P.attn_tolerance_ok(og[rows], want)
+            assert ok, f"head {h}, prefix {n}: max abs err {max_abs}, worst err/tol {worst}"
+            assert np.abs(lg[rows] - lse_w).max() < 2e-3, (h, n)
+    # every length = the whole cache: the result of the call without a length array (which may
+    # run on the other kernel), within the tolerance of either
+    full = torch.full((Nq,), filled, dtype=torch.int32, device=DEV)
+    a = B.attn_decode(q, kc, vc, n_kv=filled, k_rope=table, q_kv_len=full)
+    b = B.attn_decode(q, kc, vc, n_kv=filled, k_rope=table)
+    torch.cuda.synchronize()
+    for h in range(H):
+        assert P.attn_tolerance_ok(P.to_np_u16(a[h]), bits_to_f32(P.to_np_u16(b[h])).astype(np.float64))[0]
