@@ -531,8 +531,9 @@ static hipError_t launch_assign_t(const AssignArgs &a, hipStream_t s) {
     if (gy > 65535) return hipErrorInvalidValue;
     // the centroid norms: by a kernel of their own when there are many workgroups (each would
     // repeat the fp64 sums of its unit's table); inside the assignment kernel when there are few
-    // (the extra launch then costs more than the repeated sums: 0.165 -> 0.154 ms per cfg2 encode)
-    const bool norms_given = (int64_t)a.H * gy > 2048;
+    // (the extra launch then costs more than the repeated sums: 0.165 -> 0.154 ms per cfg2 encode;
+    // the bound scales with the table size, measured at K = 64 and K = 512)
+    const bool norms_given = (int64_t)a.H * gy * a.K > 2048 * 64;
     if (norms_given) {
         hipLaunchKernelGGL(centroid_prep_kernel, dim3((unsigned)a.H), dim3(kPrepThreads), 0, s, a.cent, a.K, Kpad,
                            a.nh3, a.cmax);
