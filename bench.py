@@ -213,6 +213,17 @@ PAPER_PRESETS = {
 }
 TABLE1_CHUNK_TOKENS = 34800     # the chunk length at which the stored sizes give Table 1's ratios
 
+# What the paper itself reports for this path (Sec. 5; no kernel-level throughput is given there):
+# context for a reader of the result line, measured on other hardware with real models, not a target.
+PAPER_CONTEXT = {
+    "note": "the paper's own figures: end-to-end, NVIDIA H100 (CUDA + Triton kernels), real model KV; context only",
+    "qvg_extra_time_in_a_full_run": "0.74 s of 43 s = 1.7 % (H100, Self-Forcing 480p, batch 1; Table 6)",
+    "kmeans_and_quantization_share_at_37440_token_chunks": "1.3 % (H100, Self-Forcing; Table 4)",
+    "end_to_end_latency_overhead": "2.1 % LongCat-Video-13B, 1.5 % HY-WorldPlay-8B, 4.3 % Self-Forcing (H100; Sec. 5)",
+    "centroid_caching": "k-means overhead reduced 3x (Sec. 4.3)",
+    "compression_ratio_int2": "6.94x / 7.05x QVG, 4.97x / 5.20x QVG-Pro (Table 1)",
+}
+
 
 def staged_cold_start(torch, B, synth, x, n_clusters, S, group_size, n_stages, iters, bits, scale_format):
     """Start centroids of S smoothing stages for a first chunk: stage s starts from seeded picks
@@ -576,6 +587,7 @@ def main():
         result["cfg4_layer"] = long_supplement(torch, B, synth, CONFIGS, "cfg4_dit_large")
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl)
+    result["paper_context"] = PAPER_CONTEXT
     print(json.dumps(result))
 
 
