@@ -42,6 +42,25 @@ __device__ __forceinline__ void insert3(float v, int idx, float &b1, float &b2, 
 }
 
 __device__ __forceinline__ double shfl_xor_f64(double v, int m) { return __shfl_xor(v, m, 64); }
+// Sum over each aligned group of 16 lanes, every lane getting the total, by data-parallel-primitive
+// moves (VALU; the general lane exchange goes through the LDS pipe and its latency, four times in
+// a row per table piece).  Pairings: lane ^ 1, lane ^ 2, then the mirror images inside 8 and
+// inside 16 lanes, whose partners hold what lane ^ 4 and lane ^ 8 hold, so the sums are those of
+// the xor butterfly bit for bit.
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)u, CTRL, 0xf, 0xf, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(u >> 32), CTRL, 0xf, 0xf, false);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ double sum16_f64(double v) {
+    v += dpp_f64<0xB1>(v);       // quad_perm [1,0,3,2]
+    v += dpp_f64<0x4E>(v);       // quad_perm [2,3,0,1]
+    v += dpp_f64<0x141>(v);      // row_half_mirror
+    v += dpp_f64<0x140>(v);      // row_mirror
+    return v;
+}
 template <bool V> struct BoolK { static constexpr bool value = V; };
 // (a & mask) | (b & ~mask): v_bfi_b32
 __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
@@ -77,8 +96,7 @@ void centroid_prep_kernel(const bf16_t *cent, int K, int Kpad, uint2 *nh3, float
             const double lo = (double)bf16_lo(w[e]), hi = (double)bf16_hi(w[e]);
             s += lo * lo; s += hi * hi;
         }
-        s += shfl_xor_f64(s, 1); s += shfl_xor_f64(s, 2);
-        s += shfl_xor_f64(s, 4); s += shfl_xor_f64(s, 8);
+        s = sum16_f64(s);
         if (c16 == 0) {
             float nh = -3.0e38f;
             if (row < K) {
@@ -190,38 +208,51 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
     if (tid == 0) smax = 0u;
     __syncthreads();
     const bf16_t *cg = a.cent + (int64_t)h * K * kHeadDim;
-    for (int i = tid; i < Kpad * 16; i += kAsgThreads) {           // Kpad*16 is a multiple of the block: whole waves
-        const int row = i >> 4, c16 = i & 15;
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (row < K) {
-            v = *reinterpret_cast<const uint4 *>(cg + (int64_t)row * kHeadDim + c16 * 8);
-            if (a.cent_copy && blockIdx.y == 0)                     // the table's way out to the caller, for free
-                *reinterpret_cast<uint4 *>(a.cent_copy + (int64_t)h * a.cent_copy_stride + (int64_t)row * kHeadDim + c16 * 8) = v;
-        }
-        *reinterpret_cast<uint4 *>(lc + row * kCPitch + c16 * 8) = v;
-        if (norms_given) continue;                                  // uniform
-        double sq = 0.0;
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    // Eight 16-byte pieces per thread are requested before the first is used: taken one at a time
+    // (load, store to LDS, norm) every piece waits a whole memory round trip (0.85 us measured),
+    // which was most of what a workgroup with a single 256-token step spent on a 256-row table.
+    constexpr int kStageBatch = 8;
+    for (int i0 = tid; i0 < Kpad * 16; i0 += kAsgThreads * kStageBatch) {      // Kpad*16 is a multiple of the block: whole waves
+        uint4 vb[kStageBatch];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const double lo = (double)bf16_lo(w[e]), hi = (double)bf16_hi(w[e]);
-            sq += lo * lo; sq += hi * hi;
+        for (int u = 0; u < kStageBatch; ++u) {
+            const int i = i0 + u * kAsgThreads;
+            const int row = i >> 4, c16 = i & 15;
+            vb[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (i < Kpad * 16 && row < K) vb[u] = *reinterpret_cast<const uint4 *>(cg + (int64_t)row * kHeadDim + c16 * 8);
         }
-        sq += shfl_xor_f64(sq, 1); sq += shfl_xor_f64(sq, 2);
-        sq += shfl_xor_f64(sq, 4); sq += shfl_xor_f64(sq, 8);
-        if (c16 == 0) {
-            float nh = -3.0e38f;
-            if (row < K) {
-                nh = (float)(-0.5 * sq);
-                const float up = (float)sq * (1.0f + 0x1p-22f);      // upper bound of ||c||^2 in fp32, as its bit pattern
-                atomicMax(&smax, __float_as_uint(up));
+#pragma unroll
+        for (int u = 0; u < kStageBatch; ++u) {
+            const int i = i0 + u * kAsgThreads;
+            if (i >= Kpad * 16) break;                                  // uniform
+            const int row = i >> 4, c16 = i & 15;
+            const uint4 v = vb[u];
+            if (row < K && a.cent_copy && blockIdx.y == 0)              // the table's way out to the caller, for free
+                *reinterpret_cast<uint4 *>(a.cent_copy + (int64_t)h * a.cent_copy_stride + (int64_t)row * kHeadDim + c16 * 8) = v;
+            *reinterpret_cast<uint4 *>(lc + row * kCPitch + c16 * 8) = v;
+            if (norms_given) continue;                                  // uniform
+            double sq = 0.0;
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const double lo = (double)bf16_lo(w[e]), hi = (double)bf16_hi(w[e]);
+                sq += lo * lo; sq += hi * hi;
             }
-            const float hi = __uint_as_float(__float_as_uint(nh) & 0xffff0000u);
-            const float r1 = nh - hi;
-            const float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
-            const float lo = __uint_as_float(__float_as_uint(r1 - mid) & 0xffff0000u);
-            *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) =
-                make_uint4((__float_as_uint(hi) >> 16) | (__float_as_uint(mid) & 0xffff0000u), __float_as_uint(lo) >> 16, 0u, 0u);
+            sq = sum16_f64(sq);
+            if (c16 == 0) {
+                float nh = -3.0e38f;
+                if (row < K) {
+                    nh = (float)(-0.5 * sq);
+                    const float up = (float)sq * (1.0f + 0x1p-22f);      // upper bound of ||c||^2 in fp32, as its bit pattern
+                    atomicMax(&smax, __float_as_uint(up));
+                }
+                const float hi = __uint_as_float(__float_as_uint(nh) & 0xffff0000u);
+                const float r1 = nh - hi;
+                const float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
+                const float lo = __uint_as_float(__float_as_uint(r1 - mid) & 0xffff0000u);
+                *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) =
+                    make_uint4((__float_as_uint(hi) >> 16) | (__float_as_uint(mid) & 0xffff0000u), __float_as_uint(lo) >> 16, 0u, 0u);
+            }
         }
     }
     if (norms_given)
