@@ -103,6 +103,28 @@ def cpu_baseline(wl, budget_s=12.0):
     }
 
 
+def _large_decode_setup(torch, B, wl, dev):
+    """A cache of 3 layers of the workload at full length with random content (ids, levels, scales,
+    tables) and the output tensor: the same construction for the benchmark line and for the
+    profiling run.  (The order of the allocations matters: with the 9 GB of temporaries of the
+    random levels freed before the output tensor is allocated the decode runs 15 % faster than on
+    tensors allocated from a fresh heap, which is a property of the allocator's page sizes, not of
+    the kernel; both runs therefore build their tensors this way.)"""
+    units = 2 * 3 * wl.heads
+    n = wl.tokens_per_layer
+    big = B.alloc_cache(units, n, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
+    g = torch.Generator(device=dev); g.manual_seed(1)
+    big.ids.copy_(torch.randint(0, wl.n_clusters, big.ids.shape, generator=g, device=dev, dtype=torch.uint8))
+    # codes: every 2-bit field one of the levels 0, +1, -1 (0b00, 0b01, 0b11)
+    f = torch.tensor([0, 1, 3], dtype=torch.uint8, device=dev)[
+        torch.randint(0, 3, big.codes.shape + (4,), generator=g, device=dev)]
+    big.codes.copy_(f[..., 0] | (f[..., 1] << 2) | (f[..., 2] << 4) | (f[..., 3] << 6)); del f
+    big.scales.copy_(torch.rand(big.scales.shape, generator=g, device=dev).to(torch.float16))
+    big.centroids.copy_(torch.randn(big.centroids.shape, generator=g, device=dev).to(torch.bfloat16))
+    outbuf = torch.empty(units, n, wl.head_dim, dtype=torch.bfloat16, device=dev)
+    return big, outbuf, units, n
+
+
 def large_supplement(torch, B, synth, CONFIGS):
     """cfg3-shaped batches that exceed the 256 MB Infinity Cache: decode of 3 layers' full cache
     and single-pass / warm encode of one chunk of all 30 layers."""
@@ -133,18 +155,7 @@ def large_supplement(torch, B, synth, CONFIGS):
                      "assign_TFLOPs": round(flops / ms / 1e9, 1)}
     del x, cache, ws
     # ---- decode: 3 layers' full cache = 72 units x 126360 tokens
-    units = 2 * 3 * wl.heads
-    n = wl.tokens_per_layer
-    big = B.alloc_cache(units, n, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
-    g = torch.Generator(device=dev); g.manual_seed(1)
-    big.ids.copy_(torch.randint(0, wl.n_clusters, big.ids.shape, generator=g, device=dev, dtype=torch.uint8))
-    # codes: every 2-bit field one of the levels 0, +1, -1 (0b00, 0b01, 0b11)
-    f = torch.tensor([0, 1, 3], dtype=torch.uint8, device=dev)[
-        torch.randint(0, 3, big.codes.shape + (4,), generator=g, device=dev)]
-    big.codes.copy_(f[..., 0] | (f[..., 1] << 2) | (f[..., 2] << 4) | (f[..., 3] << 6)); del f
-    big.scales.copy_(torch.rand(big.scales.shape, generator=g, device=dev).to(torch.float16))
-    big.centroids.copy_(torch.randn(big.centroids.shape, generator=g, device=dev).to(torch.bfloat16))
-    outbuf = torch.empty(units, n, wl.head_dim, dtype=torch.bfloat16, device=dev)
+    big, outbuf, units, n = _large_decode_setup(torch, B, wl, dev)
     fn = lambda: B.decode(big, out=outbuf)
     fn(); torch.cuda.synchronize()
     ms = _event_ms(fn, 10)
@@ -414,11 +425,7 @@ def run_only(args, torch, B, synth, workload, CONFIGS):
     elif args.only in ("large_decode", "large_encode"):
         wl = CONFIGS["cfg3_dit_small"]
         if args.only == "large_decode":
-            units, n = 2 * 3 * wl.heads, wl.tokens_per_layer
-            big = B.alloc_cache(units, n, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
-            big.ids.random_(0, wl.n_clusters); big.codes.zero_(); big.scales.fill_(0.25)
-            big.centroids.copy_(torch.randn(big.centroids.shape, device=dev).to(torch.bfloat16))
-            outbuf = torch.empty(units, n, wl.head_dim, dtype=torch.bfloat16, device=dev)
+            big, outbuf, units, n = _large_decode_setup(torch, B, wl, dev)
             fn = lambda: B.decode(big, out=outbuf)
             nbytes = units * n * 256 + _format_bytes(wl, units, n, wl.chunk)
         else:

@@ -42,10 +42,13 @@ constexpr int kXcds = 8;                         // MI355X: 8 XCDs, each with it
 // word (16 words per token and round, so the offsets below are the same in units of the word).
 // SC: number of smoothing stages when known at compile time (the loops over the stages unroll and
 // their loads are issued together), 0 = run-time S.
-template <int T_, bool CHECK, int SM, int FMT, int SC>
+// WIDE: ids are 16-bit words (more than 256 centroids; SM == 1 only).  A template parameter: as a
+// run-time switch around the id load it cost the byte-id kernels 15 % (0.667 -> 0.767 ms at the
+// cfg3 shape).
+template <int T_, bool CHECK, int SM, int FMT, int SC, bool WIDE>
 __device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_t n_left, uint32_t lane16,
                                             uint32_t G, uint32_t gidx, uint32_t kmax,
-                                            const uint8_t *ids_b, int id_wide, const void *codes_v,
+                                            const uint8_t *ids_b, const void *codes_v,
                                             const void *scales_v, const bf16_t *tab, const bf16_t *cg,
                                             bf16_t *out_b, int64_t stride_token) {
     constexpr int TM = T_ > 0 ? T_ : kMaxStages;
@@ -70,7 +73,7 @@ __device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_
             for (int t = 0; t < TM; ++t) { code[u][t] = 0u; sc[u][t] = 0u; }
         }
         if (ok[u]) {
-            if (SM == 1) idv[u] = load_id(ids_b, ln, id_wide);
+            if (SM == 1) idv[u] = WIDE ? (uint32_t)reinterpret_cast<const uint16_t *>(ids_b)[ln] : (uint32_t)ids_b[ln];
             else {                                   // up to four id bytes of the token, stage s in byte s
                 idv[u] = 0u;
 #pragma unroll
@@ -176,7 +179,7 @@ __device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_
 
 // One workgroup = one slice of one chunk of one unit.  It stages the chunk's centroid table
 // in LDS once (the only shared operand) and then streams its tokens.
-template <int T_, int SM, int FMT, int SC>   // T_ > 0: compile-time stage count; T_ == 0: run-time.  SM, FMT, SC: see decode_pass
+template <int T_, int SM, int FMT, int SC, bool WIDE>   // T_ > 0: compile-time stage count; T_ == 0: run-time.  SM, FMT, SC, WIDE: see decode_pass
 __global__ __launch_bounds__(kDecThreads)
 void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, int blocks_per_xcd) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -212,7 +215,7 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
 
     // per-block base pointers (uniform), per-lane 32-bit offsets
     const int64_t hn0 = (int64_t)h * a.kv_stride + tok0;
-    const uint8_t *ids_b = a.ids + hn0 * S * (a.id_wide ? 2 : 1);
+    const uint8_t *ids_b = a.ids + hn0 * S * (WIDE ? 2 : 1);
     const void *codes_b = a.codes + hn0 * T * ((FMT & kFmtInt4) ? 64 : 32);
     const void *scales_b = reinterpret_cast<const uint8_t *>(a.scales) + hn0 * T * G * ((FMT & kFmtE4M3) ? 1 : 2);
     bf16_t *out_b = a.out + (int64_t)h * a.stride_head + tok0 * a.stride_token;
@@ -220,16 +223,16 @@ void decode_kernel(DecodeArgs a, int slices, uint32_t slice_len, int n_blocks, i
 
     for (uint32_t first = 0; first < n_left; first += kDecTokPerIter) {
         if (first + kDecTokPerIter <= n_left)
-            decode_pass<T_, false, SM, FMT, SC>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, a.id_wide, codes_b, scales_b,
+            decode_pass<T_, false, SM, FMT, SC, WIDE>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
                                        tab, cg, out_b, a.stride_token);
         else
-            decode_pass<T_, true, SM, FMT, SC>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, a.id_wide, codes_b, scales_b,
+            decode_pass<T_, true, SM, FMT, SC, WIDE>(T, S, first + row, n_left, lane16, G, gidx, kmax, ids_b, codes_b, scales_b,
                                       tab, cg, out_b, a.stride_token);
     }
 }
 
-template <int T_, int SM, int FMT = 0, int SC = 0>
-static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
+template <int T_, int SM, int FMT, int SC, bool WIDE>
+static hipError_t launch_decode_w(const DecodeArgs &a, hipStream_t s) {
     // slices per chunk: enough workgroups to fill 256 CUs x 2 twice over, but as few as possible
     // beyond that (every workgroup re-reads the chunk's table; measured flat from 512 to 4096)
     const int64_t unit_chunks = (int64_t)a.H * a.n_chunks;
@@ -245,12 +248,19 @@ static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
     if (nb > 0x7fffffff - kXcds) return hipErrorInvalidValue;
     const int bpx = (int)((nb + kXcds - 1) / kXcds);
     const size_t smem = (SM == 3) ? 16 : (size_t)(SM == 1 ? 1 : a.S) * a.K * kHeadDim * sizeof(bf16_t);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<T_, SM, FMT, SC>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<T_, SM, FMT, SC, WIDE>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((decode_kernel<T_, SM, FMT, SC>), dim3((unsigned)(bpx * kXcds)), dim3(kDecThreads), smem, s, a,
+    hipLaunchKernelGGL((decode_kernel<T_, SM, FMT, SC, WIDE>), dim3((unsigned)(bpx * kXcds)), dim3(kDecThreads), smem, s, a,
                        (int)slices, (uint32_t)slice_len, (int)nb, bpx);
     return hipGetLastError();
+}
+
+// 16-bit ids come with one smoothing stage only (SM == 1)
+template <int T_, int SM, int FMT = 0, int SC = 0>
+static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
+    if (SM == 1 && a.id_wide) return launch_decode_w<T_, SM, FMT, SC, SM == 1>(a, s);
+    return launch_decode_w<T_, SM, FMT, SC, false>(a, s);
 }
 
 // the other stored formats: run-time round count, except the paper's own 2-bit / E4M3 / one round
