@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # HBM bytes per launch read off rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each scaled by what the
 # same counter reads for a plain 1 GiB device copy); the runs are summarised under profiles/.
 # None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {("cfg2_window21", "attn"): 208384628}   # profiles/attn_cfg2_window21_hbm_counters.txt
+MEASURED_TRAFFIC_BYTES = {("cfg2_window21", "attn"): 208394824}   # profiles/attn_cfg2_window21_hbm_counters.txt
 
 
 def _event_ms(fn, reps):
@@ -106,10 +106,7 @@ def cpu_baseline(wl, budget_s=12.0):
 def _large_decode_setup(torch, B, wl, dev):
     """A cache of 3 layers of the workload at full length with random content (ids, levels, scales,
     tables) and the output tensor: the same construction for the benchmark line and for the
-    profiling run.  (The order of the allocations matters: with the 9 GB of temporaries of the
-    random levels freed before the output tensor is allocated the decode runs 15 % faster than on
-    tensors allocated from a fresh heap, which is a property of the allocator's page sizes, not of
-    the kernel; both runs therefore build their tensors this way.)"""
+    profiling run."""
     units = 2 * 3 * wl.heads
     n = wl.tokens_per_layer
     big = B.alloc_cache(units, n, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)

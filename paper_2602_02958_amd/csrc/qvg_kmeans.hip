@@ -27,6 +27,7 @@ constexpr int kRankK = kMaxClusters;                // histogram width
 // the scan (start of cluster k = tokens of lower clusters + tokens of k in earlier ranges) it
 // places the range 64 tokens at a time.  Inside a step, lanes with equal ids are ranked by
 // lane number (ballot-built peer masks), so equal ids keep their token order.
+template <bool WIDE>                       // 16-bit ids (more than 256 centroids)
 __global__ __launch_bounds__(kRankThreads)
 void kmeans_rank_kernel(UpdateArgs a) {
     __shared__ int cnt[kRankWaves][kRankK];   // histogram per range, then running cursor
@@ -34,10 +35,9 @@ void kmeans_rank_kernel(UpdateArgs a) {
     const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int K = a.K;
     const int64_t N = a.n_tokens;
-    const int wide = a.id_wide;
     const int64_t id0 = (int64_t)h * a.ids_stride * a.ids_step + a.ids_off;   // token n at element id0 + n * step
     const int64_t step = a.ids_step;
-    auto id_of = [&](int64_t n) { return (int)load_id(a.ids, id0 + n * step, wide); };
+    auto id_of = [&](int64_t n) { return (int)load_id(a.ids, id0 + n * step, WIDE ? 1 : 0); };
     int32_t *perm = a.perm + (int64_t)h * N;
     int32_t *offs = a.offsets + (int64_t)h * (K + 1);
 
@@ -119,7 +119,7 @@ void kmeans_rank_kernel(UpdateArgs a) {
         uint64_t peers = __ballot(valid);
 #pragma unroll
         for (int b = 0; b < 9; ++b) {
-            if (b == 8 && K <= 256) break;                          // uniform: the ninth bit only with 16-bit ids
+            if (b == 8 && !WIDE) break;                             // the ninth bit only with 16-bit ids
             const uint64_t m = __ballot((id >> b) & 1);
             peers &= ((id >> b) & 1) ? m : ~m;
         }
@@ -412,7 +412,8 @@ hipError_t launch_residual(const ResidualArgs &a, hipStream_t s) {
 }
 
 hipError_t launch_update(const UpdateArgs &a, hipStream_t s) {
-    hipLaunchKernelGGL(kmeans_rank_kernel, dim3((unsigned)a.H), dim3(kRankThreads), 0, s, a);
+    if (a.id_wide) hipLaunchKernelGGL(kmeans_rank_kernel<true>, dim3((unsigned)a.H), dim3(kRankThreads), 0, s, a);
+    else hipLaunchKernelGGL(kmeans_rank_kernel<false>, dim3((unsigned)a.H), dim3(kRankThreads), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if ((int64_t)a.K * a.H <= kMeanSmallGrid) {
