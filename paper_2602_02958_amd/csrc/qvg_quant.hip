@@ -19,7 +19,7 @@ namespace qvg {
 constexpr int kQtThreads = 256;
 constexpr int kQtTokens = kQtThreads / 16;      // tokens per pass of a block
 
-template <int BITS, bool FP8>
+template <int BITS, bool FP8, bool WIDE>       // WIDE: 16-bit ids (more than 256 centroids)
 __global__ __launch_bounds__(kQtThreads)
 void quantize_kernel(QuantArgs a, int passes) {
     const int h = blockIdx.x;
@@ -39,7 +39,7 @@ void quantize_kernel(QuantArgs a, int passes) {
         for (int i = 0; i < 8; ++i) r[i] = 0.0f;
         const int64_t hn = (int64_t)h * a.out_stride + n;
         if (valid) {
-            const uint32_t id = min(load_id(a.ids, hn * a.ids_step + a.ids_off, a.id_wide), kmax);
+            const uint32_t id = min(load_id(a.ids, hn * a.ids_step + a.ids_off, WIDE ? 1 : 0), kmax);
             const uint4 xv = *reinterpret_cast<const uint4 *>(a.x + (int64_t)h * a.stride_head + n * a.stride_token + lane16 * 8);
             const uint4 cv = *reinterpret_cast<const uint4 *>(cent + (int64_t)id * kHeadDim + lane16 * 8);
             const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w}, cw[4] = {cv.x, cv.y, cv.z, cv.w};
@@ -88,7 +88,10 @@ static hipError_t launch_quantize_t(const QuantArgs &a, hipStream_t s) {
     while (passes < 16 && (steps / (2 * passes)) * a.H >= 4096) passes *= 2;
     const int64_t gy = (steps + passes - 1) / passes;
     if (gy > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((quantize_kernel<BITS, FP8>), dim3((unsigned)a.H, (unsigned)gy), dim3(kQtThreads), 0, s, a, passes);
+    if (a.id_wide)
+        hipLaunchKernelGGL((quantize_kernel<BITS, FP8, true>), dim3((unsigned)a.H, (unsigned)gy), dim3(kQtThreads), 0, s, a, passes);
+    else
+        hipLaunchKernelGGL((quantize_kernel<BITS, FP8, false>), dim3((unsigned)a.H, (unsigned)gy), dim3(kQtThreads), 0, s, a, passes);
     return hipGetLastError();
 }
 
