@@ -615,17 +615,23 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         }
     };
     // ids run one tile further ahead than codes and scales (the centroid rows they select are
-    // gathered a whole tile before they are needed); a token that does not exist gets id 0
+    // gathered a whole tile before they are needed); a token that does not exist gets id 0.
+    // The fetch only issues the load (of token 0 for a token that does not exist, so that the
+    // load needs no branch); the zeroing and the clamp to the table's last row come with the
+    // store: done at the fetch they made the fetching wavefronts wait for the id, and with it
+    // for every load issued before it
+    auto ids_valid = [&](const Tile &t) {
+        return t.valid ? (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv) : 0;
+    };
     auto fetch_ids = [&](const Tile &t, Fetch &f) {
-        f.id = 0u;
         if (tid < 2 * kAtKv) {
-            const int nvalid = t.valid ? (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv) : 0;
             const int n = tid & 63;
-            if (n < nvalid) f.id = min((uint32_t)((tid >> 6) ? v_ids : k_ids)[t.t0 + n], kmax);
+            f.id = (uint32_t)((tid >> 6) ? v_ids : k_ids)[n < ids_valid(t) ? t.t0 + n : 0];
         }
     };
-    auto park_ids = [&](const Fetch &f, int ordinal) {
-        if (tid < 2 * kAtKv) idring[(ordinal & 3) * 2 * kAtKv + tid] = (id_t)f.id;
+    auto park_ids = [&](const Tile &t, const Fetch &f, int ordinal) {
+        if (tid < 2 * kAtKv)
+            idring[(ordinal & 3) * 2 * kAtKv + tid] = (id_t)(((tid & 63) < ids_valid(t)) ? min(f.id, kmax) : 0u);
     };
     auto park_tile = [&](const Fetch &f, int sb) {
         unsigned char *st = stage + sb * kStBytes;
@@ -665,9 +671,9 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         constexpr bool FULL = decltype(full)::value;
         const unsigned char *st = stage + sb * kStBytes;
         const int nvalid = FULL ? kAtKv : (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv);
+        Raw<T> rs[2];                      // both sides are read before either is decoded
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
-            Raw<T> r;
             typedef typename std::conditional<I4, uint32_t, uint16_t>::type code_t;   // a thread's 8 channels of a round
             const code_t *cp = reinterpret_cast<const code_t *>(st + s * kStCodes) + tok * T * 16 + c8;
             typedef typename std::conditional<FP8, uint8_t, uint16_t>::type scale_t;
@@ -676,11 +682,15 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
             for (int e = 0; e < 2; ++e) {
 #pragma unroll
                 for (int k = 0; k < T; ++k) {
-                    r.code[e][k] = cp[(e * T + k) * 16];
-                    r.sc[e][k] = sp[(e * T + k) * G];
+                    rs[s].code[e][k] = cp[(e * T + k) * 16];
+                    rs[s].sc[e][k] = sp[(e * T + k) * G];
                 }
-                r.cen[e] = (FULL || tok + e < nvalid) ? cen[s][e] : make_uint4(0u, 0u, 0u, 0u);
+                rs[s].cen[e] = (FULL || tok + e < nvalid) ? cen[s][e] : make_uint4(0u, 0u, 0u, 0u);
             }
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const Raw<T> &r = rs[s];
             float accA[8], accB[8];
             dequant2x8<T, T, 1, (FP8 ? kFmtE4M3 : 0) | (I4 ? kFmtInt4 : 0)>(r, T, accA, accB);
             if (s == 0) {
@@ -710,9 +720,9 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     Tile n3 = nn.valid ? next_tile(sp, nn) : nn;
     Fetch f;
     uint4 cen[2][2];
-    fetch_tile(BoolC<false>{}, cur, f);  fetch_ids(cur, f);  park_tile(f, 0);  park_ids(f, 0);
-    fetch_tile(BoolC<false>{}, nxt, f);  fetch_ids(nxt, f);  park_tile(f, 1);  park_ids(f, 1);
-    fetch_ids(nn, f);  park_ids(f, 2);
+    fetch_tile(BoolC<false>{}, cur, f);  fetch_ids(cur, f);  park_tile(f, 0);  park_ids(cur, f, 0);
+    fetch_tile(BoolC<false>{}, nxt, f);  fetch_ids(nxt, f);  park_tile(f, 1);  park_ids(nxt, f, 1);
+    fetch_ids(nn, f);  park_ids(nn, f, 2);
     __syncthreads();
     gather_rows(cur, 0, cen);
     decode_to_lds(BoolC<false>{}, cur, 0, cen, 0);
@@ -841,7 +851,7 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
             if (FULL || nn.valid) gather_rows(nn, jt + 2, cen);
         }
         if (FULL || nn.valid) park_tile(f, buf);                   // staging buf is free since the last barrier
-        park_ids(f, jt + 3);
+        park_ids(n3, f, jt + 3);
         __syncthreads();
         buf ^= 1;
         jt += 1;
