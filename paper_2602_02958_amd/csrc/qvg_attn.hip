@@ -838,11 +838,17 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     // hold 64 tokens.  Returns false after the last tile.
     auto tile_step = [&](auto full, bool decode_first /* uniform; only honoured with FULL */) -> bool {
         constexpr bool FULL = decltype(full)::value;
-        if (FULL || nn.valid) fetch_tile(full, nn, f);             // lands during this iteration
-        fetch_ids(n3, f);
+        // codes and scales of `nn` and ids of `n3` land during this iteration; a wavefront that
+        // decodes first issues them after the decode, whose waits for the gathered rows would
+        // otherwise (the load counter is in order) also wait for these fresh loads
         if (FULL && decode_first) {
             decode_to_lds(full, nxt, buf ^ 1, cen, buf ^ 1);
             gather_rows(nn, jt + 2, cen);
+            fetch_tile(full, nn, f);
+            fetch_ids(n3, f);
+        } else {
+            if (FULL || nn.valid) fetch_tile(full, nn, f);
+            fetch_ids(n3, f);
         }
         compute(full);
         if (!FULL && !nxt.valid) return false;
