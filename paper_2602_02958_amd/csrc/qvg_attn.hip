@@ -381,15 +381,30 @@ void attn_kernel_direct(AttnArgs a) {
         // ---- S^T = K_tile . Q^T -------------------------------------------
         floatx16_t S[2];
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
+        for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) S[nb][r] = 0.0f;
-            const uint16_t *arow = kt + (nb * 32 + col) * kKtPitch + half * 8;
+        {
+            // K fragments are read kKAhead contractions ahead of their use (with fewer in flight
+            // every pair of contractions waited for a whole LDS round trip)
+            constexpr int kKAhead = 4;
+            const uint16_t *arow = kt + col * kKtPitch + half * 8;
+            auto kfrag = [&](int i) {
+                return *reinterpret_cast<const bf16x8_t *>(arow + (i >> 3) * 32 * kKtPitch + (i & 7) * 16);
+            };
+            bf16x8_t kf[16];
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kk * 16);
-                S[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    av, __builtin_bit_cast(bf16x8_t, qa[kk]), S[nb], 0, 0, 0);
+            for (int i = 0; i < kKAhead; ++i) kf[i] = kfrag(i);
+            __builtin_amdgcn_sched_group_barrier(0x100, kKAhead, 0);     // the first LDS reads
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                S[i >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    kf[i], __builtin_bit_cast(bf16x8_t, qa[i & 7]), S[i >> 3], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one contraction
+                if (i + kKAhead < 16) {
+                    kf[i + kKAhead] = kfrag(i + kKAhead);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                }
             }
         }
         // ---- online soft-max (base 2) --------------------------------------
@@ -443,15 +458,27 @@ void attn_kernel_direct(AttnArgs a) {
             l = sum_f16_pairs(pb[st], l);
         }
         // ---- O^T += V_tile^T . P --------------------------------------------
+        {
+            constexpr int kVAhead = 4;                            // V fragments in flight, as for K above
+            auto vfrag = [&](int i) {
+                const int mb = i >> 2, st = i & 3;
+                const int key = mb * 2;                           // swizzle key of rows 32*mb .. 32*mb + 31
+                return *reinterpret_cast<const halfx8_t *>(
+                    vt + (mb * 32 + col) * kVtPitch + (((2 * st + half) ^ key) * 8));
+            };
+            halfx8_t vf[16];
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-            const int key = mb * 2;                               // swizzle key of rows 32*mb .. 32*mb + 31
-            const uint16_t *vrow = vt + (mb * 32 + col) * kVtPitch;
+            for (int i = 0; i < kVAhead; ++i) vf[i] = vfrag(i);
+            __builtin_amdgcn_sched_group_barrier(0x100, kVAhead, 1);
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                const halfx8_t av = *reinterpret_cast<const halfx8_t *>(vrow + (((2 * st + half) ^ key) * 8));
-                O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
-                    av, __builtin_bit_cast(halfx8_t, pb[st]), O[mb], 0, 0, 0);
+            for (int i = 0; i < 16; ++i) {
+                O[i >> 2] = __builtin_amdgcn_mfma_f32_32x32x16_f16(
+                    vf[i], __builtin_bit_cast(halfx8_t, pb[i & 3]), O[i >> 2], 0, 0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                if (i + kVAhead < 16) {
+                    vf[i + kVAhead] = vfrag(i + kVAhead);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+                }
             }
         }
         if (!nxt.valid) break;
