@@ -597,7 +597,10 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     // predicates at all, the common case) and the general one.
     constexpr int kTokPieces = T * CB / 16;                          // code pieces of one token
     constexpr int kPieces = 2 * kAtKv * kTokPieces;                  // code pieces, both sides
-    constexpr int kPiecesPerThread = (kPieces + kAtThreads - 1) / kAtThreads;
+    // the code pieces are fetched and parked by the first half of the wavefronts only: those
+    // decode first and otherwise wait for the others at the barrier of every tile
+    constexpr int kFetchThreads = kAtThreads / 2;
+    constexpr int kPiecesPerThread = (kPieces + kFetchThreads - 1) / kFetchThreads;
     const int scPiecesSide = kAtKv * T * G * SZ / 16;                // scale pieces per side (<= 256)
     const int scBytesTok = T * G * SZ;                               // even (the host sees to it)
     struct Fetch { uint4 code[kPiecesPerThread]; uint4 sc; uint32_t id; };
@@ -607,9 +610,9 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         const int nvalid = FULL ? kAtKv : (t.valid ? (int)((t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv) : 0);
 #pragma unroll
         for (int i = 0; i < kPiecesPerThread; ++i) {
-            const int p = tid + i * kAtThreads;
+            const int p = tid + i * kFetchThreads;
             if (!FULL) f.code[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (p < kPieces) {
+            if (tid < kFetchThreads && p < kPieces) {
                 const bool vside = p >= kPieces / 2;
                 const int ps = p - (vside ? kPieces / 2 : 0);
                 if (FULL || ps / kTokPieces < nvalid)
@@ -664,8 +667,8 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         unsigned char *st = stage + sb * kStBytes;
 #pragma unroll
         for (int i = 0; i < kPiecesPerThread; ++i) {
-            const int p = tid + i * kAtThreads;
-            if (p < kPieces) {
+            const int p = tid + i * kFetchThreads;
+            if (tid < kFetchThreads && p < kPieces) {
                 const bool vside = p >= kPieces / 2;
                 const int ps = p - (vside ? kPieces / 2 : 0);
                 *reinterpret_cast<uint4 *>(st + (vside ? kStCodes : 0) + ps * 16) = f.code[i];
