@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # HBM bytes per launch read off rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each scaled by what the
 # same counter reads for a plain 1 GiB device copy); the runs are summarised under profiles/.
 # None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {("cfg2_window21", "attn"): 208411100}   # profiles/attn_cfg2_window21_hbm_counters.txt
+MEASURED_TRAFFIC_BYTES = {("cfg2_window21", "attn"): 211390939}   # profiles/attn_cfg2_window21_hbm_counters.txt
 
 
 def _event_ms(fn, reps):
