@@ -102,17 +102,27 @@ struct Raw {                       // what one thread loads for its 2 tokens x 8
 // ids of this thread's two tokens of a tile (0 for tokens past the chunk end / an invalid tile);
 // with S smoothing stages a token has S id bytes, stage s in byte s of the result
 // (ids of 16 bits, for tables of more than 256 rows, come with one stage only)
-__device__ __forceinline__ void load_ids(const CacheSide &s, const Tile &t, int tp, uint32_t kmax, int S,
+// The ids of a thread's two tokens, as stored: one load per token (the S id bytes of a token
+// are contiguous; 1, 2 or 4 of them are one load when the array is aligned for it) and no
+// arithmetic on what it returns.  The clamp to the table's last row is applied where the id is
+// used (load_raw): applied here, every tile waited for the ids right after requesting them,
+// and, the load counter being in order, for the codes, scales and rows requested just before.
+// A token that does not exist reads the unit's token 0 instead (it exists), so that the load
+// needs no branch; load_raw never uses such an id.
+__device__ __forceinline__ void load_ids(const CacheSide &s, const Tile &t, int tp, int S,
                                          int wide, uint32_t id[2]) {
+    const bool al = ((uintptr_t)s.ids & (uintptr_t)(S - 1)) == 0;
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
-        const int n = t.t0 + 2 * tp + e;
-        id[e] = 0u;
-        if (t.valid && n < t.cend) {
-            if (wide) id[e] = min(load_id(s.ids, n, 1), kmax);
-            else
-                for (int st = 0; st < S; ++st)
-                    id[e] |= min((uint32_t)s.ids[(int64_t)n * S + st], kmax) << (8 * st);
+        const int n0 = t.t0 + 2 * tp + e;
+        const int64_t n = (t.valid && n0 < t.cend) ? n0 : 0;
+        if (wide) id[e] = load_id(s.ids, n, 1);
+        else if (S == 1) id[e] = s.ids[n];
+        else if (S == 2 && al) id[e] = *reinterpret_cast<const uint16_t *>(s.ids + n * 2);
+        else if (S == 4 && al) id[e] = *reinterpret_cast<const uint32_t *>(s.ids + n * 4);
+        else {
+            id[e] = 0u;
+            for (int st = 0; st < S; ++st) id[e] |= (uint32_t)s.ids[n * S + st] << (8 * st);
         }
     }
 }
@@ -123,6 +133,7 @@ template <int T_, int TM, int SM, int FMT>
 __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int tp, int c8, int T,
                                          int G, int g, int K, int S, const uint32_t id[2], Raw<TM, SM> &r) {
     const bf16_t *cent = s.cent + (int64_t)t.chunk * S * K * kHeadDim;      // [S][K][d] of this chunk
+    const uint32_t kmax = (uint32_t)K - 1u;        // ids are clamped to the table's last row
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
         const int n = t.t0 + 2 * tp + e;
@@ -148,17 +159,17 @@ __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int 
             for (int k = 0; k < TM; ++k)
                 if (k < T) { r.code[e][k] = cp[k * 16]; r.sc[e][k] = sp[k * G]; }
             if (SM == 1) {
-                r.cen[e] = *reinterpret_cast<const uint4 *>(cent + (int64_t)id[e] * kHeadDim + c8 * 8);
+                r.cen[e] = *reinterpret_cast<const uint4 *>(cent + (int64_t)min(id[e], kmax) * kHeadDim + c8 * 8);
             } else if (SM > 1) {
 #pragma unroll
                 for (int st = 0; st < SM; ++st)
                     r.rows[e][st] = *reinterpret_cast<const uint4 *>(
-                        cent + ((int64_t)st * K + ((id[e] >> (8 * st)) & 0xffu)) * kHeadDim + c8 * 8);
+                        cent + ((int64_t)st * K + min((id[e] >> (8 * st)) & 0xffu, kmax)) * kHeadDim + c8 * 8);
             } else {
                 for (int st = 0; st < S; ++st) {
                     float row[8];
                     unpack_bf16x8(*reinterpret_cast<const uint4 *>(
-                                      cent + ((int64_t)st * K + ((id[e] >> (8 * st)) & 0xffu)) * kHeadDim + c8 * 8), row);
+                                      cent + ((int64_t)st * K + min((id[e] >> (8 * st)) & 0xffu, kmax)) * kHeadDim + c8 * 8), row);
 #pragma unroll
                     for (int i = 0; i < 8; ++i) r.ci[e][i] = st ? r.ci[e][i] + row[i] : row[i];
                 }
@@ -287,7 +298,6 @@ void attn_kernel_direct(AttnArgs a) {
     const int T = T_ > 0 ? T_ : a.T, B = a.B, K = a.K;
     const int S = SM > 0 ? SM : a.S;
     const int G = kHeadDim / B;
-    const uint32_t kmax = (uint32_t)K - 1u;
 
     CacheSide ks, vs;
     constexpr int kCodeBytes = (FMT & kFmtInt4) ? 64 : 32, kScaleBytes = (FMT & kFmtE4M3) ? 1 : 2;
@@ -355,13 +365,13 @@ void attn_kernel_direct(AttnArgs a) {
     Tile nn = nxt.valid ? next_tile(sp, nxt) : nxt;
     uint32_t idk[2], idv[2];
     Raw<TM, SM> rk, rv;
-    load_ids(ks, cur, tp, kmax, S, a.id_wide, idk);
-    load_ids(vs, cur, tp, kmax, S, a.id_wide, idv);
+    load_ids(ks, cur, tp, S, a.id_wide, idk);
+    load_ids(vs, cur, tp, S, a.id_wide, idv);
     load_raw<T_, TM, SM, FMT>(ks, cur, tp, c8, T, G, g, K, S, idk, rk);
     load_raw<T_, TM, SM, FMT>(vs, cur, tp, c8, T, G, g, K, S, idv, rv);
     if (ROPE) load_rope(a.rope, cur, tp, c8, rp);
-    load_ids(ks, nxt, tp, kmax, S, a.id_wide, idk);
-    load_ids(vs, nxt, tp, kmax, S, a.id_wide, idv);
+    load_ids(ks, nxt, tp, S, a.id_wide, idk);
+    load_ids(vs, nxt, tp, S, a.id_wide, idv);
     decode_to_lds(rk, rv, 0);
     __syncthreads();
 
@@ -372,8 +382,8 @@ void attn_kernel_direct(AttnArgs a) {
             load_raw<T_, TM, SM, FMT>(ks, nxt, tp, c8, T, G, g, K, S, idk, rk);
             load_raw<T_, TM, SM, FMT>(vs, nxt, tp, c8, T, G, g, K, S, idv, rv);
             if (ROPE) load_rope(a.rope, nxt, tp, c8, rp);
-            load_ids(ks, nn, tp, kmax, S, a.id_wide, idk);
-            load_ids(vs, nn, tp, kmax, S, a.id_wide, idv);
+            load_ids(ks, nn, tp, S, a.id_wide, idk);
+            load_ids(vs, nn, tp, S, a.id_wide, idv);
         }
         const uint16_t *kt = Kt + buf * kKtElems;
         const uint16_t *vt = Vt + buf * kVtElems;
