@@ -40,6 +40,9 @@
  * With more than 256 centroids (the codebook-size study of Sec. 5, Table 5, goes to K = 512) an id
  * is a 16-bit word: every "uint8_t *ids" argument then points at uint16 data, 2-byte aligned;
  * this form has one smoothing stage only (QVG_ERR_UNSUPPORTED otherwise).
+ * The encoder writes ids below K only; a decoder (qvg_decode*, qvg_attn_decode*) that meets a
+ * larger one, in a cache it did not write, reads the table's last row for it instead of memory
+ * beyond the table.
  * A cache of several chunks concatenates ids/codes/scales along N and keeps one
  * centroid table per chunk: centroids [n_chunks][K][d].
  *

@@ -248,3 +248,41 @@ def test_attention_with_a_prefix_length_per_query(L, T, Bg, S, bits, fmt, rope):
     torch.cuda.synchronize()
     for h in range(H):
         assert P.attn_tolerance_ok(P.to_np_u16(a[h]), bits_to_f32(P.to_np_u16(b[h])).astype(np.float64))[0]
+
+
+@pytest.mark.parametrize("L,T,Bg,S,bits,fmt", [(520, 2, 32, 1, 2, B.SCALE_F16),      # staged kernel
+                                               (516, 3, 64, 1, 2, B.SCALE_F16),      # general kernel, one table per chunk
+                                               (260, 1, 16, 4, 2, B.SCALE_E4M3)])    # general kernel, four tables per chunk
+def test_ids_beyond_the_table_read_its_last_row(L, T, Bg, S, bits, fmt):
+    """A cache the library did not write may hold ids >= K (a byte holds up to 255, K is 64
+    here).  Decode and attention must treat such an id as K - 1, the table's last row, and not
+    read past the table: the outputs equal, bit for bit, those of the same cache with these ids
+    set to K - 1, and that cache's attention agrees with the oracle."""
+    H, K, Nq = 2, 64, 200
+    filled = 2 * L + 77
+    kc, vc = _filled_caches(H, L, 3, filled, K, Bg, T, S=S, bits=bits, fmt=fmt)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    bad_k = (torch.rand(kc.ids.shape, generator=g) < 0.05).to(DEV)
+    bad_v = (torch.rand(vc.ids.shape, generator=g) < 0.05).to(DEV)
+    big = torch.randint(K, 256, kc.ids.shape, generator=g, dtype=torch.int32).to(torch.uint8).to(DEV)
+    ids_k, ids_v = kc.ids.clone(), vc.ids.clone()
+
+    kc.ids.copy_(torch.where(bad_k, torch.full_like(ids_k, K - 1), ids_k))
+    vc.ids.copy_(torch.where(bad_v, torch.full_like(ids_v, K - 1), ids_v))
+    khat, vhat = B.decode(kc, n_tokens=filled), B.decode(vc, n_tokens=filled)
+    out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled)
+    torch.cuda.synchronize()
+    for h in range(H):
+        _check_against_oracle(q, out, lse, P.to_np_u16(khat[h]), P.to_np_u16(vhat[h]), h)
+
+    kc.ids.copy_(torch.where(bad_k, big, ids_k))
+    vc.ids.copy_(torch.where(bad_v, big, ids_v))
+    assert int((kc.ids >= K).sum()) > 0 and int((vc.ids >= K).sum()) > 0
+    khat2, vhat2 = B.decode(kc, n_tokens=filled), B.decode(vc, n_tokens=filled)
+    out2, lse2 = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled)
+    torch.cuda.synchronize()
+    assert torch.equal(khat2.view(torch.int16), khat.view(torch.int16))
+    assert torch.equal(vhat2.view(torch.int16), vhat.view(torch.int16))
+    assert torch.equal(out2.view(torch.int16), out.view(torch.int16))
+    assert torch.equal(lse2, lse)
