@@ -286,3 +286,35 @@ def test_ids_beyond_the_table_read_its_last_row(L, T, Bg, S, bits, fmt):
     assert torch.equal(vhat2.view(torch.int16), vhat.view(torch.int16))
     assert torch.equal(out2.view(torch.int16), out.view(torch.int16))
     assert torch.equal(lse2, lse)
+
+
+@pytest.mark.parametrize("S", [2, 4])
+def test_id_arrays_at_any_byte_address(S):
+    """Byte ids need no alignment (include/qvg.h asks for none): with several smoothing stages a
+    token's S id bytes are read as one word when the array allows it and byte by byte otherwise.
+    The same caches with their id arrays moved to an odd address must decode and attend to the
+    same bits."""
+    import dataclasses
+    H, K, L, T, Bg, Nq = 2, 64, 260, 1, 16, 200
+    filled = 2 * L + 31
+    kc, vc = _filled_caches(H, L, 3, filled, K, Bg, T, S=S, bits=2, fmt=B.SCALE_E4M3)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    khat, vhat = B.decode(kc, n_tokens=filled), B.decode(vc, n_tokens=filled)
+    out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled)
+
+    def moved(c):
+        buf = torch.zeros(c.ids.numel() + 1, dtype=torch.uint8, device=DEV)
+        ids = buf[1:].view(c.ids.shape)
+        ids.copy_(c.ids)
+        assert ids.data_ptr() % 2 == 1 and ids.is_contiguous()
+        return dataclasses.replace(c, ids=ids)
+    kc2, vc2 = moved(kc), moved(vc)
+    khat2, vhat2 = B.decode(kc2, n_tokens=filled), B.decode(vc2, n_tokens=filled)
+    out2, lse2 = B.attn_decode(q, kc2, vc2, want_lse=True, n_kv=filled)
+    torch.cuda.synchronize()
+    assert torch.equal(khat2.view(torch.int16), khat.view(torch.int16))
+    assert torch.equal(vhat2.view(torch.int16), vhat.view(torch.int16))
+    assert torch.equal(out2.view(torch.int16), out.view(torch.int16))
+    assert torch.equal(lse2, lse)
+    for h in range(H):
+        _check_against_oracle(q, out2, lse2, P.to_np_u16(khat2[h]), P.to_np_u16(vhat2[h]), h)
