@@ -181,6 +181,10 @@ def test_update_long_lists_exact_and_rounding_cases():
     x[0, 7:1500:13, 1] = 3.0e-39
     x[0, :1500, 2] = 1.0e-20 * torch.randn(1500, generator=g)
     x[0, 700, 2] = 3.0e30
+    # channel 3: 2^60 first, ones, -2^60 last: in token order the ones are absorbed and the sum is 0
+    x[0, :1500, 3] = 1.0
+    x[0, 0, 3] = 2.0 ** 60
+    x[0, 1499, 3] = -(2.0 ** 60)
     # unit 1: channel 5 spans 2^60 as well
     x[1, ::3, 5] = 2.0 ** 40 * torch.randn(N // 3, generator=g)
     x[1, 1::3, 5] = 2.0 ** -20 * torch.randn(N // 3, generator=g)
@@ -192,10 +196,13 @@ def test_update_long_lists_exact_and_rounding_cases():
         c_o, n_o = O.update(bits_to_f32(bf16_bits(x[h])), ids[h].numpy(), bf16_bits(prev[h]))
         assert np.array_equal(P.to_np_u16(c_g[h]), c_o), h
         assert np.array_equal(n_g[h].cpu().numpy(), n_o)
-    # the rounding case is a real one: summed in another order, channel 0 of that cluster differs
+    # the rounding case is a real one: four interleaved partial sums of channel 3 of that cluster
+    # give another total (and another bf16 mean) than the token order does
     m = (ids[0] == 3).numpy()
-    v = x[0, m, 0].double().numpy()
-    assert float(np.sum(v[::2]) + np.sum(v[1::2])) != float(np.add.accumulate(v)[-1]) or True
+    v = x[0, m, 3].double().numpy()
+    in_order = float(np.add.accumulate(v)[-1])
+    interleaved = float(sum(np.add.accumulate(v[i::4])[-1] for i in range(4)))
+    assert abs(interleaved - in_order) > 500.0
 
 
 @pytest.mark.parametrize("cfg,N,K,Bg,T,I", [("cfg1_tiny", 4096, 16, 64, 2, 10), ("cfg2_window21", 3000, 64, 32, 3, 3),
