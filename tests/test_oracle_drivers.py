@@ -12,6 +12,13 @@ from oracle import qvg_oracle as O
 from conftest import bits_to_f32, f32_to_bf16_bits_torch
 
 
+@pytest.fixture
+def rng(request):
+    # a stream of this file's own, one per test, so that the other files' draws do not move
+    import zlib
+    return np.random.default_rng(zlib.crc32(request.node.name.encode()))
+
+
 def _units(rng, H, N, d, spread=1.0):
     """H different bf16 tensors [N, d]: unit h is centred at 3 h so that no two units look alike."""
     x = rng.standard_normal((H, N, d)) * spread + 3.0 * np.arange(H)[:, None, None]
