@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the QVG KV-cache codec hot path on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2_window21]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5_long]
 
 One step = encode the new chunk + decode the whole cache + fused dequant-attention
-(paper_2602_02958_amd/workload.py).  Prints ONE JSON line.  `value` is the bf16-equivalent
-KV throughput of the whole step: 256 B x (vectors encoded + vectors decoded + vectors read by
-the fused attention) / step time, inputs resident in HBM.  Per-phase rates, the roofline of
-the dominant kernel (and of the other two phases), a large-shape supplement that does not fit
-the Infinity Cache, and the CPU oracle timed on the host cores are in the same line.
+(paper_2602_02958_amd/workload.py) on ONE layer of the workload at its full cache length; the
+default workload is the largest configuration (cfg5_long: 24 units = 12 heads x K,V, 160 chunks of
+4680 tokens = 748800 cached tokens per head, 4680 queries).  Prints ONE JSON line.  `value` is
+the bf16-equivalent KV throughput of the whole step: 256 B x (vectors encoded + vectors decoded +
+vectors read by the fused attention) / step time, inputs resident in HBM.  Per-phase rates with
+their HBM fractions, the roofline of the dominant kernel, batches of all layers' chunks that fill
+the chip (the shapes the HBM target of the encoder is stated for), the smaller window
+configuration, and the CPU oracle timed on the host cores are in the same line.
 """
 from __future__ import annotations
 
@@ -25,9 +28,23 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 # HBM bytes per launch read off rocprofv3 counters (FETCH_SIZE + WRITE_SIZE, each scaled by what the
-# same counter reads for a plain 1 GiB device copy); the runs are summarised under profiles/.
-# None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {("cfg2_window21", "attn"): 211390939}   # profiles/attn_cfg2_window21_hbm_counters.txt
+# same counter reads for a plain 1 GiB device copy): written by paper_2602_02958_amd/profsum.py
+# from a profiling run of `bench.py --only <part>`, one line per (workload, part):
+#   <workload> <part> fetch_bytes=<int> write_bytes=<int>
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic(workload, part):
+    """Counter bytes per launch of one part (attn / decode / encode_I0 ...) on a workload, or None."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            t = line.split()
+            if len(t) >= 4 and t[0] == workload and t[1] == part:
+                kv = dict(x.split("=") for x in t[2:] if "=" in x)
+                return int(kv["fetch_bytes"]) + int(kv["write_bytes"])
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
 
 
 def _event_ms(fn, reps):
@@ -50,11 +67,14 @@ def _format_bytes(wl, units, tokens, chunk):
     return units * (tokens * per_tok + tables)
 
 
-def cpu_baseline(wl, budget_s=12.0):
+def cpu_baseline(wl, budget_s=10.0, max_chunks=16):
     """The oracle as it stands, on the host cores, on a bounded sample of the same step: all units
-    encode one chunk, a cache of the workload's length is decoded (the encoded chunk repeated: the
-    oracle's decode cost does not depend on the content), and a subset of the queries attends over
-    the decoded cache.  The number of queries is chosen from a 16-query trial to fill budget_s."""
+    encode one chunk; a cache of min(the workload's length, max_chunks chunks) is decoded (the
+    encoded chunk repeated: the oracle's decode cost does not depend on the content); a subset of
+    the queries attends over that decoded cache.  The number of queries is chosen from an 8-query
+    trial to fill budget_s.  `value` is the step's own definition applied to the sample:
+    256 B x (vectors encoded + decoded + read by attention, the last scaled by the share of the
+    query batch) / time."""
     import numpy as np
     import torch
     from oracle import qvg_oracle as O
@@ -63,7 +83,7 @@ def cpu_baseline(wl, budget_s=12.0):
     heads = wl.heads
     units = 2 * heads
     n_enc = wl.chunk
-    n_chunks = wl.n_chunks
+    n_chunks = min(wl.n_chunks, max_chunks)
     xk = synth.MixtureStream(wl, heads, 0).next_chunk(n_enc)
     xv = synth.MixtureStream(wl, heads, 1).next_chunk(n_enc)
     x = torch.cat([xk, xv], 0)
@@ -80,9 +100,9 @@ def cpu_baseline(wl, budget_s=12.0):
     n_tok = dec.shape[1]
     qall = synth.queries(wl, heads, wl.n_queries).view(torch.int16).numpy().view(np.uint16)
     t0 = time.perf_counter()
-    O.attention_batch(np.ascontiguousarray(qall[:, :16]), dec[:heads], dec[heads:])
+    O.attention_batch(np.ascontiguousarray(qall[:, :8]), dec[:heads], dec[heads:])
     t_trial = time.perf_counter() - t0
-    nq = int(min(wl.n_queries, max(16, 16 * budget_s / max(t_trial, 1e-3))))
+    nq = int(min(wl.n_queries, max(8, 8 * budget_s / max(t_trial, 1e-3))))
     t0 = time.perf_counter()
     O.attention_batch(np.ascontiguousarray(qall[:, :nq]), dec[:heads], dec[heads:])
     t_att = time.perf_counter() - t0
@@ -94,9 +114,9 @@ def cpu_baseline(wl, budget_s=12.0):
         "value": round(total_vec * 256 / total_t / 1e9, 6), "unit": "GB/s", "cores": cores,
         "kind": "oracle",
         "sample": (f"{units} units: encode of one {n_enc}-token chunk (I={wl.kmeans_iters_warm}) {t_enc:.2f}s, "
-                   f"decode of {n_tok} tokens {t_dec:.2f}s, attention of {nq} of {wl.n_queries} queries x "
-                   f"{heads} heads over {n_tok} tokens {t_att:.2f}s (its vectors counted as {nq}/{wl.n_queries} "
-                   f"of a step's)"),
+                   f"decode of {n_tok} of {wl.tokens_per_layer} cached tokens {t_dec:.2f}s, attention of {nq} of "
+                   f"{wl.n_queries} queries x {heads} heads over those {n_tok} tokens {t_att:.2f}s (its vectors "
+                   f"counted as {nq}/{wl.n_queries} of a pass over them)"),
         "encode_GBps": round(vec_enc * 256 / t_enc / 1e9, 6),
         "decode_GBps": round(vec_dec * 256 / t_dec / 1e9, 6),
         "attn_q_tokens_per_s": round(heads * nq / t_att, 3),
@@ -122,24 +142,27 @@ def _large_decode_setup(torch, B, wl, dev):
     return big, outbuf, units, n
 
 
-def large_supplement(torch, B, synth, CONFIGS):
-    """cfg3-shaped batches that exceed the 256 MB Infinity Cache: decode of 3 layers' full cache
-    and single-pass / warm encode of one chunk of all 30 layers."""
-    wl = CONFIGS["cfg3_dit_small"]
-    dev = "cuda"
-    out = {"workload": "cfg3_dit_small"}
-    # ---- encode: one chunk, all layers x heads x (K,V) = 720 units
+def _large_encode_setup(torch, B, synth, wl, dev):
+    """One chunk of every layer x head x (K, V) of the workload (720 units for the 30 x 12 models):
+    the batch that fills the chip several times over and does not fit the Infinity Cache."""
     units = 2 * wl.layers * wl.heads
-    st = synth.MixtureStream(wl, units, 0, dev)
-    x = st.next_chunk(wl.chunk)
+    x = synth.MixtureStream(wl, units, 0, dev).next_chunk(wl.chunk)
     init = synth.cold_start_centroids(x, wl.n_clusters)
     cache = B.alloc_cache(units, wl.chunk, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
     p = B.make_params(units, wl.n_clusters, wl.group_size, wl.n_stages, wl.kmeans_iters_cold)
     ws = torch.empty(B.workspace_bytes(p, B.ENTRY_ENCODE, wl.chunk), dtype=torch.uint8, device=dev)
-    B.encode_chunk(x, init, wl.group_size, wl.n_stages, wl.kmeans_iters_cold, cache=cache, workspace=ws)
+    B.encode_chunk(x, init, wl.group_size, wl.n_stages, 5, cache=cache, workspace=ws)
     warm = cache.centroids[:, 0].contiguous()
+    return units, x, init, warm, cache, ws
+
+
+def large_encode_supplement(torch, B, synth, wl):
+    """Single-pass / warm / cold encode of one chunk of all layers of a workload."""
+    dev = "cuda"
+    units, x, init, warm, cache, ws = _large_encode_setup(torch, B, synth, wl, dev)
     vec = units * wl.chunk
     alg = vec * 256 + _format_bytes(wl, units, wl.chunk, wl.chunk)
+    out = {"workload": wl.name, "units": units, "tokens": wl.chunk, "algorithmic_bytes": int(alg)}
     for name, iters in (("encode_I0", 0), ("encode_I3", 3), ("encode_I10", 10)):
         fn = lambda: B.encode_chunk(x, warm if iters < 10 else init, wl.group_size, wl.n_stages, iters,
                                     cache=cache, workspace=ws)
@@ -149,8 +172,17 @@ def large_supplement(torch, B, synth, CONFIGS):
         out[name] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(vec * 256 / ms / 1e6, 1),
                      "hbm_GBps_algorithmic": round(alg / ms / 1e6, 1),
                      "hbm_frac": round(alg / ms / 1e6 / HBM_PEAK_GBPS, 4),
-                     "assign_TFLOPs": round(flops / ms / 1e9, 1)}
-    del x, cache, ws
+                     "assign_TFLOPs": round(flops / ms / 1e9, 1),
+                     "traffic": measured_traffic(wl.name, "large_" + name)}
+    return out
+
+
+def large_supplement(torch, B, synth, CONFIGS):
+    """cfg3-shaped batches that exceed the 256 MB Infinity Cache: decode of 3 layers' full cache,
+    encode of one chunk of all 30 layers, attention of one layer."""
+    wl = CONFIGS["cfg3_dit_small"]
+    dev = "cuda"
+    out = large_encode_supplement(torch, B, synth, wl)
     # ---- decode: 3 layers' full cache = 72 units x 126360 tokens
     big, outbuf, units, n = _large_decode_setup(torch, B, wl, dev)
     fn = lambda: B.decode(big, out=outbuf)
@@ -160,7 +192,8 @@ def large_supplement(torch, B, synth, CONFIGS):
     alg = vec * 256 + _format_bytes(wl, units, n, wl.chunk)
     out["decode"] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(vec * 256 / ms / 1e6, 1),
                      "hbm_GBps_algorithmic": round(alg / ms / 1e6, 1),
-                     "hbm_frac": round(alg / ms / 1e6 / HBM_PEAK_GBPS, 4), "units": units, "tokens": n}
+                     "hbm_frac": round(alg / ms / 1e6 / HBM_PEAK_GBPS, 4), "units": units, "tokens": n,
+                     "traffic": measured_traffic(wl.name, "large_decode")}
     del outbuf
     # ---- fused attention: one layer, 4680 queries of 12 heads over the 126360-token cache
     hd = wl.heads
@@ -413,31 +446,24 @@ def integration_supplement(torch, B, s):
 def run_only(args, torch, B, synth, workload, CONFIGS):
     """One part of the path, repeated: what rocprofv3 is pointed at."""
     dev = "cuda"
+    wl = CONFIGS[args.workload]
     if args.only == "copy":
         n = 1 << 30
         a = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
         b = torch.empty_like(a)
         fn = lambda: b.copy_(a)
         nbytes = 2 * n
-    elif args.only in ("large_decode", "large_encode"):
+    elif args.only == "large_decode":
         wl = CONFIGS["cfg3_dit_small"]
-        if args.only == "large_decode":
-            big, outbuf, units, n = _large_decode_setup(torch, B, wl, dev)
-            fn = lambda: B.decode(big, out=outbuf)
-            nbytes = units * n * 256 + _format_bytes(wl, units, n, wl.chunk)
-        else:
-            units = 2 * wl.layers * wl.heads
-            x = synth.MixtureStream(wl, units, 0, dev).next_chunk(wl.chunk)
-            init = synth.cold_start_centroids(x, wl.n_clusters)
-            cache = B.alloc_cache(units, wl.chunk, wl.chunk, wl.n_clusters, wl.group_size, wl.n_stages, wl.head_dim, dev)
-            p = B.make_params(units, wl.n_clusters, wl.group_size, wl.n_stages, max(args.iters, 1))
-            ws = torch.empty(B.workspace_bytes(p, B.ENTRY_ENCODE, wl.chunk), dtype=torch.uint8, device=dev)
-            B.encode_chunk(x, init, wl.group_size, wl.n_stages, 5, cache=cache, workspace=ws)
-            warm = cache.centroids[:, 0].contiguous()
-            fn = lambda: B.encode_chunk(x, warm, wl.group_size, wl.n_stages, args.iters, cache=cache, workspace=ws)
-            nbytes = units * wl.chunk * 256 + _format_bytes(wl, units, wl.chunk, wl.chunk)
+        big, outbuf, units, n = _large_decode_setup(torch, B, wl, dev)
+        fn = lambda: B.decode(big, out=outbuf)
+        nbytes = units * n * 256 + _format_bytes(wl, units, n, wl.chunk)
+    elif args.only == "large_encode":
+        # one chunk of all layers of --workload (cfg3_dit_small and cfg5_long: 720 units)
+        units, x, init, warm, cache, ws = _large_encode_setup(torch, B, synth, wl, dev)
+        fn = lambda: B.encode_chunk(x, warm, wl.group_size, wl.n_stages, args.iters, cache=cache, workspace=ws)
+        nbytes = units * wl.chunk * 256 + _format_bytes(wl, units, wl.chunk, wl.chunk)
     else:
-        wl = CONFIGS[args.workload]
         s = workload.build_streaming(wl)
         workload.step(s)
         vec = workload.vectors_per_step(s)
@@ -448,15 +474,85 @@ def run_only(args, torch, B, synth, workload, CONFIGS):
         elif args.only == "encode":
             fn = lambda: workload.step_encode(s, iters=args.iters)
             nbytes = vec["encode"] * 256 + _format_bytes(wl, units, s.x_new.shape[1], wl.chunk)
+        elif args.only == "step":
+            fn = lambda: workload.step(s)
+            nbytes = 0
         else:
             fn = lambda: workload.step_attn(s)
-            nbytes = _format_bytes(wl, units, n_tok, wl.chunk)
+            nbytes = _format_bytes(wl, units, n_tok, wl.chunk) + 2 * wl.heads * wl.n_queries * wl.head_dim * 2
     for _ in range(max(args.warmup, 1)):
         fn()
     torch.cuda.synchronize()
     ms = _event_ms(fn, args.steps)
-    return {"only": args.only, "ms": round(ms, 5), "algorithmic_bytes": int(nbytes),
+    return {"only": args.only, "workload": wl.name, "ms": round(ms, 5), "algorithmic_bytes": int(nbytes),
             "GBps_algorithmic": round(nbytes / ms / 1e6, 1), "launches": args.steps + max(args.warmup, 1)}
+
+
+def measure_step(torch, B, workload, wl, steps, warmup):
+    """Build one layer of `wl` at its full cache length, time `steps` steps after `warmup`, then each
+    phase on its own.  -> (streaming state, ms per step, ms of the attention launch inside the
+    timed steps, vectors per step, phases dict)."""
+    s = workload.build_streaming(wl)
+    torch.cuda.synchronize()
+    for _ in range(warmup):
+        workload.step(s)
+    torch.cuda.synchronize()
+    # HIP events around the dominant kernel's launch in every timed step, on the stream the library
+    # launches on (torch's current stream)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        workload.step_encode(s)
+        workload.step_decode(s)
+        ev[i][0].record()
+        workload.step_attn(s)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+    ms_att_in_step = sum(a.elapsed_time(b) for a, b in ev) / max(steps, 1)
+    vec = workload.vectors_per_step(s)
+
+    # ---- per-phase timing (HIP events on the launch stream) -----------------
+    reps = max(5, steps)
+    ms_dec = _event_ms(lambda: workload.step_decode(s), reps)
+    ms_att = _event_ms(lambda: workload.step_attn(s), max(3, steps // 4))
+    ms_enc = {i: _event_ms(lambda i=i: workload.step_encode(s, iters=i), reps)
+              for i in (0, wl.kmeans_iters_warm, wl.kmeans_iters_cold)}
+    units = 2 * wl.heads
+    n_tok = s.cache.ids.shape[1]
+    n_new = s.x_new.shape[1]
+    stored = _format_bytes(wl, units, n_tok, wl.chunk)
+    dec_alg = vec["decode"] * 256 + stored
+    enc_alg = vec["encode"] * 256 + _format_bytes(wl, units, n_new, wl.chunk)
+    att_flops = 4.0 * wl.n_queries * n_tok * wl.head_dim * wl.heads
+    note = ""
+    if dec_alg < 2.6e8:
+        note = "cache-resident size (compressed + bf16 < 256 MB Infinity Cache)"
+    elif stored < 2.6e8:
+        note = ("the compressed cache (%d MB) fits the 256 MB Infinity Cache and is re-read from it by every "
+                "repetition" % (stored >> 20))
+    phases = {
+        "decode": {"ms": round(ms_dec, 4), "GBps_bf16_equiv": round(vec["decode"] * 256 / ms_dec / 1e6, 1),
+                   "algorithmic_bytes": int(dec_alg),
+                   "hbm_GBps_algorithmic": round(dec_alg / ms_dec / 1e6, 1),
+                   "hbm_frac": round(dec_alg / ms_dec / 1e6 / HBM_PEAK_GBPS, 4),
+                   "traffic": measured_traffic(wl.name, "decode"), "note": note},
+        "attn": {"ms": round(ms_att, 4), "q_tokens_per_s": round(wl.n_queries * wl.heads / ms_att * 1e3, 1),
+                 "cache_tokens_per_s": round(n_tok * wl.heads / ms_att * 1e3, 1),
+                 "TFLOPs": round(att_flops / ms_att / 1e9, 2),
+                 "mfma_frac": round(att_flops / ms_att / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                 "flops_per_launch": att_flops,
+                 "algorithmic_bytes": int(stored + 2 * wl.heads * wl.n_queries * wl.head_dim * 2),
+                 "traffic": measured_traffic(wl.name, "attn")},
+    }
+    for i, ms in ms_enc.items():
+        phases[f"encode_I{i}"] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(vec["encode"] * 256 / ms / 1e6, 1),
+                                  "algorithmic_bytes": int(enc_alg),
+                                  "hbm_GBps_algorithmic": round(enc_alg / ms / 1e6, 1),
+                                  "hbm_frac": round(enc_alg / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                                  "traffic": measured_traffic(wl.name, f"encode_I{i}")}
+    return s, ms_step, ms_att_in_step, vec, phases
 
 
 def main():
@@ -464,14 +560,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2_window21")
+    ap.add_argument("--workload", default="cfg5_long")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large", action="store_true")
     ap.add_argument("--only", default=None,
-                    choices=["decode", "encode", "attn", "copy", "large_decode", "large_encode", "presets", "long"],
+                    choices=["decode", "encode", "attn", "step", "copy", "large_decode", "large_encode", "presets", "long"],
                     help="profiling aid: run just this part --steps times and print a short JSON "
                          "(copy = a plain device copy of 1 GiB, the reference the HBM counters "
-                         "are scaled by)")
+                         "are scaled by; large_encode = one chunk of all layers of --workload)")
     ap.add_argument("--iters", type=int, default=0, help="Lloyd iterations for --only encode / large_encode")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -492,81 +588,39 @@ def main():
         print(json.dumps(long_supplement(torch, B, synth, CONFIGS, "cfg4_dit_large")))
         return
     if args.only == "presets":
+        w2 = CONFIGS["cfg2_window21"]
         print(json.dumps(presets_supplement(torch, B, synth, CONFIGS)))
         print(json.dumps(codebook_supplement(torch, B, synth, CONFIGS)))
-        print(json.dumps(warm_start_supplement(torch, B, synth, wl)))
+        print(json.dumps(warm_start_supplement(torch, B, synth, w2)))
         return
     if args.only:
         print(json.dumps(run_only(args, torch, B, synth, workload, CONFIGS)))
         return
-    s = workload.build_streaming(wl)
-    torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
-        workload.step(s)
-    torch.cuda.synchronize()
-    # HIP events around the dominant kernel's launch in every timed step, on the stream the library
-    # launches on (torch's current stream)
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        workload.step_encode(s)
-        workload.step_decode(s)
-        ev[i][0].record()
-        workload.step_attn(s)
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    ms_att_in_step = sum(a.elapsed_time(b) for a, b in ev) / max(args.steps, 1)
-
-    vec = workload.vectors_per_step(s)
+    s, ms_step, ms_att_in_step, vec, phases = measure_step(torch, B, workload, wl, args.steps, args.warmup)
     total_vec = vec["encode"] + vec["decode"] + vec["attn"]
     value = total_vec * 256 / ms_step / 1e6          # GB/s
-
-    # ---- per-phase timing (HIP events on the launch stream) -----------------
-    reps = max(5, args.steps)
-    ms_dec = _event_ms(lambda: workload.step_decode(s), reps)
-    ms_att = _event_ms(lambda: workload.step_attn(s), max(3, args.steps // 2))
-    ms_enc = {i: _event_ms(lambda i=i: workload.step_encode(s, iters=i), reps) for i in (0, wl.kmeans_iters_warm, wl.kmeans_iters_cold)}
     units = 2 * wl.heads
     n_tok = s.cache.ids.shape[1]
     n_new = s.x_new.shape[1]
-    dec_alg = vec["decode"] * 256 + _format_bytes(wl, units, n_tok, wl.chunk)
-    enc_alg = vec["encode"] * 256 + _format_bytes(wl, units, n_new, wl.chunk)
-    att_flops = 4.0 * wl.n_queries * n_tok * wl.head_dim * wl.heads
-    phases = {
-        "decode": {"ms": round(ms_dec, 4), "GBps_bf16_equiv": round(vec["decode"] * 256 / ms_dec / 1e6, 1),
-                   "hbm_GBps_algorithmic": round(dec_alg / ms_dec / 1e6, 1),
-                   "hbm_frac": round(dec_alg / ms_dec / 1e6 / HBM_PEAK_GBPS, 4),
-                   "note": ("cache-resident size (compressed + bf16 < 256 MB Infinity Cache)" if dec_alg < 2.6e8 else
-                            "the compressed cache (%d MB) fits the 256 MB Infinity Cache and is re-read from it by "
-                            "every repetition; the HBM-bound figure is large.decode" % (_format_bytes(wl, units, n_tok, wl.chunk) >> 20)
-                            if _format_bytes(wl, units, n_tok, wl.chunk) < 2.6e8 else "")},
-        "attn": {"ms": round(ms_att, 4), "q_tokens_per_s": round(wl.n_queries * wl.heads / ms_att * 1e3, 1),
-                 "cache_tokens_per_s": round(n_tok * wl.heads / ms_att * 1e3, 1),
-                 "TFLOPs": round(att_flops / ms_att / 1e9, 2),
-                 "mfma_frac": round(att_flops / ms_att / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
-    }
-    for i, ms in ms_enc.items():
-        phases[f"encode_I{i}"] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(vec["encode"] * 256 / ms / 1e6, 1),
-                                  "hbm_GBps_algorithmic": round(enc_alg / ms / 1e6, 1),
-                                  "hbm_frac": round(enc_alg / ms / 1e6 / HBM_PEAK_GBPS, 4)}
     # dominant kernel of the step by time: the fused attention kernel (one launch per step); its
     # duration is the HIP-event average over the timed steps above
+    att_flops = phases["attn"]["flops_per_launch"]
     att_tflops = att_flops / ms_att_in_step / 1e9
     roofline = {"bound": "mfma", "kernel": "attn_kernel_staged", "achieved": round(att_tflops, 2),
                 "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(att_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                 "ms_per_launch": round(ms_att_in_step, 4),
                 "flops_per_launch": att_flops,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, "attn"))}
+                "share_of_step_time": round(ms_att_in_step / ms_step, 4),
+                "traffic": measured_traffic(wl.name, "attn")}
     result = {
         "metric": "KV encode/decode GB/s (bf16-equiv) + fused dequant-attn tokens/s, % HBM roofline",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "units": units, "tokens_in_cache": n_tok, "chunk": n_new,
+        "config": {"workload": wl.name, "layers_in_step": "1 of %d" % wl.layers, "units": units,
+                   "tokens_in_cache": n_tok, "chunk": n_new,
                    "n_queries": wl.n_queries, "K": wl.n_clusters, "T": wl.n_stages, "B": wl.group_size,
                    "kmeans_iters_in_step": wl.kmeans_iters_warm,
                    "step": "encode chunk + decode cache + fused attention",
@@ -574,17 +628,31 @@ def main():
         "roofline": roofline,
         "phases": phases,
     }
+    integ_state = s if wl.name == "cfg2_window21" else None
     if not args.no_large:
+        if integ_state is None:
+            del s
+            torch.cuda.empty_cache()
         try:
+            # the batches the encoder's HBM target is stated for: one chunk of all layers
+            result["large_encode_" + wl.name] = large_encode_supplement(torch, B, synth, wl)
+            torch.cuda.empty_cache()
             result["large"] = large_supplement(torch, B, synth, CONFIGS)
         except torch.OutOfMemoryError as e:     # a smaller card than the one this is written for
             result["large"] = {"error": str(e)[:200]}
-    if not args.no_large:
+        torch.cuda.empty_cache()
+        w2 = CONFIGS["cfg2_window21"]
+        if integ_state is None:
+            s2, ms2, ms2_att, vec2, ph2 = measure_step(torch, B, workload, w2, max(5, args.steps // 2), 2)
+            result["cfg2_window21"] = {"ms_per_step": round(ms2, 4),
+                                       "value": round((vec2["encode"] + vec2["decode"] + vec2["attn"]) * 256 / ms2 / 1e6, 2),
+                                       "attn_ms_in_step": round(ms2_att, 4), "phases": ph2}
+            integ_state = s2
         result["paper_presets"] = presets_supplement(torch, B, synth, CONFIGS)
         result["codebook_size"] = codebook_supplement(torch, B, synth, CONFIGS)
-        result["warm_start"] = warm_start_supplement(torch, B, synth, wl)
-        result["attn_integration"] = integration_supplement(torch, B, s)
-        del s
+        result["warm_start"] = warm_start_supplement(torch, B, synth, w2)
+        result["attn_integration"] = integration_supplement(torch, B, integ_state)
+        del integ_state
         torch.cuda.empty_cache()
         result["long_horizon"] = long_supplement(torch, B, synth, CONFIGS)
         torch.cuda.empty_cache()
