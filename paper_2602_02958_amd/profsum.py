@@ -2,10 +2,13 @@
 
     python -m paper_2602_02958_amd.profsum stats   <dir> [--top N]
     python -m paper_2602_02958_amd.profsum counters <dir> [<dir> ...]
+    python -m paper_2602_02958_amd.profsum derived <kernel substring> <dir> [<dir> ...]
     python -m paper_2602_02958_amd.profsum traffic <workload> <part> <kernel substring>
                                                    <fetch dir> <write dir> <copy fetch dir> <copy write dir>
 
-`stats` prints the kernel table of a `--kernel-trace --stats` run; `counters` prints, per library
+`derived` turns the raw counters of the kernels matching the substring into busy fractions of the
+chip's 1024 SIMDs (GRBM_GUI_ACTIVE is summed over the 8 XCDs; SQ_ACTIVE_INST_* count issue slots of
+4 cycles).  `stats` prints the kernel table of a `--kernel-trace --stats` run; `counters` prints, per library
 kernel, the average of every counter a `--pmc` run collected (counters are summed over the
 dispatch's workgroups); `traffic` prints one line `<workload> <part> fetch_bytes=.. write_bytes=..`
 for profiles/hbm_traffic.txt, scaling FETCH_SIZE / WRITE_SIZE (KiB per dispatch) by what the same
@@ -63,6 +66,37 @@ def counters(dirs):
     return "\n".join(out)
 
 
+def derived(needle, dirs):
+    out = []
+    merged = collections.defaultdict(dict)
+    for d in dirs:
+        for k, cs in counter_means(d).items():
+            if needle in k:
+                merged[k].update({c: m for c, (m, n) in cs.items()})
+    for k, c in sorted(merged.items()):
+        out.append(short(k, 100))
+        if "GRBM_GUI_ACTIVE" not in c:
+            continue
+        cyc = c["GRBM_GUI_ACTIVE"] / 8.0
+        simd = cyc * 1024.0
+        out.append(f"  cycles per launch {cyc:,.0f}  (x 1024 SIMDs = {simd:,.0f} SIMD-cycles)")
+        def pct(name, mul=1.0, label=None):
+            if name in c:
+                out.append(f"  {label or name:<44} {c[name] * mul / simd * 100:6.1f} % of SIMD-cycles   ({name} = {c[name]:,.0f})")
+        pct("SQ_VALU_MFMA_BUSY_CYCLES", 1.0, "matrix pipe busy")
+        pct("SQ_ACTIVE_INST_VALU", 4.0, "VALU issue (incl. MFMA issue slots)")
+        pct("SQ_ACTIVE_INST_SCA", 4.0, "scalar issue")
+        pct("SQ_ACTIVE_INST_LDS", 4.0, "LDS issue")
+        pct("SQ_WAVE_CYCLES", 4.0, "resident wavefronts x 100 %")
+        for name in ("SQ_INSTS_VALU", "SQ_INSTS_SALU", "SQ_INSTS_LDS", "SQ_INSTS_VALU_MFMA_MOPS_BF16",
+                     "SQ_INSTS_VALU_MFMA_MOPS_F16", "SQ_WAIT_INST_ANY", "SQ_WAIT_INST_LDS", "SQ_ACTIVE_INST_ANY"):
+            if name in c:
+                out.append(f"  {name:<44} {c[name]:,.0f}")
+        if "SQ_LDS_BANK_CONFLICT" in c and c.get("SQ_LDS_IDX_ACTIVE"):
+            out.append(f"  LDS bank-conflict cycles / LDS active cycles  {c['SQ_LDS_BANK_CONFLICT'] / c['SQ_LDS_IDX_ACTIVE'] * 100:6.1f} %")
+    return "\n".join(out)
+
+
 def _kib(dir_, counter, needle):
     best = None
     for k, cs in counter_means(dir_).items():
@@ -93,6 +127,8 @@ def main(argv):
         print(stats(argv[1], top))
     elif argv[0] == "counters":
         print(counters(argv[1:]))
+    elif argv[0] == "derived":
+        print(derived(argv[1], argv[2:]))
     elif argv[0] == "traffic":
         print(traffic(*argv[1:8]))
     else:
