@@ -14,7 +14,8 @@
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer, 16-byte aligned, owned by the
- *     caller; the library allocates no device memory and keeps no state.
+ *     caller; the library allocates no device memory and keeps no state (the one exception is
+ *     the static scratch array of qvg_encode_chunk_static, described there).
  *     `const qvg_params*`, `size_t*` are HOST pointers.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     only enqueue work on it and never synchronise.
@@ -69,7 +70,9 @@ typedef enum qvg_status {
     QVG_ERR_UNSUPPORTED = -3,  /* valid in the paper, not built here              */
     QVG_ERR_WORKSPACE = -4,    /* workspace missing or too small                  */
     QVG_ERR_ALIGN = -5,        /* pointer or stride breaks the alignment rule     */
-    QVG_ERR_LAUNCH = -6        /* the HIP runtime refused a launch or a copy      */
+    QVG_ERR_LAUNCH = -6,       /* the HIP runtime refused a launch or a copy      */
+    QVG_ERR_SCRATCH_LIMIT = -7 /* qvg_encode_chunk_static: the sizes need more scratch memory than
+                                  QVG_STATIC_SCRATCH_BYTES                         */
 } qvg_status;
 
 /* Codec parameters, in the paper's symbols (Sec. 4, Sec. 5 "Implementation"). */
@@ -128,6 +131,31 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens,
                      uint8_t *ids_out, uint8_t *codes_out, void *scales_f16_out,
                      int64_t out_stride_head_tokens,
                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * qvg_encode_chunk for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same call without the workspace
+ * arguments.  The workspace lives in a static device array inside the library,
+ * QVG_STATIC_SCRATCH_BYTES per GPU the library runs on, held until the process ends; the call
+ * allocates and frees nothing.  Arguments, results and errors are those of qvg_encode_chunk, plus
+ *   QVG_ERR_SCRATCH_LIMIT  when qvg_workspace_bytes(p, QVG_ENTRY_ENCODE, n_tokens, 0) exceeds
+ *                          QVG_STATIC_SCRATCH_BYTES (nothing was enqueued).  One layer's chunk of
+ *                          every configuration this library is measured on fits (24 units x 4680
+ *                          tokens, K = 256: 3.7 MB; 80 units x 10800 tokens, K = 128: 9 MB);
+ *                          several smoothing stages need two bf16 copies of the chunk and fit only
+ *                          for small chunks.
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap in time (on
+ * different streams, or from different threads on the same stream without ordering) race.  Calls
+ * on one stream are ordered and safe.  The array keeps the previous call's contents; nothing in it
+ * needs to start at zero.
+ */
+#define QVG_STATIC_SCRATCH_BYTES (16u << 20)
+int qvg_encode_chunk_static(const qvg_params *p, int64_t n_tokens,
+                            const void *x_bf16, int64_t stride_head, int64_t stride_token,
+                            const void *init_centroids_bf16, void *centroids_bf16_out,
+                            int64_t cent_out_stride_head,
+                            uint8_t *ids_out, uint8_t *codes_out, void *scales_f16_out,
+                            int64_t out_stride_head_tokens, void *stream);
 
 /*
  * Decode (Sec. 4.2 "dequantization process", Eq. 7; Sec. 4.3 "Dequantization

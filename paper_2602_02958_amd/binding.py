@@ -20,7 +20,7 @@ _lib = None
 ENTRY_ENCODE, ENTRY_DECODE, ENTRY_ATTN, ENTRY_KMEANS_UPDATE, ENTRY_KMEANS_ASSIGN = 0, 1, 2, 3, 4
 SCALE_F16, SCALE_E4M3 = 0, 1
 
-EXPORTS = ["qvg_encode_chunk", "qvg_decode", "qvg_decode_ex", "qvg_attn_decode", "qvg_attn_decode_ex",
+EXPORTS = ["qvg_encode_chunk", "qvg_encode_chunk_static", "qvg_decode", "qvg_decode_ex", "qvg_attn_decode", "qvg_attn_decode_ex",
            "qvg_attn_decode_causal", "qvg_attn_merge",
            "qvg_kmeans_assign",
            "qvg_kmeans_update", "qvg_workspace_bytes", "qvg_compressed_bytes",
@@ -53,6 +53,8 @@ def lib():
         L.qvg_encode_chunk.restype = C.c_int
         L.qvg_encode_chunk.argtypes = [pp, i64, vp, i64, i64, vp, vp, i64, u8p, u8p, vp, i64, vp,
                                        C.c_size_t, vp]
+        L.qvg_encode_chunk_static.restype = C.c_int
+        L.qvg_encode_chunk_static.argtypes = [pp, i64, vp, i64, i64, vp, vp, i64, u8p, u8p, vp, i64, vp]
         L.qvg_decode.restype = C.c_int
         L.qvg_decode.argtypes = [pp, i64, i64, vp, u8p, u8p, vp, vp, i64, i64, vp]
         L.qvg_decode_ex.restype = C.c_int
@@ -174,11 +176,14 @@ def alloc_cache(n_heads, n_tokens, chunk_len, n_clusters, group_size, n_stages, 
 
 
 def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: Encoded | None = None,
-                 chunk_index: int = 0, workspace=None, bits=2, scale_format=SCALE_F16) -> Encoded:
+                 chunk_index: int = 0, workspace=None, bits=2, scale_format=SCALE_F16,
+                 static_scratch: bool = False) -> Encoded:
     """qvg_encode_chunk.  x [H, N, d] bf16, init_centroids [H, K, d] bf16, or [H, S, K, d] for S
     smoothing stages.  Without `cache` a one-chunk cache is allocated and returned; with it, the
     chunk is written in place at chunk_index (tokens chunk_index*chunk_len ...), using the output
-    strides; the cache's formats then apply (bits and scale_format describe a new cache)."""
+    strides; the cache's formats then apply (bits and scale_format describe a new cache).
+    static_scratch: call qvg_encode_chunk_static instead (no workspace: the library's own static
+    scratch array; with a `cache` given the call allocates nothing at all)."""
     sh, st_ = _view3(x, "x")
     H, N, d = x.shape
     _check(init_centroids, torch.bfloat16, "init_centroids")
@@ -200,17 +205,21 @@ def encode_chunk(x, init_centroids, group_size, n_stages, kmeans_iters, cache: E
         raise ValueError("cache was allocated for other parameters")
     p = make_params(H, K, group_size, n_stages, kmeans_iters, head_dim=d, n_smooth_stages=S, bits=bits,
                     scale_format=scale_format)
+    T, G = n_stages, d // group_size
+    outs = (C.c_void_p(cache.centroids.data_ptr() + chunk_index * S * K * d * 2), n_chunks * S * K * d,
+            C.c_void_p(cache.ids.data_ptr() + off * S * cache.ids.element_size()),
+            C.c_void_p(cache.codes.data_ptr() + off * T * (d * bits // 8)),
+            C.c_void_p(cache.scales.data_ptr() + off * T * G * cache.scales.element_size()), n_total)
+    if static_scratch:
+        st = lib().qvg_encode_chunk_static(C.byref(p), N, _ptr(x), sh, st_, _ptr(init_centroids), *outs, _stream())
+        if st != 0:
+            raise QvgError(st, "qvg_encode_chunk_static")
+        return cache
     need = workspace_bytes(p, ENTRY_ENCODE, N)
     if need and (workspace is None or workspace.numel() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
-    T, G = n_stages, d // group_size
-    st = lib().qvg_encode_chunk(
-        C.byref(p), N, _ptr(x), sh, st_, _ptr(init_centroids),
-        C.c_void_p(cache.centroids.data_ptr() + chunk_index * S * K * d * 2), n_chunks * S * K * d,
-        C.c_void_p(cache.ids.data_ptr() + off * S * cache.ids.element_size()),
-        C.c_void_p(cache.codes.data_ptr() + off * T * (d * bits // 8)),
-        C.c_void_p(cache.scales.data_ptr() + off * T * G * cache.scales.element_size()), n_total,
-        _ptr(workspace) if need else None, need, _stream())
+    st = lib().qvg_encode_chunk(C.byref(p), N, _ptr(x), sh, st_, _ptr(init_centroids), *outs,
+                                _ptr(workspace) if need else None, need, _stream())
     if st != 0:
         raise QvgError(st, "qvg_encode_chunk")
     return cache

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "qvg.h"
 #include "qvg_internal.hpp"
 
@@ -91,6 +93,7 @@ const char *qvg_status_string(int status) {
         case QVG_ERR_WORKSPACE: return "workspace missing or too small";
         case QVG_ERR_ALIGN: return "pointer not 16-byte aligned or stride not a multiple of 8 elements";
         case QVG_ERR_LAUNCH: return "HIP runtime error while enqueuing";
+        case QVG_ERR_SCRATCH_LIMIT: return "the call needs more scratch memory than the library's static buffer holds";
         default: return "unknown status";
     }
 }
@@ -286,6 +289,56 @@ int qvg_encode_chunk(const qvg_params *p, int64_t n_tokens, const void *x, int64
         }
     }
     return QVG_OK;
+}
+
+}  // extern "C"
+
+// ---- scratch memory owned by the library, for qvg_encode_chunk_static -------------------------
+// One array per GPU the library's code object is loaded on (each device has its own copy at its
+// own address), alive until the process ends.  The name below is only a handle on the host: the
+// device address comes from hipGetSymbolAddress, once per device, and only that address is ever
+// passed to a kernel or a copy.
+static __device__ __align__(256) unsigned char scratch[QVG_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+// device address of `scratch` on the current device (looked up on the first call on that device)
+int static_scratch_address(void **out) {
+    static std::mutex mu;
+    static void *address[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return QVG_ERR_LAUNCH;
+    if (dev < 0 || dev >= kMaxDevices) return QVG_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return QVG_ERR_LAUNCH;
+        address[dev] = ptr;
+    }
+    *out = address[dev];
+    return QVG_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int qvg_encode_chunk_static(const qvg_params *p, int64_t n_tokens, const void *x, int64_t stride_head,
+                            int64_t stride_token, const void *init_centroids, void *centroids_out,
+                            int64_t cent_out_stride_head, uint8_t *ids_out, uint8_t *codes_out,
+                            void *scales_out, int64_t out_stride_head_tokens, void *stream) {
+    int st = check_params(p);
+    if (st != QVG_OK) return st;
+    if (n_tokens < 0 || n_tokens > kMaxTokensPerChunk) return QVG_ERR_BAD_PARAM;
+    // the same workspace layout as qvg_encode_chunk, placed in the static array
+    const size_t need = n_tokens == 0 ? 0 : encode_ws(p, n_tokens, true, p->kmeans_iters > 0 || p->n_smooth_stages > 1,
+                                                      p->kmeans_iters > 0).total;
+    if (need > (size_t)QVG_STATIC_SCRATCH_BYTES) return QVG_ERR_SCRATCH_LIMIT;
+    void *ws = nullptr;
+    if (need > 0 && (st = static_scratch_address(&ws)) != QVG_OK) return st;
+    // nothing in the workspace has to start at zero: every kernel writes what it later reads
+    return qvg_encode_chunk(p, n_tokens, x, stride_head, stride_token, init_centroids, centroids_out,
+                            cent_out_stride_head, ids_out, codes_out, scales_out, out_stride_head_tokens,
+                            need > 0 ? ws : nullptr, need, stream);
 }
 
 int qvg_decode(const qvg_params *p, int64_t n_tokens, int64_t chunk_len, const void *centroids,

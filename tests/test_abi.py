@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_version_and_status_strings():
     assert B.lib().qvg_version() >= 100
-    for st in range(0, -7, -1):
+    for st in range(0, -8, -1):
         assert len(B.status_string(st)) > 0
     assert B.status_string(-99) == "unknown status"
 
@@ -151,3 +151,21 @@ def test_workspace_sizes():
     assert need >= 2 * 24 * 256 * 256 + 24 * 4680 * 4 + 24 * 257 * 4
     assert B.workspace_bytes(p, B.ENTRY_DECODE, 4680) == 0
     assert B.workspace_bytes(p, B.ENTRY_ATTN, 4680, 128) == 0
+
+
+def test_static_scratch_entry_rejects_what_does_not_fit_before_touching_the_gpu():
+    """qvg_encode_chunk_static: sizes whose workspace exceeds QVG_STATIC_SCRATCH_BYTES are refused
+    with their own status, from the host-side size arithmetic alone."""
+    L = B.lib()
+    text = open(os.path.join(ROOT, "include", "qvg.h")).read()
+    limit = eval(re.search(r"#define QVG_STATIC_SCRATCH_BYTES \((.*?)\)", text).group(1).replace("u", ""))
+    fake = C.c_void_p(0x1000)
+    big = B.make_params(720, 256, 64, 2, kmeans_iters=3)            # all 30 layers at once: two 47 MB tables
+    assert B.workspace_bytes(big, B.ENTRY_ENCODE, 4680) > limit
+    st = L.qvg_encode_chunk_static(C.byref(big), 4680, fake, 4680 * 128, 128, fake, fake, 0, fake, fake, fake, 0, None)
+    assert st == -7 and "static" in B.status_string(st)
+    ok = B.make_params(24, 256, 64, 4, kmeans_iters=10)             # one layer's chunk fits
+    assert B.workspace_bytes(ok, B.ENTRY_ENCODE, 4680) <= limit
+    # bad parameters are reported as for qvg_encode_chunk
+    assert L.qvg_encode_chunk_static(C.byref(B.make_params(0, 256, 64, 2)), 10, fake, 1280, 128, fake, fake, 0,
+                                     fake, fake, fake, 0, None) == -2
