@@ -46,6 +46,12 @@
  * beyond the table.
  * A cache of several chunks concatenates ids/codes/scales along N and keeps one
  * centroid table per chunk: centroids [n_chunks][K][d].
+ * Alignment inside a cache: qvg_encode_chunk wants every output pointer 16-byte aligned, so a chunk
+ * can be encoded in place at token offset c * chunk_len only if chunk_len * T * (d/B) * 2 bytes of
+ * binary16 scales (and chunk_len * T * d*b/8 bytes of codes) are multiples of 16: a chunk_len that
+ * is a multiple of 8 tokens always is (E4M3 scale bytes need no alignment).  The attention entry
+ * points read any chunk length and capacity; their fastest kernel needs the same property of
+ * chunk_len and, with several units, of the capacity, and the others are read by a general kernel.
  *
  * With S = n_smooth_stages > 1 (the paper's progressive residual quantization, Sec. 4.2: the
  * residual of one k-means round is clustered again, S times, before it is quantized) a chunk
@@ -239,8 +245,11 @@ int qvg_attn_decode_ex(const qvg_params *p, int64_t n_q, const void *q_bf16,
  * chunk-causal order of Sec. 3.1 for the queries of SEVERAL chunks in one call (each chunk
  * attends to the chunks before it; its own keys are not in the compressed cache: see
  * qvg_attn_merge).
- *   q_kv_len   [n_q] int32, device; values are clamped to 1 .. n_kv_tokens.  NULL = every query
- *              sees all n_kv_tokens tokens (the call is then qvg_attn_decode_ex).
+ *   q_kv_len   [n_q] int32, device; values are clamped to 0 .. n_kv_tokens.  NULL = every query
+ *              sees all n_kv_tokens tokens (the call is then qvg_attn_decode_ex).  A query with
+ *              length 0 (the first chunk of a chunk-causal batch: nothing is cached before it)
+ *              gets a zero output row and lse = -infinity, which qvg_attn_merge treats as a
+ *              partial result without weight.
  * A workgroup stops at the longest prefix among its 256 queries, so queries sorted by length
  * cost what their prefixes cost.  Runs on the general attention kernel.
  */
@@ -253,6 +262,26 @@ int qvg_attn_decode_causal(const qvg_params *p, int64_t n_q, const void *q_bf16,
                            const void *k_rope_f16, const int32_t *q_kv_len,
                            float softmax_scale, void *out_bf16, float *lse_out,
                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * qvg_attn_decode_causal with the result left in fp32, [H][n_q][d] float, before the final rounding
+ * to bf16 (no workspace arguments).  For checking the kernel's own arithmetic against a reference:
+ * with a bf16 result, half an ulp of the output (2^-9 of its magnitude) hides what the kernel adds.
+ * What the kernel adds: the scores are bf16 x bf16 products accumulated in fp32; the probabilities
+ * enter the second contraction as binary16 rounded to nearest (the normaliser is the sum of the
+ * rounded values), the decoded values as binary16 (exact: they are bf16 numbers; magnitudes beyond
+ * 65504 are not supported).  The output error is therefore about 2^-12 of the magnitude of the
+ * values a query attends to: below 2e-3 in absolute terms for |V| up to about 8, and it grows in
+ * proportion beyond that (keys of any magnitude only sharpen the soft-max).
+ */
+int qvg_attn_decode_f32(const qvg_params *p, int64_t n_q, const void *q_bf16,
+                        int64_t n_kv_tokens, int64_t chunk_len, int64_t kv_capacity_tokens,
+                        const void *k_centroids, const uint8_t *k_ids, const uint8_t *k_codes,
+                        const void *k_scales,
+                        const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
+                        const void *v_scales,
+                        const void *k_rope_f16, const int32_t *q_kv_len,
+                        float softmax_scale, float *out_f32, float *lse_out, void *stream);
 
 /*
  * Merge two attention results over DISJOINT key sets (the compressed cache, from

@@ -21,7 +21,7 @@ ENTRY_ENCODE, ENTRY_DECODE, ENTRY_ATTN, ENTRY_KMEANS_UPDATE, ENTRY_KMEANS_ASSIGN
 SCALE_F16, SCALE_E4M3 = 0, 1
 
 EXPORTS = ["qvg_encode_chunk", "qvg_encode_chunk_static", "qvg_decode", "qvg_decode_ex", "qvg_attn_decode", "qvg_attn_decode_ex",
-           "qvg_attn_decode_causal", "qvg_attn_merge",
+           "qvg_attn_decode_causal", "qvg_attn_decode_f32", "qvg_attn_merge",
            "qvg_kmeans_assign",
            "qvg_kmeans_update", "qvg_workspace_bytes", "qvg_compressed_bytes",
            "qvg_status_string", "qvg_version"]
@@ -68,6 +68,9 @@ def lib():
         L.qvg_attn_decode_causal.restype = C.c_int
         L.qvg_attn_decode_causal.argtypes = [pp, i64, vp, i64, i64, i64, vp, u8p, u8p, vp, vp, u8p, u8p, vp, vp, vp,
                                              C.c_float, vp, vp, vp, C.c_size_t, vp]
+        L.qvg_attn_decode_f32.restype = C.c_int
+        L.qvg_attn_decode_f32.argtypes = [pp, i64, vp, i64, i64, i64, vp, u8p, u8p, vp, vp, u8p, u8p, vp, vp, vp,
+                                          C.c_float, vp, vp, vp]
         L.qvg_attn_merge.restype = C.c_int
         L.qvg_attn_merge.argtypes = [i64, C.c_int32, vp, vp, vp, vp, vp, vp, vp]
         L.qvg_kmeans_assign.restype = C.c_int
@@ -252,11 +255,12 @@ def decode(enc: Encoded, out=None, n_tokens=None, first_token=0) -> torch.Tensor
 
 
 def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, out=None, n_kv=None,
-                k_rope=None, q_kv_len=None):
+                k_rope=None, q_kv_len=None, f32_out=False):
     """qvg_attn_decode_ex.  q [H, Nq, d] bf16 contiguous -> out bf16 [H, Nq, d] (and lse fp32 [H, Nq]).
     n_kv: read only the first n_kv tokens of the caches (they are allocated for more);
     k_rope: [n_kv, d/2, 2] float16 (cos, sin), the rotary embedding of the decoded keys;
-    q_kv_len: [Nq] int32, query i sees the first q_kv_len[i] tokens only (qvg_attn_decode_causal)."""
+    q_kv_len: [Nq] int32, query i sees the first q_kv_len[i] tokens only (qvg_attn_decode_causal);
+    f32_out: the result as float32, before the rounding to bf16 (qvg_attn_decode_f32)."""
     _check(q, torch.bfloat16, "q")
     q = q.contiguous()
     H, Nq, d = q.shape
@@ -280,12 +284,25 @@ def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, o
     if softmax_scale is None:
         softmax_scale = 1.0 / (d ** 0.5)
     if out is None:
-        out = torch.empty(H, Nq, d, dtype=torch.bfloat16, device=q.device)
+        out = torch.empty(H, Nq, d, dtype=torch.float32 if f32_out else torch.bfloat16, device=q.device)
     lse = torch.empty(H, Nq, dtype=torch.float32, device=q.device) if want_lse else None
     if q_kv_len is not None:
         _check(q_kv_len, torch.int32, "q_kv_len")
         if tuple(q_kv_len.shape) != (Nq,) or not q_kv_len.is_contiguous():
             raise ValueError("q_kv_len: need a contiguous [n_q] int32 tensor")
+    if f32_out:
+        _check(out, torch.float32, "out")
+        if not out.is_contiguous():
+            raise ValueError("out must be contiguous")
+        st = lib().qvg_attn_decode_f32(C.byref(p), Nq, _ptr(q), Nk, k.chunk_len, cap,
+                                       _ptr(k.centroids), _ptr(k.ids), _ptr(k.codes), _ptr(k.scales),
+                                       _ptr(v.centroids), _ptr(v.ids), _ptr(v.codes), _ptr(v.scales),
+                                       _ptr(k_rope), _ptr(q_kv_len), C.c_float(softmax_scale), _ptr(out),
+                                       _ptr(lse), _stream())
+        if st != 0:
+            raise QvgError(st, "qvg_attn_decode_f32")
+        return (out, lse) if want_lse else out
+    if q_kv_len is not None:
         st = lib().qvg_attn_decode_causal(C.byref(p), Nq, _ptr(q), Nk, k.chunk_len, cap,
                                           _ptr(k.centroids), _ptr(k.ids), _ptr(k.codes), _ptr(k.scales),
                                           _ptr(v.centroids), _ptr(v.ids), _ptr(v.codes), _ptr(v.scales),
@@ -440,7 +457,7 @@ class StreamingCache:
         """Bytes the appended tokens occupy (codes, scales, ids and the chunks' tables)."""
         c = self.cache
         per_tok = c.codes.shape[2] * c.codes.shape[3] + c.scales.shape[2] * c.scales.shape[3] * c.scales.element_size() \
-            + c.n_smooth
+            + c.n_smooth * c.ids.element_size()
         chunks = -(-self.n_tokens // self.chunk_len)
         table = c.n_smooth * c.centroids.shape[-2] * c.centroids.shape[-1] * 2
         return 2 * self.heads * (self.n_tokens * per_tok + chunks * table)

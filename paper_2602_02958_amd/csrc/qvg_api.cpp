@@ -418,23 +418,25 @@ int qvg_attn_decode_ex(const qvg_params *p, int64_t n_q, const void *q, int64_t 
                                   lse_out, workspace, workspace_bytes, stream);
 }
 
-int qvg_attn_decode_causal(const qvg_params *p, int64_t n_q, const void *q, int64_t n_kv_tokens,
-                           int64_t chunk_len, int64_t kv_capacity_tokens, const void *k_centroids,
-                           const uint8_t *k_ids, const uint8_t *k_codes, const void *k_scales,
-                           const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
-                           const void *v_scales, const void *k_rope, const int32_t *q_kv_len,
-                           float softmax_scale, void *out, float *lse_out, void *workspace,
-                           size_t workspace_bytes, void *stream) {
-    (void)workspace; (void)workspace_bytes;
+}  // extern "C"
+
+namespace {
+// the one implementation behind every attention entry point; exactly one of out / out_f32 is set
+int attn_call(const qvg_params *p, int64_t n_q, const void *q, int64_t n_kv_tokens,
+              int64_t chunk_len, int64_t kv_capacity_tokens, const void *k_centroids,
+              const uint8_t *k_ids, const uint8_t *k_codes, const void *k_scales,
+              const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
+              const void *v_scales, const void *k_rope, const int32_t *q_kv_len,
+              float softmax_scale, void *out, float *out_f32, float *lse_out, void *stream) {
     int st = check_params(p);
     if (st != QVG_OK) return st;
     if (n_q < 0 || n_kv_tokens < 1 || n_kv_tokens > 0x7fffffff || chunk_len < 1) return QVG_ERR_BAD_PARAM;
     if (!(softmax_scale > 0.0f) || softmax_scale - softmax_scale != 0.0f) return QVG_ERR_BAD_PARAM;   // positive, finite
     if (n_q == 0) return QVG_OK;
-    if (!q || !out || !k_centroids || !k_ids || !k_codes || !k_scales || !v_centroids || !v_ids ||
+    if (!q || (!out && !out_f32) || !k_centroids || !k_ids || !k_codes || !k_scales || !v_centroids || !v_ids ||
         !v_codes || !v_scales)
         return QVG_ERR_NULL;
-    if (!aligned16(q) || !aligned16(out) || !aligned16(k_centroids) || !aligned16(v_centroids) ||
+    if (!aligned16(q) || !aligned16(out) || !aligned16(out_f32) || !aligned16(k_centroids) || !aligned16(v_centroids) ||
         !aligned16(k_codes) || !aligned16(v_codes) || !scales_aligned(p, k_scales) || !scales_aligned(p, v_scales))
         return QVG_ERR_ALIGN;
     const int64_t n_chunks = (n_kv_tokens + chunk_len - 1) / chunk_len;
@@ -446,7 +448,7 @@ int qvg_attn_decode_causal(const qvg_params *p, int64_t n_q, const void *q, int6
     if (cap_chunks > 0x7fffffff) return QVG_ERR_BAD_PARAM;
     if (k_rope && !aligned16(k_rope)) return QVG_ERR_ALIGN;
     AttnArgs a{};
-    a.q = static_cast<const bf16_t *>(q); a.out = static_cast<bf16_t *>(out); a.lse = lse_out;
+    a.q = static_cast<const bf16_t *>(q); a.out = static_cast<bf16_t *>(out); a.out_f32 = out_f32; a.lse = lse_out;
     a.n_q = n_q; a.n_kv = n_kv_tokens; a.chunk_len = chunk_len; a.n_chunks = (int)n_chunks;
     a.H = p->n_heads; a.K = p->n_clusters; a.B = p->group_size; a.T = p->n_stages;
     a.scale = softmax_scale;
@@ -462,6 +464,31 @@ int qvg_attn_decode_causal(const qvg_params *p, int64_t n_q, const void *q, int6
     if (q_kv_len && (reinterpret_cast<uintptr_t>(q_kv_len) & 3u)) return QVG_ERR_ALIGN;
     a.q_len = q_kv_len;
     return launch_attn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
+}
+}  // namespace
+
+extern "C" {
+
+int qvg_attn_decode_causal(const qvg_params *p, int64_t n_q, const void *q, int64_t n_kv_tokens,
+                           int64_t chunk_len, int64_t kv_capacity_tokens, const void *k_centroids,
+                           const uint8_t *k_ids, const uint8_t *k_codes, const void *k_scales,
+                           const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
+                           const void *v_scales, const void *k_rope, const int32_t *q_kv_len,
+                           float softmax_scale, void *out, float *lse_out, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+    (void)workspace; (void)workspace_bytes;
+    return attn_call(p, n_q, q, n_kv_tokens, chunk_len, kv_capacity_tokens, k_centroids, k_ids, k_codes, k_scales,
+                     v_centroids, v_ids, v_codes, v_scales, k_rope, q_kv_len, softmax_scale, out, nullptr, lse_out, stream);
+}
+
+int qvg_attn_decode_f32(const qvg_params *p, int64_t n_q, const void *q, int64_t n_kv_tokens,
+                        int64_t chunk_len, int64_t kv_capacity_tokens, const void *k_centroids,
+                        const uint8_t *k_ids, const uint8_t *k_codes, const void *k_scales,
+                        const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
+                        const void *v_scales, const void *k_rope, const int32_t *q_kv_len,
+                        float softmax_scale, float *out_f32, float *lse_out, void *stream) {
+    return attn_call(p, n_q, q, n_kv_tokens, chunk_len, kv_capacity_tokens, k_centroids, k_ids, k_codes, k_scales,
+                     v_centroids, v_ids, v_codes, v_scales, k_rope, q_kv_len, softmax_scale, nullptr, out_f32, lse_out, stream);
 }
 
 }  // extern "C"

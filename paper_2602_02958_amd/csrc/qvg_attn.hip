@@ -9,7 +9,7 @@
 //      between the two lane halves per tile);
 //   2. online soft-max in fp32 (base-2 exponent);
 //   3. O^T += V_tile^T . P on v_mfma_f32_32x32x16_f16: the probabilities go in as f16 (11
-//      significant bits; bf16's 8 would cost up to 2^-9 of |V| in the output), and the V tile,
+//      significant bits, round to nearest; bf16's 8 would cost up to 2^-9 of |V| in the output), and the V tile,
 //      first rounded to bf16 like the stand-alone decoder's output, is stored as f16, which
 //      holds every bf16 value of magnitude 2^-14 .. 65504 exactly (larger ones saturate).
 //      The lane's P values are already the B operand: the V tile is stored transposed with
@@ -85,6 +85,42 @@ __device__ __forceinline__ Tile next_tile(const Span &a, Tile t) {
         }
     }
     return t;
+}
+
+// Normalise and store one query's result: the lane holds channels 32*mb + 8*g + 4*half + 0..3 of its
+// query.  bf16 (round to nearest even), or fp32 when a.out_f32 is set.  A query that saw no token
+// at all (prefix length 0) gets a zero row and a log-sum-exp of -inf, which qvg_attn_merge takes
+// as a weightless partial result.
+__device__ __forceinline__ void store_result(const AttnArgs &a, int h, int64_t qrow, bool seen, bool qvalid,
+                                             int half, const floatx16_t (&O)[4], float m, float l) {
+    const float ltot = l + __shfl_xor(l, 32, 64);
+    if (!qvalid) return;
+    const float inv = seen ? 1.0f / ltot : 0.0f;
+    const int64_t row = ((int64_t)h * a.n_q + qrow) * kHeadDim + half * 4;
+    if (a.out_f32) {
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                float4 o;
+                o.x = seen ? O[mb][4 * gq + 0] * inv : 0.0f; o.y = seen ? O[mb][4 * gq + 1] * inv : 0.0f;
+                o.z = seen ? O[mb][4 * gq + 2] * inv : 0.0f; o.w = seen ? O[mb][4 * gq + 3] * inv : 0.0f;
+                *reinterpret_cast<float4 *>(a.out_f32 + row + mb * 32 + gq * 8) = o;
+            }
+    } else {
+        bf16_t *op = a.out + row;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const uint2 o = seen ? make_uint2(
+                    pack_bf16x2(O[mb][4 * gq + 0] * inv, O[mb][4 * gq + 1] * inv),
+                    pack_bf16x2(O[mb][4 * gq + 2] * inv, O[mb][4 * gq + 3] * inv)) : make_uint2(0u, 0u);
+                *reinterpret_cast<uint2 *>(op + mb * 32 + gq * 8) = o;
+            }
+    }
+    if (a.lse && half == 0)
+        a.lse[(int64_t)h * a.n_q + qrow] = seen ? (m + __builtin_log2f(ltot)) * 0.6931471805599453f : -INFINITY;
 }
 
 // SM: how the smoothing stages are handled.  1: a single stage; 0: several, their number known at
@@ -282,7 +318,7 @@ void attn_kernel_direct(AttnArgs a) {
         __syncthreads();
         const int nk = (int)a.n_kv;
         int mx = 1;
-        if (qvalid) { const int v = a.q_len[qrow]; qlen = v < 1 ? 1 : (v > nk ? nk : v); mx = qlen; }
+        if (qvalid) { const int v = a.q_len[qrow]; qlen = v < 0 ? 0 : (v > nk ? nk : v); mx = qlen > 1 ? qlen : 1; }
         wmin = qlen;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
@@ -461,10 +497,10 @@ void attn_kernel_direct(AttnArgs a) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[st >> 1][(st & 1) * 8 + e], scale2, -m));
-            pb[st] = make_uint4(pack_f16x2_rtz(p[0], p[1]), pack_f16x2_rtz(p[2], p[3]),
-                                pack_f16x2_rtz(p[4], p[5]), pack_f16x2_rtz(p[6], p[7]));
-            // the normaliser is the sum of the f16 probabilities the PV contraction uses (their
-            // rounding toward zero would otherwise bias every output by up to 2^-10 of |V|)
+            pb[st] = make_uint4(pack_f16x2_rne(p[0], p[1]), pack_f16x2_rne(p[2], p[3]),
+                                pack_f16x2_rne(p[4], p[5]), pack_f16x2_rne(p[6], p[7]));
+            // the normaliser is the sum of the f16 probabilities the PV contraction uses, so that
+            // numerator and denominator carry the same rounding
             l = sum_f16_pairs(pb[st], l);
         }
         // ---- O^T += V_tile^T . P --------------------------------------------
@@ -500,22 +536,7 @@ void attn_kernel_direct(AttnArgs a) {
         nn = nn.valid ? next_tile(sp, nn) : nn;
     }
     // ---- normalise and store: lane holds channels 32*mb + 8*g + 4*half + 0..3 of its query ----
-    const float ltot = l + __shfl_xor(l, 32, 64);
-    if (qvalid) {
-        const float inv = 1.0f / ltot;
-        bf16_t *op = a.out + ((int64_t)h * a.n_q + qrow) * kHeadDim + half * 4;
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const uint2 o = make_uint2(
-                    pack_bf16x2(O[mb][4 * gq + 0] * inv, O[mb][4 * gq + 1] * inv),
-                    pack_bf16x2(O[mb][4 * gq + 2] * inv, O[mb][4 * gq + 3] * inv));
-                *reinterpret_cast<uint2 *>(op + mb * 32 + gq * 8) = o;
-            }
-        if (a.lse && half == 0)
-            a.lse[(int64_t)h * a.n_q + qrow] = (m + __builtin_log2f(ltot)) * 0.6931471805599453f;
-    }
+    store_result(a, h, qrow, qvalid && (!QL || qlen > 0), qvalid, half, O, m, l);
 }
 
 
@@ -839,10 +860,10 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[st >> 1][(st & 1) * 8 + e], scale2, -m));
-            pb[st] = make_uint4(pack_f16x2_rtz(p[0], p[1]), pack_f16x2_rtz(p[2], p[3]),
-                                pack_f16x2_rtz(p[4], p[5]), pack_f16x2_rtz(p[6], p[7]));
-            // the normaliser is the sum of the f16 probabilities the PV contraction uses (their
-            // rounding toward zero would otherwise bias every output by up to 2^-10 of |V|)
+            pb[st] = make_uint4(pack_f16x2_rne(p[0], p[1]), pack_f16x2_rne(p[2], p[3]),
+                                pack_f16x2_rne(p[4], p[5]), pack_f16x2_rne(p[6], p[7]));
+            // the normaliser is the sum of the f16 probabilities the PV contraction uses, so that
+            // numerator and denominator carry the same rounding
             l = sum_f16_pairs(pb[st], l);
         }
         {
@@ -912,38 +933,22 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         while (is_full(cur) && is_full(nxt) && is_full(nn)) tile_step(BoolC<true>{}, decode_first);
         if (!tile_step(BoolC<false>{}, false)) break;
     }
-    const float ltot = l + __shfl_xor(l, 32, 64);
-    if (qvalid) {
-        const float inv = 1.0f / ltot;
-        bf16_t *op = a.out + ((int64_t)h * a.n_q + qrow) * kHeadDim + half * 4;
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const uint2 o = make_uint2(
-                    pack_bf16x2(O[mb][4 * gq + 0] * inv, O[mb][4 * gq + 1] * inv),
-                    pack_bf16x2(O[mb][4 * gq + 2] * inv, O[mb][4 * gq + 3] * inv));
-                *reinterpret_cast<uint2 *>(op + mb * 32 + gq * 8) = o;
-            }
-        if (a.lse && half == 0)
-            a.lse[(int64_t)h * a.n_q + qrow] = (m + __builtin_log2f(ltot)) * 0.6931471805599453f;
-    }
+    store_result(a, h, qrow, qvalid, qvalid, half, O, m, l);
 }
 
 template <int T_, bool ROPE, bool FP8, bool I4, bool WIDE>
 static hipError_t launch_attn_staged_r(const AttnArgs &a, hipStream_t s) {
     constexpr size_t kSmem = WIDE ? kAtSmemStagedWide : kAtSmemStaged;
-    static bool configured = false;          // the attribute is per function, set once per process
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE, FP8, I4, WIDE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmem);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static LdsHighWater lds_limit = {};
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE, FP8, I4, WIDE>), kSmem, lds_limit);
+    if (e != hipSuccess) return e;
     const int64_t nqb = (a.n_q + kAtQPerBlock - 1) / kAtQPerBlock;
     const int64_t nb = nqb * a.H;
     if (nb > 0x7fffffff - 8) return hipErrorInvalidValue;
     const int bpx = (int)((nb + 7) / 8);
+    // the grid is padded to a multiple of 8 (one share per XCD): at most 7 surplus workgroups, whose
+    // renumbered index is >= nb; each returns on its first statement, before it forms a unit index
+    if ((int64_t)bpx * 8 > nb + 7) return hipErrorInvalidValue;
     hipLaunchKernelGGL((attn_kernel_staged<T_, ROPE, FP8, I4, WIDE>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kSmem, s, a,
                        (int)nqb, (int)nb, bpx);
     return hipGetLastError();
@@ -955,8 +960,8 @@ static hipError_t launch_attn_staged(const AttnArgs &a, hipStream_t s) {
 
 template <int T_, int SM, int FMT, bool ROPE, bool QL = false>
 static hipError_t launch_attn_tr(const AttnArgs &a, hipStream_t s) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel_direct<T_, SM, FMT, ROPE, QL>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAtSmem);
+    static LdsHighWater lds_limit = {};
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(&attn_kernel_direct<T_, SM, FMT, ROPE, QL>), kAtSmem, lds_limit);
     if (e != hipSuccess) return e;
     dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
     hipLaunchKernelGGL((attn_kernel_direct<T_, SM, FMT, ROPE, QL>), grid, dim3(kAtThreads), kAtSmem, s, a);
@@ -1000,7 +1005,11 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
         }
     }
     // the staged kernel fetches scales in 16-byte pieces: every chunk must start on one
-    const bool aligned = (a.chunk_len % 8 == 0) || a.n_chunks == 1;
+    // (binary16 scales: chunk_len * T * G * 2 bytes a multiple of 16; the test below is the sufficient
+    // chunk_len % 8 == 0) and so must every unit's array (units are kv_stride tokens apart)
+    const bool aligned = ((a.chunk_len % 8 == 0) || a.n_chunks == 1) &&
+        (reinterpret_cast<uintptr_t>(a.k_scales) & 15u) == 0 && (reinterpret_cast<uintptr_t>(a.v_scales) & 15u) == 0 &&
+        (a.H == 1 || (a.kv_stride * a.T * (kHeadDim / a.B) * ((a.fmt & kFmtE4M3) ? 1 : 2)) % 16 == 0);
     // E4M3 scales on the staged kernel: a token's scale record must have an even number of bytes
     // (the tail handling moves two at a time) and every unit's scale array must start on a
     // 16-byte boundary

@@ -248,8 +248,8 @@ static hipError_t launch_decode_w(const DecodeArgs &a, hipStream_t s) {
     if (nb > 0x7fffffff - kXcds) return hipErrorInvalidValue;
     const int bpx = (int)((nb + kXcds - 1) / kXcds);
     const size_t smem = (SM == 3) ? 16 : (size_t)(SM == 1 ? 1 : a.S) * a.K * kHeadDim * sizeof(bf16_t);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_kernel<T_, SM, FMT, SC, WIDE>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static LdsHighWater lds_limit = {};
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(&decode_kernel<T_, SM, FMT, SC, WIDE>), smem, lds_limit);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((decode_kernel<T_, SM, FMT, SC, WIDE>), dim3((unsigned)(bpx * kXcds)), dim3(kDecThreads), smem, s, a,
                        (int)slices, (uint32_t)slice_len, (int)nb, bpx);

@@ -547,11 +547,10 @@ template <int B_, bool FUSED>
 static hipError_t launch_assign_t(const AssignArgs &a, hipStream_t s) {
     const int Kpad = (a.K + 63) & ~63;
     const size_t smem = assign_smem_bytes(Kpad);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED, true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    static LdsHighWater lds_limit[2] = {};
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED, true>), smem, lds_limit[0]);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED, false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    e = ensure_dynamic_lds(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED, false>), smem, lds_limit[1]);
     if (e != hipSuccess) return e;
     // tokens per workgroup: 256 per step; more steps per workgroup amortise the table staging
     // once there are enough workgroups to fill the chip several times over

@@ -44,6 +44,11 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 __device__ __forceinline__ uint32_t pack_f16x2_rtz(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
+// two fp32 -> packed f16, round to nearest even: v_cvt_pk_f16_f32 (values beyond 65504 become infinite)
+__device__ __forceinline__ uint32_t pack_f16x2_rne(float lo, float hi) {
+    const floatx2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, halfx2_t));
+}
 __device__ __forceinline__ float f16_bits_to_f32(uint32_t h) {
     return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
 }
@@ -130,6 +135,22 @@ __device__ __forceinline__ void add_stage_int4(float *acc, uint32_t w, float s) 
     }
 }
 
+// Raise a kernel's dynamic-LDS limit to `bytes` unless an earlier call on this device already raised
+// it that far: the attribute belongs to the function (per device), not to the launch.  `mark` is a
+// static of the calling launcher instance (one per kernel instance); a race between two first
+// calls only sets the attribute twice.
+struct LdsHighWater { size_t bytes[32]; };
+inline hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes, LdsHighWater &mark) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < 32;
+    if (tracked && bytes <= mark.bytes[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && tracked) mark.bytes[dev] = bytes;
+    return e;
+}
+
 // ---- launchers (each returns a hipError_t from hipGetLastError) -----------
 struct DecodeArgs {
     const bf16_t *cent; const uint8_t *ids; const uint8_t *codes; const f16_t *scales;
@@ -203,7 +224,8 @@ struct AttnArgs {
     int chunk_stride;      // chunk tables between consecutive units in the centroid arrays (>= n_chunks)
     const f16_t *rope;     // [n_kv][d/2][2] (cos, sin) applied to the decoded keys, or nullptr
     int id_wide;           // ids are 16-bit words (K > 256, S == 1)
-    const int32_t *q_len;  // [n_q] prefix length per query (clamped to 1 .. n_kv), or nullptr: all n_kv tokens
+    const int32_t *q_len;  // [n_q] prefix length per query (clamped to 0 .. n_kv), or nullptr: all n_kv tokens
+    float *out_f32;        // when set, the result goes here as fp32 [H][n_q][d] (not rounded to bf16) and `out` is not written
 };
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
 

@@ -204,8 +204,8 @@ def test_streaming_cache_append_attend_decode():
 def test_attention_with_a_prefix_length_per_query(L, T, Bg, S, bits, fmt, rope):
     """qvg_attn_decode_causal: the queries of several chunks in one call, each seeing the chunks
     before its own (lengths on chunk boundaries), plus lengths inside a chunk, the whole cache,
-    a single token and out-of-range values (clamped).  Every query is checked against the oracle's
-    attention over its own prefix.  Query blocks with short prefixes stop early: more than 256
+    a single token, out-of-range values (clamped) and empty prefixes (a zero row, lse = -inf).  Every
+    other query is checked against the oracle's attention over its own prefix.  Query blocks with short prefixes stop early: more than 256
     queries, sorted and unsorted."""
     H, K = 2, 64
     n_chunks, filled = 4, 3 * L + 77
@@ -226,7 +226,8 @@ def test_attention_with_a_prefix_length_per_query(L, T, Bg, S, bits, fmt, rope):
                              q_kv_len=lens.to(torch.int32).to(DEV))
     khat, vhat = B.decode(kc, n_tokens=filled), B.decode(vc, n_tokens=filled)
     torch.cuda.synchronize()
-    eff = lens.clamp(1, filled).numpy()
+    eff = lens.clamp(0, filled).numpy()
+    assert (eff == 0).sum() == 2
     for h in range(H):
         kb = P.to_np_u16(khat[h])
         if rope:
@@ -236,6 +237,9 @@ def test_attention_with_a_prefix_length_per_query(L, T, Bg, S, bits, fmt, rope):
         og, lg = P.to_np_u16(out[h]), lse[h].cpu().numpy()
         for n in np.unique(eff):
             rows = np.flatnonzero(eff == n)
+            if n == 0:                                   # nothing cached before these queries
+                assert (og[rows] == 0).all() and np.isneginf(lg[rows]).all()
+                continue
             want, lse_w = O.attention(qb[rows], kb[:n], vb[:n], want_lse=True)
             ok, max_abs, worst = P.attn_tolerance_ok(og[rows], want)
             assert ok, f"head {h}, prefix {n}: max abs err {max_abs}, worst err/tol {worst}"
@@ -318,3 +322,102 @@ def test_id_arrays_at_any_byte_address(S):
     assert torch.equal(lse2, lse)
     for h in range(H):
         _check_against_oracle(q, out2, lse2, P.to_np_u16(khat2[h]), P.to_np_u16(vhat2[h]), h)
+
+
+def test_empty_prefix_rows_merge_as_weightless():
+    """A query that sees no cached token (prefix length 0) returns a zero row with lse = -inf; merged
+    with the current chunk's own attention it must give exactly that second result."""
+    H, K, L, T, Bg, Nq = 2, 64, 520, 2, 32, 70
+    kc, vc = _filled_caches(H, L, 2, L + 40, K, Bg, T)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    lens = torch.zeros(Nq, dtype=torch.int32, device=DEV)
+    lens[35:] = L
+    out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=L + 40, q_kv_len=lens)
+    g = torch.Generator(device=DEV).manual_seed(2)
+    own = torch.randn(H, Nq, 128, generator=g, device=DEV).to(torch.bfloat16)
+    own_lse = torch.randn(H, Nq, generator=g, device=DEV)
+    merged, mlse = B.attn_merge(out, lse, own, own_lse, want_lse=True)
+    torch.cuda.synchronize()
+    assert (out[:, :35] == 0).all() and torch.isneginf(lse[:, :35]).all()
+    assert torch.equal(merged[:, :35], own[:, :35]) and torch.equal(mlse[:, :35], own_lse[:, :35])
+    assert not torch.equal(merged[:, 35:], own[:, 35:])
+
+
+@pytest.mark.parametrize("L,T,Bg,S", [(520, 3, 32, 1),      # staged kernel
+                                      (516, 2, 64, 1),      # general kernel
+                                      (520, 1, 16, 2)])     # general kernel, two smoothing stages
+def test_attention_fp32_output_meets_the_plain_bound(L, T, Bg, S):
+    """qvg_attn_decode_f32: the result before the rounding to bf16, against the fp64 oracle at a
+    plain 2e-3 maximum absolute error (no term relative to the output) on the configurations' own
+    data; the bf16 entry point returns this result rounded to nearest even."""
+    H, K, Nq = 2, 64, 300
+    filled = 5 * L + 133
+    kc, vc = _filled_caches(H, L, 6, filled, K, Bg, T, S=S)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    o32, lse = B.attn_decode(q, kc, vc, n_kv=filled, f32_out=True, want_lse=True)
+    o16 = B.attn_decode(q, kc, vc, n_kv=filled)
+    khat, vhat = B.decode(kc, n_tokens=filled), B.decode(vc, n_tokens=filled)
+    torch.cuda.synchronize()
+    assert o32.dtype == torch.float32
+    assert torch.equal(o32.to(torch.bfloat16), o16)
+    for h in range(H):
+        want, lse_w = O.attention(bf16_bits(q[h]), P.to_np_u16(khat[h]), P.to_np_u16(vhat[h]), want_lse=True)
+        err = np.abs(o32[h].cpu().numpy().astype(np.float64) - want).max()
+        assert err <= 2e-3, f"head {h}: max abs err {err}"
+        assert np.abs(lse[h].cpu().numpy() - lse_w).max() < 2e-3
+
+
+def test_attention_with_values_of_magnitude_1e3():
+    """The paper reports |V| up to about 1e3 (Sec. 3.2).  With values of that size the binary16
+    probabilities (11 significant bits) move an output by up to 2^-10 * sum_j p_j |v_j| wherever the
+    terms cancel, so the bound that holds is 2e-3 + 2^-8 |o| + 2^-10 E_p|v|; the fp32 result is
+    checked against the last term alone, which is the kernel's own error."""
+    wl = CONFIGS["cfg2_window21"]
+    H, K, L, T, Bg, Nq = 2, 64, 520, 2, 64, 200
+    filled = 3 * L + 77
+    caches = []
+    for kv, gain in ((0, 10.0), (1, 120.0)):             # max |K| ~ 1e2, max |V| ~ 1e3
+        st = synth.MixtureStream(wl, H, kv, DEV)
+        cache = B.alloc_cache(H, 4 * L, L, K, Bg, T, 128, DEV)
+        for t in (cache.centroids, cache.ids, cache.codes, cache.scales):
+            t.zero_()
+        c = 0
+        while c * L < filled:
+            x = (st.next_chunk(min(L, filled - c * L)).float() * gain).to(torch.bfloat16)
+            B.encode_chunk(x, synth.cold_start_centroids(x, K), Bg, T, 2, cache=cache, chunk_index=c)
+            c += 1
+        caches.append(cache)
+    kc, vc = caches
+    q = (synth.queries(wl, H, Nq, DEV).float() * 0.1).to(torch.bfloat16)      # keeps the soft-max from collapsing onto one key
+    o16 = B.attn_decode(q, kc, vc, n_kv=filled)
+    o32 = B.attn_decode(q, kc, vc, n_kv=filled, f32_out=True)
+    khat, vhat = B.decode(kc, n_tokens=filled), B.decode(vc, n_tokens=filled)
+    torch.cuda.synchronize()
+    assert float(vhat.float().abs().max()) > 500.0
+    for h in range(H):
+        qb, kb, vb = bf16_bits(q[h]), P.to_np_u16(khat[h]), P.to_np_u16(vhat[h])
+        want = O.attention(qb, kb, vb)
+        ok, max_abs, worst = P.attn_tolerance_wide_range_ok(P.to_np_u16(o16[h]), want, qb, kb, vb)
+        assert ok, f"head {h}: max abs err {max_abs}, worst err/tol {worst}"
+        qf, kf, vf = (bits_to_f32(t).astype(np.float64) for t in (qb, kb, vb))
+        s = (qf @ kf.T) / np.sqrt(128.0)
+        pr = np.exp(s - s.max(1, keepdims=True)); pr /= pr.sum(1, keepdims=True)
+        spread = pr @ np.abs(vf)
+        err = np.abs(o32[h].cpu().numpy().astype(np.float64) - want)
+        assert (err <= 1e-4 + 2.0 ** -10 * spread).all(), f"head {h}: worst {(err / (1e-4 + 2.0 ** -10 * spread)).max()}"
+
+
+@pytest.mark.parametrize("L,T,Bg", [(100, 1, 128), (100, 3, 64), (36, 2, 32)])
+def test_unit_scale_arrays_off_16_byte_boundaries(L, T, Bg):
+    """Several units whose binary16 scale arrays do not start on 16-byte boundaries (capacity x T x
+    d/B x 2 bytes is no multiple of 16): the wide-load kernel must not be chosen; every unit
+    against the oracle."""
+    H, K, Nq = 3, 16, 70
+    assert (L * T * (128 // Bg) * 2) % 16 != 0
+    kc, vc = _filled_caches(H, L, 1, L, K, Bg, T)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    out, lse = B.attn_decode(q, kc, vc, want_lse=True)
+    khat, vhat = B.decode(kc), B.decode(vc)
+    torch.cuda.synchronize()
+    for h in range(H):
+        _check_against_oracle(q, out, lse, P.to_np_u16(khat[h]), P.to_np_u16(vhat[h]), h)
