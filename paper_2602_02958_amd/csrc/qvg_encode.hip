@@ -14,16 +14,24 @@
 // MFMA step: a small kernel has split it, per centroid, into three bf16 pieces whose sum is
 // the fp32 value exactly, and the matching token operand holds three ones.
 //
-// Exactness.  The reference result is the argmin of fp64 distances.  The fp32 scores
-// carry a rounding error, so the kernel keeps the three largest scores per token
-// (cluster index carried in the 7 low mantissa bits) and certifies the winner only
-// when it leads by more than a bound on that error,
+// Exactness.  The reference result is the argmin of fp64 distances.  The fp32 scores carry a
+// rounding error, so the kernel keeps the two best scores per token (cluster index carried in the
+// 7 low mantissa bits) and certifies the winner only when it leads by more than a bound on that
+// error,
 //     thr = 2^-14 * (||x||^2 / 2 + max_j ||c_j||^2),
-// which covers the 131 accumulation roundings of half an ulp each plus the index tag for both
-// scores (with more than 256 centroids the tag has 8 bits and the factor is 1.5 * 2^-14).  Otherwise the candidates are re-evaluated in fp64: the two leaders
-// cooperatively by the wavefront, or, if the third score is inside the band as well,
-// all K centroids with the channels summed in index order (the reference order).
-// Equal fp64 distances go to the lower index.
+// which covers the 134 accumulation roundings of half an ulp each plus the index tag for both
+// scores (with more than 256 centroids the tag has 8 bits and the factor is 1.5 * 2^-14).
+// Otherwise all K centroids are re-evaluated in fp64 with the channels summed in index order (the
+// reference order); equal fp64 distances go to the lower index.
+//
+// Ranking cost is what bounds the pass (one score per token and centroid, 256 of them per lane
+// and step at K = 256), so it is kept to 2.5 vector instructions per score: the token's own
+// -||x||^2/2 enters the same extra MFMA step, which makes every score -||x - c||^2/2 <= 0, and for
+// non-positive floats the UNSIGNED order of the bit patterns is the reversed float order.  The
+// tagged patterns are then ranked with integer min3 / med3 / min on two scores at a time (no
+// NaN-quieting copies, no second tag compare).  A score that rounding pushes above zero compares
+// as better than every negative one, which is the right direction, and any mis-order among such
+// scores is inside the band and goes to the fp64 scan.
 #include "qvg_internal.hpp"
 
 namespace qvg {
@@ -31,15 +39,8 @@ namespace qvg {
 constexpr int kAsgThreads = 256;
 constexpr int kAsgWaves = kAsgThreads / 64;
 constexpr int kAsgTile = 64;                    // tokens per wavefront step (two MFMA column blocks)
-constexpr int kCPitch = 136;                    // bf16 elements per LDS centroid row (272 B): 128 + (hi, mid, lo of -||c||^2/2) + 5 zeros
+constexpr int kCPitch = 136;                    // bf16 elements per LDS centroid row (272 B): 128 + (hi, mid, lo of -||c||^2/2) + 1, 1, 1 + 2 zeros
 constexpr int kPrepThreads = 256;
-
-__device__ __forceinline__ void insert3(float v, int idx, float &b1, float &b2, float &b3,
-                                        int &i1, int &i2) {
-    if (v > b1) { b3 = b2; b2 = b1; i2 = i1; b1 = v; i1 = idx; }
-    else if (v > b2) { b3 = b2; b2 = v; i2 = idx; }
-    else if (v > b3) { b3 = v; }
-}
 
 __device__ __forceinline__ double shfl_xor_f64(double v, int m) { return __shfl_xor(v, m, 64); }
 // Sum over each aligned group of 16 lanes, every lane getting the total, by data-parallel-primitive
@@ -120,13 +121,16 @@ void centroid_prep_kernel(const bf16_t *cent, int K, int Kpad, uint2 *nh3, float
 // T rounds of Eq. 2 (b = 2: scale = max|r|, levels -1, 0, 1) on the 64 residuals r[] a lane
 // holds of one token (channels 64*half ..), packed and stored as they are made.
 // GL groups of NL elements lie inside the lane (B_ = 128: one group shared with the other half).
-template <int B_>
+// TT > 0: the number of rounds is known at compile time (the loop unrolls, and the last round
+// neither updates the residual nor takes the next maximum: a fifth of a round's instructions).
+template <int B_, int TT>
 __device__ __forceinline__ void quantize_token(float *r, int T, bool valid, int half, uint8_t *codes_tok,
                                                f16_t *scales_tok) {
     constexpr int G = kHeadDim / B_;                 // groups per token
     constexpr int GL = (B_ >= 64) ? 1 : 64 / B_;     // groups held by this lane
     constexpr int NL = (B_ >= 64) ? 64 : B_;         // elements per group in this lane
-    for (int t = 0; t < T; ++t) {
+    auto round = [&](int t, auto last_k) {
+        constexpr bool last = decltype(last_k)::value;
         uint32_t word[4];
         uint32_t sh[GL];
 #pragma unroll
@@ -151,7 +155,7 @@ __device__ __forceinline__ void quantize_token(float *r, int T, bool valid, int 
                     for (int i = 0; i < 8; ++i) {
                         float q = __builtin_rintf(rg[o + i] * inv);
                         if (decltype(clamp)::value) q = __builtin_amdgcn_fmed3f(q, -1.0f, 1.0f);
-                        rg[o + i] = __builtin_fmaf(-sf, q, rg[o + i]);
+                        if (!last) rg[o + i] = __builtin_fmaf(-sf, q, rg[o + i]);
                         cf = __builtin_fmaf(q, (float)(1 << (2 * i)), cf);
                     }
                     const int e = g * NL + o;        // first channel (within the lane) of this field group
@@ -179,12 +183,21 @@ __device__ __forceinline__ void quantize_token(float *r, int T, bool valid, int 
                 *reinterpret_cast<uint2 *>(sp + half * 4) =
                     make_uint2(sh[0] | (sh[1 % GL] << 16), sh[2 % GL] | (sh[3 % GL] << 16));
         }
+    };
+    if (TT > 0) {
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+            if (t + 1 < TT) round(t, BoolK<false>{}); else round(t, BoolK<true>{});
+        }
+    } else {
+        for (int t = 0; t < T; ++t) round(t, BoolK<false>{});
     }
 }
 
 // grid: x = unit, y = block of 256 * tiles_per_wave tokens.  With the unit as the fastest grid
 // index and H a multiple of 8, all blocks of a unit run on one XCD and share its table in L2.
-template <int B_, bool FUSED, bool NORMS_GIVEN>
+// T_: number of quantization rounds of the fused pass when known at compile time (0: a.T)
+template <int B_, bool FUSED, bool NORMS_GIVEN, int T_>
 __global__ __launch_bounds__(kAsgThreads, 2)
 void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
     constexpr bool norms_given = NORMS_GIVEN;
@@ -251,26 +264,22 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                 const float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
                 const float lo = __uint_as_float(__float_as_uint(r1 - mid) & 0xffff0000u);
                 *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) =
-                    make_uint4((__float_as_uint(hi) >> 16) | (__float_as_uint(mid) & 0xffff0000u), __float_as_uint(lo) >> 16, 0u, 0u);
+                    make_uint4((__float_as_uint(hi) >> 16) | (__float_as_uint(mid) & 0xffff0000u),
+                               (__float_as_uint(lo) >> 16) | 0x3F800000u, 0x3F803F80u, 0u);
             }
         }
     }
     if (norms_given)
         for (int row = tid; row < Kpad; row += kAsgThreads) {
             const uint2 p = a.nh3[(int64_t)h * Kpad + row];
-            *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) = make_uint4(p.x, p.y, 0u, 0u);
+            *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) = make_uint4(p.x, p.y | 0x3F800000u, 0x3F803F80u, 0u);
         }
     __syncthreads();
     const float cmax = norms_given ? a.cmax[h] : __uint_as_float(smax);
     bf16_t *scr = lscr + wave * kHeadDim;
-    // token operand of the extra MFMA step: three ones against (hi, mid, lo), lanes 0..31 only
     // 7 tag bits name a row among 256; with more rows the tag takes 8 (and the band below widens)
     const uint32_t tagbits = K > 256 ? 0xFFu : 0x7Fu;
     const uint32_t tagmask = vgpr_const(~tagbits);
-    // +inf kept in a register the compiler cannot see through: med3(a, b, +inf) then stays one
-    // instruction (as a constant it is rewritten into max(a, b) plus a NaN-quieting copy)
-    const float pinf = __uint_as_float(vgpr_const(0x7f800000u));
-    const uint4 ones = half ? make_uint4(0u, 0u, 0u, 0u) : make_uint4(0x3F803F80u, 0x00003F80u, 0u, 0u);
 
     const int64_t blk0 = (int64_t)blockIdx.y * tiles_per_wave * (kAsgWaves * kAsgTile);
     const bf16_t *xh = a.x + (int64_t)h * a.stride_head + half * 64;
@@ -320,12 +329,39 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             }
             xn[tb] = s + __shfl_xor(s, 32, 64);
         }
+        // token operand of the extra MFMA step (lanes 0..31 only; the other half holds zeros): three
+        // ones against the row's (hi, mid, lo) of -||c||^2/2, and the token's own -||x||^2/2, split
+        // into three bf16 pieces the same way, against the row's three ones.  Every score is then
+        // -||x - c||^2/2 up to rounding; the term is the same for all centroids of a token, so it
+        // moves no comparison between them.
+        uint4 bias[2];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            const float nx = -0.5f * xn[tb];
+            const float hi = __uint_as_float(__float_as_uint(nx) & 0xffff0000u);
+            const float r1 = nx - hi;
+            const float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
+            const float lo = __uint_as_float(__float_as_uint(r1 - mid) & 0xffff0000u);
+            bias[tb] = half ? make_uint4(0u, 0u, 0u, 0u)
+                            : make_uint4(0x3F803F80u, 0x00003F80u | (__float_as_uint(hi) & 0xffff0000u),
+                                         (__float_as_uint(mid) >> 16) | (__float_as_uint(lo) & 0xffff0000u), 0u);
+        }
 
         // ---- scores on the matrix cores, running top three per lane and token ----
         // Blocks of 32 centroids, software-pipelined: the MFMAs of block jb+1 are issued between
         // the VALU instructions that rank the scores of block jb (an MFMA occupies the matrix
         // pipe for 8 VALU issue slots), so one wavefront keeps both pipes busy.
-        float b1[2] = {-INFINITY, -INFINITY}, b2[2] = {-INFINITY, -INFINITY}, b3[2] = {-INFINITY, -INFINITY};
+        // the two best scores of each token as tagged bit patterns; smaller unsigned = better
+        uint32_t b1[2] = {~0u, ~0u}, b2[2] = {~0u, ~0u};
+        // two more scores of token block tb: 2 tag inserts (v_and_or_b32, the tag is scalar
+        // arithmetic), v_med3_u32, v_min3_u32, v_min_u32
+        auto rank_pair = [&](int tb, float s0, float s1, uint32_t t0) {
+            const uint32_t v0 = (__float_as_uint(s0) & tagmask) | t0;
+            const uint32_t v1 = (__float_as_uint(s1) & tagmask) | (t0 + 1u);
+            const uint32_t md = max(min(v0, v1), min(max(v0, v1), b1[tb]));        // median of (v0, v1, b1): v_med3_u32
+            b1[tb] = min(min(b1[tb], v0), v1);
+            b2[tb] = min(b2[tb], md);
+        };
         auto score_block = [&](int jb, floatx16_t (&acc)[2]) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) { acc[0][r] = 0.0f; acc[1][r] = 0.0f; }
@@ -337,9 +373,8 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                 acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, xa[1][kk]), acc[1], 0, 0, 0);
             }
             const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kHeadDim);
-            const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, ones);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, bias[0]), acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, bias[1]), acc[1], 0, 0, 0);
         };
         auto rank_block = [&](int jb, const floatx16_t (&acc)[2]) {
             uint32_t tag0 = (uint32_t)jb << 4;
@@ -347,14 +382,7 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    // (score & ~0x7F) | tag: one v_and_or_b32, the tag is scalar arithmetic.
-                    // max(a, b) is written med3(a, b, +inf): no NaN-quieting copy is needed.
-                    const float v = __uint_as_float((__float_as_uint(acc[tb][r]) & tagmask) | (tag0 + r));
-                    b3[tb] = __builtin_amdgcn_fmed3f(b2[tb], b3[tb], v);
-                    b2[tb] = __builtin_amdgcn_fmed3f(b1[tb], b2[tb], v);
-                    b1[tb] = __builtin_amdgcn_fmed3f(b1[tb], v, pinf);
-                }
+                for (int r = 0; r < 16; r += 2) rank_pair(tb, acc[tb][r], acc[tb][r + 1], tag0 + r);
         };
         if (FUSED) {
             // the fused pass has no registers for a second set of accumulators
@@ -370,7 +398,6 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             const int nb = Kpad >> 5;                    // even: Kpad is a multiple of 64
             floatx16_t accA[2], accB[2];
             bf16x8_t av[2][3];
-            const bf16x8_t bones = __builtin_bit_cast(bf16x8_t, ones);
             auto load_group = [&](int jb, int g, bf16x8_t (&dst)[3]) {
                 const bf16_t *arow = lc + (jb * 32 + col) * kCPitch;
 #pragma unroll
@@ -387,30 +414,27 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
 #pragma unroll
                         for (int r = 0; r < 16; ++r) { acc[0][r] = 0.0f; acc[1][r] = 0.0f; }
                     }
-                    const bf16x8_t b0 = kk < 8 ? __builtin_bit_cast(bf16x8_t, xa[0][kk < 8 ? kk : 0]) : bones;
-                    const bf16x8_t b1 = kk < 8 ? __builtin_bit_cast(bf16x8_t, xa[1][kk < 8 ? kk : 0]) : bones;
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(src[i], b0, acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(src[i], b1, acc[1], 0, 0, 0);
+                    const bf16x8_t t0 = __builtin_bit_cast(bf16x8_t, kk < 8 ? xa[0][kk < 8 ? kk : 0] : bias[0]);
+                    const bf16x8_t t1 = __builtin_bit_cast(bf16x8_t, kk < 8 ? xa[1][kk < 8 ? kk : 0] : bias[1]);
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(src[i], t0, acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(src[i], t1, acc[1], 0, 0, 0);
                 }
             };
-            // scores 11 c .. 11 c + 10 (of 32: 16 per token block) of a finished block
+            // pairs 6 c .. 6 c + 5 (of 16: 8 per token block; the last part has 4) of a finished block
             auto rank_part = [&](int jb, const floatx16_t (&acc)[2], int c) {
                 uint32_t tag0 = (uint32_t)jb << 4;
                 asm volatile("" : "+s"(tag0));  // opaque, see rank_block
 #pragma unroll
-                for (int sidx = 11 * c; sidx < (c == 2 ? 32 : 11 * c + 11); ++sidx) {
-                    const int tb = sidx >> 4, r = sidx & 15;
-                    const float v = __uint_as_float((__float_as_uint(acc[tb][r]) & tagmask) | (tag0 + r));
-                    b3[tb] = __builtin_amdgcn_fmed3f(b2[tb], b3[tb], v);
-                    b2[tb] = __builtin_amdgcn_fmed3f(b1[tb], b2[tb], v);
-                    b1[tb] = __builtin_amdgcn_fmed3f(b1[tb], v, pinf);
+                for (int pidx = 6 * c; pidx < (c == 2 ? 16 : 6 * c + 6); ++pidx) {
+                    const int tb = pidx >> 3, r = (pidx & 7) * 2;
+                    rank_pair(tb, acc[tb][r], acc[tb][r + 1], tag0 + r);
                 }
             };
             auto interleave6 = [&]() {
 #pragma unroll
                 for (int i = 0; i < 6; ++i) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
                 }
             };
             // one block: its three groups; `prev` (if any) is ranked in their shadow; the operands
@@ -438,29 +462,36 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             rank_block(nb - 1, accB);
         }
         // tag -> centroid index: row 8*(r/4) + 4*half + r%4 of block jb
-        auto tag_to_idx = [&](float v) {
-            const uint32_t t = __float_as_uint(v) & tagbits;
+        auto tag_to_idx = [&](uint32_t v) {
+            const uint32_t t = v & tagbits;
             return (int)((t >> 4) * 32 + ((t >> 2) & 3) * 8 + half * 4 + (t & 3));
         };
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
             if (n0 + tb * 32 >= N) break;                        // uniform: second block past the end
-            float c1 = b1[tb], c2 = b2[tb], c3 = b3[tb];
+            uint32_t c1 = b1[tb], c2 = b2[tb];
             int i1 = tag_to_idx(c1), i2 = tag_to_idx(c2);
-            {   // merge with the other half of the wavefront (same token, other centroids)
-                const float p1 = __shfl_xor(c1, 32, 64), p2 = __shfl_xor(c2, 32, 64),
-                            p3 = __shfl_xor(c3, 32, 64);
+            {   // merge with the other half of the wavefront (same token, other centroids): the two
+                // smallest of (c1 <= c2) and (p1 <= p2), each with its index
+                const uint32_t p1 = (uint32_t)__shfl_xor((int)c1, 32, 64), p2 = (uint32_t)__shfl_xor((int)c2, 32, 64);
                 const int q1 = __shfl_xor(i1, 32, 64), q2 = __shfl_xor(i2, 32, 64);
-                insert3(p1, q1, c1, c2, c3, i1, i2);
-                insert3(p2, q2, c1, c2, c3, i1, i2);
-                insert3(p3, 0, c1, c2, c3, i1, i2);
+                const bool mine = c1 <= p1;                      // which side holds the best
+                const uint32_t w1 = mine ? c1 : p1, l1 = mine ? p1 : c1;      // winner, loser of the leaders
+                const int wi = mine ? i1 : q1, li = mine ? q1 : i1;
+                const uint32_t s2 = mine ? c2 : p2;             // the winner's own runner-up
+                const int si = mine ? i2 : q2;
+                const bool second_is_loser = l1 <= s2;
+                c1 = w1; i1 = wi;
+                c2 = second_is_loser ? l1 : s2; i2 = second_is_loser ? li : si;
             }
             const float thr = (K > 256 ? 0x1.8p-14f : 0x1p-14f) * (0.5f * xn[tb] + cmax);
             int id = i1;
-            const bool amb = valid[tb] && (i2 < K) && !(c1 - c2 > thr);
-            const bool full = !(c1 - c3 > thr);
+            // not certified: the runner-up is a real centroid and lies inside the error band (as
+            // floats: the leader is the larger one unless rounding noise pushed scores above zero,
+            // in which case the difference is small or negative and the test fails as it should)
+            const bool amb = valid[tb] && (i2 < K) && !(__uint_as_float(c1) - __uint_as_float(c2) > thr);
 
-            // ---- fp64 re-evaluation of tokens the fp32 scores cannot decide ----
+            // ---- fp64 re-evaluation of tokens the fp32 scores cannot decide: all K centroids ----
             uint64_t mask = __ballot(amb) & 0xffffffffull;
             while (mask) {
                 const int tk = __builtin_ctzll(mask);
@@ -471,46 +502,27 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                         *reinterpret_cast<uint4 *>(scr + half * 64 + kk * 8) = xa[tb][kk];
                 }
                 __builtin_amdgcn_wave_barrier();
-                const int d1 = __shfl(i1, tk, 64), d2 = __shfl(i2, tk, 64);
-                const int fl = __shfl((int)full, tk, 64);
-                int winner;
-                if (!fl) {
-                    const int cand = half ? d2 : d1;
-                    const uint2 xv = *reinterpret_cast<const uint2 *>(scr + col * 4);
-                    const uint2 cv = *reinterpret_cast<const uint2 *>(lc + cand * kCPitch + col * 4);
-                    const double e0 = (double)bf16_lo(xv.x) - (double)bf16_lo(cv.x);
-                    const double e1 = (double)bf16_hi(xv.x) - (double)bf16_hi(cv.x);
-                    const double e2 = (double)bf16_lo(xv.y) - (double)bf16_lo(cv.y);
-                    const double e3 = (double)bf16_hi(xv.y) - (double)bf16_hi(cv.y);
-                    double d = e0 * e0; d += e1 * e1; d += e2 * e2; d += e3 * e3;
-                    d += shfl_xor_f64(d, 16); d += shfl_xor_f64(d, 8); d += shfl_xor_f64(d, 4);
-                    d += shfl_xor_f64(d, 2); d += shfl_xor_f64(d, 1);
-                    const double D1 = __shfl(d, 0, 64), D2 = __shfl(d, 32, 64);
-                    winner = (D2 < D1 || (D2 == D1 && d2 < d1)) ? d2 : d1;
-                } else {
-                    double bd = INFINITY; int bj = 0x7fffffff;
-                    for (int j = lane; j < K; j += 64) {
-                        const bf16_t *cr = lc + j * kCPitch;
-                        double acc = 0.0;
-                        for (int c = 0; c < kHeadDim; c += 2) {
-                            const uint32_t xw = *reinterpret_cast<const uint32_t *>(scr + c);
-                            const uint32_t cw = *reinterpret_cast<const uint32_t *>(cr + c);
-                            const double f0 = (double)bf16_lo(xw) - (double)bf16_lo(cw);
-                            acc += f0 * f0;
-                            const double f1 = (double)bf16_hi(xw) - (double)bf16_hi(cw);
-                            acc += f1 * f1;
-                        }
-                        if (acc < bd) { bd = acc; bj = j; }
+                double bd = INFINITY; int bj = 0x7fffffff;
+                for (int j = lane; j < K; j += 64) {
+                    const bf16_t *cr = lc + j * kCPitch;
+                    double acc = 0.0;
+                    for (int c = 0; c < kHeadDim; c += 2) {
+                        const uint32_t xw = *reinterpret_cast<const uint32_t *>(scr + c);
+                        const uint32_t cw = *reinterpret_cast<const uint32_t *>(cr + c);
+                        const double f0 = (double)bf16_lo(xw) - (double)bf16_lo(cw);
+                        acc += f0 * f0;
+                        const double f1 = (double)bf16_hi(xw) - (double)bf16_hi(cw);
+                        acc += f1 * f1;
                     }
-#pragma unroll
-                    for (int off = 32; off >= 1; off >>= 1) {
-                        const double od = shfl_xor_f64(bd, off);
-                        const int oj = __shfl_xor(bj, off, 64);
-                        if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
-                    }
-                    winner = bj;
+                    if (acc < bd) { bd = acc; bj = j; }
                 }
-                if (col == tk) id = winner;
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) {
+                    const double od = shfl_xor_f64(bd, off);
+                    const int oj = __shfl_xor(bj, off, 64);
+                    if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+                }
+                if (col == tk) id = bj;
                 __builtin_amdgcn_wave_barrier();
             }
 
@@ -532,8 +544,8 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                     r[kk * 8 + 2 * e + 1] = bf16_hi(xw[e]) - bf16_hi(cw[e]);
                 }
             }
-            quantize_token<B_>(r, a.T, valid[tb], half, a.codes + hn * a.T * 32,
-                               a.scales + hn * a.T * (kHeadDim / B_));
+            const int T = T_ > 0 ? T_ : a.T;
+            quantize_token<B_, T_>(r, T, valid[tb], half, a.codes + hn * T * 32, a.scales + hn * T * (kHeadDim / B_));
             __builtin_amdgcn_sched_barrier(0);       // keep the two tokens' passes apart: each needs most registers
         }
     }
@@ -543,14 +555,14 @@ static size_t assign_smem_bytes(int Kpad) {
     return (size_t)Kpad * kCPitch * 2 + (size_t)kAsgWaves * kHeadDim * 2;
 }
 
-template <int B_, bool FUSED>
+template <int B_, bool FUSED, int T_>
 static hipError_t launch_assign_t(const AssignArgs &a, hipStream_t s) {
     const int Kpad = (a.K + 63) & ~63;
     const size_t smem = assign_smem_bytes(Kpad);
     static LdsHighWater lds_limit[2] = {};
-    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED, true>), smem, lds_limit[0]);
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED, true, T_>), smem, lds_limit[0]);
     if (e != hipSuccess) return e;
-    e = ensure_dynamic_lds(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED, false>), smem, lds_limit[1]);
+    e = ensure_dynamic_lds(reinterpret_cast<const void *>(&assign_kernel<B_, FUSED, false, T_>), smem, lds_limit[1]);
     if (e != hipSuccess) return e;
     // tokens per workgroup: 256 per step; more steps per workgroup amortise the table staging
     // once there are enough workgroups to fill the chip several times over
@@ -571,22 +583,33 @@ static hipError_t launch_assign_t(const AssignArgs &a, hipStream_t s) {
         if (e != hipSuccess) return e;
     }
     if (norms_given)
-        hipLaunchKernelGGL((assign_kernel<B_, FUSED, true>), dim3((unsigned)a.H, (unsigned)gy), dim3(kAsgThreads), smem, s, a,
+        hipLaunchKernelGGL((assign_kernel<B_, FUSED, true, T_>), dim3((unsigned)a.H, (unsigned)gy), dim3(kAsgThreads), smem, s, a,
                            Kpad, tpw);
     else
-        hipLaunchKernelGGL((assign_kernel<B_, FUSED, false>), dim3((unsigned)a.H, (unsigned)gy), dim3(kAsgThreads), smem, s, a,
+        hipLaunchKernelGGL((assign_kernel<B_, FUSED, false, T_>), dim3((unsigned)a.H, (unsigned)gy), dim3(kAsgThreads), smem, s, a,
                            Kpad, tpw);
     return hipGetLastError();
 }
 
+// the fused pass with the round count of the measured configurations fixed at compile time
+// (group 64: 1, 2 and 4 rounds; group 32: 3), any other count at run time
+template <int B_>
+static hipError_t launch_fused(const AssignArgs &a, hipStream_t s) {
+    if (B_ == 64 && a.T == 1) return launch_assign_t<B_, true, (B_ == 64 ? 1 : 0)>(a, s);
+    if (B_ == 64 && a.T == 2) return launch_assign_t<B_, true, (B_ == 64 ? 2 : 0)>(a, s);
+    if (B_ == 64 && a.T == 4) return launch_assign_t<B_, true, (B_ == 64 ? 4 : 0)>(a, s);
+    if (B_ == 32 && a.T == 3) return launch_assign_t<B_, true, (B_ == 32 ? 3 : 0)>(a, s);
+    return launch_assign_t<B_, true, 0>(a, s);
+}
+
 hipError_t launch_assign(const AssignArgs &a, hipStream_t s) {
     if (a.n_tokens == 0) return hipSuccess;
-    if (!a.fused) return launch_assign_t<64, false>(a, s);
+    if (!a.fused) return launch_assign_t<64, false, 0>(a, s);
     switch (a.B) {
-        case 16: return launch_assign_t<16, true>(a, s);
-        case 32: return launch_assign_t<32, true>(a, s);
-        case 64: return launch_assign_t<64, true>(a, s);
-        default: return launch_assign_t<128, true>(a, s);
+        case 16: return launch_fused<16>(a, s);
+        case 32: return launch_fused<32>(a, s);
+        case 64: return launch_fused<64>(a, s);
+        default: return launch_fused<128>(a, s);
     }
 }
 
