@@ -407,7 +407,7 @@ def test_attention_with_values_of_magnitude_1e3():
         assert (err <= 1e-4 + 2.0 ** -10 * spread).all(), f"head {h}: worst {(err / (1e-4 + 2.0 ** -10 * spread)).max()}"
 
 
-@pytest.mark.parametrize("L,T,Bg", [(100, 1, 128), (100, 3, 64), (36, 2, 32)])
+@pytest.mark.parametrize("L,T,Bg", [(100, 1, 128), (100, 3, 128), (35, 1, 32)])
 def test_unit_scale_arrays_off_16_byte_boundaries(L, T, Bg):
     """Several units whose binary16 scale arrays do not start on 16-byte boundaries (capacity x T x
     d/B x 2 bytes is no multiple of 16): the wide-load kernel must not be chosen; every unit
