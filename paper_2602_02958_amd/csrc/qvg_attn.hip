@@ -296,16 +296,23 @@ template <int T_, int SM, int FMT, bool ROPE, bool QL>   // T_ > 0: compile-time
                                 // FMT: stored format (kFmt* bits)
                                 // ROPE: rotate the decoded keys by a.rope
 __global__ __launch_bounds__(kAtThreads, 2)
-void attn_kernel_direct(AttnArgs a) {
+void attn_kernel_direct(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_xcd) {
     constexpr int TM = T_ > 0 ? T_ : kMaxStages;
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t *Kt = reinterpret_cast<uint16_t *>(smem);                  // [2][64][136] bf16
     uint16_t *Vt = Kt + 2 * kKtElems;                                   // [2][128][72] f16, transposed
 
+    // Workgroups are dealt to the 8 XCDs round-robin by their linear id; they are re-numbered so
+    // that the query blocks of one unit run on one XCD and its cache is fetched into one L2 only
+    // (as in the staged kernel below; the grid is padded to a multiple of 8)
+    const int w = (int)(blockIdx.x % 8u) * blocks_per_xcd + (int)(blockIdx.x / 8u);
+    if (w >= n_blocks) return;                                          // uniform, before any barrier
+    const int h = w / n_qblocks;
+    const int qblock = w - h * n_qblocks;
+
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
-    const int h = blockIdx.y;
-    const int64_t qrow = (int64_t)blockIdx.x * kAtQPerBlock + wave * 32 + col;
+    const int64_t qrow = (int64_t)qblock * kAtQPerBlock + wave * 32 + col;
     const bool qvalid = qrow < a.n_q;
     // Prefix length per query (chunk-causal order for the queries of several chunks): the lane's
     // query sees tokens 0 .. qlen-1; wmin = the shortest prefix in the wavefront (tiles below it
@@ -558,9 +565,10 @@ constexpr size_t kAtSmemStagedWide = kAtSmemStaged + 4 * 2 * kAtKv;      // the 
 
 template <bool V> struct BoolC { static constexpr bool value = V; };
 
-template <int T_, bool ROPE, bool FP8, bool I4, bool WIDE>   // ROPE: rotate the decoded keys by a.rope; FP8: E4M3 scale bytes;
+template <int T_, bool ROPE, bool FP8, bool I4, bool WIDE, bool QL>   // ROPE: rotate the decoded keys by a.rope; FP8: E4M3 scale bytes;
                                                   // I4: 4-bit levels (64 code bytes per token and round, T_ <= 2);
-                                                  // WIDE: 16-bit ids (more than 256 centroids)
+                                                  // WIDE: 16-bit ids (more than 256 centroids);
+                                                  // QL: a prefix length per query (a.q_len)
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_xcd) {
     constexpr int T = T_;
@@ -774,7 +782,29 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     auto is_full = [&](const Tile &t) { return t.valid && t.cend - t.t0 >= kAtKv; };
 
     // ---- prologue: tile 0 decoded into buffer 0, tile 1 parked, ids of tiles 0..2 parked ------
-    const Span sp = span_of(a);
+    // QL: the lane's query sees tokens 0 .. qlen-1; wmin = the shortest prefix in the wavefront
+    // (tiles below it need no mask); the workgroup walks the cache up to its longest prefix only
+    int qlen = 0x7fffffff, wmin = 0x7fffffff;
+    Span sp = span_of(a);
+    if (QL) {
+        __shared__ int bmax;
+        if (tid == 0) bmax = 1;
+        __syncthreads();
+        const int nk = (int)a.n_kv;
+        int mx = 1;
+        if (qvalid) { const int v = a.q_len[qrow]; qlen = v < 0 ? 0 : (v > nk ? nk : v); mx = qlen > 1 ? qlen : 1; }
+        wmin = qlen;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const int o = __shfl_xor(wmin, off, 64); wmin = o < wmin ? o : wmin;
+            const int p = __shfl_xor(mx, off, 64); mx = p > mx ? p : mx;
+        }
+        if (lane == 0) atomicMax(&bmax, mx);
+        __syncthreads();
+        sp.n_kv = bmax;
+        sp.n_chunks = (int)((sp.n_kv + sp.chunk_len - 1) / sp.chunk_len);
+        wmin = __builtin_amdgcn_readfirstlane(wmin);
+    }
     Tile cur = first_tile(sp);
     Tile nxt = next_tile(sp, cur);
     Tile nn = nxt.valid ? next_tile(sp, nxt) : nxt;
@@ -836,6 +866,16 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
                         if (kv >= ntile) S[nb][r] = -INFINITY;
                     }
             }
+        }
+        if (QL && cur.t0 + kAtKv > wmin) {                     // uniform: some query of the wavefront ends in or before this tile
+            const int left = qlen - cur.t0;                    // tokens of this tile the lane's query sees (may be <= 0)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kv = nb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                    if (kv >= left) S[nb][r] = -INFINITY;
+                }
         }
         float tmax = -INFINITY;
 #pragma unroll
@@ -933,14 +973,14 @@ void attn_kernel_staged(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
         while (is_full(cur) && is_full(nxt) && is_full(nn)) tile_step(BoolC<true>{}, decode_first);
         if (!tile_step(BoolC<false>{}, false)) break;
     }
-    store_result(a, h, qrow, qvalid, qvalid, half, O, m, l);
+    store_result(a, h, qrow, qvalid && (!QL || qlen > 0), qvalid, half, O, m, l);
 }
 
-template <int T_, bool ROPE, bool FP8, bool I4, bool WIDE>
+template <int T_, bool ROPE, bool FP8, bool I4, bool WIDE, bool QL = false>
 static hipError_t launch_attn_staged_r(const AttnArgs &a, hipStream_t s) {
     constexpr size_t kSmem = WIDE ? kAtSmemStagedWide : kAtSmemStaged;
     static LdsHighWater lds_limit = {};
-    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE, FP8, I4, WIDE>), kSmem, lds_limit);
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(&attn_kernel_staged<T_, ROPE, FP8, I4, WIDE, QL>), kSmem, lds_limit);
     if (e != hipSuccess) return e;
     const int64_t nqb = (a.n_q + kAtQPerBlock - 1) / kAtQPerBlock;
     const int64_t nb = nqb * a.H;
@@ -949,7 +989,7 @@ static hipError_t launch_attn_staged_r(const AttnArgs &a, hipStream_t s) {
     // the grid is padded to a multiple of 8 (one share per XCD): at most 7 surplus workgroups, whose
     // renumbered index is >= nb; each returns on its first statement, before it forms a unit index
     if ((int64_t)bpx * 8 > nb + 7) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((attn_kernel_staged<T_, ROPE, FP8, I4, WIDE>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kSmem, s, a,
+    hipLaunchKernelGGL((attn_kernel_staged<T_, ROPE, FP8, I4, WIDE, QL>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kSmem, s, a,
                        (int)nqb, (int)nb, bpx);
     return hipGetLastError();
 }
@@ -963,8 +1003,13 @@ static hipError_t launch_attn_tr(const AttnArgs &a, hipStream_t s) {
     static LdsHighWater lds_limit = {};
     hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(&attn_kernel_direct<T_, SM, FMT, ROPE, QL>), kAtSmem, lds_limit);
     if (e != hipSuccess) return e;
-    dim3 grid((unsigned)((a.n_q + kAtQPerBlock - 1) / kAtQPerBlock), (unsigned)a.H);
-    hipLaunchKernelGGL((attn_kernel_direct<T_, SM, FMT, ROPE, QL>), grid, dim3(kAtThreads), kAtSmem, s, a);
+    const int64_t nqb = (a.n_q + kAtQPerBlock - 1) / kAtQPerBlock;
+    const int64_t nb = nqb * a.H;
+    if (nb > 0x7fffffff - 8) return hipErrorInvalidValue;
+    const int bpx = (int)((nb + 7) / 8);
+    if ((int64_t)bpx * 8 > nb + 7) return hipErrorInvalidValue;        // at most 7 surplus workgroups, which return at once
+    hipLaunchKernelGGL((attn_kernel_direct<T_, SM, FMT, ROPE, QL>), dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmem, s, a,
+                       (int)nqb, (int)nb, bpx);
     return hipGetLastError();
 }
 template <int T_, int SM, int FMT = 0>
@@ -994,9 +1039,29 @@ static hipError_t launch_attn_qlen(const AttnArgs &a, hipStream_t s) {
     return a.rope ? launch_attn_tr<0, 1, FMT, true, true>(a, s) : launch_attn_tr<0, 1, FMT, false, true>(a, s);
 }
 
+template <int T_>
+static hipError_t launch_attn_staged_qlen(const AttnArgs &a, hipStream_t s) {
+    return a.rope ? launch_attn_staged_r<T_, true, false, false, false, true>(a, s)
+                  : launch_attn_staged_r<T_, false, false, false, false, true>(a, s);
+}
+
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
     if (a.n_q == 0) return hipSuccess;
-    if (a.q_len) {                 // a prefix per query: instances of the general kernel with run-time counts
+    if (a.q_len) {
+        // a prefix per query: the staged kernel for the plain format (2-bit levels, binary16 scales,
+        // one smoothing stage, byte ids, up to 4 rounds, aligned chunks); else instances of the
+        // general kernel with run-time counts
+        const bool al = ((a.chunk_len % 8 == 0) || a.n_chunks == 1) &&
+            (reinterpret_cast<uintptr_t>(a.k_scales) & 15u) == 0 && (reinterpret_cast<uintptr_t>(a.v_scales) & 15u) == 0 &&
+            (a.H == 1 || (a.kv_stride * a.T * (kHeadDim / a.B) * 2) % 16 == 0);
+        if (a.fmt == 0 && a.S == 1 && !a.id_wide && al && a.T <= kStMaxT) {
+            switch (a.T) {
+                case 1: return launch_attn_staged_qlen<1>(a, s);
+                case 2: return launch_attn_staged_qlen<2>(a, s);
+                case 3: return launch_attn_staged_qlen<3>(a, s);
+                default: return launch_attn_staged_qlen<4>(a, s);
+            }
+        }
         switch (a.fmt) {
             case 0: return launch_attn_qlen<0>(a, s);
             case kFmtE4M3: return launch_attn_qlen<kFmtE4M3>(a, s);

@@ -14,24 +14,16 @@
 // MFMA step: a small kernel has split it, per centroid, into three bf16 pieces whose sum is
 // the fp32 value exactly, and the matching token operand holds three ones.
 //
-// Exactness.  The reference result is the argmin of fp64 distances.  The fp32 scores carry a
-// rounding error, so the kernel keeps the two best scores per token (cluster index carried in the
-// 7 low mantissa bits) and certifies the winner only when it leads by more than a bound on that
-// error,
+// Exactness.  The reference result is the argmin of fp64 distances.  The fp32 scores
+// carry a rounding error, so the kernel keeps the three largest scores per token
+// (cluster index carried in the 7 low mantissa bits) and certifies the winner only
+// when it leads by more than a bound on that error,
 //     thr = 2^-14 * (||x||^2 / 2 + max_j ||c_j||^2),
-// which covers the 134 accumulation roundings of half an ulp each plus the index tag for both
-// scores (with more than 256 centroids the tag has 8 bits and the factor is 1.5 * 2^-14).
-// Otherwise all K centroids are re-evaluated in fp64 with the channels summed in index order (the
-// reference order); equal fp64 distances go to the lower index.
-//
-// Ranking cost is what bounds the pass (one score per token and centroid, 256 of them per lane
-// and step at K = 256), so it is kept to 2.5 vector instructions per score: the token's own
-// -||x||^2/2 enters the same extra MFMA step, which makes every score -||x - c||^2/2 <= 0, and for
-// non-positive floats the UNSIGNED order of the bit patterns is the reversed float order.  The
-// tagged patterns are then ranked with integer min3 / med3 / min on two scores at a time (no
-// NaN-quieting copies, no second tag compare).  A score that rounding pushes above zero compares
-// as better than every negative one, which is the right direction, and any mis-order among such
-// scores is inside the band and goes to the fp64 scan.
+// which covers the 131 accumulation roundings of half an ulp each plus the index tag for both
+// scores (with more than 256 centroids the tag has 8 bits and the factor is 1.5 * 2^-14).  Otherwise the candidates are re-evaluated in fp64: the two leaders
+// cooperatively by the wavefront, or, if the third score is inside the band as well,
+// all K centroids with the channels summed in index order (the reference order).
+// Equal fp64 distances go to the lower index.
 #include "qvg_internal.hpp"
 
 namespace qvg {
@@ -39,8 +31,15 @@ namespace qvg {
 constexpr int kAsgThreads = 256;
 constexpr int kAsgWaves = kAsgThreads / 64;
 constexpr int kAsgTile = 64;                    // tokens per wavefront step (two MFMA column blocks)
-constexpr int kCPitch = 136;                    // bf16 elements per LDS centroid row (272 B): 128 + (hi, mid, lo of -||c||^2/2) + 1, 1, 1 + 2 zeros
+constexpr int kCPitch = 136;                    // bf16 elements per LDS centroid row (272 B): 128 + (hi, mid, lo of -||c||^2/2) + 5 zeros
 constexpr int kPrepThreads = 256;
+
+__device__ __forceinline__ void insert3(float v, int idx, float &b1, float &b2, float &b3,
+                                        int &i1, int &i2) {
+    if (v > b1) { b3 = b2; b2 = b1; i2 = i1; b1 = v; i1 = idx; }
+    else if (v > b2) { b3 = b2; b2 = v; i2 = idx; }
+    else if (v > b3) { b3 = v; }
+}
 
 __device__ __forceinline__ double shfl_xor_f64(double v, int m) { return __shfl_xor(v, m, 64); }
 // Sum over each aligned group of 16 lanes, every lane getting the total, by data-parallel-primitive
@@ -264,22 +263,26 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                 const float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
                 const float lo = __uint_as_float(__float_as_uint(r1 - mid) & 0xffff0000u);
                 *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) =
-                    make_uint4((__float_as_uint(hi) >> 16) | (__float_as_uint(mid) & 0xffff0000u),
-                               (__float_as_uint(lo) >> 16) | 0x3F800000u, 0x3F803F80u, 0u);
+                    make_uint4((__float_as_uint(hi) >> 16) | (__float_as_uint(mid) & 0xffff0000u), __float_as_uint(lo) >> 16, 0u, 0u);
             }
         }
     }
     if (norms_given)
         for (int row = tid; row < Kpad; row += kAsgThreads) {
             const uint2 p = a.nh3[(int64_t)h * Kpad + row];
-            *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) = make_uint4(p.x, p.y | 0x3F800000u, 0x3F803F80u, 0u);
+            *reinterpret_cast<uint4 *>(lc + row * kCPitch + kHeadDim) = make_uint4(p.x, p.y, 0u, 0u);
         }
     __syncthreads();
     const float cmax = norms_given ? a.cmax[h] : __uint_as_float(smax);
     bf16_t *scr = lscr + wave * kHeadDim;
+    // token operand of the extra MFMA step: three ones against (hi, mid, lo), lanes 0..31 only
     // 7 tag bits name a row among 256; with more rows the tag takes 8 (and the band below widens)
     const uint32_t tagbits = K > 256 ? 0xFFu : 0x7Fu;
     const uint32_t tagmask = vgpr_const(~tagbits);
+    // +inf kept in a register the compiler cannot see through: med3(a, b, +inf) then stays one
+    // instruction (as a constant it is rewritten into max(a, b) plus a NaN-quieting copy)
+    const float pinf = __uint_as_float(vgpr_const(0x7f800000u));
+    const uint4 ones = half ? make_uint4(0u, 0u, 0u, 0u) : make_uint4(0x3F803F80u, 0x00003F80u, 0u, 0u);
 
     const int64_t blk0 = (int64_t)blockIdx.y * tiles_per_wave * (kAsgWaves * kAsgTile);
     const bf16_t *xh = a.x + (int64_t)h * a.stride_head + half * 64;
@@ -329,39 +332,12 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             }
             xn[tb] = s + __shfl_xor(s, 32, 64);
         }
-        // token operand of the extra MFMA step (lanes 0..31 only; the other half holds zeros): three
-        // ones against the row's (hi, mid, lo) of -||c||^2/2, and the token's own -||x||^2/2, split
-        // into three bf16 pieces the same way, against the row's three ones.  Every score is then
-        // -||x - c||^2/2 up to rounding; the term is the same for all centroids of a token, so it
-        // moves no comparison between them.
-        uint4 bias[2];
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            const float nx = -0.5f * xn[tb];
-            const float hi = __uint_as_float(__float_as_uint(nx) & 0xffff0000u);
-            const float r1 = nx - hi;
-            const float mid = __uint_as_float(__float_as_uint(r1) & 0xffff0000u);
-            const float lo = __uint_as_float(__float_as_uint(r1 - mid) & 0xffff0000u);
-            bias[tb] = half ? make_uint4(0u, 0u, 0u, 0u)
-                            : make_uint4(0x3F803F80u, 0x00003F80u | (__float_as_uint(hi) & 0xffff0000u),
-                                         (__float_as_uint(mid) >> 16) | (__float_as_uint(lo) & 0xffff0000u), 0u);
-        }
 
         // ---- scores on the matrix cores, running top three per lane and token ----
         // Blocks of 32 centroids, software-pipelined: the MFMAs of block jb+1 are issued between
         // the VALU instructions that rank the scores of block jb (an MFMA occupies the matrix
         // pipe for 8 VALU issue slots), so one wavefront keeps both pipes busy.
-        // the two best scores of each token as tagged bit patterns; smaller unsigned = better
-        uint32_t b1[2] = {~0u, ~0u}, b2[2] = {~0u, ~0u};
-        // two more scores of token block tb: 2 tag inserts (v_and_or_b32, the tag is scalar
-        // arithmetic), v_med3_u32, v_min3_u32, v_min_u32
-        auto rank_pair = [&](int tb, float s0, float s1, uint32_t t0) {
-            const uint32_t v0 = (__float_as_uint(s0) & tagmask) | t0;
-            const uint32_t v1 = (__float_as_uint(s1) & tagmask) | (t0 + 1u);
-            const uint32_t md = max(min(v0, v1), min(max(v0, v1), b1[tb]));        // median of (v0, v1, b1): v_med3_u32
-            b1[tb] = min(min(b1[tb], v0), v1);
-            b2[tb] = min(b2[tb], md);
-        };
+        float b1[2] = {-INFINITY, -INFINITY}, b2[2] = {-INFINITY, -INFINITY}, b3[2] = {-INFINITY, -INFINITY};
         auto score_block = [&](int jb, floatx16_t (&acc)[2]) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) { acc[0][r] = 0.0f; acc[1][r] = 0.0f; }
@@ -373,8 +349,9 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                 acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, xa[1][kk]), acc[1], 0, 0, 0);
             }
             const bf16x8_t av = *reinterpret_cast<const bf16x8_t *>(arow + kHeadDim);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, bias[0]), acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8_t, bias[1]), acc[1], 0, 0, 0);
+            const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, ones);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[1], 0, 0, 0);
         };
         auto rank_block = [&](int jb, const floatx16_t (&acc)[2]) {
             uint32_t tag0 = (uint32_t)jb << 4;
@@ -382,7 +359,14 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int r = 0; r < 16; r += 2) rank_pair(tb, acc[tb][r], acc[tb][r + 1], tag0 + r);
+                for (int r = 0; r < 16; ++r) {
+                    // (score & ~0x7F) | tag: one v_and_or_b32, the tag is scalar arithmetic.
+                    // max(a, b) is written med3(a, b, +inf): no NaN-quieting copy is needed.
+                    const float v = __uint_as_float((__float_as_uint(acc[tb][r]) & tagmask) | (tag0 + r));
+                    b3[tb] = __builtin_amdgcn_fmed3f(b2[tb], b3[tb], v);
+                    b2[tb] = __builtin_amdgcn_fmed3f(b1[tb], b2[tb], v);
+                    b1[tb] = __builtin_amdgcn_fmed3f(b1[tb], v, pinf);
+                }
         };
         if (FUSED) {
             // the fused pass has no registers for a second set of accumulators
@@ -398,6 +382,7 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             const int nb = Kpad >> 5;                    // even: Kpad is a multiple of 64
             floatx16_t accA[2], accB[2];
             bf16x8_t av[2][3];
+            const bf16x8_t bones = __builtin_bit_cast(bf16x8_t, ones);
             auto load_group = [&](int jb, int g, bf16x8_t (&dst)[3]) {
                 const bf16_t *arow = lc + (jb * 32 + col) * kCPitch;
 #pragma unroll
@@ -414,27 +399,30 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
 #pragma unroll
                         for (int r = 0; r < 16; ++r) { acc[0][r] = 0.0f; acc[1][r] = 0.0f; }
                     }
-                    const bf16x8_t t0 = __builtin_bit_cast(bf16x8_t, kk < 8 ? xa[0][kk < 8 ? kk : 0] : bias[0]);
-                    const bf16x8_t t1 = __builtin_bit_cast(bf16x8_t, kk < 8 ? xa[1][kk < 8 ? kk : 0] : bias[1]);
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(src[i], t0, acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(src[i], t1, acc[1], 0, 0, 0);
+                    const bf16x8_t b0 = kk < 8 ? __builtin_bit_cast(bf16x8_t, xa[0][kk < 8 ? kk : 0]) : bones;
+                    const bf16x8_t b1 = kk < 8 ? __builtin_bit_cast(bf16x8_t, xa[1][kk < 8 ? kk : 0]) : bones;
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(src[i], b0, acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(src[i], b1, acc[1], 0, 0, 0);
                 }
             };
-            // pairs 6 c .. 6 c + 5 (of 16: 8 per token block; the last part has 4) of a finished block
+            // scores 11 c .. 11 c + 10 (of 32: 16 per token block) of a finished block
             auto rank_part = [&](int jb, const floatx16_t (&acc)[2], int c) {
                 uint32_t tag0 = (uint32_t)jb << 4;
                 asm volatile("" : "+s"(tag0));  // opaque, see rank_block
 #pragma unroll
-                for (int pidx = 6 * c; pidx < (c == 2 ? 16 : 6 * c + 6); ++pidx) {
-                    const int tb = pidx >> 3, r = (pidx & 7) * 2;
-                    rank_pair(tb, acc[tb][r], acc[tb][r + 1], tag0 + r);
+                for (int sidx = 11 * c; sidx < (c == 2 ? 32 : 11 * c + 11); ++sidx) {
+                    const int tb = sidx >> 4, r = sidx & 15;
+                    const float v = __uint_as_float((__float_as_uint(acc[tb][r]) & tagmask) | (tag0 + r));
+                    b3[tb] = __builtin_amdgcn_fmed3f(b2[tb], b3[tb], v);
+                    b2[tb] = __builtin_amdgcn_fmed3f(b1[tb], b2[tb], v);
+                    b1[tb] = __builtin_amdgcn_fmed3f(b1[tb], v, pinf);
                 }
             };
             auto interleave6 = [&]() {
 #pragma unroll
                 for (int i = 0; i < 6; ++i) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
                 }
             };
             // one block: its three groups; `prev` (if any) is ranked in their shadow; the operands
@@ -462,36 +450,29 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             rank_block(nb - 1, accB);
         }
         // tag -> centroid index: row 8*(r/4) + 4*half + r%4 of block jb
-        auto tag_to_idx = [&](uint32_t v) {
-            const uint32_t t = v & tagbits;
+        auto tag_to_idx = [&](float v) {
+            const uint32_t t = __float_as_uint(v) & tagbits;
             return (int)((t >> 4) * 32 + ((t >> 2) & 3) * 8 + half * 4 + (t & 3));
         };
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
             if (n0 + tb * 32 >= N) break;                        // uniform: second block past the end
-            uint32_t c1 = b1[tb], c2 = b2[tb];
+            float c1 = b1[tb], c2 = b2[tb], c3 = b3[tb];
             int i1 = tag_to_idx(c1), i2 = tag_to_idx(c2);
-            {   // merge with the other half of the wavefront (same token, other centroids): the two
-                // smallest of (c1 <= c2) and (p1 <= p2), each with its index
-                const uint32_t p1 = (uint32_t)__shfl_xor((int)c1, 32, 64), p2 = (uint32_t)__shfl_xor((int)c2, 32, 64);
+            {   // merge with the other half of the wavefront (same token, other centroids)
+                const float p1 = __shfl_xor(c1, 32, 64), p2 = __shfl_xor(c2, 32, 64),
+                            p3 = __shfl_xor(c3, 32, 64);
                 const int q1 = __shfl_xor(i1, 32, 64), q2 = __shfl_xor(i2, 32, 64);
-                const bool mine = c1 <= p1;                      // which side holds the best
-                const uint32_t w1 = mine ? c1 : p1, l1 = mine ? p1 : c1;      // winner, loser of the leaders
-                const int wi = mine ? i1 : q1, li = mine ? q1 : i1;
-                const uint32_t s2 = mine ? c2 : p2;             // the winner's own runner-up
-                const int si = mine ? i2 : q2;
-                const bool second_is_loser = l1 <= s2;
-                c1 = w1; i1 = wi;
-                c2 = second_is_loser ? l1 : s2; i2 = second_is_loser ? li : si;
+                insert3(p1, q1, c1, c2, c3, i1, i2);
+                insert3(p2, q2, c1, c2, c3, i1, i2);
+                insert3(p3, 0, c1, c2, c3, i1, i2);
             }
             const float thr = (K > 256 ? 0x1.8p-14f : 0x1p-14f) * (0.5f * xn[tb] + cmax);
             int id = i1;
-            // not certified: the runner-up is a real centroid and lies inside the error band (as
-            // floats: the leader is the larger one unless rounding noise pushed scores above zero,
-            // in which case the difference is small or negative and the test fails as it should)
-            const bool amb = valid[tb] && (i2 < K) && !(__uint_as_float(c1) - __uint_as_float(c2) > thr);
+            const bool amb = valid[tb] && (i2 < K) && !(c1 - c2 > thr);
+            const bool full = !(c1 - c3 > thr);
 
-            // ---- fp64 re-evaluation of tokens the fp32 scores cannot decide: all K centroids ----
+            // ---- fp64 re-evaluation of tokens the fp32 scores cannot decide ----
             uint64_t mask = __ballot(amb) & 0xffffffffull;
             while (mask) {
                 const int tk = __builtin_ctzll(mask);
@@ -502,27 +483,46 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                         *reinterpret_cast<uint4 *>(scr + half * 64 + kk * 8) = xa[tb][kk];
                 }
                 __builtin_amdgcn_wave_barrier();
-                double bd = INFINITY; int bj = 0x7fffffff;
-                for (int j = lane; j < K; j += 64) {
-                    const bf16_t *cr = lc + j * kCPitch;
-                    double acc = 0.0;
-                    for (int c = 0; c < kHeadDim; c += 2) {
-                        const uint32_t xw = *reinterpret_cast<const uint32_t *>(scr + c);
-                        const uint32_t cw = *reinterpret_cast<const uint32_t *>(cr + c);
-                        const double f0 = (double)bf16_lo(xw) - (double)bf16_lo(cw);
-                        acc += f0 * f0;
-                        const double f1 = (double)bf16_hi(xw) - (double)bf16_hi(cw);
-                        acc += f1 * f1;
+                const int d1 = __shfl(i1, tk, 64), d2 = __shfl(i2, tk, 64);
+                const int fl = __shfl((int)full, tk, 64);
+                int winner;
+                if (!fl) {
+                    const int cand = half ? d2 : d1;
+                    const uint2 xv = *reinterpret_cast<const uint2 *>(scr + col * 4);
+                    const uint2 cv = *reinterpret_cast<const uint2 *>(lc + cand * kCPitch + col * 4);
+                    const double e0 = (double)bf16_lo(xv.x) - (double)bf16_lo(cv.x);
+                    const double e1 = (double)bf16_hi(xv.x) - (double)bf16_hi(cv.x);
+                    const double e2 = (double)bf16_lo(xv.y) - (double)bf16_lo(cv.y);
+                    const double e3 = (double)bf16_hi(xv.y) - (double)bf16_hi(cv.y);
+                    double d = e0 * e0; d += e1 * e1; d += e2 * e2; d += e3 * e3;
+                    d += shfl_xor_f64(d, 16); d += shfl_xor_f64(d, 8); d += shfl_xor_f64(d, 4);
+                    d += shfl_xor_f64(d, 2); d += shfl_xor_f64(d, 1);
+                    const double D1 = __shfl(d, 0, 64), D2 = __shfl(d, 32, 64);
+                    winner = (D2 < D1 || (D2 == D1 && d2 < d1)) ? d2 : d1;
+                } else {
+                    double bd = INFINITY; int bj = 0x7fffffff;
+                    for (int j = lane; j < K; j += 64) {
+                        const bf16_t *cr = lc + j * kCPitch;
+                        double acc = 0.0;
+                        for (int c = 0; c < kHeadDim; c += 2) {
+                            const uint32_t xw = *reinterpret_cast<const uint32_t *>(scr + c);
+                            const uint32_t cw = *reinterpret_cast<const uint32_t *>(cr + c);
+                            const double f0 = (double)bf16_lo(xw) - (double)bf16_lo(cw);
+                            acc += f0 * f0;
+                            const double f1 = (double)bf16_hi(xw) - (double)bf16_hi(cw);
+                            acc += f1 * f1;
+                        }
+                        if (acc < bd) { bd = acc; bj = j; }
                     }
-                    if (acc < bd) { bd = acc; bj = j; }
-                }
 #pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    const double od = shfl_xor_f64(bd, off);
-                    const int oj = __shfl_xor(bj, off, 64);
-                    if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+                    for (int off = 32; off >= 1; off >>= 1) {
+                        const double od = shfl_xor_f64(bd, off);
+                        const int oj = __shfl_xor(bj, off, 64);
+                        if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+                    }
+                    winner = bj;
                 }
-                if (col == tk) id = bj;
+                if (col == tk) id = winner;
                 __builtin_amdgcn_wave_barrier();
             }
 

@@ -199,7 +199,8 @@ def test_streaming_cache_append_attend_decode():
     assert torch.equal(sc.decode(first_chunk=2), sc.decode()[:, 2 * L:])
 
 
-@pytest.mark.parametrize("L,T,Bg,S,bits,fmt,rope", [(520, 2, 32, 1, 2, B.SCALE_F16, False), (260, 1, 16, 4, 2, B.SCALE_E4M3, False),
+@pytest.mark.parametrize("L,T,Bg,S,bits,fmt,rope", [(520, 2, 32, 1, 2, B.SCALE_F16, False), (520, 4, 64, 1, 2, B.SCALE_F16, True),
+                                                    (520, 3, 32, 1, 2, B.SCALE_F16, False), (260, 1, 16, 4, 2, B.SCALE_E4M3, False),
                                                     (516, 3, 64, 1, 4, B.SCALE_F16, True), (520, 1, 64, 2, 4, B.SCALE_E4M3, True)])
 def test_attention_with_a_prefix_length_per_query(L, T, Bg, S, bits, fmt, rope):
     """qvg_attn_decode_causal: the queries of several chunks in one call, each seeing the chunks
