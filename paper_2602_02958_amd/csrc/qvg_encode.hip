@@ -61,6 +61,12 @@ __device__ __forceinline__ double sum16_f64(double v) {
     v += dpp_f64<0x140>(v);      // row_mirror
     return v;
 }
+__device__ __forceinline__ double readlane_f64(double v, int lane) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), lane);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
 template <bool V> struct BoolK { static constexpr bool value = V; };
 // (a & mask) | (b & ~mask): v_bfi_b32
 __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
@@ -224,6 +230,7 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
     // (load, store to LDS, norm) every piece waits a whole memory round trip (0.85 us measured),
     // which was most of what a workgroup with a single 256-token step spent on a 256-row table.
     constexpr int kStageBatch = 8;
+    uint32_t up_max = 0u;          // this lane's largest ||c||^2 bound so far (bit pattern): one LDS atomic after the loop
     for (int i0 = tid; i0 < Kpad * 16; i0 += kAsgThreads * kStageBatch) {      // Kpad*16 is a multiple of the block: whole waves
         uint4 vb[kStageBatch];
 #pragma unroll
@@ -256,7 +263,7 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                 if (row < K) {
                     nh = (float)(-0.5 * sq);
                     const float up = (float)sq * (1.0f + 0x1p-22f);      // upper bound of ||c||^2 in fp32, as its bit pattern
-                    atomicMax(&smax, __float_as_uint(up));
+                    up_max = max(up_max, __float_as_uint(up));
                 }
                 const float hi = __uint_as_float(__float_as_uint(nh) & 0xffff0000u);
                 const float r1 = nh - hi;
@@ -267,6 +274,7 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
             }
         }
     }
+    if (!norms_given && up_max != 0u) atomicMax(&smax, up_max);
     if (norms_given)
         for (int row = tid; row < Kpad; row += kAsgThreads) {
             const uint2 p = a.nh3[(int64_t)h * Kpad + row];
@@ -483,8 +491,9 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                         *reinterpret_cast<uint4 *>(scr + half * 64 + kk * 8) = xa[tb][kk];
                 }
                 __builtin_amdgcn_wave_barrier();
-                const int d1 = __shfl(i1, tk, 64), d2 = __shfl(i2, tk, 64);
-                const int fl = __shfl((int)full, tk, 64);
+                // the token's lane index is wave-uniform: plain lane reads, no exchange through LDS
+                const int d1 = __builtin_amdgcn_readlane(i1, tk), d2 = __builtin_amdgcn_readlane(i2, tk);
+                const int fl = __builtin_amdgcn_readlane((int)full, tk);
                 int winner;
                 if (!fl) {
                     const int cand = half ? d2 : d1;
@@ -495,9 +504,13 @@ void assign_kernel(AssignArgs a, int Kpad, int tiles_per_wave) {
                     const double e2 = (double)bf16_lo(xv.y) - (double)bf16_lo(cv.y);
                     const double e3 = (double)bf16_hi(xv.y) - (double)bf16_hi(cv.y);
                     double d = e0 * e0; d += e1 * e1; d += e2 * e2; d += e3 * e3;
-                    d += shfl_xor_f64(d, 16); d += shfl_xor_f64(d, 8); d += shfl_xor_f64(d, 4);
-                    d += shfl_xor_f64(d, 2); d += shfl_xor_f64(d, 1);
-                    const double D1 = __shfl(d, 0, 64), D2 = __shfl(d, 32, 64);
+                    // the 32 lanes of a candidate: two rows of 16 summed by DPP moves, the two row
+                    // sums read as scalars (no exchange through LDS: each cost a round trip, ten
+                    // in a row per token).  Both candidates go through the same operations, so
+                    // equal rows give equal sums.
+                    d = sum16_f64(d);
+                    const double D1 = readlane_f64(d, 0) + readlane_f64(d, 16);
+                    const double D2 = readlane_f64(d, 32) + readlane_f64(d, 48);
                     winner = (D2 < D1 || (D2 == D1 && d2 < d1)) ? d2 : d1;
                 } else {
                     double bd = INFINITY; int bj = 0x7fffffff;
