@@ -167,7 +167,7 @@ def large_encode_supplement(torch, B, synth, wl):
         fn = lambda: B.encode_chunk(x, warm if iters < 10 else init, wl.group_size, wl.n_stages, iters,
                                     cache=cache, workspace=ws)
         fn(); torch.cuda.synchronize()
-        ms = _event_ms(fn, 3)
+        ms = _event_ms(fn, 10 if iters == 0 else 4)
         flops = 2.0 * wl.n_clusters * wl.head_dim * (iters + 1) * vec
         out[name] = {"ms": round(ms, 4), "GBps_bf16_equiv": round(vec * 256 / ms / 1e6, 1),
                      "hbm_GBps_algorithmic": round(alg / ms / 1e6, 1),
