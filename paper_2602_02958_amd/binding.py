@@ -254,13 +254,23 @@ def decode(enc: Encoded, out=None, n_tokens=None, first_token=0) -> torch.Tensor
     return out
 
 
+def attn_workspace(heads: int, n_q: int, chunk_len: int, n_chunks: int, device) -> torch.Tensor:
+    """A workspace for attn_decode that holds the decoded tiles of n_chunks chunks (and the
+    queries' running state, which is used when the cache has more chunks than that)."""
+    p = make_params(heads, 2, 128, 1)
+    padded = -(-chunk_len // 64) * 64 * n_chunks
+    return torch.empty(workspace_bytes(p, ENTRY_ATTN, padded, n_q), dtype=torch.uint8, device=device)
+
+
 def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, out=None, n_kv=None,
-                k_rope=None, q_kv_len=None, f32_out=False):
+                k_rope=None, q_kv_len=None, f32_out=False, workspace=None):
     """qvg_attn_decode_ex.  q [H, Nq, d] bf16 contiguous -> out bf16 [H, Nq, d] (and lse fp32 [H, Nq]).
     n_kv: read only the first n_kv tokens of the caches (they are allocated for more);
     k_rope: [n_kv, d/2, 2] float16 (cos, sin), the rotary embedding of the decoded keys;
     q_kv_len: [Nq] int32, query i sees the first q_kv_len[i] tokens only (qvg_attn_decode_causal);
-    f32_out: the result as float32, before the rounding to bf16 (qvg_attn_decode_f32)."""
+    f32_out: the result as float32, before the rounding to bf16 (qvg_attn_decode_f32);
+    workspace: uint8 tensor (attn_workspace): every tile is then decoded once per unit into it and
+    shared by all query blocks, a slab of chunks at a time, instead of once per 256 queries."""
     _check(q, torch.bfloat16, "q")
     q = q.contiguous()
     H, Nq, d = q.shape
@@ -314,8 +324,8 @@ def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, o
     st = lib().qvg_attn_decode_ex(C.byref(p), Nq, _ptr(q), Nk, k.chunk_len, cap,
                                   _ptr(k.centroids), _ptr(k.ids), _ptr(k.codes), _ptr(k.scales),
                                   _ptr(v.centroids), _ptr(v.ids), _ptr(v.codes), _ptr(v.scales),
-                                  _ptr(k_rope), C.c_float(softmax_scale), _ptr(out), _ptr(lse), None, 0,
-                                  _stream())
+                                  _ptr(k_rope), C.c_float(softmax_scale), _ptr(out), _ptr(lse),
+                                  _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream())
     if st != 0:
         raise QvgError(st, "qvg_attn_decode_ex")
     return (out, lse) if want_lse else out
@@ -438,12 +448,12 @@ class StreamingCache:
         self.n_tokens += n
         return c
 
-    def attend(self, q, k_rope=None, softmax_scale=None, want_lse=False, out=None):
+    def attend(self, q, k_rope=None, softmax_scale=None, want_lse=False, out=None, workspace=None):
         """Attention of q [heads, n_q, d] over the tokens appended so far (decode fused in)."""
         if self.n_tokens == 0:
             raise ValueError("the cache is empty")
         return attn_decode(q, self.k, self.v, softmax_scale=softmax_scale, want_lse=want_lse, out=out,
-                           n_kv=self.n_tokens, k_rope=k_rope)
+                           n_kv=self.n_tokens, k_rope=k_rope, workspace=workspace)
 
     def decode(self, out=None, first_chunk=0, n_tokens=None) -> torch.Tensor:
         """bf16 [2 * heads, n, d] of the tokens appended so far, from chunk `first_chunk` on."""

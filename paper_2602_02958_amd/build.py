@@ -14,8 +14,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqvg.so")
-SOURCES = ["qvg_api.cpp", "qvg_decode.hip", "qvg_encode.hip", "qvg_kmeans.hip", "qvg_quant.hip", "qvg_attn.hip"]
-HEADERS = [os.path.join(CSRC, "qvg_internal.hpp"), os.path.join(ROOT, "include", "qvg.h")]
+SOURCES = ["qvg_api.cpp", "qvg_decode.hip", "qvg_encode.hip", "qvg_kmeans.hip", "qvg_quant.hip", "qvg_attn.hip", "qvg_attn_slab.hip"]
+HEADERS = [os.path.join(CSRC, "qvg_internal.hpp"), os.path.join(CSRC, "qvg_attn_tiles.hpp"),
+           os.path.join(ROOT, "include", "qvg.h")]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

@@ -116,8 +116,12 @@ int qvg_workspace_bytes(const qvg_params *p, int which_entry, int64_t n_tokens, 
             *out = n_tokens == 0 ? 0 : encode_ws(p, n_tokens, true, false, false).total;
             return QVG_OK;
         case QVG_ENTRY_DECODE:
-        case QVG_ENTRY_ATTN:
             *out = 0;
+            return QVG_OK;
+        case QVG_ENTRY_ATTN:
+            // optional: the queries' running state + the decoded tiles of n_tokens tokens (whole
+            // chunks, each counted as a multiple of 64 tokens)
+            *out = attn_slab_state_bytes(p->n_heads, n_q) + attn_slab_chunk_bytes(p->n_heads, n_tokens);
             return QVG_OK;
         default:
             return QVG_ERR_BAD_PARAM;
@@ -427,7 +431,8 @@ int attn_call(const qvg_params *p, int64_t n_q, const void *q, int64_t n_kv_toke
               const uint8_t *k_ids, const uint8_t *k_codes, const void *k_scales,
               const void *v_centroids, const uint8_t *v_ids, const uint8_t *v_codes,
               const void *v_scales, const void *k_rope, const int32_t *q_kv_len,
-              float softmax_scale, void *out, float *out_f32, float *lse_out, void *stream) {
+              float softmax_scale, void *out, float *out_f32, float *lse_out, void *workspace,
+              size_t workspace_bytes, void *stream) {
     int st = check_params(p);
     if (st != QVG_OK) return st;
     if (n_q < 0 || n_kv_tokens < 1 || n_kv_tokens > 0x7fffffff || chunk_len < 1) return QVG_ERR_BAD_PARAM;
@@ -463,6 +468,12 @@ int attn_call(const qvg_params *p, int64_t n_q, const void *q, int64_t n_kv_toke
     if (!ids_aligned(p, k_ids) || !ids_aligned(p, v_ids)) return QVG_ERR_ALIGN;
     if (q_kv_len && (reinterpret_cast<uintptr_t>(q_kv_len) & 3u)) return QVG_ERR_ALIGN;
     a.q_len = q_kv_len;
+    // a workspace that holds at least one chunk's decoded tiles switches to the shared-tile path
+    if (workspace && attn_slab_applicable(a, workspace, workspace_bytes)) {
+        if (!aligned16(workspace)) return QVG_ERR_ALIGN;
+        return launch_attn_slab(a, workspace, workspace_bytes, static_cast<hipStream_t>(stream)) == hipSuccess
+                   ? QVG_OK : QVG_ERR_LAUNCH;
+    }
     return launch_attn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QVG_OK : QVG_ERR_LAUNCH;
 }
 }  // namespace
@@ -476,9 +487,9 @@ int qvg_attn_decode_causal(const qvg_params *p, int64_t n_q, const void *q, int6
                            const void *v_scales, const void *k_rope, const int32_t *q_kv_len,
                            float softmax_scale, void *out, float *lse_out, void *workspace,
                            size_t workspace_bytes, void *stream) {
-    (void)workspace; (void)workspace_bytes;
     return attn_call(p, n_q, q, n_kv_tokens, chunk_len, kv_capacity_tokens, k_centroids, k_ids, k_codes, k_scales,
-                     v_centroids, v_ids, v_codes, v_scales, k_rope, q_kv_len, softmax_scale, out, nullptr, lse_out, stream);
+                     v_centroids, v_ids, v_codes, v_scales, k_rope, q_kv_len, softmax_scale, out, nullptr, lse_out,
+                     workspace, workspace_bytes, stream);
 }
 
 int qvg_attn_decode_f32(const qvg_params *p, int64_t n_q, const void *q, int64_t n_kv_tokens,
@@ -488,7 +499,8 @@ int qvg_attn_decode_f32(const qvg_params *p, int64_t n_q, const void *q, int64_t
                         const void *v_scales, const void *k_rope, const int32_t *q_kv_len,
                         float softmax_scale, float *out_f32, float *lse_out, void *stream) {
     return attn_call(p, n_q, q, n_kv_tokens, chunk_len, kv_capacity_tokens, k_centroids, k_ids, k_codes, k_scales,
-                     v_centroids, v_ids, v_codes, v_scales, k_rope, q_kv_len, softmax_scale, nullptr, out_f32, lse_out, stream);
+                     v_centroids, v_ids, v_codes, v_scales, k_rope, q_kv_len, softmax_scale, nullptr, out_f32, lse_out,
+                     nullptr, 0, stream);
 }
 
 }  // extern "C"

@@ -228,6 +228,13 @@ struct AttnArgs {
     float *out_f32;        // when set, the result goes here as fp32 [H][n_q][d] (not rounded to bf16) and `out` is not written
 };
 hipError_t launch_attn(const AttnArgs &a, hipStream_t s);
+// The same attention with every tile decoded once per unit into a caller-lent workspace and shared
+// by all query blocks (qvg_attn_slab.hip).  Workspace = running state of the queries (only when the
+// cache needs more than one slab) + the operand images of a slab of whole chunks.
+size_t attn_slab_state_bytes(int H, int64_t n_q);
+size_t attn_slab_chunk_bytes(int H, int64_t chunk_len);
+bool attn_slab_applicable(const AttnArgs &a, const void *ws, size_t ws_bytes);
+hipError_t launch_attn_slab(const AttnArgs &a, void *ws, size_t ws_bytes, hipStream_t s);
 
 // Rotary embedding of one lane's 8 decoded key channels (4 interleaved pairs): the values are
 // first rounded to bf16 (what the stand-alone decoder stores), then each pair (x0, x1) becomes

@@ -150,7 +150,10 @@ def test_workspace_sizes():
     need = B.workspace_bytes(p, B.ENTRY_ENCODE, 4680)
     assert need >= 2 * 24 * 256 * 256 + 24 * 4680 * 4 + 24 * 257 * 4
     assert B.workspace_bytes(p, B.ENTRY_DECODE, 4680) == 0
-    assert B.workspace_bytes(p, B.ENTRY_ATTN, 4680, 128) == 0
+    # attention's optional workspace: the decoded tiles (256 B per token and unit for K and for V, in
+    # tiles of 64 tokens) + the queries' running state (66 floats per query slot of 256-query blocks)
+    tiles = -(-4680 // 64)
+    assert B.workspace_bytes(p, B.ENTRY_ATTN, 4680, 128) == 24 * tiles * 64 * 512 + 24 * 1 * 66 * 512 * 4
 
 
 def test_static_scratch_entry_rejects_what_does_not_fit_before_touching_the_gpu():

@@ -1,0 +1,89 @@
+"""Attention with a workspace: every tile is decoded once per unit into the workspace and shared by
+all query blocks (a slab of chunks at a time, the queries' soft-max state carried between slabs).
+The arithmetic per tile is that of the fused kernels, so the result must equal theirs bit for bit
+and meet the same bound against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import qvg_oracle as O
+from paper_2602_02958_amd import binding as B
+from paper_2602_02958_amd import synth
+from paper_2602_02958_amd.configs import CONFIGS
+from conftest import bf16_bits
+import parity_util as P
+from test_gpu_attn_integration import _filled_caches, _rope_table, _check_against_oracle
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _ws(H, Nq, L, n_chunks):
+    return B.attn_workspace(H, Nq, L, n_chunks, DEV)
+
+
+@pytest.mark.parametrize("L,T,Bg,S,bits,fmt,K", [
+    (200, 3, 64, 1, 2, B.SCALE_F16, 32),      # chunks of 3 tiles + 8 tokens
+    (520, 4, 64, 1, 2, B.SCALE_F16, 256),
+    (516, 2, 32, 1, 2, B.SCALE_F16, 64),
+    (520, 1, 64, 1, 2, B.SCALE_E4M3, 64),     # the paper's QVG format
+    (520, 1, 16, 4, 2, B.SCALE_E4M3, 64),     # QVG-Pro: four smoothing stages
+    (520, 1, 16, 2, 4, B.SCALE_E4M3, 64),
+    (520, 1, 64, 1, 4, B.SCALE_E4M3, 64),     # INT4
+    (136, 5, 128, 1, 2, B.SCALE_F16, 16),     # run-time round count
+])
+def test_shared_tiles_equal_the_fused_kernels(L, T, Bg, S, bits, fmt, K):
+    H, Nq = 3, 600                             # three query blocks per unit, the last one partial
+    filled = 2 * L + 133                       # the last chunk is short
+    kc, vc = _filled_caches(H, L, 4, filled, K, Bg, T, S=S, bits=bits, fmt=fmt)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    khat, vhat = B.decode(kc), B.decode(vc)
+    for n_kv in (filled, 2 * L, L + 7, 64, 1):
+        fused, lse_f = B.attn_decode(q, kc, vc, want_lse=True, n_kv=n_kv)
+        n_chunks = -(-n_kv // L)
+        for slab_chunks in (n_chunks, 1):     # one slab; one chunk per slab (state carried n_chunks - 1 times)
+            out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=n_kv, workspace=_ws(H, Nq, L, slab_chunks))
+            torch.cuda.synchronize()
+            assert torch.equal(out, fused), (n_kv, slab_chunks)
+            assert torch.equal(lse, lse_f), (n_kv, slab_chunks)
+        for h in range(H):
+            _check_against_oracle(q, out, lse, P.to_np_u16(khat[h, :n_kv]), P.to_np_u16(vhat[h, :n_kv]), h)
+
+
+def test_shared_tiles_with_rotary_embedding():
+    H, L, K, Bg, T, Nq = 2, 520, 64, 32, 2, 700
+    filled = 2 * L + 133
+    kc, vc = _filled_caches(H, L, 3, filled, K, Bg, T)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    rope = _rope_table(filled, offset=3).to(DEV)
+    fused = B.attn_decode(q, kc, vc, n_kv=filled, k_rope=rope)
+    out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled, k_rope=rope, workspace=_ws(H, Nq, L, 2))
+    torch.cuda.synchronize()
+    assert torch.equal(out, fused)
+    khat, vhat = B.decode(kc), B.decode(vc)
+    rope_bits = rope.cpu().view(torch.int16).numpy().view(np.uint16)
+    for h in range(H):
+        krot = O.rope_keys(P.to_np_u16(khat[h, :filled]), rope_bits)
+        _check_against_oracle(q, out, lse, krot, P.to_np_u16(vhat[h, :filled]), h)
+
+
+def test_a_workspace_too_small_for_one_chunk_is_ignored():
+    H, L, K, Bg, T, Nq = 2, 520, 64, 64, 2, 600
+    kc, vc = _filled_caches(H, L, 2, 2 * L, K, Bg, T)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    fused = B.attn_decode(q, kc, vc)
+    small = torch.empty(4096, dtype=torch.uint8, device=DEV)
+    out = B.attn_decode(q, kc, vc, workspace=small)
+    torch.cuda.synchronize()
+    assert torch.equal(out, fused)
+
+
+def test_shared_tiles_16_bit_ids():
+    H, L, K, Bg, T, Nq = 2, 520, 300, 64, 1, 600
+    filled = L + 77
+    kc, vc = _filled_caches(H, L, 2, filled, K, Bg, T, fmt=B.SCALE_E4M3)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    fused = B.attn_decode(q, kc, vc, n_kv=filled)
+    out = B.attn_decode(q, kc, vc, n_kv=filled, workspace=_ws(H, Nq, L, 1))
+    torch.cuda.synchronize()
+    assert torch.equal(out, fused)
