@@ -478,7 +478,7 @@ def run_only(args, torch, B, synth, workload, CONFIGS):
             fn = lambda: workload.step(s)
             nbytes = 0
         else:
-            fn = lambda: workload.step_attn(s)
+            fn = lambda: workload.step_attn(s, shared_tiles=args.only == "attn")
             nbytes = _format_bytes(wl, units, n_tok, wl.chunk) + 2 * wl.heads * wl.n_queries * wl.head_dim * 2
     for _ in range(max(args.warmup, 1)):
         fn()
@@ -564,7 +564,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-large", action="store_true")
     ap.add_argument("--only", default=None,
-                    choices=["decode", "encode", "attn", "step", "copy", "large_decode", "large_encode", "presets", "long"],
+                    choices=["decode", "encode", "attn", "attn_fused", "step", "copy", "large_decode", "large_encode", "presets", "long"],
                     help="profiling aid: run just this part --steps times and print a short JSON "
                          "(copy = a plain device copy of 1 GiB, the reference the HBM counters "
                          "are scaled by; large_encode = one chunk of all layers of --workload)")

@@ -54,11 +54,13 @@ __device__ __forceinline__ Tile slab_tile(const AttnArgs &a, const SlabArgs &sl,
 template <int TM, int SM>
 struct TileRaw { Raw<TM, SM> k, v; uint4 rp[2]; };
 
+// Two workgroups per CU (at most 128 registers) for the instances with one smoothing stage and a
+// compile-time round count: the kernel is a chain of small dependent loads and lives on occupancy.
 template <int T_, int SM, int FMT, bool ROPE>
-__global__ __launch_bounds__(kAtThreads)
+__global__ __launch_bounds__(kAtThreads, (T_ > 0 && SM == 1) ? 4 : 2)
 void slab_decode_kernel(AttnArgs a, SlabArgs sl, int run) {
     constexpr int TM = T_ > 0 ? T_ : kMaxStages;
-    __shared__ __align__(16) uint16_t Vt[kVtElems];                     // [128][72] f16, transposed, no swizzle
+    __shared__ __align__(16) uint16_t Vt[kVtElems];                     // [128][72] f16, transposed, swizzled (below)
     const int h = blockIdx.y;
     const int i0 = (int)blockIdx.x * run;
     const int i1 = (i0 + run < sl.n_tiles) ? i0 + run : sl.n_tiles;
@@ -91,7 +93,11 @@ void slab_decode_kernel(AttnArgs a, SlabArgs sl, int run) {
         load_raw<T_, TM, SM, FMT>(vs, t, tp, c8, T, G, g, K, S, idv, r.v);
         if (ROPE) load_rope(a.rope, t, tp, c8, r.rp);
     };
-    auto emit = [&](int i, const TileRaw<TM, SM> &r) {
+    // decode the tile held in r (both sides) and write its two images; `next` is called as soon as
+    // r has been consumed: it requests the following tile into the same registers, so that its
+    // loads are in flight during the transposition (with two workgroups per CU the other one's
+    // work hides the rest of their latency)
+    auto emit = [&](int i, TileRaw<TM, SM> &r, auto next) {
         float accA[8], accB[8];
         dequant2x8<T_, TM, SM, FMT>(r.k, T, accA, accB);
         if (ROPE) { rope_rotate8(accA, r.rp[0]); rope_rotate8(accB, r.rp[1]); }
@@ -99,7 +105,10 @@ void slab_decode_kernel(AttnArgs a, SlabArgs sl, int run) {
         *reinterpret_cast<uint4 *>(kt + (tok + 0) * kHeadDim + c8 * 8) = pack_bf16x8(accA);
         *reinterpret_cast<uint4 *>(kt + (tok + 1) * kHeadDim + c8 * 8) = pack_bf16x8(accB);
         dequant2x8<T_, TM, SM, FMT>(r.v, T, accA, accB);
-        uint16_t *vt = Vt + v_pos;
+        next();
+        // rows 8 c8 .. 8 c8 + 7; the 16-byte group of a row is XOR-ed with (row / 8) & 7 so that the 16
+        // lanes that write the same column of 16 different row groups spread over the banks
+        uint16_t *vt = Vt + (((v_pos >> 3) ^ (c8 & 7)) * 8 + (v_pos & 7));
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
             // round to bf16 (the decoder's output), then to f16 (exact in range): channels e, e+1
@@ -113,34 +122,29 @@ void slab_decode_kernel(AttnArgs a, SlabArgs sl, int run) {
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const int p = tid + k * kAtThreads;                          // 16-byte piece: row p / 8, group p % 8
-            *reinterpret_cast<uint4 *>(vo + p * 8) = *reinterpret_cast<const uint4 *>(Vt + (p >> 3) * kVtPitch + (p & 7) * 8);
+            *reinterpret_cast<uint4 *>(vo + p * 8) =
+                *reinterpret_cast<const uint4 *>(Vt + (p >> 3) * kVtPitch + (((p & 7) ^ ((p >> 6) & 7)) * 8));
         }
         __syncthreads();                                                 // Vt is rewritten by the next tile
     };
 
     if (i0 >= i1) return;                                                // uniform
-    // raw data one tile ahead, ids two tiles ahead; two register sets used in turn
-    TileRaw<TM, SM> ra, rb;
+    // raw data one tile ahead (requested as soon as the registers are free), ids two tiles ahead
+    TileRaw<TM, SM> r;
     Tile t = slab_tile(a, sl, i0);
     load_ids(ks, t, tp, S, a.id_wide, idk);
     load_ids(vs, t, tp, S, a.id_wide, idv);
-    fetch(t, ra);
+    fetch(t, r);
     Tile tn = slab_tile(a, sl, i0 + 1 < i1 ? i0 + 1 : sl.n_tiles);
     load_ids(ks, tn, tp, S, a.id_wide, idk);
     load_ids(vs, tn, tp, S, a.id_wide, idv);
-    for (int i = i0; i < i1; i += 2) {
-        // tile i is in ra; request tile i + 1 into rb and the ids of tile i + 2
-        fetch(tn, rb);
-        Tile t2 = slab_tile(a, sl, i + 2 < i1 ? i + 2 : sl.n_tiles);
-        load_ids(ks, t2, tp, S, a.id_wide, idk);
-        load_ids(vs, t2, tp, S, a.id_wide, idv);
-        emit(i, ra);
-        if (i + 1 >= i1) break;                                          // uniform
-        fetch(t2, ra);
-        tn = slab_tile(a, sl, i + 3 < i1 ? i + 3 : sl.n_tiles);
-        load_ids(ks, tn, tp, S, a.id_wide, idk);
-        load_ids(vs, tn, tp, S, a.id_wide, idv);
-        emit(i + 1, rb);
+    for (int i = i0; i < i1; ++i) {
+        emit(i, r, [&]() {
+            fetch(tn, r);                                                // tile i + 1 (its ids arrived an iteration ago)
+            tn = slab_tile(a, sl, i + 2 < i1 ? i + 2 : sl.n_tiles);
+            load_ids(ks, tn, tp, S, a.id_wide, idk);
+            load_ids(vs, tn, tp, S, a.id_wide, idv);
+        });
     }
 }
 
@@ -354,7 +358,7 @@ static hipError_t launch_slab_decode_t(const AttnArgs &a, const SlabArgs &sl, hi
 template <int FMT>
 static hipError_t launch_slab_decode_f(const AttnArgs &a, const SlabArgs &sl, hipStream_t s) {
     if (a.S == 1) {
-        if (FMT == 0) {
+        if constexpr (FMT == 0) {
             switch (a.T) {
                 case 1: return launch_slab_decode_t<1, 1, FMT>(a, sl, s);
                 case 2: return launch_slab_decode_t<2, 1, FMT>(a, sl, s);
@@ -362,10 +366,11 @@ static hipError_t launch_slab_decode_f(const AttnArgs &a, const SlabArgs &sl, hi
                 case 4: return launch_slab_decode_t<4, 1, FMT>(a, sl, s);
                 default: break;
             }
-        } else if (a.T == 1) {
-            return launch_slab_decode_t<1, 1, FMT>(a, sl, s);
+            return launch_slab_decode_t<0, 1, FMT>(a, sl, s);
+        } else {
+            if (a.T == 1) return launch_slab_decode_t<1, 1, FMT>(a, sl, s);
+            return launch_slab_decode_t<0, 1, FMT>(a, sl, s);
         }
-        return launch_slab_decode_t<0, 1, FMT>(a, sl, s);
     }
     if (a.T == 1 && a.S == 4) return launch_slab_decode_t<1, 4, FMT>(a, sl, s);
     if (a.T == 1 && a.S == 2) return launch_slab_decode_t<1, 2, FMT>(a, sl, s);

@@ -4,7 +4,9 @@ One "step" is one pass of the whole hot path (paper Sec. 4.1-4.3) over one batch
   1. encode the newly generated chunk of K and V (all heads in one call, warm-started from the
      previous chunk's centroids, Sec. 4.3) straight into the cache,
   2. decode the whole cache back to bf16,
-  3. attention of the new chunk's queries over the compressed cache (decode fused in).
+  3. attention of the new chunk's queries over the compressed cache (decode fused in; with a
+     workspace for the decoded tiles of a slab of chunks, so that every tile is decoded once per
+     unit instead of once per block of 256 queries).
 K heads and V heads are stacked as independent units: units [0, heads) are K, [heads, 2*heads) V.
 Used by bench.py and by the full-size parity test, so that both run the same launches.
 """
@@ -32,6 +34,7 @@ class Streaming:
     attn_out: torch.Tensor
     workspace: torch.Tensor
     kept_chunks: dict           # chunk index -> bf16 input kept for parity sampling
+    attn_ws: torch.Tensor = None    # workspace of the attention (decoded tiles of a slab of chunks), or None
 
     @property
     def k(self) -> B.Encoded:
@@ -46,8 +49,11 @@ class Streaming:
         return B.Encoded(c.centroids[h:], c.ids[h:], c.codes[h:], c.scales[h:], c.chunk_len)
 
 
+ATTN_SLAB_CHUNKS = 16          # chunks whose decoded tiles the attention workspace holds (0: no workspace)
+
+
 def build_streaming(wl: Workload, device="cuda", layer: int = 0, keep_inputs=(), n_tokens=None,
-                    n_q=None) -> Streaming:
+                    n_q=None, attn_slab_chunks=None) -> Streaming:
     """Fill all but the last chunk of the cache (cold start on the first chunk, warm afterwards),
     and leave the last chunk ready to be encoded by step()."""
     heads = wl.heads
@@ -82,10 +88,12 @@ def build_streaming(wl: Workload, device="cuda", layer: int = 0, keep_inputs=(),
     if n_chunks == 1:
         init = synth.cold_start_centroids(x, wl.n_clusters)
     q = synth.queries(wl, heads, n_q, device)
+    slab = ATTN_SLAB_CHUNKS if attn_slab_chunks is None else attn_slab_chunks
+    attn_ws = B.attn_workspace(heads, n_q, L, min(slab, n_chunks), device) if slab > 0 else None
     return Streaming(wl, heads, cache, x, init.clone(), q, n_chunks - 1,
                      torch.empty(units, n_tokens, wl.head_dim, dtype=torch.bfloat16, device=device),
                      torch.empty(heads, n_q, wl.head_dim, dtype=torch.bfloat16, device=device),
-                     ws, kept)
+                     ws, kept, attn_ws)
 
 
 def step_encode(s: Streaming, iters=None):
@@ -100,8 +108,8 @@ def step_decode(s: Streaming):
     B.decode(s.cache, out=s.decoded)
 
 
-def step_attn(s: Streaming):
-    B.attn_decode(s.q, s.k, s.v, out=s.attn_out)
+def step_attn(s: Streaming, shared_tiles=True):
+    B.attn_decode(s.q, s.k, s.v, out=s.attn_out, workspace=s.attn_ws if shared_tiles else None)
 
 
 def step(s: Streaming):
