@@ -194,12 +194,27 @@ int qvg_decode_ex(const qvg_params *p, int64_t n_tokens, int64_t chunk_len,
 /*
  * Attention over the compressed cache: O = softmax(softmax_scale * Q K_hat^T) V_hat
  * per unit, no mask, where K_hat and V_hat are what qvg_decode would return (bf16),
- * produced tile by tile in LDS and never written to memory.
+ * produced tile by tile in LDS and never written to memory (or, with a workspace, written one
+ * slab of chunks at a time into it: see `workspace`).
  *   q_bf16   [H][n_q][d] contiguous       out_bf16 [H][n_q][d] contiguous
  *   K and V caches: n_kv_tokens tokens in chunks of chunk_len, each with the
  *   layout qvg_decode reads; both use the parameters in *p.
  *   lse_out  [H][n_q] fp32 natural-log sum of exp of the scaled scores, or NULL
- *   workspace: none needed today (pass NULL, 0).
+ *   workspace: optional device memory, 16-byte aligned.  Without it (NULL, 0) every block of 256
+ *              queries decodes the cache for itself inside one kernel.  With it every 64-token tile
+ *              is decoded ONCE per unit into the workspace (K_hat as bf16, V_hat as binary16, 512
+ *              bytes per token and unit) and read from there by all query blocks: a slab of as many
+ *              whole chunks as fit at a time, two launches per slab, the queries' running soft-max
+ *              state (264 bytes per query and unit) carried in the workspace from slab to slab.
+ *              The full-precision cache is never held beyond one slab.  Useful from 512 queries
+ *              per unit upward (the dequantization is what bounds the one-kernel form).
+ *              qvg_workspace_bytes(p, QVG_ENTRY_ATTN, tokens, n_q) gives the bytes that hold
+ *              `tokens` tokens of decoded tiles plus the state, where tokens = number of chunks in
+ *              a slab x chunk_len rounded up to a multiple of 64.  A workspace that cannot hold one
+ *              chunk (plus the state, when the cache has more chunks than fit) is ignored, and so is
+ *              any workspace when n_q <= 256 or a prefix length per query is given.  Contents are
+ *              scratch: nothing has to be initialised and nothing survives the call.  The result
+ *              equals the one-kernel form's bit for bit (same operands, same order of operations).
  * n_kv_tokens >= 1; n_q == 0 is a no-op; softmax_scale must be positive and finite.
  */
 int qvg_attn_decode(const qvg_params *p, int64_t n_q, const void *q_bf16,
@@ -251,7 +266,7 @@ int qvg_attn_decode_ex(const qvg_params *p, int64_t n_q, const void *q_bf16,
  *              gets a zero output row and lse = -infinity, which qvg_attn_merge treats as a
  *              partial result without weight.
  * A workgroup stops at the longest prefix among its 256 queries, so queries sorted by length
- * cost what their prefixes cost.  Runs on the general attention kernel.
+ * cost what their prefixes cost.  The workspace is not used by this form (pass NULL, 0).
  */
 int qvg_attn_decode_causal(const qvg_params *p, int64_t n_q, const void *q_bf16,
                            int64_t n_kv_tokens, int64_t chunk_len, int64_t kv_capacity_tokens,

@@ -3,7 +3,7 @@
     python -m paper_2602_02958_amd.profsum stats   <dir> [--top N]
     python -m paper_2602_02958_amd.profsum counters <dir> [<dir> ...]
     python -m paper_2602_02958_amd.profsum derived <kernel substring> <dir> [<dir> ...]
-    python -m paper_2602_02958_amd.profsum traffic <workload> <part> <kernel substring>
+    python -m paper_2602_02958_amd.profsum traffic <workload> <part> <kernel substring>[*n][,<substring>[*n]..]
                                                    <fetch dir> <write dir> <copy fetch dir> <copy write dir>
 
 `derived` turns the raw counters of the kernels matching the substring into busy fractions of the
@@ -12,7 +12,8 @@ chip's 1024 SIMDs (GRBM_GUI_ACTIVE is summed over the 8 XCDs; SQ_ACTIVE_INST_* c
 kernel, the average of every counter a `--pmc` run collected (counters are summed over the
 dispatch's workgroups); `traffic` prints one line `<workload> <part> fetch_bytes=.. write_bytes=..`
 for profiles/hbm_traffic.txt, scaling FETCH_SIZE / WRITE_SIZE (KiB per dispatch) by what the same
-counters read for the plain 1 GiB device copy of `bench.py --only copy`.
+counters read for the plain 1 GiB device copy of `bench.py --only copy`; a part made of several
+kernels, each launched n times per call, is given as `a*n,b*n` and its bytes are summed.
 Measurement bookkeeping only: nothing of the codec is computed here.
 """
 from __future__ import annotations
@@ -112,8 +113,12 @@ def _kib(dir_, counter, needle):
 def traffic(workload, part, needle, fetch_dir, write_dir, copy_fetch_dir, copy_write_dir):
     f_scale = COPY_BYTES / (_kib(copy_fetch_dir, "FETCH_SIZE", "copyBuffer") * 1024.0)
     w_scale = COPY_BYTES / (_kib(copy_write_dir, "WRITE_SIZE", "copyBuffer") * 1024.0)
-    fb = _kib(fetch_dir, "FETCH_SIZE", needle) * 1024.0 * f_scale
-    wb = _kib(write_dir, "WRITE_SIZE", needle) * 1024.0 * w_scale
+    fb = wb = 0.0
+    for item in needle.split(","):
+        name, _, times = item.partition("*")
+        n = float(times) if times else 1.0
+        fb += n * _kib(fetch_dir, "FETCH_SIZE", name) * 1024.0 * f_scale
+        wb += n * _kib(write_dir, "WRITE_SIZE", name) * 1024.0 * w_scale
     return (f"{workload} {part} fetch_bytes={int(round(fb))} write_bytes={int(round(wb))} "
             f"kernel={needle} fetch_scale={f_scale:.3f} write_scale={w_scale:.3f}")
 

@@ -49,7 +49,7 @@ class Streaming:
         return B.Encoded(c.centroids[h:], c.ids[h:], c.codes[h:], c.scales[h:], c.chunk_len)
 
 
-ATTN_SLAB_CHUNKS = 16          # chunks whose decoded tiles the attention workspace holds (0: no workspace)
+ATTN_SLAB_CHUNKS = 32          # chunks whose decoded tiles the attention workspace holds (0: no workspace)
 
 
 def build_streaming(wl: Workload, device="cuda", layer: int = 0, keep_inputs=(), n_tokens=None,
