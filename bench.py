@@ -433,7 +433,7 @@ def integration_supplement(torch, B, s):
     nbytes = oa.numel() * 2 * 3 + la.numel() * 4 * 2
     out["merge"] = {"ms": round(ms, 5), "rows": int(la.numel()), "GBps_algorithmic": round(nbytes / ms / 1e6, 1)}
     # chunk-causal order in one call: the queries split into as many groups as the cache has chunks,
-    # group c seeing the first c chunks (a prefix length per query; the general kernel)
+    # group c seeing the first c chunks (a prefix length per query)
     n_chunks = -(-n_kv // wl.chunk)
     grp = torch.arange(wl.n_queries, device="cuda") * n_chunks // wl.n_queries + 1
     lens = torch.clamp(grp * wl.chunk, max=n_kv).to(torch.int32)
@@ -444,6 +444,7 @@ def integration_supplement(torch, B, s):
         ms = _event_ms(fn, 5)
         fl = 4.0 * float(ql.sum().item()) * wl.head_dim * wl.heads
         out[name] = {"ms": round(ms, 4), "TFLOPs": round(fl / ms / 1e9, 1)}
+        out[name + "_shared_tiles"] = _attn_shared(torch, B, s.q, s.k, s.v, s.attn_out, 5, fl, q_kv_len=ql)
     return out
 
 

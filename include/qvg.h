@@ -212,7 +212,7 @@ int qvg_decode_ex(const qvg_params *p, int64_t n_tokens, int64_t chunk_len,
  *              `tokens` tokens of decoded tiles plus the state, where tokens = number of chunks in
  *              a slab x chunk_len rounded up to a multiple of 64.  A workspace that cannot hold one
  *              chunk (plus the state, when the cache has more chunks than fit) is ignored, and so is
- *              any workspace when n_q <= 256 or a prefix length per query is given.  Contents are
+ *              any workspace when n_q <= 256.  Contents are
  *              scratch: nothing has to be initialised and nothing survives the call.  The result
  *              equals the one-kernel form's bit for bit (same operands, same order of operations).
  * n_kv_tokens >= 1; n_q == 0 is a no-op; softmax_scale must be positive and finite.
@@ -266,7 +266,8 @@ int qvg_attn_decode_ex(const qvg_params *p, int64_t n_q, const void *q_bf16,
  *              gets a zero output row and lse = -infinity, which qvg_attn_merge treats as a
  *              partial result without weight.
  * A workgroup stops at the longest prefix among its 256 queries, so queries sorted by length
- * cost what their prefixes cost.  The workspace is not used by this form (pass NULL, 0).
+ * cost what their prefixes cost (with a workspace every tile of the cache is still decoded once;
+ * the query blocks stop reading at their longest prefix).
  */
 int qvg_attn_decode_causal(const qvg_params *p, int64_t n_q, const void *q_bf16,
                            int64_t n_kv_tokens, int64_t chunk_len, int64_t kv_capacity_tokens,

@@ -317,7 +317,8 @@ def attn_decode(q, k: Encoded, v: Encoded, softmax_scale=None, want_lse=False, o
                                           _ptr(k.centroids), _ptr(k.ids), _ptr(k.codes), _ptr(k.scales),
                                           _ptr(v.centroids), _ptr(v.ids), _ptr(v.codes), _ptr(v.scales),
                                           _ptr(k_rope), _ptr(q_kv_len), C.c_float(softmax_scale), _ptr(out),
-                                          _ptr(lse), None, 0, _stream())
+                                          _ptr(lse), _ptr(workspace), 0 if workspace is None else workspace.numel(),
+                                          _stream())
         if st != 0:
             raise QvgError(st, "qvg_attn_decode_causal")
         return (out, lse) if want_lse else out

@@ -153,9 +153,11 @@ void slab_decode_kernel(AttnArgs a, SlabArgs sl, int run) {
 // fused kernels: K [64][136] bf16, V [128][72] f16 transposed, 16-byte groups of a row XOR-ed with
 // 2 * (row / 32)).  ntile: tokens the tile holds (scores of the others are masked).
 // ---------------------------------------------------------------------------------------------
+// left: tokens of this tile the lane's query sees (only looked at when ql_mask is set: some query of
+// the wavefront ends in or before this tile).
 __device__ __forceinline__ void slab_tile_attend(const uint16_t *kt, const uint16_t *vt, const uint4 (&qa)[8], int col,
-                                                 int half, int ntile, float scale2, floatx16_t (&O)[4], float &m,
-                                                 float &l) {
+                                                 int half, int ntile, bool ql_mask, int left, float scale2,
+                                                 floatx16_t (&O)[4], float &m, float &l) {
     floatx16_t S[2];
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
@@ -189,6 +191,15 @@ __device__ __forceinline__ void slab_tile_attend(const uint16_t *kt, const uint1
             for (int r = 0; r < 16; ++r) {
                 const int kv = nb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
                 if (kv >= ntile) S[nb][r] = -INFINITY;
+            }
+    }
+    if (ql_mask) {                                                       // uniform
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kv = nb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                if (kv >= left) S[nb][r] = -INFINITY;
             }
     }
     float tmax = -INFINITY;
@@ -244,6 +255,10 @@ __device__ __forceinline__ void slab_tile_attend(const uint16_t *kt, const uint1
 }
 
 // One workgroup = 8 wavefronts = 256 queries of one unit, over the tiles of one slab.
+// QL: a prefix length per query (a.q_len): scores beyond the lane's prefix are masked in the tiles
+// at or past the shortest prefix of the wavefront, and the workgroup stops at the longest prefix
+// among its 256 queries.
+template <bool QL>
 __global__ __launch_bounds__(kAtThreads, 2)
 void attn_slab_kernel(AttnArgs a, SlabArgs sl, int n_qblocks, int n_blocks, int blocks_per_xcd) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -285,6 +300,26 @@ void attn_slab_kernel(AttnArgs a, SlabArgs sl, int n_qblocks, int n_blocks, int 
         l = st[65 * kAtThreads];
     }
     const float scale2 = a.scale * 1.4426950408889634f;
+    int qlen = 0x7fffffff, wmin = 0x7fffffff, wgmax = 0x7fffffff;
+    if (QL) {
+        __shared__ int bmax;
+        if (tid == 0) bmax = 0;
+        __syncthreads();
+        const int nk = (int)a.n_kv;
+        qlen = 0;
+        if (qvalid) { const int v = a.q_len[qrow]; qlen = v < 0 ? 0 : (v > nk ? nk : v); }
+        wmin = qvalid ? qlen : 0x7fffffff;
+        int mx = qlen;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const int o = __shfl_xor(wmin, off, 64); wmin = o < wmin ? o : wmin;
+            const int p = __shfl_xor(mx, off, 64); mx = p > mx ? p : mx;
+        }
+        if (lane == 0) atomicMax(&bmax, mx);
+        __syncthreads();
+        wgmax = bmax;
+        wmin = __builtin_amdgcn_readfirstlane(wmin);
+    }
 
     // a thread's four 16-byte pieces of a tile: K pieces tid, tid + 512 (row p / 16, group p % 16),
     // V pieces tid, tid + 512 (row p / 8, group p % 8, XOR-ed with the row's key in LDS)
@@ -322,8 +357,10 @@ void attn_slab_kernel(AttnArgs a, SlabArgs sl, int n_qblocks, int n_blocks, int 
         const bool more = i + 1 < n;                                    // uniform
         QVG_SLAB_FETCH(more ? i + 1 : i);
         const Tile t = slab_tile(a, sl, i);
+        if (QL && t.t0 >= wgmax) break;                                 // uniform: no query of the workgroup sees this tile or a later one
         const int ntile = (t.cend - t.t0 < kAtKv) ? t.cend - t.t0 : kAtKv;
-        slab_tile_attend(Kt + buf * kKtElems, Vt + buf * kVtElems, qa, col, half, ntile, scale2, O, m, l);
+        slab_tile_attend(Kt + buf * kKtElems, Vt + buf * kVtElems, qa, col, half, ntile, QL && t.t0 + kAtKv > wmin,
+                         qlen - t.t0, scale2, O, m, l);
         if (!more) break;
         QVG_SLAB_PARK(buf ^ 1);
         __syncthreads();
@@ -332,7 +369,7 @@ void attn_slab_kernel(AttnArgs a, SlabArgs sl, int n_qblocks, int n_blocks, int 
 #undef QVG_SLAB_FETCH
 #undef QVG_SLAB_PARK
     if (sl.last) {
-        store_result(a, h, qrow, qvalid, qvalid, half, O, m, l);
+        store_result(a, h, qrow, qvalid && (!QL || qlen > 0), qvalid, half, O, m, l);
     } else {
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
@@ -396,10 +433,10 @@ size_t attn_slab_chunk_bytes(int H, int64_t chunk_len) {
 }
 
 // Whether the shared-tile path serves this call with this workspace: more than one query block
-// per unit (else nothing is shared), no per-query prefix, and room for at least one chunk's tiles
-// (plus the running state when the cache needs more than one slab).
+// per unit (else nothing is shared) and room for at least one chunk's tiles (plus the running
+// state when the cache needs more than one slab).
 bool attn_slab_applicable(const AttnArgs &a, const void *ws, size_t ws_bytes) {
-    if (!ws || a.q_len || a.n_q <= kAtQPerBlock) return false;
+    if (!ws || a.n_q <= kAtQPerBlock) return false;
     const size_t chunk = attn_slab_chunk_bytes(a.H, a.chunk_len);
     if (ws_bytes >= chunk * (size_t)a.n_chunks) return true;
     const size_t state = attn_slab_state_bytes(a.H, a.n_q);
@@ -416,7 +453,9 @@ hipError_t launch_attn_slab(const AttnArgs &a, void *ws, size_t ws_bytes, hipStr
     if (slab_chunks > a.n_chunks) slab_chunks = a.n_chunks;
 
     static LdsHighWater lds_limit = {};
-    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(&attn_slab_kernel), kAtSmem, lds_limit);
+    static LdsHighWater lds_limit_ql = {};
+    hipError_t e = a.q_len ? ensure_dynamic_lds(reinterpret_cast<const void *>(&attn_slab_kernel<true>), kAtSmem, lds_limit_ql)
+                           : ensure_dynamic_lds(reinterpret_cast<const void *>(&attn_slab_kernel<false>), kAtSmem, lds_limit);
     if (e != hipSuccess) return e;
     const int64_t nqb = (a.n_q + kAtQPerBlock - 1) / kAtQPerBlock;
     const int64_t nb = nqb * a.H;
@@ -440,7 +479,8 @@ hipError_t launch_attn_slab(const AttnArgs &a, void *ws, size_t ws_bytes, hipStr
         sl.first = c0 == 0;
         sl.last = c1 == a.n_chunks;
         if ((e = launch_slab_decode(a, sl, s)) != hipSuccess) return e;
-        hipLaunchKernelGGL(attn_slab_kernel, dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmem, s, a, sl, (int)nqb, (int)nb, bpx);
+        if (a.q_len) hipLaunchKernelGGL(attn_slab_kernel<true>, dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmem, s, a, sl, (int)nqb, (int)nb, bpx);
+        else hipLaunchKernelGGL(attn_slab_kernel<false>, dim3((unsigned)(bpx * 8)), dim3(kAtThreads), kAtSmem, s, a, sl, (int)nqb, (int)nb, bpx);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;

@@ -87,3 +87,52 @@ def test_shared_tiles_16_bit_ids():
     out = B.attn_decode(q, kc, vc, n_kv=filled, workspace=_ws(H, Nq, L, 1))
     torch.cuda.synchronize()
     assert torch.equal(out, fused)
+
+
+@pytest.mark.parametrize("L,T,Bg,S,bits,fmt,rope", [(520, 2, 32, 1, 2, B.SCALE_F16, False), (520, 4, 64, 1, 2, B.SCALE_F16, True),
+                                                    (260, 1, 16, 4, 2, B.SCALE_E4M3, False)])
+def test_shared_tiles_with_a_prefix_length_per_query(L, T, Bg, S, bits, fmt, rope):
+    """A prefix length per query on the shared-tile path: chunk groups, lengths inside a chunk, the
+    whole cache, one token, empty prefixes; sorted (query blocks stop early) and unsorted.  Equal to
+    the one-kernel form bit for bit, and every query against the oracle over its own prefix."""
+    H, K, Nq = 2, 64, 700
+    n_chunks, filled = 4, 3 * L + 77
+    kc, vc = _filled_caches(H, L, n_chunks, filled, K, Bg, T, S, bits, fmt)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    g = torch.Generator().manual_seed(5)
+    lens = torch.empty(Nq, dtype=torch.int64)
+    lens[:256] = 0                                   # a whole query block that sees nothing
+    lens[256:400] = L
+    lens[400:560] = 2 * L
+    lens[560:660] = torch.randint(1, filled + 1, (100,), generator=g)
+    lens[660:] = torch.tensor([1, 2, 63, 64, 65, L - 1, L + 1, filled, filled - 1, filled + 50, 0, -5] + [3 * L] * 28)
+    table = _rope_table(filled).to(DEV) if rope else None
+    khat, vhat = B.decode(kc, n_tokens=filled), B.decode(vc, n_tokens=filled)
+    for order in ("sorted", "shuffled"):
+        if order == "shuffled":
+            lens = lens[torch.randperm(Nq, generator=g)]
+        ql = lens.to(torch.int32).to(DEV)
+        one, lse_one = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled, k_rope=table, q_kv_len=ql)
+        for slab_chunks in (n_chunks, 1):
+            out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled, k_rope=table, q_kv_len=ql,
+                                     workspace=_ws(H, Nq, L, slab_chunks))
+            torch.cuda.synchronize()
+            assert torch.equal(out, one), (order, slab_chunks)
+            assert torch.equal(lse, lse_one), (order, slab_chunks)
+    eff = lens.clamp(0, filled).numpy()
+    for h in range(H):
+        kb = P.to_np_u16(khat[h])
+        if rope:
+            kb = O.rope_keys(kb, table.cpu().numpy().view(np.uint16))
+        vb = P.to_np_u16(vhat[h])
+        qb = bf16_bits(q[h])
+        og, lg = P.to_np_u16(out[h]), lse[h].cpu().numpy()
+        for n in np.unique(eff):
+            rows = np.flatnonzero(eff == n)
+            if n == 0:
+                assert (og[rows] == 0).all() and np.isneginf(lg[rows]).all()
+                continue
+            want, lse_w = O.attention(qb[rows], kb[:n], vb[:n], want_lse=True)
+            ok, max_abs, worst = P.attn_tolerance_ok(og[rows], want)
+            assert ok, f"head {h}, prefix {n}: max abs err {max_abs}, worst err/tol {worst}"
+            assert np.abs(lg[rows] - lse_w).max() < 2e-3, (h, n)
