@@ -78,6 +78,18 @@ def test_a_workspace_too_small_for_one_chunk_is_ignored():
     assert torch.equal(out, fused)
 
 
+def test_a_misaligned_workspace_is_refused():
+    H, L, K, Bg, T, Nq = 2, 520, 64, 64, 2, 600
+    kc, vc = _filled_caches(H, L, 2, 2 * L, K, Bg, T)
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    ws = _ws(H, Nq, L, 2)
+    odd = torch.empty(ws.numel() + 16, dtype=torch.uint8, device=DEV)[4:]
+    assert odd.data_ptr() % 16 != 0
+    with pytest.raises(B.QvgError) as e:
+        B.attn_decode(q, kc, vc, workspace=odd)
+    assert e.value.status == -5
+
+
 def test_shared_tiles_16_bit_ids():
     H, L, K, Bg, T, Nq = 2, 520, 300, 64, 1, 600
     filled = L + 77
