@@ -31,11 +31,13 @@ def _ws(H, Nq, L, n_chunks):
     (520, 1, 16, 2, 4, B.SCALE_E4M3, 64),
     (520, 1, 64, 1, 4, B.SCALE_E4M3, 64),     # INT4
     (136, 5, 128, 1, 2, B.SCALE_F16, 16),     # run-time round count
+    (64, 2, 64, 1, 2, B.SCALE_F16, 16),       # a chunk is exactly one tile
+    (40, 2, 64, 1, 2, B.SCALE_F16, 16),       # every tile is a partial one
 ])
 def test_shared_tiles_equal_the_fused_kernels(L, T, Bg, S, bits, fmt, K):
     H, Nq = 3, 600                             # three query blocks per unit, the last one partial
-    filled = 2 * L + 133                       # the last chunk is short
-    kc, vc = _filled_caches(H, L, 4, filled, K, Bg, T, S=S, bits=bits, fmt=fmt)
+    filled = (2 * L + 133) if L >= 136 else (9 * L + 17)    # the last chunk is short
+    kc, vc = _filled_caches(H, L, -(-filled // L) + 1, filled, K, Bg, T, S=S, bits=bits, fmt=fmt)
     q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
     khat, vhat = B.decode(kc), B.decode(vc)
     for n_kv in (filled, 2 * L, L + 7, 64, 1):
