@@ -39,8 +39,8 @@
  * m/8 * 2^-6), scales [N][T][d/B] uint8; the encoder never writes the NaN code 0x7F, and a
  * decoder that meets it reads 480.  E4M3 scale arrays need no alignment.
  * With more than 256 centroids (the codebook-size study of Sec. 5, Table 5, goes to K = 512) an id
- * is a 16-bit word: every "uint8_t *ids" argument then points at uint16 data, 2-byte aligned;
- * this form has one smoothing stage only (QVG_ERR_UNSUPPORTED otherwise).
+ * is a 16-bit word: every "uint8_t *ids" argument then points at uint16 data, 2-byte aligned
+ * (with S smoothing stages: S consecutive words per token).
  * The encoder writes ids below K only; a decoder (qvg_decode*, qvg_attn_decode*) that meets a
  * larger one, in a cache it did not write, reads the table's last row for it instead of memory
  * beyond the table.

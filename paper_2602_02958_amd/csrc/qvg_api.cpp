@@ -28,7 +28,6 @@ int check_params(const qvg_params *p) {
     // valid in the paper, not built here
     if (p->head_dim != kHeadDim) return QVG_ERR_UNSUPPORTED;
     if (p->n_smooth_stages > kMaxSmooth) return QVG_ERR_UNSUPPORTED;
-    if (p->n_clusters > 256 && p->n_smooth_stages > 1) return QVG_ERR_UNSUPPORTED;    // 16-bit ids: one stage
     const int B = p->group_size;
     if (B != 16 && B != 32 && B != 64 && B != 128) return QVG_ERR_UNSUPPORTED;
     return QVG_OK;

@@ -91,6 +91,7 @@ void attn_kernel_direct(AttnArgs a, int n_qblocks, int n_blocks, int blocks_per_
     ks.ids = a.k_ids + (int64_t)h * a.kv_stride * S * (a.id_wide ? 2 : 1);  ks.codes = a.k_codes + (int64_t)h * a.kv_stride * T * kCodeBytes;
     ks.scales = reinterpret_cast<const uint8_t *>(a.k_scales) + (int64_t)h * a.kv_stride * T * G * kScaleBytes;
     ks.cent = a.k_cent + (int64_t)h * a.chunk_stride * S * K * kHeadDim;
+    ks.wide = vs.wide = a.id_wide;
     vs.ids = a.v_ids + (int64_t)h * a.kv_stride * S * (a.id_wide ? 2 : 1);  vs.codes = a.v_codes + (int64_t)h * a.kv_stride * T * kCodeBytes;
     vs.scales = reinterpret_cast<const uint8_t *>(a.v_scales) + (int64_t)h * a.kv_stride * T * G * kScaleBytes;
     vs.cent = a.v_cent + (int64_t)h * a.chunk_stride * S * K * kHeadDim;
@@ -764,8 +765,9 @@ static hipError_t launch_attn_t(const AttnArgs &a, hipStream_t s) {
 // fixed at compile time, anything else with run-time counts
 template <int FMT>
 static hipError_t launch_attn_multi(const AttnArgs &a, hipStream_t s) {
-    if (a.T == 1 && a.S == 4) return launch_attn_t<1, 4, FMT>(a, s);
-    if (a.T == 1 && a.S == 2) return launch_attn_t<1, 2, FMT>(a, s);
+    // (16-bit ids with several stages: the run-time-count instances, which read the ids stage by stage)
+    if (a.T == 1 && a.S == 4 && !a.id_wide) return launch_attn_t<1, 4, FMT>(a, s);
+    if (a.T == 1 && a.S == 2 && !a.id_wide) return launch_attn_t<1, 2, FMT>(a, s);
     return a.T == 1 ? launch_attn_t<1, 0, FMT>(a, s) : launch_attn_t<0, 0, FMT>(a, s);
 }
 
@@ -830,7 +832,7 @@ hipError_t launch_attn(const AttnArgs &a, hipStream_t s) {
         // levels, E4M3 scales, one round) has a staged instance, everything else runs on the general kernel
         if (a.fmt == kFmtE4M3 && fp8_staged_any && a.T == 1) return launch_attn_staged<1, true, false, true>(a, s);
         switch (a.fmt) {
-            case 0: return launch_attn_t<0, 1>(a, s);
+            case 0: return a.S > 1 ? launch_attn_multi<0>(a, s) : launch_attn_t<0, 1>(a, s);
             case kFmtE4M3: return launch_attn_fmt<kFmtE4M3>(a, s);
             case kFmtInt4: return launch_attn_fmt<kFmtInt4>(a, s);
             default: return launch_attn_fmt<kFmtInt4 | kFmtE4M3>(a, s);

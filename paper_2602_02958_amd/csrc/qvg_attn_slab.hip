@@ -74,6 +74,7 @@ void slab_decode_kernel(AttnArgs a, SlabArgs sl, int run) {
     ks.ids = a.k_ids + (int64_t)h * a.kv_stride * S * (a.id_wide ? 2 : 1);  ks.codes = a.k_codes + (int64_t)h * a.kv_stride * T * kCodeBytes;
     ks.scales = reinterpret_cast<const uint8_t *>(a.k_scales) + (int64_t)h * a.kv_stride * T * G * kScaleBytes;
     ks.cent = a.k_cent + (int64_t)h * a.chunk_stride * S * K * kHeadDim;
+    ks.wide = vs.wide = a.id_wide;
     vs.ids = a.v_ids + (int64_t)h * a.kv_stride * S * (a.id_wide ? 2 : 1);  vs.codes = a.v_codes + (int64_t)h * a.kv_stride * T * kCodeBytes;
     vs.scales = reinterpret_cast<const uint8_t *>(a.v_scales) + (int64_t)h * a.kv_stride * T * G * kScaleBytes;
     vs.cent = a.v_cent + (int64_t)h * a.chunk_stride * S * K * kHeadDim;
@@ -423,8 +424,8 @@ static hipError_t launch_slab_decode_f(const AttnArgs &a, const SlabArgs &sl, hi
             return launch_slab_decode_t<0, 1, FMT>(a, sl, s);
         }
     }
-    if (a.T == 1 && a.S == 4) return launch_slab_decode_t<1, 4, FMT>(a, sl, s);
-    if (a.T == 1 && a.S == 2) return launch_slab_decode_t<1, 2, FMT>(a, sl, s);
+    if (a.T == 1 && a.S == 4 && !a.id_wide) return launch_slab_decode_t<1, 4, FMT>(a, sl, s);
+    if (a.T == 1 && a.S == 2 && !a.id_wide) return launch_slab_decode_t<1, 2, FMT>(a, sl, s);
     return launch_slab_decode_t<0, 0, FMT>(a, sl, s);
 }
 

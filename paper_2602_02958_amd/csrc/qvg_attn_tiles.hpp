@@ -32,6 +32,7 @@ struct CacheSide {                 // one of K / V, already offset to this unit
     const bf16_t *cent;            // [n_chunks][K][d]
     const uint8_t *ids; const uint8_t *codes;
     const uint8_t *scales;         // binary16 or E4M3 bytes, per the format
+    int wide;                      // ids are 16-bit words (more than 256 centroids)
 };
 
 struct Tile {                      // one 64-token tile; tiles never straddle a chunk
@@ -114,7 +115,8 @@ struct Raw {                       // what one thread loads for its 2 tokens x 8
 
 // ids of this thread's two tokens of a tile (0 for tokens past the chunk end / an invalid tile);
 // with S smoothing stages a token has S id bytes, stage s in byte s of the result
-// (ids of 16 bits, for tables of more than 256 rows, come with one stage only)
+// (ids of 16 bits, for tables of more than 256 rows: one stage here; with several stages the
+// run-time-count path of load_raw reads them itself)
 // The ids of a thread's two tokens, as stored: one load per token (the S id bytes of a token
 // are contiguous; 1, 2 or 4 of them are one load when the array is aligned for it) and no
 // arithmetic on what it returns.  The clamp to the table's last row is applied where the id is
@@ -181,8 +183,11 @@ __device__ __forceinline__ void load_raw(const CacheSide &s, const Tile &t, int 
             } else {
                 for (int st = 0; st < S; ++st) {
                     float row[8];
+                    // 16-bit ids with several stages do not fit the packed word: read where they are used
+                    const uint32_t sid = s.wide ? (uint32_t)reinterpret_cast<const uint16_t *>(s.ids)[(int64_t)n * S + st]
+                                                : (id[e] >> (8 * st)) & 0xffu;
                     unpack_bf16x8(*reinterpret_cast<const uint4 *>(
-                                      cent + ((int64_t)st * K + min((id[e] >> (8 * st)) & 0xffu, kmax)) * kHeadDim + c8 * 8), row);
+                                      cent + ((int64_t)st * K + min(sid, kmax)) * kHeadDim + c8 * 8), row);
 #pragma unroll
                     for (int i = 0; i < 8; ++i) r.ci[e][i] = st ? r.ci[e][i] + row[i] : row[i];
                 }

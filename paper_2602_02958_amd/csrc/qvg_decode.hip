@@ -42,7 +42,8 @@ constexpr int kXcds = 8;                         // MI355X: 8 XCDs, each with it
 // word (16 words per token and round, so the offsets below are the same in units of the word).
 // SC: number of smoothing stages when known at compile time (the loops over the stages unroll and
 // their loads are issued together), 0 = run-time S.
-// WIDE: ids are 16-bit words (more than 256 centroids; SM == 1 only).  A template parameter: as a
+// WIDE: ids are 16-bit words (more than 256 centroids; one stage, or several with the tables in
+// global memory, which is where tables of that size always are).  A template parameter: as a
 // run-time switch around the id load it cost the byte-id kernels 15 % (0.667 -> 0.767 ms at the
 // cfg3 shape).
 template <int T_, bool CHECK, int SM, int FMT, int SC, bool WIDE>
@@ -59,7 +60,11 @@ __device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_
     const scale_t *scales_b = static_cast<const scale_t *>(scales_v);
     auto hs = [](uint32_t bits) { return 0.5f * scale_bits_to_f32<FP8>(bits); };
     const int S = SC > 0 ? SC : S_;
-    uint32_t idv[kDecUnroll];
+    // a token's ids packed into one word: 8 bits per stage, 16 with 16-bit ids
+    constexpr int IB = (WIDE && SM != 1) ? 16 : 8;
+    typedef typename std::conditional<(WIDE && SM != 1), uint64_t, uint32_t>::type idpack_t;
+    constexpr uint32_t IMASK = (1u << IB) - 1u;
+    idpack_t idv[kDecUnroll];
     uint32_t code[kDecUnroll][TM];
     uint32_t sc[kDecUnroll][TM];
     bool ok[kDecUnroll];
@@ -78,7 +83,9 @@ __device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_
                 idv[u] = 0u;
 #pragma unroll
                 for (int st = 0; st < (SC > 0 ? SC : kMaxSmooth); ++st)
-                    if (st < S) idv[u] |= (uint32_t)ids_b[ln * (uint32_t)S + st] << (8 * st);
+                    if (st < S)
+                        idv[u] |= (idpack_t)(WIDE ? (uint32_t)reinterpret_cast<const uint16_t *>(ids_b)[ln * (uint32_t)S + st]
+                                                  : (uint32_t)ids_b[ln * (uint32_t)S + st]) << (IB * st);
             }
             const uint32_t co = ln * (uint32_t)T * 16u + lane16;       // in code words
             const uint32_t so = ln * (uint32_t)T * G + gidx;
@@ -93,8 +100,8 @@ __device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_
         float accA[8], accB[8];
         // centroid rows; an id beyond the table (corrupt input) is clamped
         if (SM == 1) {
-            unpack_bf16x8(*reinterpret_cast<const uint4 *>(tab + min(idv[up], kmax) * kHeadDim + lane16 * 8), accA);
-            unpack_bf16x8(*reinterpret_cast<const uint4 *>(tab + min(idv[up + 1], kmax) * kHeadDim + lane16 * 8), accB);
+            unpack_bf16x8(*reinterpret_cast<const uint4 *>(tab + min((uint32_t)idv[up], kmax) * kHeadDim + lane16 * 8), accA);
+            unpack_bf16x8(*reinterpret_cast<const uint4 *>(tab + min((uint32_t)idv[up + 1], kmax) * kHeadDim + lane16 * 8), accB);
         } else {
             // Eq. 7 with S tables: the rows are added in stage order in fp32
             const bf16_t *tb = (SM == 2) ? tab : cg;
@@ -102,8 +109,8 @@ __device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_
                 uint4 wa[SC > 0 ? SC : 1], wb[SC > 0 ? SC : 1];
 #pragma unroll
                 for (int st = 0; st < SC; ++st) {
-                    const uint32_t ia = min((idv[up] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
-                    const uint32_t ib = min((idv[up + 1] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
+                    const uint32_t ia = min((uint32_t)(idv[up] >> (IB * st)) & IMASK, kmax) + (uint32_t)st * (kmax + 1u);
+                    const uint32_t ib = min((uint32_t)(idv[up + 1] >> (IB * st)) & IMASK, kmax) + (uint32_t)st * (kmax + 1u);
                     wa[st] = *reinterpret_cast<const uint4 *>(tb + ia * kHeadDim + lane16 * 8);
                     wb[st] = *reinterpret_cast<const uint4 *>(tb + ib * kHeadDim + lane16 * 8);
                 }
@@ -120,8 +127,8 @@ __device__ __forceinline__ void decode_pass(int T, int S_, uint32_t ln0, uint32_
                 }
             } else {
                 for (int st = 0; st < S; ++st) {
-                    const uint32_t ia = min((idv[up] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
-                    const uint32_t ib = min((idv[up + 1] >> (8 * st)) & 0xffu, kmax) + (uint32_t)st * (kmax + 1u);
+                    const uint32_t ia = min((uint32_t)(idv[up] >> (IB * st)) & IMASK, kmax) + (uint32_t)st * (kmax + 1u);
+                    const uint32_t ib = min((uint32_t)(idv[up + 1] >> (IB * st)) & IMASK, kmax) + (uint32_t)st * (kmax + 1u);
                     float ra[8], rb[8];
                     unpack_bf16x8(*reinterpret_cast<const uint4 *>(tb + ia * kHeadDim + lane16 * 8), ra);
                     unpack_bf16x8(*reinterpret_cast<const uint4 *>(tb + ib * kHeadDim + lane16 * 8), rb);
@@ -256,10 +263,11 @@ static hipError_t launch_decode_w(const DecodeArgs &a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// 16-bit ids come with one smoothing stage only (SM == 1)
+// 16-bit ids: one smoothing stage (SM == 1), or several with the tables in global memory (SM == 3:
+// S tables of more than 256 rows never fit the 64 KB that SM == 2 keeps in LDS)
 template <int T_, int SM, int FMT = 0, int SC = 0>
 static hipError_t launch_decode_t(const DecodeArgs &a, hipStream_t s) {
-    if (SM == 1 && a.id_wide) return launch_decode_w<T_, SM, FMT, SC, SM == 1>(a, s);
+    if ((SM == 1 || SM == 3) && a.id_wide) return launch_decode_w<T_, SM, FMT, SC, SM == 1 || SM == 3>(a, s);
     return launch_decode_w<T_, SM, FMT, SC, false>(a, s);
 }
 

@@ -13,7 +13,7 @@ constexpr int kHeadDim = 128;      // only head_dim the kernels are written for
 constexpr int kMaxStages = 8;
 constexpr int kMaxSmooth = 4;       // smoothing stages (k-means rounds on the residual)
 constexpr int kMaxTokensPerChunk = 1 << 20;
-constexpr int kMaxClusters = 512;   // up to 256: one id byte per token; beyond: two (one smoothing stage only)
+constexpr int kMaxClusters = 512;   // up to 256: one id byte per token and stage; beyond: two
 
 typedef uint16_t bf16_t;           // bit pattern of a bfloat16
 typedef uint16_t f16_t;            // bit pattern of an IEEE binary16
@@ -160,7 +160,7 @@ struct DecodeArgs {
     int fmt;    // kFmt* bits; scales then points at bytes, codes rows are 64 B per round with 4-bit levels
     int64_t kv_stride;     // tokens between consecutive units in ids / codes / scales (>= n_tokens)
     int chunk_stride;      // chunk tables between consecutive units in cent (>= n_chunks)
-    int id_wide;           // ids are 16-bit words (K > 256, S == 1)
+    int id_wide;           // ids are 16-bit words (K > 256)
 };
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t s);
 
@@ -223,7 +223,7 @@ struct AttnArgs {
     int64_t kv_stride;     // tokens between consecutive units in ids / codes / scales (>= n_kv)
     int chunk_stride;      // chunk tables between consecutive units in the centroid arrays (>= n_chunks)
     const f16_t *rope;     // [n_kv][d/2][2] (cos, sin) applied to the decoded keys, or nullptr
-    int id_wide;           // ids are 16-bit words (K > 256, S == 1)
+    int id_wide;           // ids are 16-bit words (K > 256)
     const int32_t *q_len;  // [n_q] prefix length per query (clamped to 0 .. n_kv), or nullptr: all n_kv tokens
     float *out_f32;        // when set, the result goes here as fp32 [H][n_q][d] (not rounded to bf16) and `out` is not written
 };

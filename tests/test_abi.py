@@ -59,7 +59,7 @@ def test_params_struct_layout():
 
 @pytest.mark.parametrize("kw,status", [
     (dict(n_heads=0), -2), (dict(n_clusters=0), -2), (dict(n_clusters=257), 0), (dict(n_clusters=512), 0),
-    (dict(n_clusters=513), -2), (dict(n_clusters=512, n_smooth_stages=2), -3),
+    (dict(n_clusters=513), -2), (dict(n_clusters=512, n_smooth_stages=2), 0),
     (dict(n_stages=0), -2), (dict(n_stages=9), -2), (dict(group_size=48), -2),
     (dict(head_dim=64), -3), (dict(bits=4), 0), (dict(bits=3), -2), (dict(bits=8), -2),
     (dict(scale_format=1), 0), (dict(scale_format=2), -2), (dict(scale_format=-1), -2),
