@@ -43,11 +43,15 @@ def test_shared_tiles_equal_the_fused_kernels(L, T, Bg, S, bits, fmt, K):
     for n_kv in (filled, 2 * L, L + 7, 64, 1):
         fused, lse_f = B.attn_decode(q, kc, vc, want_lse=True, n_kv=n_kv)
         n_chunks = -(-n_kv // L)
-        for slab_chunks in (n_chunks, 1):     # one slab; one chunk per slab (state carried n_chunks - 1 times)
-            out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=n_kv, workspace=_ws(H, Nq, L, slab_chunks))
+        # one slab; one chunk per slab (state carried n_chunks - 1 times); slabs of two and of three chunks
+        for slab_chunks in sorted({n_chunks, 1, min(2, n_chunks), min(3, n_chunks)}):
+            ws = _ws(H, Nq, L, slab_chunks)
+            out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=n_kv, workspace=ws)
+            out2, lse2 = B.attn_decode(q, kc, vc, want_lse=True, n_kv=n_kv, workspace=ws)   # straight after, same workspace
             torch.cuda.synchronize()
             assert torch.equal(out, fused), (n_kv, slab_chunks)
             assert torch.equal(lse, lse_f), (n_kv, slab_chunks)
+            assert torch.equal(out2, fused) and torch.equal(lse2, lse_f), (n_kv, slab_chunks)
         for h in range(H):
             _check_against_oracle(q, out, lse, P.to_np_u16(khat[h, :n_kv]), P.to_np_u16(vhat[h, :n_kv]), h)
 
@@ -150,3 +154,25 @@ def test_shared_tiles_with_a_prefix_length_per_query(L, T, Bg, S, bits, fmt, rop
             ok, max_abs, worst = P.attn_tolerance_ok(og[rows], want)
             assert ok, f"head {h}, prefix {n}: max abs err {max_abs}, worst err/tol {worst}"
             assert np.abs(lg[rows] - lse_w).max() < 2e-3, (h, n)
+
+
+def test_calls_back_to_back_on_two_streams_share_one_workspace():
+    """A cache of 9 chunks with a workspace for 4 (three slabs, the last one short or not), calls
+    following each other without a synchronisation, on the current and on another stream: every
+    call's kernels are ordered by the stream they are enqueued on, the workspace keeps nothing
+    that a later call relies on."""
+    H, L, K, Bg, T, Nq = 3, 330, 64, 64, 2, 900
+    q = synth.queries(CONFIGS["cfg2_window21"], H, Nq, DEV)
+    ws = _ws(H, Nq, L, 4)
+    results = []
+    for stream in (torch.cuda.current_stream(), torch.cuda.Stream()):
+        with torch.cuda.stream(stream):
+            for filled in (8 * L + 100, 7 * L + 1, 9 * L):             # 3, 2 and 3 slabs; the caches differ in length
+                kc, vc = _filled_caches(H, L, 9, filled, K, Bg, T)
+                out, lse = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled, workspace=ws)
+                fused, lse_f = B.attn_decode(q, kc, vc, want_lse=True, n_kv=filled)
+                results.append((out, lse, fused, lse_f))
+    torch.cuda.synchronize()
+    for out, lse, fused, lse_f in results:
+        assert torch.equal(out, fused) and torch.equal(lse, lse_f)
+    assert not torch.equal(results[0][0], results[1][0])             # different prefixes, different results
