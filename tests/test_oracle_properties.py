@@ -14,7 +14,8 @@ from hypothesis.extra import numpy as hnp  # noqa: E402
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 from oracle import qvg_oracle as O  # noqa: E402
 
-SETTINGS = dict(max_examples=60, deadline=None)
+# the same drawn examples on every run (a failure must be reproducible, and a pass must stay one), nothing written to disk
+SETTINGS = dict(max_examples=200, deadline=None, derandomize=True, database=None)
 
 
 @settings(**SETTINGS)
@@ -70,7 +71,7 @@ def test_quant_round_bound_for_any_group(fmt, B, data):
             assert np.abs(ag[n, g]).max() <= bound * (1 + 1e-6) + 1e-45
 
 
-@settings(max_examples=25, deadline=None)
+@settings(max_examples=60, deadline=None, derandomize=True, database=None)
 @given(st.sampled_from([(1, 2, 2, 0, 64), (1, 3, 2, 0, 32), (2, 1, 4, 1, 16), (1, 1, 2, 1, 64)]),
        st.integers(1, 40), st.integers(1, 9), st.integers(0, 2), st.integers(0, 2 ** 31 - 1))
 def test_decode_plus_what_remained_is_the_input(form, N, K, iters, seed):
@@ -94,7 +95,7 @@ def test_decode_plus_what_remained_is_the_input(form, N, K, iters, seed):
     # magnitude that passes through the fp32 additions of either chain
     size = np.abs(xin).max() + np.abs(O.bf16_to_f32(e["cent"]).astype(np.float64)).max() * S
     # a residual that feeds another smoothing stage travels as bf16: half a unit of its last place per such stage
-    tol = 2.0 ** -19 * size * (S + T) + (S - 1) * 2.0 ** -9 * size + 1e-30
+    tol = 2.0 ** -19 * size * (S + T) + (S - 1) * 2.0 ** -8 * size + 1e-30       # bf16: 8 significant bits
     assert np.abs(f32.astype(np.float64) + e["resid"].astype(np.float64) - xin).max() <= tol
     # the stored output is the fp32 sum rounded once to bf16
     assert np.array_equal(out, O.f32_to_bf16(f32))
